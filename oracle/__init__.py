@@ -1,0 +1,216 @@
+"""ctypes front end of the fp64 CPU oracle (hgca_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the
+benchmark's CPU-baseline leg, never by the HIP library or its binding.
+Arrays are numpy; bf16 tensors are passed as uint16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hgca_oracle.c")
+_LIB = os.path.join(_HERE, "libhgca_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (portable x86-64 code, no FP contraction)."""
+    hdr = os.path.join(_HERE, "hgca_oracle.h")
+    if not force and os.path.exists(_LIB):
+        newest = max(os.path.getmtime(_SRC), os.path.getmtime(hdr))
+        if os.path.getmtime(_LIB) >= newest:
+            return _LIB
+    cmd = ["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-fopenmp",
+           "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("batch", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("scale", ctypes.c_double)]
+
+
+class _Kv(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("seq_lens", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+                ("cap", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        for name in ("oracle_scores", "oracle_attend_all", "oracle_attend_indexed",
+                     "oracle_attend_union", "oracle_select", "oracle_merge",
+                     "oracle_hybrid_step", "oracle_num_threads"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+@dataclass
+class Tier:
+    """One KV tier (recent window or older pool) as the oracle sees it."""
+    k: np.ndarray                       # contiguous [B,Hkv,cap,d] or paged [n_blocks,Hkv,bs,d]
+    v: np.ndarray
+    cap: int                            # max logical tokens per sequence
+    seq_lens: Optional[np.ndarray] = None      # int32 [B]
+    block_table: Optional[np.ndarray] = None   # int32 [B,max_blocks]
+    block_size: int = 0
+
+    def lens(self, batch: int) -> np.ndarray:
+        if self.seq_lens is None:
+            return np.full(batch, self.cap, dtype=np.int32)
+        return self.seq_lens
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _shape(q: np.ndarray, tier: Tier, scale: float) -> _Shape:
+    assert q.ndim == 3 and q.flags.c_contiguous
+    code = _dtype_code(q)
+    assert _dtype_code(tier.k) == code and _dtype_code(tier.v) == code
+    return _Shape(code, q.shape[0], q.shape[1], tier.k.shape[1], q.shape[2], float(scale))
+
+
+def _kv(t: Tier, batch: int) -> _Kv:
+    assert t.k.flags.c_contiguous and t.v.flags.c_contiguous
+    max_blocks = 0
+    if t.block_table is not None:
+        assert t.block_table.dtype == np.int32 and t.block_table.flags.c_contiguous
+        assert t.block_table.shape[0] == batch and t.block_size > 0
+        max_blocks = t.block_table.shape[1]
+    if t.seq_lens is not None:
+        assert t.seq_lens.dtype == np.int32 and t.seq_lens.shape == (batch,)
+    return _Kv(_ptr(t.k), _ptr(t.v), _ptr(t.seq_lens), _ptr(t.block_table),
+               int(t.cap), int(t.block_size), int(max_blocks))
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def scores(q, tier: Tier, scale: float) -> np.ndarray:
+    sh, kv = _shape(q, tier, scale), _kv(tier, q.shape[0])
+    out = np.empty((q.shape[0], q.shape[1], tier.cap), dtype=np.float64)
+    _check(lib().oracle_scores(ctypes.byref(sh), _ptr(q), ctypes.byref(kv), _ptr(out)), "scores")
+    return out
+
+
+def attend_all(q, tier: Tier, scale: float):
+    sh, kv = _shape(q, tier, scale), _kv(tier, q.shape[0])
+    o = np.empty(q.shape, dtype=np.float64)
+    lse = np.empty(q.shape[:2], dtype=np.float64)
+    _check(lib().oracle_attend_all(ctypes.byref(sh), _ptr(q), ctypes.byref(kv),
+                                   _ptr(o), _ptr(lse)), "attend_all")
+    return o, lse
+
+
+def _idx_args(idx, cnt, q):
+    assert idx.dtype == np.int32 and cnt.dtype == np.int32
+    assert idx.flags.c_contiguous and cnt.flags.c_contiguous
+    assert idx.shape[:2] == q.shape[:2] and cnt.shape == q.shape[:2]
+    return int(idx.shape[2])
+
+
+def attend_indexed(q, tier: Tier, idx, cnt, scale: float):
+    sh, kv = _shape(q, tier, scale), _kv(tier, q.shape[0])
+    k_max = _idx_args(idx, cnt, q)
+    o = np.empty(q.shape, dtype=np.float64)
+    lse = np.empty(q.shape[:2], dtype=np.float64)
+    _check(lib().oracle_attend_indexed(ctypes.byref(sh), _ptr(q), ctypes.byref(kv), _ptr(idx),
+                                       _ptr(cnt), k_max, _ptr(o), _ptr(lse)), "attend_indexed")
+    return o, lse
+
+
+def attend_union(q, window: Tier, pool: Tier, idx, cnt, scale: float):
+    sh = _shape(q, window, scale)
+    assert _dtype_code(pool.k) == sh.dtype
+    kw, kp = _kv(window, q.shape[0]), _kv(pool, q.shape[0])
+    k_max = 0 if idx is None else _idx_args(idx, cnt, q)
+    o = np.empty(q.shape, dtype=np.float64)
+    lse = np.empty(q.shape[:2], dtype=np.float64)
+    _check(lib().oracle_attend_union(ctypes.byref(sh), _ptr(q), ctypes.byref(kw), ctypes.byref(kp),
+                                     _ptr(idx), _ptr(cnt), k_max, _ptr(o), _ptr(lse)), "attend_union")
+    return o, lse
+
+
+def _k_args(k, batch):
+    if np.isscalar(k):
+        return None, int(k)
+    k = np.ascontiguousarray(k, dtype=np.int32)
+    assert k.shape == (batch,)
+    return k, 0
+
+
+def select(q, pool: Tier, k, k_max: int, scale: float, round_scores_to_f32: bool = True):
+    sh, kv = _shape(q, pool, scale), _kv(pool, q.shape[0])
+    k_arr, k_uni = _k_args(k, q.shape[0])
+    idx = np.empty(q.shape[:2] + (k_max,), dtype=np.int32)
+    cnt = np.empty(q.shape[:2], dtype=np.int32)
+    _check(lib().oracle_select(ctypes.byref(sh), _ptr(q), ctypes.byref(kv), _ptr(k_arr), k_uni,
+                               int(k_max), int(bool(round_scores_to_f32)), _ptr(idx), _ptr(cnt)),
+           "select")
+    return idx, cnt
+
+
+def merge(o_a, lse_a, o_b, lse_b):
+    o_a = np.ascontiguousarray(o_a, dtype=np.float64)
+    o_b = np.ascontiguousarray(o_b, dtype=np.float64)
+    lse_a = np.ascontiguousarray(lse_a, dtype=np.float64)
+    lse_b = np.ascontiguousarray(lse_b, dtype=np.float64)
+    assert o_a.shape == o_b.shape and lse_a.shape == lse_b.shape == o_a.shape[:-1]
+    d = o_a.shape[-1]
+    rows = int(np.prod(o_a.shape[:-1], dtype=np.int64))
+    o = np.empty_like(o_a)
+    lse = np.empty_like(lse_a)
+    _check(lib().oracle_merge(ctypes.c_int64(rows), d, _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b),
+                              _ptr(o), _ptr(lse)), "merge")
+    return o, lse
+
+
+def hybrid_step(q, window: Tier, pool: Tier, k, k_max: int, scale: float, idx=None, cnt=None):
+    """Dense window, selection (unless idx/cnt are given), sparse part, merge."""
+    sh = _shape(q, window, scale)
+    kw, kp = _kv(window, q.shape[0]), _kv(pool, q.shape[0])
+    k_arr, k_uni = _k_args(k, q.shape[0])
+    do_select = idx is None
+    if do_select:
+        idx = np.empty(q.shape[:2] + (k_max,), dtype=np.int32)
+        cnt = np.empty(q.shape[:2], dtype=np.int32)
+    else:
+        assert _idx_args(idx, cnt, q) == k_max
+    o = np.empty(q.shape, dtype=np.float64)
+    lse = np.empty(q.shape[:2], dtype=np.float64)
+    _check(lib().oracle_hybrid_step(ctypes.byref(sh), _ptr(q), ctypes.byref(kw), ctypes.byref(kp),
+                                    _ptr(k_arr), k_uni, int(k_max), int(do_select), _ptr(idx), _ptr(cnt),
+                                    _ptr(o), _ptr(lse)), "hybrid_step")
+    return o, lse, idx, cnt
