@@ -1,0 +1,141 @@
+/*
+ * libhgca -- decode-time hybrid attention of HGCA (arXiv 2507.03153) for one
+ * AMD MI355X (gfx950).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * The paper (Sec. 3.3, Alg. 2) computes one decode step of an attention layer
+ * in two coordinated parts and a lossless aggregation:
+ *   1. dense attention of the new query over the W most recent KV entries,
+ *      returning the partial output O and its log-sum-exp;
+ *   2. per-head sparse attention over the salient entries selected from the
+ *      older, offloaded context, returning O and lse likewise;
+ *   3. merge_state: O = (e^{lse_c} O_c + e^{lse_g} O_g) / (e^{lse_c} + e^{lse_g}).
+ * Selection of the salient entries (Sec. 3.2.2) is per head.  In the paper the
+ * older context lives in host memory and parts 2 runs on CPU cores; here both
+ * tiers are HBM buffers on the same GPU and all parts are GPU kernels.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - `hgca_shape` and `hgca_kv_view` structs are HOST memory, read during the
+ *    call only.  Every other pointer is DEVICE memory owned by the caller.
+ *    The library never allocates, frees or synchronises: a call validates its
+ *    arguments on the host, enqueues kernels on `hip_stream` (a hipStream_t
+ *    passed as void*, NULL = the default stream) and returns.
+ *  - q is [B, Hq, d] in `shape.dtype` (fp32, or bf16 as 16-bit patterns).
+ *    Query head h reads KV head h / (Hq / Hkv).
+ *  - A KV tier (`hgca_kv_view`) is contiguous, k/v = [B, Hkv, cap, d], or paged,
+ *    k/v = [n_blocks, Hkv, block_size, d] with logical token t of sequence b in
+ *    physical block block_table[b * max_blocks + t / block_size], slot
+ *    t % block_size.  Valid tokens of sequence b are [0, seq_lens[b]) (all `cap`
+ *    when seq_lens is NULL).  The order of tokens inside a tier does not matter
+ *    to the result (softmax attention is a function of the key set).
+ *  - Scores are s_j = sm_scale * <q, k_j>; lse is the natural log of sum e^{s_j}.
+ *  - Partial outputs are fp32: O [B, Hq, d], lse [B, Hq].  An empty set gives
+ *    O = 0 and lse = -inf.
+ *  - q, k, v and O pointers must be 16-byte aligned.  head_dim is 64 or 128.
+ *  - `ws` is scratch the caller provides (split partials, score lists,
+ *    histograms); its required size for a call is `hgca_workspace_bytes` with
+ *    the maxima of that call.  Its contents are undefined between calls; two
+ *    calls that run concurrently (different streams) need different `ws`.
+ *  - Return value: HGCA_OK, or a negative hgca_status for errors the host can
+ *    see (bad arguments, unsupported shape, short workspace, launch failure).
+ *    On error nothing has been enqueued.  batch == 0 is a valid no-op.
+ */
+#ifndef HGCA_H
+#define HGCA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HGCA_OK = 0,
+    HGCA_ERR_INVALID_ARG = -1,   /* null/misaligned pointer, negative size, k > k_max ... */
+    HGCA_ERR_UNSUPPORTED = -2,   /* head_dim, dtype, group size or block size not built */
+    HGCA_ERR_WORKSPACE = -3,     /* ws is NULL or smaller than hgca_workspace_bytes()     */
+    HGCA_ERR_DEVICE = -4         /* the HIP runtime refused a launch                      */
+} hgca_status;
+
+typedef enum { HGCA_F32 = 0, HGCA_BF16 = 1 } hgca_dtype;
+
+typedef struct {
+    int32_t dtype;        /* hgca_dtype of q, K and V                 */
+    int32_t batch;        /* B                                        */
+    int32_t n_q_heads;    /* Hq                                       */
+    int32_t n_kv_heads;   /* Hkv, divides Hq; Hq/Hkv in {1,2,4,8}     */
+    int32_t head_dim;     /* d, 64 or 128                             */
+    float   sm_scale;     /* multiplies <q,k>; typically 1/sqrt(d)    */
+} hgca_shape;
+
+typedef struct {
+    const void    *k, *v;         /* device; v may be NULL where only keys are read   */
+    const int32_t *seq_lens;      /* device [B] or NULL                                */
+    const int32_t *block_table;   /* device [B, max_blocks] or NULL (= contiguous)     */
+    int32_t cap;                  /* capacity in tokens per sequence (logical)         */
+    int32_t block_size;           /* paged only: tokens per block, a multiple of 16    */
+    int32_t max_blocks;           /* paged only: row length of block_table             */
+} hgca_kv_view;
+
+/* Text for a status code (static storage). */
+const char *hgca_status_string(int status);
+
+/* Bytes of `ws` sufficient for any of the calls below on `shape` with a window
+ * of at most max_window tokens, a pool of at most max_pool tokens and at most
+ * k_max selected entries per head.  Returns 0 if the shape is invalid. */
+size_t hgca_workspace_bytes(const hgca_shape *shape, int32_t max_window,
+                            int32_t max_pool, int32_t k_max);
+
+/* GPU-local dense attention (Sec. 3.3 "GPU-local dense attention"; Alg. 2,
+ * gpu_attention): softmax attention of each query head over ALL valid tokens
+ * of `window`, which the caller has already extended with the token being
+ * decoded.  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32). */
+int hgca_dense_window_attn(const hgca_shape *shape, const void *q,
+                           const hgca_kv_view *window,
+                           float *o_out, float *lse_out,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Per-head selection of salient entries of the older context (Sec. 3.2.2,
+ * head-granularity sparsification; fixed-budget top-k form of Sec. 2.2):
+ * for every (b, h) score every valid pool token with the current query and keep
+ * the k_b = min(k, len_b) highest scores, k = k_per_seq[b] (device [B]) if
+ * given, else k_uniform.  Equal scores: the lower position wins.  Scores are
+ * compared in fp32.  idx_out [B,Hq,k_max] receives the kept logical positions in
+ * ascending order, padded with -1; cnt_out [B,Hq] receives k_b.  k_max is the
+ * row length of idx_out: min(k_uniform, pool->cap) must not exceed it (checked
+ * on the host; per-sequence budgets are clamped to k_max on the device).
+ * Only pool->k is read. */
+int hgca_select_salient(const hgca_shape *shape, const void *q,
+                        const hgca_kv_view *pool,
+                        const int32_t *k_per_seq, int32_t k_uniform,
+                        int32_t k_max, int32_t *idx_out, int32_t *cnt_out,
+                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Per-head sparse attention (Sec. 3.3 "CPU-local sparse attention"; Alg. 2,
+ * cpu_attention): softmax attention of query head (b,h) over pool rows
+ * idx[b,h,0 .. cnt[b,h]).  Entries at or beyond cnt[b,h] are ignored; the
+ * listed positions must be valid and distinct (a repeated position is counted
+ * twice).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32). */
+int hgca_sparse_attn(const hgca_shape *shape, const void *q,
+                     const hgca_kv_view *pool,
+                     const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                     float *o_out, float *lse_out,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/* merge_state (Sec. 3.3 "Merging states"): combines two partial results over
+ * disjoint key sets into the result of one softmax over their union.  Evaluated
+ * with both exponents shifted by max(lse_a, lse_b).  o_out is [B,Hq,d] in
+ * o_dtype (fp32 or bf16) and may alias o_a or o_b when o_dtype is fp32 (the
+ * paper merges in place); lse_out [B,Hq] is optional (NULL to skip) and may
+ * alias lse_a or lse_b.  Only batch, n_q_heads and head_dim of `shape` are used. */
+int hgca_lse_merge(const hgca_shape *shape,
+                   const float *o_a, const float *lse_a,
+                   const float *o_b, const float *lse_b,
+                   void *o_out, int32_t o_dtype, float *lse_out,
+                   void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGCA_H */

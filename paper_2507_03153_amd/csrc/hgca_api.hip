@@ -1,0 +1,247 @@
+// C ABI of libhgca: argument validation, workspace layout, kernel sequencing.
+// See include/hgca.h for the contract of every entry point.
+#include "../../include/hgca.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+
+#include "hgca_launch.hpp"
+
+namespace {
+
+using namespace hgca;
+
+constexpr size_t kAlign = 256;
+constexpr int kTargetWorkgroups = 2048;          // aim for ~8 workgroups per CU (256 CUs)
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int group_of(const hgca_shape *s) { return s->n_q_heads / s->n_kv_heads; }
+
+int check_shape(const hgca_shape *s)
+{
+    if (!s) return HGCA_ERR_INVALID_ARG;
+    if (s->batch < 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0) return HGCA_ERR_INVALID_ARG;
+    if (s->n_q_heads % s->n_kv_heads != 0) return HGCA_ERR_INVALID_ARG;
+    if (s->dtype != HGCA_F32 && s->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
+    if (s->head_dim != 64 && s->head_dim != 128) return HGCA_ERR_UNSUPPORTED;
+    const int g = group_of(s);
+    if (g != 1 && g != 2 && g != 4 && g != 8) return HGCA_ERR_UNSUPPORTED;
+    if (!(s->sm_scale == s->sm_scale)) return HGCA_ERR_INVALID_ARG;   // NaN
+    return HGCA_OK;
+}
+
+int check_view(const hgca_kv_view *v, bool need_v)
+{
+    if (!v) return HGCA_ERR_INVALID_ARG;
+    if (v->cap < 0) return HGCA_ERR_INVALID_ARG;
+    if (v->cap > 0) {
+        if (!v->k || !aligned16(v->k)) return HGCA_ERR_INVALID_ARG;
+        if (need_v && (!v->v || !aligned16(v->v))) return HGCA_ERR_INVALID_ARG;
+    }
+    if (v->block_table) {
+        if (v->block_size <= 0 || v->max_blocks <= 0) return HGCA_ERR_INVALID_ARG;
+        if (v->block_size % 16 != 0) return HGCA_ERR_UNSUPPORTED;
+        if ((int64_t)v->max_blocks * v->block_size < v->cap) return HGCA_ERR_INVALID_ARG;
+    }
+    return HGCA_OK;
+}
+
+KvDev to_dev(const hgca_kv_view *v)
+{
+    KvDev d{};
+    d.k = static_cast<const char *>(v->k);
+    d.v = static_cast<const char *>(v->v);
+    d.seq_lens = v->seq_lens;
+    d.block_table = v->block_table;
+    d.cap = v->cap;
+    d.block_size = v->block_table ? v->block_size : 1;
+    d.max_blocks = v->block_table ? v->max_blocks : 0;
+    return d;
+}
+
+ShapeDev to_dev(const hgca_shape *s)
+{
+    ShapeDev d{};
+    d.batch = s->batch;
+    d.n_q_heads = s->n_q_heads;
+    d.n_kv_heads = s->n_kv_heads;
+    d.group = group_of(s);
+    d.sm_scale = s->sm_scale;
+    return d;
+}
+
+// Tokens per split for a set of at most n tokens processed by `units` independent
+// (sequence, head unit) pairs: a multiple of 64 in [kMinChunk, kMaxChunk] that yields
+// roughly kTargetWorkgroups workgroups.
+int pick_chunk(int64_t n, int64_t units)
+{
+    if (n <= 0 || units <= 0) return kMinChunk;
+    const int64_t want_splits = std::max<int64_t>(1, kTargetWorkgroups / units);
+    int64_t chunk = (n + want_splits - 1) / want_splits;
+    chunk = (chunk + 63) / 64 * 64;
+    return (int)std::min<int64_t>(kMaxChunk, std::max<int64_t>(kMinChunk, chunk));
+}
+
+int n_splits_for(int64_t n, int chunk) { return (int)((n + chunk - 1) / chunk); }
+
+// Workspace layout: [partials o | partials m | partials l | scores].
+struct WsLayout {
+    size_t part_o, part_m, part_l, scores, total;
+};
+
+WsLayout layout(const hgca_shape *s, int64_t max_attn_tokens, int64_t max_pool)
+{
+    const size_t rows = (size_t)s->batch * s->n_q_heads;
+    const size_t max_splits = (size_t)n_splits_for(std::max<int64_t>(max_attn_tokens, 1), kMinChunk);
+    WsLayout w{};
+    size_t at = 0;
+    w.part_o = at; at += align_up(rows * max_splits * s->head_dim * sizeof(float));
+    w.part_m = at; at += align_up(rows * max_splits * sizeof(float));
+    w.part_l = at; at += align_up(rows * max_splits * sizeof(float));
+    w.scores = at; at += align_up(rows * (size_t)std::max<int64_t>(max_pool, 0) * sizeof(float));
+    w.total = std::max<size_t>(at, kAlign);
+    return w;
+}
+
+Partials partials_at(void *ws, const WsLayout &w, int n_splits)
+{
+    char *base = static_cast<char *>(ws);
+    Partials p{};
+    p.o = reinterpret_cast<float *>(base + w.part_o);
+    p.m = reinterpret_cast<float *>(base + w.part_m);
+    p.l = reinterpret_cast<float *>(base + w.part_l);
+    p.n_splits = n_splits;
+    return p;
+}
+
+int from_hip(hipError_t e) { return e == hipSuccess ? HGCA_OK : HGCA_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+const char *hgca_status_string(int status)
+{
+    switch (status) {
+    case HGCA_OK: return "ok";
+    case HGCA_ERR_INVALID_ARG: return "invalid argument";
+    case HGCA_ERR_UNSUPPORTED: return "unsupported shape, dtype or layout";
+    case HGCA_ERR_WORKSPACE: return "workspace missing or too small";
+    case HGCA_ERR_DEVICE: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+size_t hgca_workspace_bytes(const hgca_shape *shape, int32_t max_window, int32_t max_pool, int32_t k_max)
+{
+    if (check_shape(shape) != HGCA_OK || max_window < 0 || max_pool < 0 || k_max < 0) return 0;
+    return layout(shape, std::max(max_window, k_max), max_pool).total;
+}
+
+int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
+                           float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;       // nothing to do
+    if ((rc = check_view(window, true)) != HGCA_OK) return rc;
+    if (!q || !o_out || !lse_out || !aligned16(q) || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    const WsLayout w = layout(shape, window->cap, 0);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    AttnArgs a{};
+    a.sh = to_dev(shape);
+    a.q = q;
+    a.kv = to_dev(window);
+    a.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads);
+    a.part = partials_at(ws, w, n_splits_for(window->cap, a.chunk));
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
+    return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
+}
+
+int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *k_per_seq,
+                        int32_t k_uniform, int32_t k_max, int32_t *idx_out, int32_t *cnt_out, void *ws,
+                        size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(pool, false)) != HGCA_OK) return rc;
+    if (!q || !aligned16(q) || !cnt_out || k_max < 0 || (k_max > 0 && !idx_out)) return HGCA_ERR_INVALID_ARG;
+    if (!k_per_seq && (k_uniform < 0 || std::min(k_uniform, pool->cap) > k_max)) return HGCA_ERR_INVALID_ARG;
+    const WsLayout w = layout(shape, 0, pool->cap);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    ScoreArgs sa{};
+    sa.sh = to_dev(shape);
+    sa.q = q;
+    sa.kv = to_dev(pool);
+    sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws) + w.scores);
+    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads);
+    sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
+    if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
+
+    SelectArgs se{};
+    se.sh = sa.sh;
+    se.kv = sa.kv;
+    se.scores = sa.scores;
+    se.k_per_seq = k_per_seq;
+    se.k_uniform = k_uniform;
+    se.k_max = k_max;
+    se.idx = idx_out;
+    se.cnt = cnt_out;
+    return from_hip(launch_select(se, s));
+}
+
+int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *idx,
+                     const int32_t *cnt, int32_t k_max, float *o_out, float *lse_out, void *ws, size_t ws_bytes,
+                     void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(pool, true)) != HGCA_OK) return rc;
+    if (!q || !o_out || !lse_out || !aligned16(q) || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    if (k_max < 0 || !cnt || (k_max > 0 && !idx)) return HGCA_ERR_INVALID_ARG;
+    const WsLayout w = layout(shape, k_max, 0);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    AttnArgs a{};
+    a.sh = to_dev(shape);
+    a.q = q;
+    a.kv = to_dev(pool);
+    a.idx = idx;
+    a.cnt = cnt;
+    a.k_max = k_max;
+    a.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads);
+    a.part = partials_at(ws, w, std::max(1, n_splits_for(k_max, a.chunk)));
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
+    return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
+}
+
+int hgca_lse_merge(const hgca_shape *shape, const float *o_a, const float *lse_a, const float *o_b,
+                   const float *lse_b, void *o_out, int32_t o_dtype, float *lse_out, void *hip_stream)
+{
+    if (!shape || shape->batch < 0 || shape->n_q_heads <= 0) return HGCA_ERR_INVALID_ARG;
+    if (shape->head_dim != 64 && shape->head_dim != 128) return HGCA_ERR_UNSUPPORTED;
+    if (o_dtype != HGCA_F32 && o_dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return HGCA_OK;
+    if (!o_a || !lse_a || !o_b || !lse_b || !o_out) return HGCA_ERR_INVALID_ARG;
+    if (o_dtype == HGCA_BF16 && (o_out == (const void *)o_a || o_out == (const void *)o_b))
+        return HGCA_ERR_INVALID_ARG;             // a bf16 result cannot overwrite an fp32 input in place
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    return from_hip(launch_merge(shape->head_dim, rows, o_a, lse_a, o_b, lse_b, o_out, o_dtype, lse_out,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+// Device-side helpers shared by the HGCA kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hgca {
+
+constexpr int kWave = 64;
+
+struct bf16_t { uint16_t bits; };   // storage tag: upper half of an IEEE fp32
+
+// One KV tier as the kernels see it (mirrors hgca_kv_view, pointers are device memory).
+struct KvDev {
+    const char *k, *v;
+    const int32_t *seq_lens;
+    const int32_t *block_table;
+    int32_t cap, block_size, max_blocks;
+};
+
+// Shape scalars passed by value to kernels.
+struct ShapeDev {
+    int32_t batch, n_q_heads, n_kv_heads, group;
+    float sm_scale;
+};
+
+template <typename T> struct Elem;
+
+template <> struct Elem<float> {
+    static constexpr int kPerLoad = 4;            // elements in one 16-byte load
+    static __device__ __forceinline__ void expand(const uint4 &r, float *f) {
+        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+        f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+    }
+};
+
+template <> struct Elem<bf16_t> {
+    static constexpr int kPerLoad = 8;
+    static __device__ __forceinline__ void expand(const uint4 &r, float *f) {
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+        f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+        f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+};
+
+__device__ __forceinline__ int32_t tier_len(const KvDev &kv, int b) {
+    return kv.seq_lens ? min(max(kv.seq_lens[b], 0), kv.cap) : kv.cap;   // never beyond the buffer
+}
+
+// Byte offset of row (b, kvh, t) inside a tier's k or v buffer.
+template <int kRowBytes>
+__device__ __forceinline__ size_t row_offset(const KvDev &kv, int n_kv_heads, int b, int kvh, int32_t t) {
+    if (kv.block_table) {
+        const int32_t blk = kv.block_table[(size_t)b * kv.max_blocks + t / kv.block_size];
+        const int32_t slot = t % kv.block_size;
+        return (((size_t)blk * n_kv_heads + kvh) * kv.block_size + slot) * kRowBytes;
+    }
+    return (((size_t)b * n_kv_heads + kvh) * kv.cap + t) * kRowBytes;
+}
+
+__device__ __forceinline__ uint4 load16(const char *p) {
+    return *reinterpret_cast<const uint4 *>(p);
+}
+
+template <int kWidth>
+__device__ __forceinline__ float group_sum(float v) {      // sum over kWidth adjacent lanes
+#pragma unroll
+    for (int off = kWidth / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+}  // namespace hgca

@@ -1,0 +1,65 @@
+// Host-side launch functions of the HGCA kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hgca_device.hpp"
+
+namespace hgca {
+
+constexpr int kMaxChunk = 512;     // tokens of one split (one workgroup) at most
+constexpr int kMinChunk = 64;
+
+// Split partials of softmax attention: for every (b, h, split)
+//   m = max score, l = sum e^{s-m}, o[d] = sum e^{s-m} v   (not normalised).
+struct Partials {
+    float *o;      // [B*Hq, n_splits, d]
+    float *m;      // [B*Hq, n_splits]
+    float *l;      // [B*Hq, n_splits]
+    int32_t n_splits;
+};
+
+struct AttnArgs {
+    ShapeDev sh;
+    const void *q;
+    KvDev kv;
+    const int32_t *idx;    // gather only: [B, Hq, k_max]
+    const int32_t *cnt;    // gather only: [B, Hq]
+    int32_t k_max;
+    int32_t chunk;         // tokens per split
+    Partials part;
+};
+
+// dtype: 0 fp32, 1 bf16; head_dim 64|128.  Dense handles the `group` query heads
+// of one KV head per workgroup; gather handles one query head per workgroup.
+hipError_t launch_attn_partial_dense(int dtype, int head_dim, const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_partial_gather(int dtype, int head_dim, const AttnArgs &a, hipStream_t s);
+
+hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float *o, float *lse, hipStream_t s);
+
+hipError_t launch_merge(int head_dim, int64_t n_rows, const float *o_a, const float *lse_a, const float *o_b,
+                        const float *lse_b, void *o_out, int o_dtype, float *lse_out, hipStream_t s);
+
+struct ScoreArgs {
+    ShapeDev sh;
+    const void *q;
+    KvDev kv;
+    float *scores;         // [B, Hq, cap] fp32
+    int32_t chunk;
+    int32_t n_chunks;
+};
+hipError_t launch_scores(int dtype, int head_dim, const ScoreArgs &a, hipStream_t s);
+
+struct SelectArgs {
+    ShapeDev sh;
+    KvDev kv;              // only seq_lens / cap are used
+    const float *scores;   // [B, Hq, cap]
+    const int32_t *k_per_seq;
+    int32_t k_uniform, k_max;
+    int32_t *idx;          // [B, Hq, k_max]
+    int32_t *cnt;          // [B, Hq]
+};
+hipError_t launch_select(const SelectArgs &a, hipStream_t s);
+
+}  // namespace hgca

@@ -1,0 +1,179 @@
+"""Thin ctypes binding of libhgca.so (the C ABI declared in include/hgca.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  Tensors are torch tensors on the GPU; torch is used for device
+memory and streams.  There is no CPU fallback: without the built library, or
+with a tensor that is not on a GPU, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch  # noqa: F401  (loads the HIP runtime the library binds to; must precede CDLL)
+
+F32, BF16 = 0, 1
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, -1, -2, -3, -4
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhgca.so")
+
+EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
+           "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("sm_scale", ctypes.c_float)]
+
+
+class KvView(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+                ("block_table", ctypes.c_void_p), ("cap", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32)]
+
+
+class HgcaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2507_03153_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(f"{_LIB_PATH} is missing: build it with "
+                                    "`python -m paper_2507_03153_amd.build`; there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        ps, pk = ctypes.POINTER(Shape), ctypes.POINTER(KvView)
+        L.hgca_status_string.restype = ctypes.c_char_p
+        L.hgca_status_string.argtypes = [ctypes.c_int]
+        L.hgca_workspace_bytes.restype = sz
+        L.hgca_workspace_bytes.argtypes = [ps, i32, i32, i32]
+        L.hgca_dense_window_attn.restype = ctypes.c_int
+        L.hgca_dense_window_attn.argtypes = [ps, vp, pk, vp, vp, vp, sz, vp]
+        L.hgca_select_salient.restype = ctypes.c_int
+        L.hgca_select_salient.argtypes = [ps, vp, pk, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.hgca_sparse_attn.restype = ctypes.c_int
+        L.hgca_sparse_attn.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.hgca_lse_merge.restype = ctypes.c_int
+        L.hgca_lse_merge.argtypes = [ps, vp, vp, vp, vp, vp, i32, vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().hgca_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise HgcaError(status, where)
+
+
+@dataclass
+class Tier:
+    """One KV tier on the GPU.  k/v: contiguous [B,Hkv,cap,d] or paged [n_blocks,Hkv,bs,d]."""
+    k: torch.Tensor
+    v: Optional[torch.Tensor]
+    cap: int
+    seq_lens: Optional[torch.Tensor] = None      # int32 [B]
+    block_table: Optional[torch.Tensor] = None   # int32 [B,max_blocks]
+    block_size: int = 0
+
+    def view(self) -> KvView:
+        for t in (self.k, self.v, self.seq_lens, self.block_table):
+            if t is not None:
+                _require_gpu(t)
+        mb = 0 if self.block_table is None else int(self.block_table.shape[1])
+        return KvView(_ptr(self.k), _ptr(self.v), _ptr(self.seq_lens), _ptr(self.block_table),
+                      int(self.cap), int(self.block_size), mb)
+
+
+def _require_gpu(t: torch.Tensor) -> None:
+    if not t.is_cuda:
+        raise ValueError("libhgca takes GPU tensors only (no CPU path exists)")
+    if not t.is_contiguous():
+        raise ValueError("libhgca takes contiguous tensors")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    return ctypes.c_void_p(t.data_ptr()) if t.numel() else ctypes.c_void_p(t.data_ptr() or 0)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"q/K/V must be float32 or bfloat16, got {t.dtype}")
+
+
+def make_shape(q: torch.Tensor, n_kv_heads: int, sm_scale: float) -> Shape:
+    _require_gpu(q)
+    B, Hq, d = q.shape
+    return Shape(_dtype_code(q), B, Hq, int(n_kv_heads), d, float(sm_scale))
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def workspace_bytes(shape: Shape, max_window: int, max_pool: int, k_max: int) -> int:
+    return int(lib().hgca_workspace_bytes(ctypes.byref(shape), int(max_window), int(max_pool), int(k_max)))
+
+
+def alloc_workspace(shape: Shape, max_window: int, max_pool: int, k_max: int, device) -> torch.Tensor:
+    n = workspace_bytes(shape, max_window, max_pool, k_max)
+    if n == 0:
+        raise HgcaError(ERR_INVALID_ARG, "hgca_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def dense_window_attn(shape: Shape, q, window: Tier, o_out, lse_out, ws, stream=None) -> None:
+    for t in (q, o_out, lse_out, ws):
+        _require_gpu(t)
+    kv = window.view()
+    _check(lib().hgca_dense_window_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out), _ptr(lse_out),
+                                        _ptr(ws), ws.numel(), _stream(stream)), "hgca_dense_window_attn")
+
+
+def select_salient(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out, ws, stream=None) -> None:
+    """k: int (uniform budget) or int32 GPU tensor [B] (per-sequence budgets)."""
+    for t in (q, idx_out, cnt_out, ws):
+        _require_gpu(t)
+    kv = pool.view()
+    if isinstance(k, torch.Tensor):
+        _require_gpu(k)
+        k_ptr, k_uni = _ptr(k), 0
+    else:
+        k_ptr, k_uni = None, int(k)
+    _check(lib().hgca_select_salient(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), k_ptr, k_uni, int(k_max),
+                                     _ptr(idx_out), _ptr(cnt_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_select_salient")
+
+
+def sparse_attn(shape: Shape, q, pool: Tier, idx, cnt, k_max: int, o_out, lse_out, ws, stream=None) -> None:
+    for t in (q, idx, cnt, o_out, lse_out, ws):
+        _require_gpu(t)
+    kv = pool.view()
+    _check(lib().hgca_sparse_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
+                                  _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_sparse_attn")
+
+
+def lse_merge(shape: Shape, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None) -> None:
+    for t in (o_a, lse_a, o_b, lse_b, o_out):
+        _require_gpu(t)
+    _check(lib().hgca_lse_merge(ctypes.byref(shape), _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b), _ptr(o_out),
+                                _dtype_code(o_out), _ptr(lse_out), _stream(stream)), "hgca_lse_merge")

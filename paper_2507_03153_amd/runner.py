@@ -1,0 +1,87 @@
+"""Plumbing around the four library calls: upload a generated layer to the GPU,
+own the output / workspace buffers, and enqueue one hybrid layer-step.
+
+Order of a step (paper Alg. 2, decode branch): the dense window part and the
+(select ->) sparse part are independent and may run on two streams; the merge
+joins them.  Nothing here computes: every step is a libhgca call.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import hgca
+from .workloads import Layer, TierData
+
+
+def _to_gpu(a: Optional[np.ndarray], device) -> Optional[torch.Tensor]:
+    if a is None:
+        return None
+    if a.dtype == np.uint16:                                   # bf16 bit patterns
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def upload_tier(t: TierData, device) -> hgca.Tier:
+    return hgca.Tier(_to_gpu(t.k, device), _to_gpu(t.v, device), t.cap, _to_gpu(t.seq_lens, device),
+                     _to_gpu(t.block_table, device), t.block_size)
+
+
+@dataclass
+class DeviceLayer:
+    q: torch.Tensor
+    window: hgca.Tier
+    pool: hgca.Tier
+    k: object                   # int or int32 GPU tensor [B]
+    k_max: int
+    shape: hgca.Shape
+
+    @staticmethod
+    def upload(layer: Layer, device="cuda:0") -> "DeviceLayer":
+        q = _to_gpu(layer.q, device)
+        k = layer.k if np.isscalar(layer.k) else _to_gpu(np.ascontiguousarray(layer.k, np.int32), device)
+        shape = hgca.make_shape(q, layer.cfg.Hkv, layer.scale)
+        return DeviceLayer(q, upload_tier(layer.window, device), upload_tier(layer.pool, device), k,
+                           layer.k_max, shape)
+
+
+class HybridStep:
+    """Buffers for one layer-step on `shape`; `run` enqueues dense, select, sparse and merge."""
+
+    def __init__(self, shape: hgca.Shape, max_window: int, max_pool: int, k_max: int, device="cuda:0",
+                 out_dtype=torch.float32, two_streams: bool = False):
+        B, Hq, d = shape.batch, shape.n_q_heads, shape.head_dim
+        f32 = dict(dtype=torch.float32, device=device)
+        self.shape, self.k_max, self.device = shape, k_max, device
+        self.o_w, self.lse_w = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
+        self.o_s, self.lse_s = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
+        self.o = torch.empty(B, Hq, d, dtype=out_dtype, device=device)
+        self.lse = torch.empty(B, Hq, **f32)
+        self.idx = torch.full((B, Hq, max(k_max, 1)), -1, dtype=torch.int32, device=device)
+        self.cnt = torch.zeros(B, Hq, dtype=torch.int32, device=device)
+        # the two branches may overlap, so each owns a workspace
+        self.ws_dense = hgca.alloc_workspace(shape, max_window, 0, 0, device)
+        self.ws_sparse = hgca.alloc_workspace(shape, 0, max_pool, k_max, device)
+        self.side = torch.cuda.Stream(device=device) if two_streams else None
+        self._fork = torch.cuda.Event() if two_streams else None
+        self._join = torch.cuda.Event() if two_streams else None
+
+    def run(self, L: DeviceLayer, select: bool = True, stream=None) -> None:
+        main = torch.cuda.current_stream() if stream is None else stream
+        side = main
+        if self.side is not None:
+            side = self.side
+            self._fork.record(main)
+            side.wait_event(self._fork)
+        if select:
+            hgca.select_salient(self.shape, L.q, L.pool, L.k, self.k_max, self.idx, self.cnt, self.ws_sparse, side)
+        hgca.sparse_attn(self.shape, L.q, L.pool, self.idx, self.cnt, self.k_max, self.o_s, self.lse_s,
+                         self.ws_sparse, side)
+        hgca.dense_window_attn(self.shape, L.q, L.window, self.o_w, self.lse_w, self.ws_dense, main)
+        if self.side is not None:
+            self._join.record(side)
+            main.wait_event(self._join)
+        hgca.lse_merge(self.shape, self.o_s, self.lse_s, self.o_w, self.lse_w, self.o, self.lse, main)

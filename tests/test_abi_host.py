@@ -1,0 +1,141 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/hgca.h declares,
+sizes its workspace sensibly and rejects bad arguments before touching the device.
+No call here reaches a kernel launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def hg():
+    from paper_2507_03153_amd import build, hgca
+    build.build(force=False)
+    hgca.lib()
+    return hgca
+
+
+def test_every_declared_symbol_is_exported(hg):
+    with open(os.path.join(ROOT, "include", "hgca.h")) as f:
+        header = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = set(re.findall(r"\b(hgca_\w+)\s*\(", header))
+    assert declared == set(hg.EXPORTS)
+    L = ctypes.CDLL(os.path.join(ROOT, "paper_2507_03153_amd", "libhgca.so"))
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings(hg):
+    texts = {hg.status_string(s) for s in (0, -1, -2, -3, -4)}
+    assert len(texts) == 5 and hg.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes(hg):
+    sh = hg.Shape(hg.BF16, 8, 32, 8, 128, 0.088)
+    small = hg.workspace_bytes(sh, 4096, 0, 0)
+    full = hg.workspace_bytes(sh, 4096, 28672, 2048)
+    assert 0 < small < full
+    assert full >= 8 * 32 * 28672 * 4                        # room for one fp32 score per pool token and head
+    assert hg.workspace_bytes(sh, 0, 0, 0) > 0
+    assert hg.workspace_bytes(hg.Shape(hg.BF16, 8, 32, 5, 128, 1.0), 16, 16, 4) == 0
+    assert hg.workspace_bytes(sh, -1, 0, 0) == 0
+
+
+FAKE = ctypes.c_void_p(0x10000)       # non-null, 16-byte aligned, never dereferenced on these paths
+ODD = ctypes.c_void_p(0x10004)
+
+
+def _view(hg, cap=64, k=FAKE, v=FAKE, table=None, bs=0, mb=0):
+    return hg.KvView(k, v, None, table, cap, bs, mb)
+
+
+def _dense(hg, sh, view, q=FAKE, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    return hg.lib().hgca_dense_window_attn(ctypes.byref(sh), q, ctypes.byref(view), o, lse, ws, ws_bytes, None)
+
+
+def test_dense_rejects_bad_arguments(hg):
+    good = hg.Shape(hg.F32, 1, 4, 4, 64, 0.125)
+    v = _view(hg)
+    assert _dense(hg, hg.Shape(hg.F32, 1, 4, 3, 64, 0.125), v) == hg.ERR_INVALID_ARG     # Hq % Hkv
+    assert _dense(hg, hg.Shape(hg.F32, 1, 4, 4, 80, 0.125), v) == hg.ERR_UNSUPPORTED     # head_dim
+    assert _dense(hg, hg.Shape(7, 1, 4, 4, 64, 0.125), v) == hg.ERR_UNSUPPORTED          # dtype
+    assert _dense(hg, hg.Shape(hg.F32, 1, 48, 4, 64, 0.125), v) == hg.ERR_UNSUPPORTED    # group of 12
+    assert _dense(hg, hg.Shape(hg.F32, -1, 4, 4, 64, 0.125), v) == hg.ERR_INVALID_ARG
+    assert _dense(hg, hg.Shape(hg.F32, 1, 4, 4, 64, float("nan")), v) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, v, q=None) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, v, q=ODD) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, v, o=None) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, v, lse=None) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, _view(hg, k=None)) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, _view(hg, v=None)) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, _view(hg, k=ODD)) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, _view(hg, cap=-3)) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, _view(hg, table=FAKE, bs=24, mb=8)) == hg.ERR_UNSUPPORTED    # block size % 16
+    assert _dense(hg, good, _view(hg, table=FAKE, bs=16, mb=3)) == hg.ERR_INVALID_ARG    # table too short
+    assert _dense(hg, good, _view(hg, table=FAKE, bs=0, mb=4)) == hg.ERR_INVALID_ARG
+    assert _dense(hg, good, v, ws=None) == hg.ERR_WORKSPACE
+    assert _dense(hg, good, v, ws_bytes=16) == hg.ERR_WORKSPACE
+    need = hg.workspace_bytes(good, 64, 0, 0)
+    assert _dense(hg, good, v, ws_bytes=need - 1) == hg.ERR_WORKSPACE
+    assert hg.lib().hgca_dense_window_attn(None, FAKE, ctypes.byref(v), FAKE, FAKE, FAKE, 1 << 40, None) \
+        == hg.ERR_INVALID_ARG
+    assert hg.lib().hgca_dense_window_attn(ctypes.byref(good), FAKE, None, FAKE, FAKE, FAKE, 1 << 40, None) \
+        == hg.ERR_INVALID_ARG
+
+
+def test_select_and_sparse_reject_bad_arguments(hg):
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    v = _view(hg, cap=256)
+    L = hg.lib()
+
+    def select(k_ptr=None, k_uni=8, k_max=8, idx=FAKE, cnt=FAKE, ws=FAKE, ws_bytes=1 << 40, view=v, q=FAKE):
+        return L.hgca_select_salient(ctypes.byref(sh), q, ctypes.byref(view), k_ptr, k_uni, k_max, idx, cnt, ws,
+                                     ws_bytes, None)
+
+    assert select(k_uni=9) == hg.ERR_INVALID_ARG              # k > k_max
+    assert select(k_uni=-1) == hg.ERR_INVALID_ARG
+    assert select(k_max=-1) == hg.ERR_INVALID_ARG
+    assert select(idx=None) == hg.ERR_INVALID_ARG
+    assert select(cnt=None) == hg.ERR_INVALID_ARG
+    assert select(q=None) == hg.ERR_INVALID_ARG
+    assert select(ws_bytes=1024) == hg.ERR_WORKSPACE
+    assert select(view=_view(hg, cap=256, k=None, v=None)) == hg.ERR_INVALID_ARG
+    need = hg.workspace_bytes(sh, 0, 256, 8)
+    assert select(ws_bytes=need - 1) == hg.ERR_WORKSPACE
+
+    def sparse(idx=FAKE, cnt=FAKE, k_max=8, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40, view=v):
+        return L.hgca_sparse_attn(ctypes.byref(sh), FAKE, ctypes.byref(view), idx, cnt, k_max, o, lse, ws,
+                                  ws_bytes, None)
+
+    assert sparse(idx=None) == hg.ERR_INVALID_ARG
+    assert sparse(cnt=None) == hg.ERR_INVALID_ARG
+    assert sparse(k_max=-2) == hg.ERR_INVALID_ARG
+    assert sparse(o=ODD) == hg.ERR_INVALID_ARG
+    assert sparse(view=_view(hg, cap=256, v=None)) == hg.ERR_INVALID_ARG      # sparse attention reads V
+    assert sparse(ws=None) == hg.ERR_WORKSPACE
+
+
+def test_merge_rejects_bad_arguments(hg):
+    sh = hg.Shape(hg.F32, 2, 4, 4, 128, 1.0)
+    L = hg.lib()
+
+    def merge(o_a=FAKE, l_a=FAKE, o_b=ctypes.c_void_p(0x20000), l_b=FAKE, out=ctypes.c_void_p(0x30000),
+              dt=hg.F32, shape=sh):
+        return L.hgca_lse_merge(ctypes.byref(shape), o_a, l_a, o_b, l_b, out, dt, None, None)
+
+    assert merge(o_a=None) == hg.ERR_INVALID_ARG
+    assert merge(l_b=None) == hg.ERR_INVALID_ARG
+    assert merge(out=None) == hg.ERR_INVALID_ARG
+    assert merge(dt=5) == hg.ERR_UNSUPPORTED
+    assert merge(out=FAKE, dt=hg.BF16) == hg.ERR_INVALID_ARG                  # bf16 result over an fp32 input
+    assert merge(shape=hg.Shape(hg.F32, 2, 4, 4, 96, 1.0)) == hg.ERR_UNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors(hg):
+    import torch
+    q = torch.zeros(1, 4, 64)
+    with pytest.raises(ValueError):
+        hg.make_shape(q, 4, 0.125)
