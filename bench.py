@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid decode-attention layer-step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--streams 1|2] [--no-cpu]
+
+A step is one pass of the whole hot path over one batch: hgca_dense_window_attn,
+hgca_select_salient, hgca_sparse_attn and hgca_lse_merge on the 8B-shape 32K-context
+workload (C2: bf16, B=8, Hq=32, Hkv=8, d=128, window 4096, pool 28672, k=2048) with
+seeded synthetic K/V already resident in HBM.  Steps cycle over L independently drawn
+layers so that consecutive steps do not re-read K/V still held in L2 / Infinity Cache.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+METRIC = "hybrid decode-attn layer-steps/s + achieved HBM GB/s vs peak (8B shape, 32K)"
+
+# HBM bytes per launch of the pool-score kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters on a copy kernel of known size); see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def log(msg: str) -> None:
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--layers", type=int, default=4, help="independent KV draws cycled through")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: dense window part overlaps select+sparse (the paper's two concurrent parts)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work of the baseline sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2507_03153_amd import hgca, runner, workloads as wl
+
+    hgca.lib()                                                  # no fallback: fails loudly if not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    cfg = wl.CONFIGS["C2"]
+    w_lens, p_lens, k = wl.seq_lengths(cfg)
+    nbytes = wl.step_bytes(cfg, w_lens, p_lens, k)
+
+    t0 = time.time()
+    host_layers = [wl.make_layer(cfg, layer) for layer in range(args.layers)]
+    layers = [runner.DeviceLayer.upload(L, dev) for L in host_layers]
+    log(f"[bench] {args.layers} layers of C2 generated and uploaded in {time.time() - t0:.1f}s "
+        f"({sum(L.kv_bytes() for L in host_layers) / 2**30:.2f} GiB of KV)")
+    step = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, cfg.k, dev, two_streams=(args.streams == 2))
+    main_stream = torch.cuda.current_stream()
+
+    prepared = [step.prepare(L) for L in layers]               # arguments marshalled once per layer
+
+    def run_steps(n: int, select: bool, first: int = 0) -> None:
+        for i in range(n):
+            prepared[(first + i) % len(prepared)](select)
+
+    # ---- full step: all four calls ----------------------------------------------------------
+    run_steps(args.warmup, True)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(main_stream)
+    run_steps(args.steps, True, args.warmup)
+    e1.record(main_stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3 / args.steps
+    full_ms = e0.elapsed_time(e1) / args.steps
+    ms_per_step = max(full_ms, wall_ms)                         # host-side launch cost counts too
+
+    # ---- steady step: selection reused (Alg. 2's decode branch loads pre-selected entries) ------
+    run_steps(args.warmup, False)
+    torch.cuda.synchronize()
+    e0.record(main_stream)
+    run_steps(args.steps, False, args.warmup)
+    e1.record(main_stream)
+    torch.cuda.synchronize()
+    steady_ms = e0.elapsed_time(e1) / args.steps
+
+    # ---- per-call device time, one stream, events on the launch stream ---------------------------
+    def time_call(fn, n=args.steps) -> float:
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i in range(min(args.warmup, 5)):
+            fn(layers[i % len(layers)])
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            L = layers[i % len(layers)]
+            a.record(main_stream)
+            fn(L)
+            b.record(main_stream)
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+    scores_buf = torch.empty(cfg.B, cfg.Hq, cfg.P, dtype=torch.float32, device=dev)
+    sh = layers[0].shape
+    calls = {
+        "dense_window_attn": lambda L: hgca.dense_window_attn(sh, L.q, L.window, step.o_w, step.lse_w, step.ws_dense),
+        "pool_scores": lambda L: hgca.pool_scores(sh, L.q, L.pool, scores_buf),
+        "select_salient": lambda L: hgca.select_salient(sh, L.q, L.pool, L.k, cfg.k, step.idx, step.cnt,
+                                                        step.ws_sparse),
+        "sparse_attn": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, cfg.k, step.o_s, step.lse_s,
+                                                  step.ws_sparse),
+        "lse_merge": lambda L: hgca.lse_merge(sh, step.o_s, step.lse_s, step.o_w, step.lse_w, step.o, step.lse),
+    }
+    call_ms = {name: time_call(fn) for name, fn in calls.items()}
+    call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": cfg.B * cfg.Hkv * cfg.P * cfg.d * 2,
+                  "select_salient": nbytes["select"], "sparse_attn": nbytes["sparse"]}
+    call_gbps = {n: call_bytes[n] / (call_ms[n] * 1e-3) / 1e9 for n in call_bytes}
+    log("[bench] per call (ms, GB/s): " + ", ".join(
+        f"{n}={call_ms[n]:.4f}" + (f"/{call_gbps[n]:.0f}" if n in call_gbps else "") for n in call_ms))
+
+    # dominant kernel: the pool-score pass (K of the whole older context, once per KV head)
+    score_bytes = call_bytes["pool_scores"]
+    roof = {"bound": "hbm", "kernel": "attn_split_kernel<bf16,128,4,scores> (hgca_pool_scores)",
+            "achieved": score_bytes / (call_ms["pool_scores"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": score_bytes / (call_ms["pool_scores"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": score_bytes,
+            "avg_launch_ms": call_ms["pool_scores"]}
+
+    out = {
+        "metric": METRIC, "value": 1e3 / ms_per_step, "unit": "layer-steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C2: Llama-3-8B-like layer, bf16, B=8, Hq=32, Hkv=8, d=128, ctx 32768 "
+                               "(window 4096 + pool 28672), per-head top-k 2048; full step = dense + select + "
+                               "sparse + merge", "layers_cycled": args.layers, "streams": args.streams},
+        "achieved_hbm_gbps": nbytes["full"] / (ms_per_step * 1e-3) / 1e9,
+        "hbm_frac": nbytes["full"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_step": nbytes["full"],
+        "steady": {"ms_per_step": steady_ms, "layer_steps_per_s": 1e3 / steady_ms,
+                   "achieved_hbm_gbps": nbytes["steady"] / (steady_ms * 1e-3) / 1e9,
+                   "hbm_frac": nbytes["steady"] / (steady_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                   "algorithmic_bytes_per_step": nbytes["steady"]},
+        "per_call_ms": call_ms, "per_call_gbps": call_gbps,
+        "device_ms_per_step": full_ms, "wall_ms_per_step": wall_ms,
+        "roofline": roof,
+    }
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(host_layers[0], args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(L, target_s: float) -> dict:
+    """The fp64 oracle as it stands, timed on this machine's host cores on the first sequences of layer 0."""
+    import numpy as np
+    import oracle
+
+    def tier(t, nb):
+        return oracle.Tier(np.ascontiguousarray(t.k[:nb]), np.ascontiguousarray(t.v[:nb]), t.cap)
+
+    def run(nb):
+        t0 = time.perf_counter()
+        oracle.hybrid_step(np.ascontiguousarray(L.q[:nb]), tier(L.window, nb), tier(L.pool, nb), L.k, L.k_max, L.scale)
+        return time.perf_counter() - t0
+
+    B = L.cfg.B
+    t1 = run(1)                                                 # one sequence: sizes the sample
+    nb = int(max(1, min(B, target_s / max(t1, 1e-3))))
+    t = run(nb) if nb > 1 else t1
+    steps_per_s = (nb / B) / t                                  # a layer-step covers all B sequences
+    return {"value": steps_per_s, "unit": "layer-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{nb} of {B} sequences of one C2 layer-step (all 32 heads, full window+pool), "
+                      f"{t:.2f}s of fp64 oracle time, scaled by {nb}/{B}"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -96,6 +96,16 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q,
                            float *o_out, float *lse_out,
                            void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Raw attention scores of the older context (Sec. 3.3, s_j = q . k_j; what
+ * Alg. 2's cpu_attention hands to the re-evaluation as A_cpu, before the
+ * softmax): scores_out[b,h,t] = sm_scale * <q[b,h], K[b,h/G,t]> for every valid
+ * token t of `pool`; scores_out is fp32 [B,Hq,pool->cap], entries at
+ * t >= seq_lens[b] are left untouched.  Only pool->k is read.  This is the first
+ * pass of hgca_select_salient, exposed on its own. */
+int hgca_pool_scores(const hgca_shape *shape, const void *q,
+                     const hgca_kv_view *pool, float *scores_out,
+                     void *hip_stream);
+
 /* Per-head selection of salient entries of the older context (Sec. 3.2.2,
  * head-granularity sparsification; fixed-budget top-k form of Sec. 2.2):
  * for every (b, h) score every valid pool token with the current query and keep

@@ -1,12 +1,17 @@
-// Split-K softmax attention of one decode query per head (generic VALU path):
-// dense over a KV tier (all heads of a GQA group share each K/V row that is
-// read), index-gathered per query head, and the raw score pass used by the
-// selection.  One workgroup = one split of one (sequence, head unit).
+// Split-K softmax attention of one decode query per head, and the raw score pass
+// used by the selection.  One workgroup = one split of one (sequence, head unit).
 //
-// Every lane moves 16 bytes per load; the lanes that share a row reduce their
-// partial dot products with wave shuffles; the weights of a split are staged in
-// LDS between the K pass and the V pass; the four waves reduce their output
-// accumulators through LDS and write one partial (m, l, o) per head and split.
+// Two ways to form the scores of a split:
+//   * VALU path (any dtype / head_dim; the gather kernel; fp32): every lane moves
+//     16 bytes of a K row, the lanes that share a row reduce their partial dot
+//     products with wave shuffles;
+//   * MFMA path (bf16, dense over a tier): a wave loads 16-token K tiles straight
+//     into the A-operand layout of v_mfma_f32_16x16x32_bf16, the B operand holds
+//     the query heads of the GQA group (zero-padded to 16 columns), so one K row
+//     read serves all heads of the group at no VALU cost.
+// After the scores, both paths share the rest: softmax statistics of the split in
+// LDS, a V pass with coalesced 16-byte loads and fp32 FMAs, a reduction through
+// shuffles and LDS, and one partial (m, l, o) per head and split.
 #include "hgca_launch.hpp"
 
 namespace hgca {
@@ -18,6 +23,9 @@ enum Mode { kDense = 0, kGather = 1, kScores = 2 };
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
 constexpr int kUnroll = 4;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 struct KernelArgs {
     ShapeDev sh;
@@ -31,86 +39,26 @@ struct KernelArgs {
     float *scores;
 };
 
-template <typename T, int D, int NH, int MODE>
-__global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
+// ---- pieces shared by all split kernels ---------------------------------------------------
+
+template <int D, int NH>
+__device__ __forceinline__ void write_empty_partial(const Partials &part, int64_t bh0, int split)
 {
-    constexpr int EPL = Elem<T>::kPerLoad;       // elements per lane per load
-    constexpr int LPR = D / EPL;                 // lanes per row
-    constexpr int RPW = kWave / LPR;             // rows per wave per load
-    constexpr int RPI = kWaves * RPW;            // rows per workgroup iteration
-    constexpr int ROW_BYTES = D * (int)sizeof(T);
-
-    __shared__ float s_p[NH][kMaxChunk];         // scores of the split, then weights
-    __shared__ float s_red[kWaves][NH][D];
-    __shared__ float s_m[NH], s_l[NH];
-
-    const int split = blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
-    const int Hq = a.sh.n_q_heads, Hkv = a.sh.n_kv_heads;
-    const int kvh = (MODE == kGather) ? unit / a.sh.group : unit;
-    const int h0 = (MODE == kGather) ? unit : unit * NH;          // first of the NH heads handled
-    const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
-    const int r = lane / LPR, c = lane % LPR;
-
-    const int64_t bh0 = (int64_t)b * Hq + h0;
-    const int n = (MODE == kGather) ? min(a.cnt[bh0], a.k_max) : tier_len(a.kv, b);
-    const int t0 = split * a.chunk;
-
-    if (t0 >= n) {                               // empty split (uniform over the workgroup)
-        if (MODE != kScores) {
-            for (int i = tid; i < NH * D; i += kBlock) {
-                const int g = i / D, col = i % D;
-                a.part.o[((bh0 + g) * a.part.n_splits + split) * D + col] = 0.f;
-            }
-            if (tid < NH) {
-                a.part.m[(bh0 + tid) * a.part.n_splits + split] = -INFINITY;
-                a.part.l[(bh0 + tid) * a.part.n_splits + split] = 0.f;
-            }
-        }
-        return;
+    for (int i = threadIdx.x; i < NH * D; i += kBlock) {
+        const int g = i / D, col = i % D;
+        part.o[((bh0 + g) * part.n_splits + split) * D + col] = 0.f;
     }
-    const int nt = min(a.chunk, n - t0);         // 1 .. chunk tokens in this split
-    const int32_t *idx_row = (MODE == kGather) ? a.idx + bh0 * a.k_max + t0 : nullptr;
-
-    float qf[NH][EPL];
-#pragma unroll
-    for (int g = 0; g < NH; ++g)
-        Elem<T>::expand(load16(a.q + ((bh0 + g) * D + c * EPL) * (int64_t)sizeof(T)), qf[g]);
-
-    // ---- K pass: scores of the split into LDS --------------------------------------
-    for (int base = 0; base < nt; base += RPI * kUnroll) {
-        uint4 kr[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int j = min(base + u * RPI + w * RPW + r, nt - 1);
-            const int32_t tok = (MODE == kGather) ? idx_row[j] : t0 + j;
-            kr[u] = load16(a.kv.k + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * RPI + w * RPW + r;
-            float kf[EPL];
-            Elem<T>::expand(kr[u], kf);
-#pragma unroll
-            for (int g = 0; g < NH; ++g) {
-                float dot = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) dot = fmaf(qf[g][e], kf[e], dot);
-                dot = group_sum<LPR>(dot);
-                if (c == 0 && j < nt) s_p[g][j] = dot * a.sh.sm_scale;
-            }
-        }
+    if (threadIdx.x < NH) {
+        part.m[(bh0 + threadIdx.x) * part.n_splits + split] = -INFINITY;
+        part.l[(bh0 + threadIdx.x) * part.n_splits + split] = 0.f;
     }
-    __syncthreads();
+}
 
-    if (MODE == kScores) {
-        for (int i = tid; i < NH * nt; i += kBlock) {
-            const int g = i / nt, j = i % nt;
-            a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
-        }
-        return;
-    }
-
-    // ---- softmax statistics of the split, one wave per head ----------------------------
+// s_p[g][0..nt) holds scores on entry and weights e^{s-m} on exit; one wave per head.
+template <int NH>
+__device__ __forceinline__ void split_softmax(float (*s_p)[kMaxChunk], float *s_m, float *s_l, int nt)
+{
+    const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     for (int g = w; g < NH; g += kWaves) {
         float m = -INFINITY;
         for (int j = lane; j < nt; j += kWave) m = fmaxf(m, s_p[g][j]);
@@ -124,9 +72,24 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
         l = wave_sum(l);
         if (lane == 0) { s_m[g] = m; s_l[g] = l; }
     }
-    __syncthreads();
+}
 
-    // ---- V pass: o[g][:] = sum_j p[g][j] * v_j ---------------------------------------------
+// o[g][:] = sum_j p[g][j] v_j over the split, reduced over the workgroup and written as a partial.
+template <typename T, int D, int NH, bool GATHER>
+__device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[kMaxChunk],
+                                           float (*s_red)[NH][D], const float *s_m, const float *s_l,
+                                           int b, int kvh, int64_t bh0, int split, int t0, int nt,
+                                           const int32_t *idx_row)
+{
+    constexpr int EPL = Elem<T>::kPerLoad;       // elements per lane per load
+    constexpr int LPR = D / EPL;                 // lanes per row
+    constexpr int RPW = kWave / LPR;             // rows per wave per load
+    constexpr int RPI = kWaves * RPW;            // rows per workgroup iteration
+    constexpr int ROW_BYTES = D * (int)sizeof(T);
+    const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
+    const int r = lane / LPR, c = lane % LPR;
+    const int Hkv = a.sh.n_kv_heads;
+
     float acc[NH][EPL];
 #pragma unroll
     for (int g = 0; g < NH; ++g)
@@ -138,8 +101,8 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int j = min(base + u * RPI + w * RPW + r, nt - 1);
-            const int32_t tok = (MODE == kGather) ? idx_row[j] : t0 + j;
-            vr[u] = load16(a.kv.v + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
+            const int32_t tok = GATHER ? idx_row[j] : t0 + j;
+            vr[u] = load16_stream(a.kv.v + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -181,30 +144,265 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
     }
 }
 
-// Folds the split partials of one (b, h) row: M = max m_s, L = sum l_s e^{m_s-M},
-// O = sum o_s e^{m_s-M} / L, lse = M + ln L.  One thread per output column.
-template <int D>
-__global__ __launch_bounds__(D) void combine_kernel(Partials p, float *o, float *lse)
+// ---- VALU path -----------------------------------------------------------------------------
+
+template <typename T, int D, int NH, int MODE>
+__global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 {
+    constexpr int EPL = Elem<T>::kPerLoad;
+    constexpr int LPR = D / EPL;
+    constexpr int RPW = kWave / LPR;
+    constexpr int RPI = kWaves * RPW;
+    constexpr int ROW_BYTES = D * (int)sizeof(T);
+
+    __shared__ float s_p[NH][kMaxChunk];         // scores of the split, then weights
+    __shared__ float s_red[kWaves][NH][D];
+    __shared__ float s_m[NH], s_l[NH];
+
+    const int split = blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
+    const int Hq = a.sh.n_q_heads, Hkv = a.sh.n_kv_heads;
+    const int kvh = (MODE == kGather) ? unit / a.sh.group : unit;
+    const int h0 = (MODE == kGather) ? unit : unit * NH;          // first of the NH heads handled
+    const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
+    const int r = lane / LPR, c = lane % LPR;
+
+    const int64_t bh0 = (int64_t)b * Hq + h0;
+    const int n = (MODE == kGather) ? min(a.cnt[bh0], a.k_max) : tier_len(a.kv, b);
+    const int t0 = split * a.chunk;
+
+    if (t0 >= n) {                               // empty split (uniform over the workgroup)
+        if (MODE != kScores) write_empty_partial<D, NH>(a.part, bh0, split);
+        return;
+    }
+    const int nt = min(a.chunk, n - t0);         // 1 .. chunk tokens in this split
+    const int32_t *idx_row = (MODE == kGather) ? a.idx + bh0 * a.k_max + t0 : nullptr;
+
+    float qf[NH][EPL];
+#pragma unroll
+    for (int g = 0; g < NH; ++g)
+        Elem<T>::expand(load16(a.q + ((bh0 + g) * D + c * EPL) * (int64_t)sizeof(T)), qf[g]);
+
+    // K pass: scores of the split into LDS
+    for (int base = 0; base < nt; base += RPI * kUnroll) {
+        uint4 kr[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = min(base + u * RPI + w * RPW + r, nt - 1);
+            const int32_t tok = (MODE == kGather) ? idx_row[j] : t0 + j;
+            kr[u] = load16_stream(a.kv.k + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * RPI + w * RPW + r;
+            float kf[EPL];
+            Elem<T>::expand(kr[u], kf);
+#pragma unroll
+            for (int g = 0; g < NH; ++g) {
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) dot = fmaf(qf[g][e], kf[e], dot);
+                dot = group_sum<LPR>(dot);
+                if (c == 0 && j < nt) s_p[g][j] = dot * a.sh.sm_scale;
+            }
+        }
+    }
+    __syncthreads();
+
+    if (MODE == kScores) {
+        for (int i = tid; i < NH * nt; i += kBlock) {
+            const int g = i / nt, j = i % nt;
+            a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
+        }
+        return;
+    }
+
+    split_softmax<NH>(s_p, s_m, s_l, nt);
+    __syncthreads();
+    value_pass<T, D, NH, MODE == kGather>(a, s_p, s_red, s_m, s_l, b, kvh, bh0, split, t0, nt, idx_row);
+}
+
+// ---- MFMA path (bf16 K/V, dense over a tier) -------------------------------------------------
+
+// B operand of the score MFMAs: column n = lane % 16 is query head h0 + n of the group (zero beyond
+// the group); k-slice kk holds q[32*kk + 8*(lane/16) .. +8), the same d-slice the A operand takes.
+template <int D, int G>
+__device__ __forceinline__ void load_q_operand(const char *q, int64_t bh0, bf16x8 (&qb)[D / 32])
+{
+    const int lane = threadIdx.x % kWave, n = lane % 16, g = lane / 16;
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) {
+        uint4 r = make_uint4(0u, 0u, 0u, 0u);
+        if (n < G) r = load16(q + ((bh0 + n) * D + 32 * kk + 8 * g) * 2);
+        qb[kk] = __builtin_bit_cast(bf16x8, r);
+    }
+}
+
+// K tiles reach the MFMA through LDS: a wave loads a 16-token tile with fully coalesced 16-byte
+// loads (consecutive lanes take consecutive 16-byte pieces of a row), parks it in its own LDS stage
+// with one 16-byte pad per row (conflict-free b128 reads), and reads it back in A-operand layout.
+template <int D> struct Stage {
+    static constexpr int kPieces = D / 8;                    // 16-byte pieces per K row
+    static constexpr int kRowStride = kPieces + 1;           // in uint4, padded
+    static constexpr int kRowsPerLoad = kWave / kPieces;     // rows one load instruction covers
+    static constexpr int kLoads = 16 / kRowsPerLoad;         // load instructions per tile
+    static constexpr int kWaveVecs = 16 * kRowStride;        // uint4 per wave
+};
+
+// Scaled scores of tokens [t0, t0+nt) of (b, kvh) for the G heads of the group, written to
+// s_sc[n][j] (n < G, j < nt rounded up to 16; entries at j >= nt are finite filler).
+template <int D, int G>
+__device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, float (*s_sc)[kMaxChunk], int b,
+                                            int kvh, int64_t bh0, int t0, int nt)
+{
+    using S = Stage<D>;
+    constexpr int ROW_BYTES = D * 2;
+    const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int lrow = lane / S::kPieces, piece = lane % S::kPieces;   // role while loading
+    const int row = lane % 16, g = lane / 16;                        // role as A operand / C result
+    uint4 *st = stage + w * S::kWaveVecs;
+    bf16x8 qb[D / 32];
+    load_q_operand<D, G>(a.q, bh0, qb);
+
+    const int n_tiles = (nt + 15) / 16;
+    for (int ti = w; ti < n_tiles; ti += kWaves) {
+        uint4 kr[S::kLoads];
+#pragma unroll
+        for (int i = 0; i < S::kLoads; ++i) {
+            const int j = min(ti * 16 + i * S::kRowsPerLoad + lrow, nt - 1);
+            kr[i] = load16_stream(a.kv.k + row_offset<ROW_BYTES>(a.kv, a.sh.n_kv_heads, b, kvh, t0 + j) + 16 * piece);
+        }
+#pragma unroll
+        for (int i = 0; i < S::kLoads; ++i) st[(i * S::kRowsPerLoad + lrow) * S::kRowStride + piece] = kr[i];
+        __builtin_amdgcn_wave_barrier();         // same wave writes and reads its stage; LDS keeps wave order
+        floatx4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) {
+            const uint4 ka = st[row * S::kRowStride + 4 * kk + g];
+            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qb[kk], c, 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (row < G) {                           // C layout: column n = row, tokens 4*g .. 4*g+3 of the tile
+            const float sc = a.sh.sm_scale;
+            *reinterpret_cast<float4 *>(&s_sc[row][ti * 16 + 4 * g]) =
+                make_float4(c[0] * sc, c[1] * sc, c[2] * sc, c[3] * sc);
+        }
+    }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
+{
+    __shared__ uint4 s_stage[kWaves * Stage<D>::kWaveVecs];
+    __shared__ __attribute__((aligned(16))) float s_sc[G][kMaxChunk];
+
+    const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int n = tier_len(a.kv, b);
+    const int t0 = chunk_id * a.chunk;
+    if (t0 >= n) return;
+    const int nt = min(a.chunk, n - t0);
+    const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
+    mfma_scores<D, G>(a, s_stage, s_sc, b, kvh, bh0, t0, nt);
+    __syncthreads();
+
+    // coalesced streaming stores, 16 bytes per lane where the row alignment allows it
+    const int64_t cap = a.kv.cap;
+    float *out = a.scores + bh0 * cap + t0;
+    const bool vec_ok = (cap % 4) == 0;
+    const int n4 = (nt + 3) / 4;
+    for (int i = threadIdx.x; i < G * n4; i += kBlock) {
+        const int g = i / n4, j = 4 * (i % n4);
+        const float4 v = *reinterpret_cast<const float4 *>(&s_sc[g][j]);
+        float *o = out + g * cap + j;
+        if (vec_ok && j + 3 < nt) {
+            __builtin_nontemporal_store(v.x, o);
+            __builtin_nontemporal_store(v.y, o + 1);
+            __builtin_nontemporal_store(v.z, o + 2);
+            __builtin_nontemporal_store(v.w, o + 3);
+        } else {
+            if (j < nt) o[0] = v.x;
+            if (j + 1 < nt) o[1] = v.y;
+            if (j + 2 < nt) o[2] = v.z;
+            if (j + 3 < nt) o[3] = v.w;
+        }
+    }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
+{
+    // the K stage is dead once the scores are in s_p; the output reduction reuses its space
+    constexpr int kStageBytes = kWaves * Stage<D>::kWaveVecs * 16;
+    constexpr int kRedBytes = kWaves * G * D * 4;
+    __shared__ __attribute__((aligned(16))) char s_buf[kStageBytes > kRedBytes ? kStageBytes : kRedBytes];
+    __shared__ __attribute__((aligned(16))) float s_p[G][kMaxChunk];
+    __shared__ float s_m[G], s_l[G];
+
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
+    const int n = tier_len(a.kv, b);
+    const int t0 = split * a.chunk;
+    if (t0 >= n) {
+        write_empty_partial<D, G>(a.part, bh0, split);
+        return;
+    }
+    const int nt = min(a.chunk, n - t0);
+    mfma_scores<D, G>(a, reinterpret_cast<uint4 *>(s_buf), s_p, b, kvh, bh0, t0, nt);
+    __syncthreads();
+    split_softmax<G>(s_p, s_m, s_l, nt);
+    __syncthreads();
+    value_pass<bf16_t, D, G, false>(a, s_p, reinterpret_cast<float (*)[G][D]>(s_buf), s_m, s_l, b, kvh, bh0, split,
+                                    t0, nt, nullptr);
+}
+
+// ---- combine and merge ------------------------------------------------------------------------------
+
+// Folds the split partials of one (b, h) row: M = max m_s, L = sum l_s e^{m_s-M},
+// O = sum o_s e^{m_s-M} / L, lse = M + ln L.  Thread (sg, c4) sums the splits sg, sg+SG, ... of four
+// adjacent columns; the SG groups are then added through LDS.
+template <int D>
+__global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, float *o, float *lse)
+{
+    constexpr int C4 = D / 4;                    // threads across the columns (one float4 each)
+    constexpr int SG = kBlock / C4;              // split groups
+    __shared__ float4 s_acc[SG][C4];
+    __shared__ float s_L[SG];
+
     const int64_t row = blockIdx.x;
-    const int col = threadIdx.x;
+    const int tid = threadIdx.x, sg = tid / C4, c4 = tid % C4;
     const float *pm = p.m + row * p.n_splits;
     const float *pl = p.l + row * p.n_splits;
     float M = -INFINITY;
     for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, pm[s]);
-    if (M == -INFINITY) {                        // every split empty
-        o[row * D + col] = 0.f;
-        if (col == 0) lse[row] = -INFINITY;
+    if (M == -INFINITY) {                        // every split empty (uniform over the workgroup)
+        if (tid < D) o[row * D + tid] = 0.f;
+        if (tid == 0) lse[row] = -INFINITY;
         return;
     }
-    float L = 0.f, acc = 0.f;
-    for (int s = 0; s < p.n_splits; ++s) {
-        const float wgt = expf(pm[s] - M);        // 0 for empty splits (m = -inf)
+    float L = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = sg; s < p.n_splits; s += SG) {
+        const float wgt = expf(pm[s] - M);       // 0 for empty splits (m = -inf)
+        const float4 v = *reinterpret_cast<const float4 *>(p.o + (row * p.n_splits + s) * D + 4 * c4);
         L = fmaf(pl[s], wgt, L);
-        acc = fmaf(p.o[(row * p.n_splits + s) * D + col], wgt, acc);
+        acc.x = fmaf(v.x, wgt, acc.x); acc.y = fmaf(v.y, wgt, acc.y);
+        acc.z = fmaf(v.z, wgt, acc.z); acc.w = fmaf(v.w, wgt, acc.w);
     }
-    o[row * D + col] = acc / L;
-    if (col == 0) lse[row] = M + logf(L);
+    s_acc[sg][c4] = acc;
+    if (c4 == 0) s_L[sg] = L;
+    __syncthreads();
+    if (tid < C4) {
+        float Lt = 0.f;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int g = 0; g < SG; ++g) {
+            const float4 v = s_acc[g][tid];
+            t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+            Lt += s_L[g];
+        }
+        const float inv = 1.f / Lt;
+        *reinterpret_cast<float4 *>(o + row * D + 4 * tid) = make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
+        if (tid == 0) lse[row] = M + logf(Lt);
+    }
 }
 
 // merge_state on one (b, h) row per workgroup, one thread per column.
@@ -237,26 +435,49 @@ __global__ __launch_bounds__(D) void merge_kernel(const float *o_a, const float 
     if (lse_out && col == 0) lse_out[row] = lse;
 }
 
+// ---- launch plumbing ------------------------------------------------------------------------------------
+
+#define HGCA_LAUNCH(kernel, grid, block, stream, ...) \
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__)
+
 template <typename T, int D, int MODE>
-hipError_t launch_split(const KernelArgs &ka, int nh, dim3 grid, hipStream_t s)
+hipError_t launch_valu_group(const KernelArgs &ka, int nh, dim3 grid, hipStream_t s)
 {
     switch (nh) {
-    case 1: hipLaunchKernelGGL((attn_split_kernel<T, D, 1, MODE>), grid, dim3(kBlock), 0, s, ka); break;
-    case 2: hipLaunchKernelGGL((attn_split_kernel<T, D, 2, MODE>), grid, dim3(kBlock), 0, s, ka); break;
-    case 4: hipLaunchKernelGGL((attn_split_kernel<T, D, 4, MODE>), grid, dim3(kBlock), 0, s, ka); break;
-    case 8: hipLaunchKernelGGL((attn_split_kernel<T, D, 8, MODE>), grid, dim3(kBlock), 0, s, ka); break;
+    case 1: HGCA_LAUNCH((attn_split_kernel<T, D, 1, MODE>), grid, dim3(kBlock), s, ka); break;
+    case 2: HGCA_LAUNCH((attn_split_kernel<T, D, 2, MODE>), grid, dim3(kBlock), s, ka); break;
+    case 4: HGCA_LAUNCH((attn_split_kernel<T, D, 4, MODE>), grid, dim3(kBlock), s, ka); break;
+    case 8: HGCA_LAUNCH((attn_split_kernel<T, D, 8, MODE>), grid, dim3(kBlock), s, ka); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-template <int MODE>
-hipError_t dispatch_split(int dtype, int head_dim, const KernelArgs &ka, int nh, dim3 grid, hipStream_t s)
+template <int D, int MODE>
+hipError_t launch_mfma_group(const KernelArgs &ka, int g, dim3 grid, hipStream_t s)
 {
-    if (dtype == 0 && head_dim == 64) return launch_split<float, 64, MODE>(ka, nh, grid, s);
-    if (dtype == 0 && head_dim == 128) return launch_split<float, 128, MODE>(ka, nh, grid, s);
-    if (dtype == 1 && head_dim == 64) return launch_split<bf16_t, 64, MODE>(ka, nh, grid, s);
-    if (dtype == 1 && head_dim == 128) return launch_split<bf16_t, 128, MODE>(ka, nh, grid, s);
+#define HGCA_MFMA_CASE(G)                                                                           \
+    case G:                                                                                         \
+        if (MODE == kScores) HGCA_LAUNCH((pool_scores_mfma_kernel<D, G>), grid, dim3(kBlock), s, ka); \
+        else HGCA_LAUNCH((dense_attn_mfma_kernel<D, G>), grid, dim3(kBlock), s, ka);                \
+        break;
+    switch (g) {
+        HGCA_MFMA_CASE(1) HGCA_MFMA_CASE(2) HGCA_MFMA_CASE(4) HGCA_MFMA_CASE(8)
+    default: return hipErrorInvalidValue;
+    }
+#undef HGCA_MFMA_CASE
+    return hipGetLastError();
+}
+
+// dense / score passes over a tier: bf16 takes the MFMA path, fp32 the VALU path
+template <int MODE>
+hipError_t launch_tier_pass(int dtype, int head_dim, const KernelArgs &ka, dim3 grid, hipStream_t s)
+{
+    const int g = ka.sh.group;
+    if (dtype == 1 && head_dim == 64) return launch_mfma_group<64, MODE>(ka, g, grid, s);
+    if (dtype == 1 && head_dim == 128) return launch_mfma_group<128, MODE>(ka, g, grid, s);
+    if (dtype == 0 && head_dim == 64) return launch_valu_group<float, 64, MODE>(ka, g, grid, s);
+    if (dtype == 0 && head_dim == 128) return launch_valu_group<float, 128, MODE>(ka, g, grid, s);
     return hipErrorInvalidValue;
 }
 
@@ -281,14 +502,20 @@ hipError_t launch_attn_partial_dense(int dtype, int head_dim, const AttnArgs &a,
 {
     if (a.sh.batch == 0 || a.part.n_splits == 0) return hipSuccess;
     dim3 grid(a.part.n_splits, a.sh.n_kv_heads, a.sh.batch);
-    return dispatch_split<kDense>(dtype, head_dim, to_kernel_args(a), a.sh.group, grid, s);
+    return launch_tier_pass<kDense>(dtype, head_dim, to_kernel_args(a), grid, s);
 }
 
 hipError_t launch_attn_partial_gather(int dtype, int head_dim, const AttnArgs &a, hipStream_t s)
 {
     if (a.sh.batch == 0 || a.part.n_splits == 0) return hipSuccess;
     dim3 grid(a.part.n_splits, a.sh.n_q_heads, a.sh.batch);
-    return dispatch_split<kGather>(dtype, head_dim, to_kernel_args(a), 1, grid, s);
+    const KernelArgs ka = to_kernel_args(a);
+    if (dtype == 0 && head_dim == 64) HGCA_LAUNCH((attn_split_kernel<float, 64, 1, kGather>), grid, dim3(kBlock), s, ka);
+    else if (dtype == 0 && head_dim == 128) HGCA_LAUNCH((attn_split_kernel<float, 128, 1, kGather>), grid, dim3(kBlock), s, ka);
+    else if (dtype == 1 && head_dim == 64) HGCA_LAUNCH((attn_split_kernel<bf16_t, 64, 1, kGather>), grid, dim3(kBlock), s, ka);
+    else if (dtype == 1 && head_dim == 128) HGCA_LAUNCH((attn_split_kernel<bf16_t, 128, 1, kGather>), grid, dim3(kBlock), s, ka);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 hipError_t launch_scores(int dtype, int head_dim, const ScoreArgs &a, hipStream_t s)
@@ -301,18 +528,15 @@ hipError_t launch_scores(int dtype, int head_dim, const ScoreArgs &a, hipStream_
     ka.chunk = a.chunk;
     ka.scores = a.scores;
     dim3 grid(a.n_chunks, a.sh.n_kv_heads, a.sh.batch);
-    return dispatch_split<kScores>(dtype, head_dim, ka, a.sh.group, grid, s);
+    return launch_tier_pass<kScores>(dtype, head_dim, ka, grid, s);
 }
 
 hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float *o, float *lse, hipStream_t s)
 {
     if (n_rows == 0) return hipSuccess;
-    if (head_dim == 64)
-        hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)n_rows), dim3(64), 0, s, p, o, lse);
-    else if (head_dim == 128)
-        hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)n_rows), dim3(128), 0, s, p, o, lse);
-    else
-        return hipErrorInvalidValue;
+    if (head_dim == 64) HGCA_LAUNCH((combine_kernel<64>), dim3((unsigned)n_rows), dim3(kBlock), s, p, o, lse);
+    else if (head_dim == 128) HGCA_LAUNCH((combine_kernel<128>), dim3((unsigned)n_rows), dim3(kBlock), s, p, o, lse);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -322,13 +546,13 @@ hipError_t launch_merge(int head_dim, int64_t n_rows, const float *o_a, const fl
     if (n_rows == 0) return hipSuccess;
     dim3 grid((unsigned)n_rows);
     if (head_dim == 64 && o_dtype == 0)
-        hipLaunchKernelGGL((merge_kernel<64, false>), grid, dim3(64), 0, s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
+        HGCA_LAUNCH((merge_kernel<64, false>), grid, dim3(64), s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
     else if (head_dim == 64 && o_dtype == 1)
-        hipLaunchKernelGGL((merge_kernel<64, true>), grid, dim3(64), 0, s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
+        HGCA_LAUNCH((merge_kernel<64, true>), grid, dim3(64), s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
     else if (head_dim == 128 && o_dtype == 0)
-        hipLaunchKernelGGL((merge_kernel<128, false>), grid, dim3(128), 0, s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
+        HGCA_LAUNCH((merge_kernel<128, false>), grid, dim3(128), s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
     else if (head_dim == 128 && o_dtype == 1)
-        hipLaunchKernelGGL((merge_kernel<128, true>), grid, dim3(128), 0, s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
+        HGCA_LAUNCH((merge_kernel<128, true>), grid, dim3(128), s, o_a, lse_a, o_b, lse_b, o_out, lse_out);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

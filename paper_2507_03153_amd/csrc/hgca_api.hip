@@ -166,6 +166,24 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
 }
 
+int hgca_pool_scores(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, float *scores_out,
+                     void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(pool, false)) != HGCA_OK) return rc;
+    if (!q || !aligned16(q) || (pool->cap > 0 && (!scores_out || !aligned16(scores_out)))) return HGCA_ERR_INVALID_ARG;
+    ScoreArgs sa{};
+    sa.sh = to_dev(shape);
+    sa.q = q;
+    sa.kv = to_dev(pool);
+    sa.scores = scores_out;
+    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads);
+    sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
+    return from_hip(launch_scores(shape->dtype, shape->head_dim, sa, static_cast<hipStream_t>(hip_stream)));
+}
+
 int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *k_per_seq,
                         int32_t k_uniform, int32_t k_max, int32_t *idx_out, int32_t *cnt_out, void *ws,
                         size_t ws_bytes, void *hip_stream)

@@ -63,6 +63,18 @@ __device__ __forceinline__ uint4 load16(const char *p) {
     return *reinterpret_cast<const uint4 *>(p);
 }
 
+// 16-byte load marked non-temporal: K/V rows are streamed once and should not displace
+// reusable lines in the caches.
+__device__ __forceinline__ uint4 load16_stream(const char *p) {
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(p);
+    uint4 r;
+    r.x = __builtin_nontemporal_load(w + 0);
+    r.y = __builtin_nontemporal_load(w + 1);
+    r.z = __builtin_nontemporal_load(w + 2);
+    r.w = __builtin_nontemporal_load(w + 3);
+    return r;
+}
+
 template <int kWidth>
 __device__ __forceinline__ float group_sum(float v) {      // sum over kWidth adjacent lanes
 #pragma unroll

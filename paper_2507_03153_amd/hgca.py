@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, -1, -2, -3,
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhgca.so")
 
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
-           "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge")
+           "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge")
 
 
 class Shape(ctypes.Structure):
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_workspace_bytes.argtypes = [ps, i32, i32, i32]
         L.hgca_dense_window_attn.restype = ctypes.c_int
         L.hgca_dense_window_attn.argtypes = [ps, vp, pk, vp, vp, vp, sz, vp]
+        L.hgca_pool_scores.restype = ctypes.c_int
+        L.hgca_pool_scores.argtypes = [ps, vp, pk, vp, vp]
         L.hgca_select_salient.restype = ctypes.c_int
         L.hgca_select_salient.argtypes = [ps, vp, pk, vp, i32, i32, vp, vp, vp, sz, vp]
         L.hgca_sparse_attn.restype = ctypes.c_int
@@ -146,6 +148,14 @@ def dense_window_attn(shape: Shape, q, window: Tier, o_out, lse_out, ws, stream=
     kv = window.view()
     _check(lib().hgca_dense_window_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out), _ptr(lse_out),
                                         _ptr(ws), ws.numel(), _stream(stream)), "hgca_dense_window_attn")
+
+
+def pool_scores(shape: Shape, q, pool: Tier, scores_out, stream=None) -> None:
+    for t in (q, scores_out):
+        _require_gpu(t)
+    kv = pool.view()
+    _check(lib().hgca_pool_scores(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(scores_out), _stream(stream)),
+           "hgca_pool_scores")
 
 
 def select_salient(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out, ws, stream=None) -> None:

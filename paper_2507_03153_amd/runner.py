@@ -69,6 +69,42 @@ class HybridStep:
         self._fork = torch.cuda.Event() if two_streams else None
         self._join = torch.cuda.Event() if two_streams else None
 
+    def prepare(self, L: DeviceLayer):
+        """Marshal the arguments of the four calls once; returns run(select=True) for the current stream
+        setup.  Keeps Python's per-call cost (struct packing) out of a launch-bound loop."""
+        import ctypes
+        lib, ref, ptr = hgca.lib(), ctypes.byref, hgca._ptr
+        sh, win, pool = self.shape, L.window.view(), L.pool.view()
+        k_ptr, k_uni = (ptr(L.k), 0) if isinstance(L.k, torch.Tensor) else (None, int(L.k))
+        main = torch.cuda.current_stream()
+        side = self.side if self.side is not None else main
+        s_main, s_side = ctypes.c_void_p(main.cuda_stream), ctypes.c_void_p(side.cuda_stream)
+        a_sel = (ref(sh), ptr(L.q), ref(pool), k_ptr, k_uni, self.k_max, ptr(self.idx), ptr(self.cnt),
+                 ptr(self.ws_sparse), self.ws_sparse.numel(), s_side)
+        a_sparse = (ref(sh), ptr(L.q), ref(pool), ptr(self.idx), ptr(self.cnt), self.k_max, ptr(self.o_s),
+                    ptr(self.lse_s), ptr(self.ws_sparse), self.ws_sparse.numel(), s_side)
+        a_dense = (ref(sh), ptr(L.q), ref(win), ptr(self.o_w), ptr(self.lse_w), ptr(self.ws_dense),
+                   self.ws_dense.numel(), s_main)
+        a_merge = (ref(sh), ptr(self.o_s), ptr(self.lse_s), ptr(self.o_w), ptr(self.lse_w), ptr(self.o),
+                   hgca._dtype_code(self.o), ptr(self.lse), s_main)
+        keep = (sh, win, pool, L)                               # the structs must outlive the closure
+
+        def run(select: bool = True) -> None:
+            if self.side is not None:
+                self._fork.record(main)
+                side.wait_event(self._fork)
+            if select:
+                hgca._check(lib.hgca_select_salient(*a_sel), "hgca_select_salient")
+            hgca._check(lib.hgca_sparse_attn(*a_sparse), "hgca_sparse_attn")
+            hgca._check(lib.hgca_dense_window_attn(*a_dense), "hgca_dense_window_attn")
+            if self.side is not None:
+                self._join.record(side)
+                main.wait_event(self._join)
+            hgca._check(lib.hgca_lse_merge(*a_merge), "hgca_lse_merge")
+
+        run.keep = keep
+        return run
+
     def run(self, L: DeviceLayer, select: bool = True, stream=None) -> None:
         main = torch.cuda.current_stream() if stream is None else stream
         side = main

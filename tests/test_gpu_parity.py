@@ -93,11 +93,23 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
     o_ref, l_ref = oracle.attend_all(L.q, tw, L.scale)
     assert_partial("dense", step.o_w, step.lse_w, o_ref, l_ref, min(tol, tight))
 
+    say("  step pool_scores")
+    sc = torch.full((cfg.B, cfg.Hq, max(cfg.P, 1)), float("nan"), dtype=torch.float32, device=D.q.device)
+    hgca.pool_scores(D.shape, D.q, D.pool, sc)
+    torch.cuda.synchronize()
+    scores = oracle.scores(L.q, tp, L.scale)
+    sc = sc.double().cpu().numpy()[:, :, :cfg.P]
+    valid = np.arange(cfg.P)[None, None, :] < p_lens[:, None, None]
+    valid = np.broadcast_to(valid, scores.shape)
+    assert np.all(np.isnan(sc[~valid])), "scores beyond seq_len were written"
+    err_s = np.max(np.abs(sc[valid] - scores[valid])) if valid.any() else 0.0
+    say(f"    scores: max|ds|={err_s:.3e} (band {BAND[cfg.dtype]:g})")
+    assert err_s <= BAND[cfg.dtype] / 2                        # a band of eps covers both sides' rounding
+
     say("  step select_salient")
     hgca.select_salient(D.shape, D.q, D.pool, D.k, L.k_max, step.idx, step.cnt, step.ws_sparse)
     torch.cuda.synchronize()
     idx_g, cnt_g = step.idx.cpu().numpy()[:, :, :L.k_max], step.cnt.cpu().numpy()
-    scores = oracle.scores(L.q, tp, L.scale)
     n_band = assert_selection("select", idx_g, cnt_g, scores, p_lens, k_b, BAND[cfg.dtype])
     idx_ref, cnt_ref = oracle.select(L.q, tp, L.k, L.k_max, L.scale)
     same = float(np.mean(np.all(idx_g == idx_ref, axis=-1))) if idx_ref.size else 1.0
@@ -193,6 +205,53 @@ def test_exact_ties_keep_the_lower_position(gpu, oracle):
         lo, hi = set(row[row < 2048].tolist()), set((row[row >= 2048] - 2048).tolist())
         assert len(row) == 100 and hi <= lo                   # a copy is kept only if its original is
         assert len(lo) - len(hi) <= 1                         # at most one tie is cut by the budget
+
+
+def test_crowded_threshold_all_scores_equal(gpu, oracle):
+    """q = 0 makes every score 0: the kept set must be the first k positions (lower position wins)."""
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=64, P=5000, k=1500)
+    L = wl.make_layer(cfg)
+    L.q[:] = 0
+    say("\n[case] all scores equal")
+    D = runner.DeviceLayer.upload(L)
+    step = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max)
+    hgca.select_salient(D.shape, D.q, D.pool, D.k, L.k_max, step.idx, step.cnt, step.ws_sparse)
+    torch.cuda.synchronize()
+    idx = step.idx.cpu().numpy()
+    assert np.all(idx == np.arange(1500, dtype=np.int32)) and np.all(step.cnt.cpu().numpy() == 1500)
+    idx_ref, _ = oracle.select(L.q, otier(oracle, L.pool), L.k, L.k_max, L.scale)
+    assert np.array_equal(idx, idx_ref)
+
+
+def test_crowded_threshold_many_duplicates(gpu, oracle):
+    """3000 identical keys straddle the k-th rank: exactly the lowest positions among them are kept."""
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=1, Hq=4, Hkv=1, W=64, P=6000, k=2000, plant_frac=0.0)
+    L = wl.make_layer(cfg)
+    rng = np.random.default_rng(7)
+    dup = np.sort(rng.choice(6000, 3000, replace=False))
+    qf = wl.to_f32(L.q)[0]
+    row = 0.5 * (qf / np.linalg.norm(qf, axis=-1, keepdims=True)).sum(0)     # scores about +0.5 for all 4 heads
+    L.pool.k[0, 0, dup] = wl.f32_to_bf16_bits(row.astype(np.float32))
+    say("\n[case] 3000 duplicated keys at the threshold")
+    D = runner.DeviceLayer.upload(L)
+    step = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max)
+    hgca.select_salient(D.shape, D.q, D.pool, D.k, L.k_max, step.idx, step.cnt, step.ws_sparse)
+    torch.cuda.synchronize()
+    idx = step.idx.cpu().numpy()
+    idx_ref, _ = oracle.select(L.q, otier(oracle, L.pool), L.k, L.k_max, L.scale)
+    scores = oracle.scores(L.q, otier(oracle, L.pool), L.scale)
+    for h in range(4):
+        s_dup = scores[0, h, dup[0]]
+        others = np.delete(scores[0, h], dup)
+        assert np.min(np.abs(others - s_dup)) > BAND["bf16"]          # no foreign near-tie: the result is unique
+        assert (others > s_dup).sum() < 2000 < (others > s_dup).sum() + 3000   # the cut falls inside the group
+        assert np.array_equal(idx[0, h], idx_ref[0, h])
+
+
+def test_pool_longer_than_the_lds_score_cache(gpu, oracle):
+    run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C4"], B=1, Hq=8, Hkv=1, W=256, P=33000, k=1200))
 
 
 def test_merge_alone_in_place_and_bf16_output(gpu, oracle):
