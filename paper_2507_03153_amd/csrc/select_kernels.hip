@@ -1,16 +1,23 @@
 // Per-head top-k of the pool scores.  One workgroup per (sequence, query head).
 //
-// The scores of the row are pulled into LDS once (when they fit), then:
-//   1. a 4096-bin histogram over [min, max] of the row locates the bin that holds
-//      the k-th largest score (the bin index is a monotone function of the score);
-//   2. the few entries of that bin are collected and ranked exactly on their
-//      order-preserving 32-bit keys (ties: lower position first), which yields the
-//      threshold key T and how many entries equal to T are kept;
-//      if the bin is crowded (e.g. many identical scores) an exact 3-pass radix
-//      select over the bin's entries does the same job;
+//   0. the row is pulled into LDS once (when it fits), padded with -inf to a whole
+//      number of 256-score steps per wave, and its [min, max] is found;
+//   1. a 4096-bin histogram over [min, max] locates the bin that holds the k-th
+//      largest score (the bin index is a monotone function of the score);
+//   2. entries above that bin are counted per wave; the few entries inside it are
+//      collected and ranked exactly (score descending, position ascending), which
+//      yields the threshold score T and how many entries equal to T are kept; if
+//      the bin is crowded (e.g. many identical scores) an exact 3-pass radix select
+//      over order-preserving 32-bit keys of the bin's entries does the same job;
 //   3. an ordered compaction emits the kept positions in ascending order: every
-//      wave owns a contiguous segment and places its entries with ballots and
-//      population counts, so the pass needs no barrier per step.
+//      wave owns a contiguous segment and places its entries with the lane masks
+//      of the comparisons, so the pass needs no barrier per step; positions are
+//      staged in LDS and leave with coalesced stores.
+//
+// A row is one CU's work; with a handful of VALU operations per score and pass the
+// kernel is bound by that CU's instruction issue, so the passes are kept lean
+// (no validity tests thanks to the padding, float compares instead of integer
+// keys, 4 scores per lane and step).
 #include "hgca_launch.hpp"
 
 namespace hgca {
@@ -20,8 +27,10 @@ namespace {
 constexpr int kSelBlock = 1024;
 constexpr int kSelWaves = kSelBlock / kWave;
 constexpr int kBins = 4096;
-constexpr int kMaxCand = 1024;
-constexpr int kMaxCacheFloats = 30720;           // 120 KiB of LDS for the row's scores
+constexpr int kBinsPerThread = kBins / kSelBlock;
+constexpr int kMaxCand = kSelBlock;              // one candidate per thread in the exact ranking
+constexpr int kStep = 4 * kWave;                 // scores a wave handles per step
+constexpr int kMaxCacheFloats = 33792;           // 132 KiB of LDS for the padded row
 
 // Larger float <=> larger key; -0.0 and +0.0 map to the same key.
 __device__ __forceinline__ uint32_t order_key(float s) {
@@ -29,14 +38,18 @@ __device__ __forceinline__ uint32_t order_key(float s) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+__device__ __forceinline__ float key_to_score(uint32_t key) {
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
 struct SelShared {
-    uint32_t hist[kBins];
-    uint32_t cand_key[kMaxCand];
+    alignas(16) uint32_t hist[kBins];            // reused as the output staging area of the compaction
+    float cand_score[kMaxCand];
     int32_t cand_idx[kMaxCand];
     uint32_t scan_scratch[kSelWaves];
     float wave_min[kSelWaves], wave_max[kSelWaves];
     uint32_t wave_gt[kSelWaves], wave_eq[kSelWaves];
-    uint32_t found[2];                           // selected bin / key, remaining rank
+    uint32_t found[2];                           // selected bin / threshold bits, remaining rank
     uint32_t n_cand;
 };
 
@@ -66,31 +79,65 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s
 // With hist[0..nb) filled: the bin that holds the entry of rank k_rem (1-based, counted from the
 // highest bin down) goes to found[0], its rank inside that bin to found[1].
 __device__ __forceinline__ void locate_rank(SelShared &sh, int nb, uint32_t k_rem) {
+    constexpr int BPT = kBinsPerThread;          // thread tid owns bins nb-1-BPT*tid .. (descending value)
     const int tid = threadIdx.x;
-    uint32_t c4[4] = {0, 0, 0, 0}, local = 0;
-    if (4 * tid < nb) {
+    uint32_t c[BPT], local = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { c4[i] = sh.hist[nb - 1 - (4 * tid + i)]; local += c4[i]; }
+    for (int i = 0; i < BPT; ++i) {
+        c[i] = (BPT * tid + i < nb) ? sh.hist[nb - 1 - (BPT * tid + i)] : 0u;
+        local += c[i];
     }
     uint32_t total;
     uint32_t running = block_exclusive_scan(local, sh.scan_scratch, &total);
-    if (4 * tid < nb) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (running < k_rem && running + c4[i] >= k_rem) {
-                sh.found[0] = (uint32_t)(nb - 1 - (4 * tid + i));
-                sh.found[1] = k_rem - running;
-            }
-            running += c4[i];
+    for (int i = 0; i < BPT; ++i) {
+        if (BPT * tid + i < nb && running < k_rem && running + c[i] >= k_rem) {
+            sh.found[0] = (uint32_t)(nb - 1 - (BPT * tid + i));
+            sh.found[1] = k_rem - running;
         }
+        running += c[i];
     }
     __syncthreads();
 }
 
 struct Binning {
     float lo, inv_w;
-    __device__ __forceinline__ int operator()(float s) const {
+    __device__ __forceinline__ int operator()(float s) const {   // -inf (padding) and NaN land in bin 0
         return max(0, min(kBins - 1, (int)((s - lo) * inv_w)));
+    }
+};
+
+// Four consecutive scores starting at position t (a multiple of 4); positions at or beyond n read -inf.
+__device__ __forceinline__ float4 load4_padded(const float *sc, bool sc_vec, int t, int n)
+{
+    if (sc_vec && t + 3 < n) return *reinterpret_cast<const float4 *>(sc + t);
+    float4 v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    if (t < n) v.x = sc[t];
+    if (t + 1 < n) v.y = sc[t + 1];
+    if (t + 2 < n) v.z = sc[t + 2];
+    if (t + 3 < n) v.w = sc[t + 3];
+    return v;
+}
+
+// Positions below the current lane among the set bits of a lane mask.
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// The padded row: wave w owns the positions [w*seg, (w+1)*seg), seg a multiple of kStep; in step i a
+// lane holds the 4 scores at w*seg + kStep*i + 4*lane.  Positions >= n hold -inf.
+template <bool CACHED>
+struct Row {
+    const float *sc, *cache;
+    bool sc_vec;
+    int n, seg;
+    __device__ __forceinline__ int steps() const { return seg / kStep; }
+    __device__ __forceinline__ int pos(int i) const {
+        return (int)(threadIdx.x / kWave) * seg + kStep * i + 4 * (int)(threadIdx.x % kWave);
+    }
+    __device__ __forceinline__ float4 at(int t) const {
+        if (CACHED) return *reinterpret_cast<const float4 *>(cache + t);
+        return load4_padded(sc, sc_vec, min(t, (n + 3) / 4 * 4), n);    // clamp: far padding needs no address
     }
 };
 
@@ -99,15 +146,39 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
                                            int32_t *out, int n, int k)
 {
     const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
-    const float *data = CACHED ? cache : sc;
+    Row<CACHED> row;
+    row.sc = sc;
+    row.cache = cache;
+    row.sc_vec = (a.kv.cap & 3) == 0;            // rows start 16-byte aligned
+    row.n = n;
+    row.seg = ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
+    const int padded = kSelWaves * row.seg;      // >= n
+    const int steps = row.steps();
 
-    // ---- pass 0: pull the row into LDS, find its range ---------------------------------------
+    // ---- pass 0: range of the row; the padded row goes to LDS ---------------------------------------
     float mn = INFINITY, mx = -INFINITY;
-    for (int t = tid; t < n; t += kSelBlock) {
-        const float s = sc[t] + 0.0f;
-        if (CACHED) cache[t] = s;
-        mn = fminf(mn, s);
-        mx = fmaxf(mx, s);
+    {
+        constexpr int U = 8;                     // 16-byte loads in flight per lane
+        const int n4 = padded / 4;
+        for (int base = 0; base < n4; base += kSelBlock * U) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                v[u] = load4_padded(sc, row.sc_vec, 4 * min(base + u * kSelBlock + tid, n4 - 1), n);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = base + u * kSelBlock + tid;
+                if (i < n4) {
+                    if (CACHED) reinterpret_cast<float4 *>(cache)[i] = v[u];
+                    const float s[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        mx = fmaxf(mx, s[e]);                            // padding is -inf: no effect
+                        mn = fminf(mn, 4 * i + e < n ? s[e] : INFINITY);
+                    }
+                }
+            }
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -115,8 +186,10 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
     }
     if (lane == 0) { sh.wave_min[w] = mn; sh.wave_max[w] = mx; }
-    for (int i = tid; i < kBins; i += kSelBlock) sh.hist[i] = 0;
+    // the padding will be counted into bin 0: start that bin at minus the number of pads
+    for (int i = tid; i < kBins; i += kSelBlock) sh.hist[i] = (i == 0) ? (uint32_t)(n - padded) : 0u;
     if (tid == 0) sh.n_cand = 0;
+    if (tid < kSelWaves) { sh.wave_gt[tid] = 0; sh.wave_eq[tid] = 0; }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kSelWaves; ++i) { mn = fminf(mn, sh.wave_min[i]); mx = fmaxf(mx, sh.wave_max[i]); }
@@ -124,41 +197,68 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     bin.lo = mn;
     bin.inv_w = (mx > mn) ? (float)kBins / (mx - mn) : 0.f;
 
-    // ---- pass 1: histogram, locate the threshold bin ------------------------------------------
-    for (int t = tid; t < n; t += kSelBlock) atomicAdd(&sh.hist[bin(data[t])], 1u);
+    // ---- pass 1: histogram, threshold bin --------------------------------------------------------------
+    for (int i = 0; i < steps; ++i) {
+        const float4 v = row.at(row.pos(i));
+        atomicAdd(&sh.hist[bin(v.x)], 1u);
+        atomicAdd(&sh.hist[bin(v.y)], 1u);
+        atomicAdd(&sh.hist[bin(v.z)], 1u);
+        atomicAdd(&sh.hist[bin(v.w)], 1u);
+    }
     __syncthreads();
     locate_rank(sh, kBins, (uint32_t)k);
     const int tb = (int)sh.found[0];
     uint32_t k_rem = sh.found[1];                // rank of the k-th entry inside bin tb
     __syncthreads();
 
-    // ---- pass 2: collect the entries of the threshold bin ---------------------------------------
-    for (int t = tid; t < n; t += kSelBlock) {
-        const float s = data[t];
-        if (bin(s) == tb) {
-            const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
-            if (slot < (uint32_t)kMaxCand) { sh.cand_key[slot] = order_key(s); sh.cand_idx[slot] = t; }
+    // ---- pass 2: count the entries above the threshold bin, collect those inside it ---------------------
+    uint32_t above = 0;
+    for (int i = 0; i < steps; ++i) {
+        const int t = row.pos(i);
+        const float4 v = row.at(t);
+        const float s[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int bn = bin(s[e]);
+            above += bn > tb;
+            if (bn == tb) {
+                if (t + e < n) {                 // padding shares bin 0 with the lowest scores
+                    const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
+                    if (slot < (uint32_t)kMaxCand) { sh.cand_score[slot] = s[e]; sh.cand_idx[slot] = t + e; }
+                }
+            }
         }
     }
+    above = (uint32_t)wave_sum((float)above);    // exact: far below 2^24 per wave
     __syncthreads();
     const uint32_t n_cand = sh.n_cand;
-    uint32_t thr, need_eq;
+    float thr;
+    uint32_t need_eq;
     if (n_cand <= (uint32_t)kMaxCand) {
-        // exact rank of every candidate in (key descending, position ascending) order
+        // exact rank of every candidate in (score descending, position ascending) order
+        float my_s = 0.f;
+        int32_t my_idx = 0;
         if ((uint32_t)tid < n_cand) {
-            const uint32_t my_key = sh.cand_key[tid];
-            const int32_t my_idx = sh.cand_idx[tid];
+            my_s = sh.cand_score[tid];
+            my_idx = sh.cand_idx[tid];
             uint32_t gt = 0, eq_lower = 0;
             for (uint32_t j = 0; j < n_cand; ++j) {
-                const uint32_t kj = sh.cand_key[j];
-                gt += kj > my_key;
-                eq_lower += (kj == my_key) && (sh.cand_idx[j] < my_idx);
+                const float sj = sh.cand_score[j];
+                gt += sj > my_s;
+                eq_lower += (sj == my_s) && (sh.cand_idx[j] < my_idx);
             }
-            if (gt + eq_lower == k_rem - 1) { sh.found[0] = my_key; sh.found[1] = k_rem - gt; }
+            if (gt + eq_lower == k_rem - 1) { sh.found[0] = __float_as_uint(my_s); sh.found[1] = k_rem - gt; }
         }
         __syncthreads();
-        thr = sh.found[0];
+        thr = __uint_as_float(sh.found[0]);
         need_eq = sh.found[1];
+        // per-wave counts of kept-or-tied entries: those above the bin plus the bin's own
+        if ((uint32_t)tid < n_cand) {
+            if (my_s > thr) atomicAdd(&sh.wave_gt[my_idx / row.seg], 1u);
+            if (my_s == thr) atomicAdd(&sh.wave_eq[my_idx / row.seg], 1u);
+        }
+        if (lane == 0) atomicAdd(&sh.wave_gt[w], above);
+        __syncthreads();
     } else {
         // crowded bin: exact radix select (12 + 12 + 8 bits) over the keys of the bin's entries
         uint32_t prefix = 0, mask = 0;
@@ -169,11 +269,16 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
             __syncthreads();
             for (int i = tid; i < nb; i += kSelBlock) sh.hist[i] = 0;
             __syncthreads();
-            for (int t = tid; t < n; t += kSelBlock) {
-                const float s = data[t];
-                const uint32_t key = order_key(s);
-                if (bin(s) == tb && (key & mask) == prefix)
-                    atomicAdd(&sh.hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+            for (int i = 0; i < steps; ++i) {
+                const int t = row.pos(i);
+                const float4 v = row.at(t);
+                const float s[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t key = order_key(s[e]);
+                    if (t + e < n && bin(s[e]) == tb && (key & mask) == prefix)
+                        atomicAdd(&sh.hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+                }
             }
             __syncthreads();
             locate_rank(sh, nb, k_rem);
@@ -181,37 +286,66 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
             mask |= (uint32_t)(nb - 1) << shift;
             k_rem = sh.found[1];
         }
-        thr = prefix;
+        thr = key_to_score(prefix);
         need_eq = k_rem;
+        // the candidates were not listed: count per wave directly
+        uint32_t my_gt = 0, my_eq = 0;
+        for (int i = 0; i < steps; ++i) {
+            const int t = row.pos(i);
+            const float4 v = row.at(t);
+            const float s[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                my_gt += t + e < n && s[e] > thr;
+                my_eq += t + e < n && s[e] == thr;
+            }
+        }
+        my_gt = (uint32_t)wave_sum((float)my_gt);
+        my_eq = (uint32_t)wave_sum((float)my_eq);
+        if (lane == 0) { sh.wave_gt[w] = my_gt; sh.wave_eq[w] = my_eq; }
+        __syncthreads();
     }
 
-    // ---- pass 3: ordered compaction; wave w owns positions [w*seg, (w+1)*seg) --------------------
-    const int seg = ((n + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-    const int beg = min(w * seg, n), end = min(beg + seg, n);
-    uint32_t my_gt = 0, my_eq = 0;               // wave-uniform counts of the own segment
-    for (int base = beg; base < end; base += kWave) {
-        const int t = base + lane;
-        uint32_t key = 0;
-        if (t < end) key = order_key(data[t]);
-        my_gt += __popcll(__ballot(t < end && key > thr));
-        my_eq += __popcll(__ballot(t < end && key == thr));
-    }
-    if (lane == 0) { sh.wave_gt[w] = my_gt; sh.wave_eq[w] = my_eq; }
-    __syncthreads();
-    uint32_t run_gt = 0, run_eq = 0;
+    // ---- pass 3: ordered compaction ----------------------------------------------------------------------
+    // The kept positions are placed in LDS (the histogram is dead by now) and copied out with
+    // coalesced stores; budgets beyond its size go to global memory directly.
+    const bool staged = k <= kBins;
+    int32_t *dst = staged ? reinterpret_cast<int32_t *>(sh.hist) : out;
+    uint32_t run_gt = 0, run_eq = 0;             // kept / tied entries before the wave's current step
     for (int i = 0; i < w; ++i) { run_gt += sh.wave_gt[i]; run_eq += sh.wave_eq[i]; }
-    for (int base = beg; base < end; base += kWave) {
-        const int t = base + lane;
-        uint32_t key = 0;
-        if (t < end) key = order_key(data[t]);
-        const bool gt = t < end && key > thr, eq = t < end && key == thr;
-        const unsigned long long m_gt = __ballot(gt), m_eq = __ballot(eq);
-        const unsigned long long below = (1ull << lane) - 1ull;
-        const uint32_t gt_before = run_gt + __popcll(m_gt & below);
-        const uint32_t eq_before = run_eq + __popcll(m_eq & below);
-        if (gt || (eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = t;
-        run_gt += __popcll(m_gt);
-        run_eq += __popcll(m_eq);
+    const bool pad_ties = thr == -INFINITY;      // only then could padding tie with the threshold
+    for (int i = 0; i < steps; ++i) {
+        const int t = row.pos(i);
+        const float4 v = row.at(t);
+        const float s[4] = {v.x, v.y, v.z, v.w};
+        bool gt[4], eq[4];
+        uint32_t gt_before = run_gt, eq_before = run_eq;    // entries before this lane's first position
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            gt[e] = s[e] > thr;
+            eq[e] = s[e] == thr && !(pad_ties && t + e >= n);
+            const unsigned long long m_gt = __ballot(gt[e]), m_eq = __ballot(eq[e]);
+            gt_before += lanes_below(m_gt);
+            eq_before += lanes_below(m_eq);
+            run_gt += __popcll(m_gt);
+            run_eq += __popcll(m_eq);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (gt[e] || (eq[e] && eq_before < need_eq)) dst[gt_before + min(eq_before, need_eq)] = t + e;
+            gt_before += gt[e];
+            eq_before += eq[e];
+        }
+    }
+    if (staged) {
+        __syncthreads();
+        if ((a.k_max & 3) == 0) {                // output rows start 16-byte aligned
+            for (int j = tid; j < k / 4; j += kSelBlock)
+                reinterpret_cast<int4 *>(out)[j] = reinterpret_cast<const int4 *>(sh.hist)[j];
+            for (int j = k / 4 * 4 + tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
+        } else {
+            for (int j = tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
+        }
     }
 }
 
@@ -237,7 +371,8 @@ __global__ __launch_bounds__(kSelBlock) void select_topk_kernel(SelectArgs a, in
         for (int t = tid; t < n; t += kSelBlock) out[t] = t;
         return;
     }
-    if (n <= cache_floats) select_row<true>(a, sh, s_cache, sc, out, n, k);
+    const int seg = ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
+    if (kSelWaves * seg <= cache_floats) select_row<true>(a, sh, s_cache, sc, out, n, k);
     else select_row<false>(a, sh, s_cache, sc, out, n, k);
 }
 
@@ -247,9 +382,9 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s)
 {
     const int64_t rows = (int64_t)a.sh.batch * a.sh.n_q_heads;
     if (rows == 0) return hipSuccess;
-    // rows that fit are cached in LDS (dynamic, beyond the 64 KiB default limit)
-    const int cache_floats = a.kv.cap <= kMaxCacheFloats ? (a.kv.cap + 3) / 4 * 4 : 0;
-    const size_t dyn = (size_t)cache_floats * sizeof(float);
+    // rows whose padded length fits are cached in LDS (dynamic, beyond the 64 KiB default limit)
+    const int seg = ((a.kv.cap + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
+    const int cache_floats = kSelWaves * seg <= kMaxCacheFloats ? kSelWaves * seg : 0;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel),
@@ -258,7 +393,8 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(select_topk_kernel, dim3((unsigned)rows), dim3(kSelBlock), dyn, s, a, cache_floats);
+    hipLaunchKernelGGL(select_topk_kernel, dim3((unsigned)rows), dim3(kSelBlock),
+                       (size_t)cache_floats * sizeof(float), s, a, cache_floats);
     return hipGetLastError();
 }
 
