@@ -9,6 +9,12 @@ workload (C2: bf16, B=8, Hq=32, Hkv=8, d=128, window 4096, pool 28672, k=2048) w
 seeded synthetic K/V already resident in HBM.  Steps cycle over L independently drawn
 layers so that consecutive steps do not re-read K/V still held in L2 / Infinity Cache.
 Prints ONE JSON line.
+
+`value` is the full step (selection every step).  In it the selection hands the scores of
+the kept entries to the sparse part, which therefore re-reads only V of those entries;
+`algorithmic_bytes_per_step` keeps counting their K rows (the definition of the metric),
+`moved_bytes_per_step` does not.  The `steady` step reuses a selection, as the paper's decode
+branch does, and gathers K and V.
 """
 from __future__ import annotations
 
@@ -39,10 +45,14 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layers", type=int, default=4, help="independent KV draws cycled through")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2: dense window part overlaps select+sparse (the paper's two concurrent parts)")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="2: the dense window part runs on a second stream beside select+sparse")
+    ap.add_argument("--no-pass-scores", action="store_true",
+                    help="sparse part recomputes its scores from K even right after a selection")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work of the baseline sample")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work of the baseline sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of known size (reference for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -55,47 +65,48 @@ def main() -> int:
     hgca.lib()                                                  # no fallback: fails loudly if not built
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
+    if args.copy_calibration:
+        return copy_calibration(torch, dev)
+
     cfg = wl.CONFIGS["C2"]
     w_lens, p_lens, k = wl.seq_lengths(cfg)
     nbytes = wl.step_bytes(cfg, w_lens, p_lens, k)
+    k_gather = nbytes["sparse"] - 4 * cfg.B * cfg.Hq * cfg.k    # K+V rows of the kept entries
+    pass_scores = not args.no_pass_scores
+    moved_full = nbytes["full"] - (k_gather // 2 if pass_scores else 0)
 
     t0 = time.time()
     host_layers = [wl.make_layer(cfg, layer) for layer in range(args.layers)]
     layers = [runner.DeviceLayer.upload(L, dev) for L in host_layers]
     log(f"[bench] {args.layers} layers of C2 generated and uploaded in {time.time() - t0:.1f}s "
         f"({sum(L.kv_bytes() for L in host_layers) / 2**30:.2f} GiB of KV)")
-    step = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, cfg.k, dev, two_streams=(args.streams == 2))
+    step = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, cfg.k, dev, two_streams=(args.streams == 2),
+                             pass_scores=pass_scores)
     main_stream = torch.cuda.current_stream()
-
     prepared = [step.prepare(L) for L in layers]               # arguments marshalled once per layer
 
     def run_steps(n: int, select: bool, first: int = 0) -> None:
         for i in range(n):
             prepared[(first + i) % len(prepared)](select)
 
-    # ---- full step: all four calls ----------------------------------------------------------
-    run_steps(args.warmup, True)
-    torch.cuda.synchronize()
-    t_wall = time.perf_counter()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(main_stream)
-    run_steps(args.steps, True, args.warmup)
-    e1.record(main_stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_wall) * 1e3 / args.steps
-    full_ms = e0.elapsed_time(e1) / args.steps
+    def timed(select: bool):
+        run_steps(args.warmup, select)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_wall = time.perf_counter()
+        e0.record(main_stream)
+        run_steps(args.steps, select, args.warmup)
+        e1.record(main_stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t_wall) * 1e3 / args.steps
+        return e0.elapsed_time(e1) / args.steps, wall
+
+    full_ms, wall_ms = timed(True)                              # all four calls
     ms_per_step = max(full_ms, wall_ms)                         # host-side launch cost counts too
+    steady_dev, steady_wall = timed(False)                      # selection reused
+    steady_ms = max(steady_dev, steady_wall)
 
-    # ---- steady step: selection reused (Alg. 2's decode branch loads pre-selected entries) ------
-    run_steps(args.warmup, False)
-    torch.cuda.synchronize()
-    e0.record(main_stream)
-    run_steps(args.steps, False, args.warmup)
-    e1.record(main_stream)
-    torch.cuda.synchronize()
-    steady_ms = e0.elapsed_time(e1) / args.steps
-
-    # ---- per-call device time, one stream, events on the launch stream ---------------------------
+    # ---- per-call device time: HIP events on the stream the kernels are launched on ---------------------
     def time_call(fn, n=args.steps) -> float:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
         for i in range(min(args.warmup, 5)):
@@ -115,25 +126,33 @@ def main() -> int:
         "dense_window_attn": lambda L: hgca.dense_window_attn(sh, L.q, L.window, step.o_w, step.lse_w, step.ws_dense),
         "pool_scores": lambda L: hgca.pool_scores(sh, L.q, L.pool, scores_buf),
         "select_salient": lambda L: hgca.select_salient(sh, L.q, L.pool, L.k, cfg.k, step.idx, step.cnt,
-                                                        step.ws_sparse),
+                                                        step.ws_sparse, sel_scores_out=step.sel_scores),
         "sparse_attn": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, cfg.k, step.o_s, step.lse_s,
                                                   step.ws_sparse),
+        "sparse_attn_given_scores": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, cfg.k, step.o_s,
+                                                               step.lse_s, step.ws_sparse,
+                                                               sel_scores=step.sel_scores),
         "lse_merge": lambda L: hgca.lse_merge(sh, step.o_s, step.lse_s, step.o_w, step.lse_w, step.o, step.lse),
     }
     call_ms = {name: time_call(fn) for name, fn in calls.items()}
     call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": cfg.B * cfg.Hkv * cfg.P * cfg.d * 2,
-                  "select_salient": nbytes["select"], "sparse_attn": nbytes["sparse"]}
+                  "select_salient": nbytes["select"], "sparse_attn": nbytes["sparse"],
+                  "sparse_attn_given_scores": nbytes["sparse"] - k_gather // 2}
     call_gbps = {n: call_bytes[n] / (call_ms[n] * 1e-3) / 1e9 for n in call_bytes}
-    log("[bench] per call (ms, GB/s): " + ", ".join(
+    log("[bench] per call (ms, moved GB/s): " + ", ".join(
         f"{n}={call_ms[n]:.4f}" + (f"/{call_gbps[n]:.0f}" if n in call_gbps else "") for n in call_ms))
 
     # dominant kernel: the pool-score pass (K of the whole older context, once per KV head)
     score_bytes = call_bytes["pool_scores"]
-    roof = {"bound": "hbm", "kernel": "attn_split_kernel<bf16,128,4,scores> (hgca_pool_scores)",
-            "achieved": score_bytes / (call_ms["pool_scores"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": score_bytes / (call_ms["pool_scores"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+    achieved = score_bytes / (call_ms["pool_scores"] * 1e-3) / 1e9
+    roof = {"bound": "hbm", "kernel": "pool_scores_mfma_kernel<128,4> (hgca_pool_scores; first kernel of "
+                                      "hgca_select_salient)",
+            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": score_bytes,
             "avg_launch_ms": call_ms["pool_scores"]}
+
+    def rate(nb, ms):
+        return nb / (ms * 1e-3) / 1e9
 
     out = {
         "metric": METRIC, "value": 1e3 / ms_per_step, "unit": "layer-steps/s", "n_gpus": 1,
@@ -141,46 +160,59 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C2: Llama-3-8B-like layer, bf16, B=8, Hq=32, Hkv=8, d=128, ctx 32768 "
                                "(window 4096 + pool 28672), per-head top-k 2048; full step = dense + select + "
-                               "sparse + merge", "layers_cycled": args.layers, "streams": args.streams},
-        "achieved_hbm_gbps": nbytes["full"] / (ms_per_step * 1e-3) / 1e9,
-        "hbm_frac": nbytes["full"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                               "sparse + merge", "layers_cycled": args.layers, "streams": args.streams,
+                   "select_passes_scores_to_sparse": pass_scores},
+        "achieved_hbm_gbps": rate(nbytes["full"], ms_per_step),
+        "hbm_frac": rate(nbytes["full"], ms_per_step) / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": nbytes["full"],
+        "moved_bytes_per_step": moved_full,
+        "moved_hbm_frac": rate(moved_full, ms_per_step) / HBM_PEAK_GBPS,
         "steady": {"ms_per_step": steady_ms, "layer_steps_per_s": 1e3 / steady_ms,
-                   "achieved_hbm_gbps": nbytes["steady"] / (steady_ms * 1e-3) / 1e9,
-                   "hbm_frac": nbytes["steady"] / (steady_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                   "achieved_hbm_gbps": rate(nbytes["steady"], steady_ms),
+                   "hbm_frac": rate(nbytes["steady"], steady_ms) / HBM_PEAK_GBPS,
                    "algorithmic_bytes_per_step": nbytes["steady"]},
         "per_call_ms": call_ms, "per_call_gbps": call_gbps,
         "device_ms_per_step": full_ms, "wall_ms_per_step": wall_ms,
         "roofline": roof,
     }
-
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host_layers[0], args.cpu_seconds)
     print(json.dumps(out), flush=True)
     return 0
 
 
+def copy_calibration(torch, dev) -> int:
+    """Plain device-to-device copies of 1 GiB: what FETCH_SIZE / WRITE_SIZE read for a known size."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(10):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 10}), flush=True)
+    return 0
+
+
 def cpu_baseline(L, target_s: float) -> dict:
-    """The fp64 oracle as it stands, timed on this machine's host cores on the first sequences of layer 0."""
-    import numpy as np
+    """The fp64 oracle as it stands, timed on this machine's host cores: whole C2 layer-steps (dense, select,
+    sparse, merge for all 8 sequences and 32 heads) repeated until about `target_s` seconds have gone."""
     import oracle
 
-    def tier(t, nb):
-        return oracle.Tier(np.ascontiguousarray(t.k[:nb]), np.ascontiguousarray(t.v[:nb]), t.cap)
+    def tier(t):
+        return oracle.Tier(t.k, t.v, t.cap)
 
-    def run(nb):
+    def one_step():
         t0 = time.perf_counter()
-        oracle.hybrid_step(np.ascontiguousarray(L.q[:nb]), tier(L.window, nb), tier(L.pool, nb), L.k, L.k_max, L.scale)
+        oracle.hybrid_step(L.q, tier(L.window), tier(L.pool), L.k, L.k_max, L.scale)
         return time.perf_counter() - t0
 
-    B = L.cfg.B
-    t1 = run(1)                                                 # one sequence: sizes the sample
-    nb = int(max(1, min(B, target_s / max(t1, 1e-3))))
-    t = run(nb) if nb > 1 else t1
-    steps_per_s = (nb / B) / t                                  # a layer-step covers all B sequences
-    return {"value": steps_per_s, "unit": "layer-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{nb} of {B} sequences of one C2 layer-step (all 32 heads, full window+pool), "
-                      f"{t:.2f}s of fp64 oracle time, scaled by {nb}/{B}"}
+    times = [one_step()]
+    while sum(times) < target_s and len(times) < 200:
+        times.append(one_step())
+    mean = sum(times) / len(times)
+    return {"value": 1.0 / mean, "unit": "layer-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{len(times)} whole C2 layer-steps on layer 0 ({sum(times):.1f}s of fp64 oracle time, "
+                      f"OpenMP over (batch, head))"}
 
 
 if __name__ == "__main__":

@@ -115,21 +115,30 @@ int hgca_pool_scores(const hgca_shape *shape, const void *q,
  * ascending order, padded with -1; cnt_out [B,Hq] receives k_b.  k_max is the
  * row length of idx_out: min(k_uniform, pool->cap) must not exceed it (checked
  * on the host; per-sequence budgets are clamped to k_max on the device).
- * Only pool->k is read. */
+ * sel_scores_out (optional, NULL to skip) is fp32 [B,Hq,k_max] and receives the
+ * score s_j of every kept entry, in the order of idx_out (entries at or beyond
+ * cnt are left untouched).  Only pool->k is read. */
 int hgca_select_salient(const hgca_shape *shape, const void *q,
                         const hgca_kv_view *pool,
                         const int32_t *k_per_seq, int32_t k_uniform,
                         int32_t k_max, int32_t *idx_out, int32_t *cnt_out,
+                        float *sel_scores_out,
                         void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Per-head sparse attention (Sec. 3.3 "CPU-local sparse attention"; Alg. 2,
  * cpu_attention): softmax attention of query head (b,h) over pool rows
  * idx[b,h,0 .. cnt[b,h]).  Entries at or beyond cnt[b,h] are ignored; the
  * listed positions must be valid and distinct (a repeated position is counted
- * twice).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32). */
+ * twice).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32).
+ * sel_scores (optional, NULL for none) is fp32 [B,Hq,k_max] holding the score
+ * s_j = sm_scale * <q, k_j> of every listed entry for THIS q, as
+ * hgca_select_salient returns it: the scores are then taken as given and the
+ * K rows are not read again (only pool->v is).  Pass NULL whenever q differs
+ * from the query the scores were computed for. */
 int hgca_sparse_attn(const hgca_shape *shape, const void *q,
                      const hgca_kv_view *pool,
                      const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                     const float *sel_scores,
                      float *o_out, float *lse_out,
                      void *ws, size_t ws_bytes, void *hip_stream);
 

@@ -18,7 +18,7 @@ namespace hgca {
 
 namespace {
 
-enum Mode { kDense = 0, kGather = 1, kScores = 2 };
+enum Mode { kDense = 0, kGather = 1, kScores = 2, kGatherScored = 3 };   // kGatherScored: scores are given
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
@@ -33,6 +33,7 @@ struct KernelArgs {
     KvDev kv;
     const int32_t *idx;
     const int32_t *cnt;
+    const float *sel_scores;
     int32_t k_max;
     int32_t chunk;
     Partials part;
@@ -161,13 +162,14 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 
     const int split = blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
     const int Hq = a.sh.n_q_heads, Hkv = a.sh.n_kv_heads;
-    const int kvh = (MODE == kGather) ? unit / a.sh.group : unit;
-    const int h0 = (MODE == kGather) ? unit : unit * NH;          // first of the NH heads handled
+    constexpr bool GATHER = MODE == kGather || MODE == kGatherScored;
+    const int kvh = GATHER ? unit / a.sh.group : unit;
+    const int h0 = GATHER ? unit : unit * NH;                     // first of the NH heads handled
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
     const int r = lane / LPR, c = lane % LPR;
 
     const int64_t bh0 = (int64_t)b * Hq + h0;
-    const int n = (MODE == kGather) ? min(a.cnt[bh0], a.k_max) : tier_len(a.kv, b);
+    const int n = GATHER ? min(a.cnt[bh0], a.k_max) : tier_len(a.kv, b);
     const int t0 = split * a.chunk;
 
     if (t0 >= n) {                               // empty split (uniform over the workgroup)
@@ -175,20 +177,26 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
         return;
     }
     const int nt = min(a.chunk, n - t0);         // 1 .. chunk tokens in this split
-    const int32_t *idx_row = (MODE == kGather) ? a.idx + bh0 * a.k_max + t0 : nullptr;
+    const int32_t *idx_row = GATHER ? a.idx + bh0 * a.k_max + t0 : nullptr;
 
+    if (MODE == kGatherScored) {                 // the caller already holds the scores of the listed entries
+        const float *given = a.sel_scores + bh0 * a.k_max + t0;
+        for (int j = tid; j < nt; j += kBlock) s_p[0][j] = given[j];
+    }
     float qf[NH][EPL];
+    if (MODE != kGatherScored) {
 #pragma unroll
-    for (int g = 0; g < NH; ++g)
-        Elem<T>::expand(load16(a.q + ((bh0 + g) * D + c * EPL) * (int64_t)sizeof(T)), qf[g]);
+        for (int g = 0; g < NH; ++g)
+            Elem<T>::expand(load16(a.q + ((bh0 + g) * D + c * EPL) * (int64_t)sizeof(T)), qf[g]);
+    }
 
     // K pass: scores of the split into LDS
-    for (int base = 0; base < nt; base += RPI * kUnroll) {
+    for (int base = 0; MODE != kGatherScored && base < nt; base += RPI * kUnroll) {
         uint4 kr[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int j = min(base + u * RPI + w * RPW + r, nt - 1);
-            const int32_t tok = (MODE == kGather) ? idx_row[j] : t0 + j;
+            const int32_t tok = GATHER ? idx_row[j] : t0 + j;
             kr[u] = load16_stream(a.kv.k + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
         }
 #pragma unroll
@@ -218,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 
     split_softmax<NH>(s_p, s_m, s_l, nt);
     __syncthreads();
-    value_pass<T, D, NH, MODE == kGather>(a, s_p, s_red, s_m, s_l, b, kvh, bh0, split, t0, nt, idx_row);
+    value_pass<T, D, NH, GATHER>(a, s_p, s_red, s_m, s_l, b, kvh, bh0, split, t0, nt, idx_row);
 }
 
 // ---- MFMA path (bf16 K/V, dense over a tier) -------------------------------------------------
@@ -489,6 +497,7 @@ KernelArgs to_kernel_args(const AttnArgs &a)
     ka.kv = a.kv;
     ka.idx = a.idx;
     ka.cnt = a.cnt;
+    ka.sel_scores = a.sel_scores;
     ka.k_max = a.k_max;
     ka.chunk = a.chunk;
     ka.part = a.part;
@@ -510,11 +519,15 @@ hipError_t launch_attn_partial_gather(int dtype, int head_dim, const AttnArgs &a
     if (a.sh.batch == 0 || a.part.n_splits == 0) return hipSuccess;
     dim3 grid(a.part.n_splits, a.sh.n_q_heads, a.sh.batch);
     const KernelArgs ka = to_kernel_args(a);
-    if (dtype == 0 && head_dim == 64) HGCA_LAUNCH((attn_split_kernel<float, 64, 1, kGather>), grid, dim3(kBlock), s, ka);
-    else if (dtype == 0 && head_dim == 128) HGCA_LAUNCH((attn_split_kernel<float, 128, 1, kGather>), grid, dim3(kBlock), s, ka);
-    else if (dtype == 1 && head_dim == 64) HGCA_LAUNCH((attn_split_kernel<bf16_t, 64, 1, kGather>), grid, dim3(kBlock), s, ka);
-    else if (dtype == 1 && head_dim == 128) HGCA_LAUNCH((attn_split_kernel<bf16_t, 128, 1, kGather>), grid, dim3(kBlock), s, ka);
+#define HGCA_GATHER_CASE(T, D)                                                                              \
+    if (a.sel_scores) HGCA_LAUNCH((attn_split_kernel<T, D, 1, kGatherScored>), grid, dim3(kBlock), s, ka);  \
+    else HGCA_LAUNCH((attn_split_kernel<T, D, 1, kGather>), grid, dim3(kBlock), s, ka)
+    if (dtype == 0 && head_dim == 64) { HGCA_GATHER_CASE(float, 64); }
+    else if (dtype == 0 && head_dim == 128) { HGCA_GATHER_CASE(float, 128); }
+    else if (dtype == 1 && head_dim == 64) { HGCA_GATHER_CASE(bf16_t, 64); }
+    else if (dtype == 1 && head_dim == 128) { HGCA_GATHER_CASE(bf16_t, 128); }
     else return hipErrorInvalidValue;
+#undef HGCA_GATHER_CASE
     return hipGetLastError();
 }
 

@@ -185,8 +185,8 @@ int hgca_pool_scores(const hgca_shape *shape, const void *q, const hgca_kv_view 
 }
 
 int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *k_per_seq,
-                        int32_t k_uniform, int32_t k_max, int32_t *idx_out, int32_t *cnt_out, void *ws,
-                        size_t ws_bytes, void *hip_stream)
+                        int32_t k_uniform, int32_t k_max, int32_t *idx_out, int32_t *cnt_out,
+                        float *sel_scores_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
@@ -216,12 +216,13 @@ int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_vi
     se.k_max = k_max;
     se.idx = idx_out;
     se.cnt = cnt_out;
+    se.sel_scores = sel_scores_out;
     return from_hip(launch_select(se, s));
 }
 
 int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *idx,
-                     const int32_t *cnt, int32_t k_max, float *o_out, float *lse_out, void *ws, size_t ws_bytes,
-                     void *hip_stream)
+                     const int32_t *cnt, int32_t k_max, const float *sel_scores, float *o_out, float *lse_out,
+                     void *ws, size_t ws_bytes, void *hip_stream)
 {
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
@@ -239,6 +240,7 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view 
     a.kv = to_dev(pool);
     a.idx = idx;
     a.cnt = cnt;
+    a.sel_scores = sel_scores;
     a.k_max = k_max;
     a.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads);
     a.part = partials_at(ws, w, std::max(1, n_splits_for(k_max, a.chunk)));

@@ -26,6 +26,7 @@ struct AttnArgs {
     KvDev kv;
     const int32_t *idx;    // gather only: [B, Hq, k_max]
     const int32_t *cnt;    // gather only: [B, Hq]
+    const float *sel_scores;   // gather only, optional: scaled scores of the listed entries (skips the K pass)
     int32_t k_max;
     int32_t chunk;         // tokens per split
     Partials part;
@@ -59,6 +60,7 @@ struct SelectArgs {
     int32_t k_uniform, k_max;
     int32_t *idx;          // [B, Hq, k_max]
     int32_t *cnt;          // [B, Hq]
+    float *sel_scores;     // optional [B, Hq, k_max]: score of every kept entry, in idx order
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t s);
 

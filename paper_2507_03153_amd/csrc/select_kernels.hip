@@ -311,6 +311,7 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     // coalesced stores; budgets beyond its size go to global memory directly.
     const bool staged = k <= kBins;
     int32_t *dst = staged ? reinterpret_cast<int32_t *>(sh.hist) : out;
+    float *sel = a.sel_scores ? a.sel_scores + (int64_t)blockIdx.x * a.k_max : nullptr;
     uint32_t run_gt = 0, run_eq = 0;             // kept / tied entries before the wave's current step
     for (int i = 0; i < w; ++i) { run_gt += sh.wave_gt[i]; run_eq += sh.wave_eq[i]; }
     const bool pad_ties = thr == -INFINITY;      // only then could padding tie with the threshold
@@ -332,7 +333,11 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (gt[e] || (eq[e] && eq_before < need_eq)) dst[gt_before + min(eq_before, need_eq)] = t + e;
+            if (gt[e] || (eq[e] && eq_before < need_eq)) {
+                const uint32_t at = gt_before + min(eq_before, need_eq);
+                dst[at] = t + e;
+                if (sel) sel[at] = s[e];
+            }
             gt_before += gt[e];
             eq_before += eq[e];
         }
@@ -368,7 +373,10 @@ __global__ __launch_bounds__(kSelBlock) void select_topk_kernel(SelectArgs a, in
     for (int j = k + tid; j < a.k_max; j += kSelBlock) out[j] = -1;
     if (k == 0) return;
     if (k == n) {                                // everything is kept
-        for (int t = tid; t < n; t += kSelBlock) out[t] = t;
+        for (int t = tid; t < n; t += kSelBlock) {
+            out[t] = t;
+            if (a.sel_scores) a.sel_scores[bh * (int64_t)a.k_max + t] = sc[t];
+        }
         return;
     }
     const int seg = ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;

@@ -62,9 +62,9 @@ def lib() -> ctypes.CDLL:
         L.hgca_pool_scores.restype = ctypes.c_int
         L.hgca_pool_scores.argtypes = [ps, vp, pk, vp, vp]
         L.hgca_select_salient.restype = ctypes.c_int
-        L.hgca_select_salient.argtypes = [ps, vp, pk, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.hgca_select_salient.argtypes = [ps, vp, pk, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         L.hgca_sparse_attn.restype = ctypes.c_int
-        L.hgca_sparse_attn.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.hgca_sparse_attn.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.hgca_lse_merge.restype = ctypes.c_int
         L.hgca_lse_merge.argtypes = [ps, vp, vp, vp, vp, vp, i32, vp, vp]
         _lib = L
@@ -158,9 +158,10 @@ def pool_scores(shape: Shape, q, pool: Tier, scores_out, stream=None) -> None:
            "hgca_pool_scores")
 
 
-def select_salient(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out, ws, stream=None) -> None:
+def select_salient(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out, ws, stream=None,
+                   sel_scores_out=None) -> None:
     """k: int (uniform budget) or int32 GPU tensor [B] (per-sequence budgets)."""
-    for t in (q, idx_out, cnt_out, ws):
+    for t in (q, idx_out, cnt_out, ws) + (() if sel_scores_out is None else (sel_scores_out,)):
         _require_gpu(t)
     kv = pool.view()
     if isinstance(k, torch.Tensor):
@@ -169,16 +170,19 @@ def select_salient(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out,
     else:
         k_ptr, k_uni = None, int(k)
     _check(lib().hgca_select_salient(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), k_ptr, k_uni, int(k_max),
-                                     _ptr(idx_out), _ptr(cnt_out), _ptr(ws), ws.numel(), _stream(stream)),
+                                     _ptr(idx_out), _ptr(cnt_out), _ptr(sel_scores_out), _ptr(ws), ws.numel(),
+                                     _stream(stream)),
            "hgca_select_salient")
 
 
-def sparse_attn(shape: Shape, q, pool: Tier, idx, cnt, k_max: int, o_out, lse_out, ws, stream=None) -> None:
-    for t in (q, idx, cnt, o_out, lse_out, ws):
+def sparse_attn(shape: Shape, q, pool: Tier, idx, cnt, k_max: int, o_out, lse_out, ws, stream=None,
+                sel_scores=None) -> None:
+    """sel_scores: scores of the listed entries for this q (from select_salient); K is then not re-read."""
+    for t in (q, idx, cnt, o_out, lse_out, ws) + (() if sel_scores is None else (sel_scores,)):
         _require_gpu(t)
     kv = pool.view()
     _check(lib().hgca_sparse_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
-                                  _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
+                                  _ptr(sel_scores), _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
            "hgca_sparse_attn")
 
 

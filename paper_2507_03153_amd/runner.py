@@ -52,16 +52,18 @@ class HybridStep:
     """Buffers for one layer-step on `shape`; `run` enqueues dense, select, sparse and merge."""
 
     def __init__(self, shape: hgca.Shape, max_window: int, max_pool: int, k_max: int, device="cuda:0",
-                 out_dtype=torch.float32, two_streams: bool = False):
+                 out_dtype=torch.float32, two_streams: bool = False, pass_scores: bool = True):
         B, Hq, d = shape.batch, shape.n_q_heads, shape.head_dim
         f32 = dict(dtype=torch.float32, device=device)
         self.shape, self.k_max, self.device = shape, k_max, device
+        self.pass_scores = pass_scores                              # select hands its scores to the sparse part
         self.o_w, self.lse_w = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
         self.o_s, self.lse_s = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
         self.o = torch.empty(B, Hq, d, dtype=out_dtype, device=device)
         self.lse = torch.empty(B, Hq, **f32)
         self.idx = torch.full((B, Hq, max(k_max, 1)), -1, dtype=torch.int32, device=device)
         self.cnt = torch.zeros(B, Hq, dtype=torch.int32, device=device)
+        self.sel_scores = torch.empty(B, Hq, max(k_max, 1), **f32)   # scores of the kept entries (select -> sparse)
         # the two branches may overlap, so each owns a workspace
         self.ws_dense = hgca.alloc_workspace(shape, max_window, 0, 0, device)
         self.ws_sparse = hgca.alloc_workspace(shape, 0, max_pool, k_max, device)
@@ -80,9 +82,11 @@ class HybridStep:
         side = self.side if self.side is not None else main
         s_main, s_side = ctypes.c_void_p(main.cuda_stream), ctypes.c_void_p(side.cuda_stream)
         a_sel = (ref(sh), ptr(L.q), ref(pool), k_ptr, k_uni, self.k_max, ptr(self.idx), ptr(self.cnt),
-                 ptr(self.ws_sparse), self.ws_sparse.numel(), s_side)
-        a_sparse = (ref(sh), ptr(L.q), ref(pool), ptr(self.idx), ptr(self.cnt), self.k_max, ptr(self.o_s),
-                    ptr(self.lse_s), ptr(self.ws_sparse), self.ws_sparse.numel(), s_side)
+                 ptr(self.sel_scores), ptr(self.ws_sparse), self.ws_sparse.numel(), s_side)
+        # with a fresh selection its scores feed the sparse part; a reused selection re-reads K
+        a_sparse = {given: (ref(sh), ptr(L.q), ref(pool), ptr(self.idx), ptr(self.cnt), self.k_max,
+                            ptr(self.sel_scores) if given else None, ptr(self.o_s), ptr(self.lse_s),
+                            ptr(self.ws_sparse), self.ws_sparse.numel(), s_side) for given in (False, True)}
         a_dense = (ref(sh), ptr(L.q), ref(win), ptr(self.o_w), ptr(self.lse_w), ptr(self.ws_dense),
                    self.ws_dense.numel(), s_main)
         a_merge = (ref(sh), ptr(self.o_s), ptr(self.lse_s), ptr(self.o_w), ptr(self.lse_w), ptr(self.o),
@@ -95,7 +99,7 @@ class HybridStep:
                 side.wait_event(self._fork)
             if select:
                 hgca._check(lib.hgca_select_salient(*a_sel), "hgca_select_salient")
-            hgca._check(lib.hgca_sparse_attn(*a_sparse), "hgca_sparse_attn")
+            hgca._check(lib.hgca_sparse_attn(*a_sparse[select and self.pass_scores]), "hgca_sparse_attn")
             hgca._check(lib.hgca_dense_window_attn(*a_dense), "hgca_dense_window_attn")
             if self.side is not None:
                 self._join.record(side)
@@ -112,10 +116,12 @@ class HybridStep:
             side = self.side
             self._fork.record(main)
             side.wait_event(self._fork)
+        given = self.sel_scores if (select and self.pass_scores) else None
         if select:
-            hgca.select_salient(self.shape, L.q, L.pool, L.k, self.k_max, self.idx, self.cnt, self.ws_sparse, side)
+            hgca.select_salient(self.shape, L.q, L.pool, L.k, self.k_max, self.idx, self.cnt, self.ws_sparse, side,
+                                sel_scores_out=given)
         hgca.sparse_attn(self.shape, L.q, L.pool, self.idx, self.cnt, self.k_max, self.o_s, self.lse_s,
-                         self.ws_sparse, side)
+                         self.ws_sparse, side, sel_scores=given)
         hgca.dense_window_attn(self.shape, L.q, L.window, self.o_w, self.lse_w, self.ws_dense, main)
         if self.side is not None:
             self._join.record(side)

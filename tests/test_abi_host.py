@@ -92,8 +92,8 @@ def test_select_and_sparse_reject_bad_arguments(hg):
     L = hg.lib()
 
     def select(k_ptr=None, k_uni=8, k_max=8, idx=FAKE, cnt=FAKE, ws=FAKE, ws_bytes=1 << 40, view=v, q=FAKE):
-        return L.hgca_select_salient(ctypes.byref(sh), q, ctypes.byref(view), k_ptr, k_uni, k_max, idx, cnt, ws,
-                                     ws_bytes, None)
+        return L.hgca_select_salient(ctypes.byref(sh), q, ctypes.byref(view), k_ptr, k_uni, k_max, idx, cnt, None,
+                                     ws, ws_bytes, None)
 
     assert select(k_uni=9) == hg.ERR_INVALID_ARG              # k > k_max
     assert select(k_uni=-1) == hg.ERR_INVALID_ARG
@@ -107,7 +107,7 @@ def test_select_and_sparse_reject_bad_arguments(hg):
     assert select(ws_bytes=need - 1) == hg.ERR_WORKSPACE
 
     def sparse(idx=FAKE, cnt=FAKE, k_max=8, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40, view=v):
-        return L.hgca_sparse_attn(ctypes.byref(sh), FAKE, ctypes.byref(view), idx, cnt, k_max, o, lse, ws,
+        return L.hgca_sparse_attn(ctypes.byref(sh), FAKE, ctypes.byref(view), idx, cnt, k_max, None, o, lse, ws,
                                   ws_bytes, None)
 
     assert sparse(idx=None) == hg.ERR_INVALID_ARG

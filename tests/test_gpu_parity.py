@@ -107,10 +107,19 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
     assert err_s <= BAND[cfg.dtype] / 2                        # a band of eps covers both sides' rounding
 
     say("  step select_salient")
-    hgca.select_salient(D.shape, D.q, D.pool, D.k, L.k_max, step.idx, step.cnt, step.ws_sparse)
+    step.sel_scores.fill_(float("nan"))
+    hgca.select_salient(D.shape, D.q, D.pool, D.k, L.k_max, step.idx, step.cnt, step.ws_sparse,
+                        sel_scores_out=step.sel_scores)
     torch.cuda.synchronize()
     idx_g, cnt_g = step.idx.cpu().numpy()[:, :, :L.k_max], step.cnt.cpu().numpy()
     n_band = assert_selection("select", idx_g, cnt_g, scores, p_lens, k_b, BAND[cfg.dtype])
+    # the scores handed on to the sparse part are those of the kept entries, in the same order
+    sel_g = step.sel_scores.double().cpu().numpy()[:, :, :L.k_max]
+    kept = np.arange(L.k_max)[None, None, :] < cnt_g[:, :, None]
+    if kept.any():
+        want = np.take_along_axis(scores, np.where(kept, idx_g, 0).astype(np.int64), axis=2)
+        assert np.max(np.abs(sel_g[kept] - want[kept])) <= BAND[cfg.dtype] / 2
+    assert np.all(np.isnan(sel_g[~kept]))
     idx_ref, cnt_ref = oracle.select(L.q, tp, L.k, L.k_max, L.scale)
     same = float(np.mean(np.all(idx_g == idx_ref, axis=-1))) if idx_ref.size else 1.0
     say(f"    select: rows identical to the oracle's: {same:.4f}; rows with a tie inside the band: {n_band}")
