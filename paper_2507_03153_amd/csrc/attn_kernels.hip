@@ -5,10 +5,11 @@
 //   * VALU path (any dtype / head_dim; the gather kernel; fp32): every lane moves
 //     16 bytes of a K row, the lanes that share a row reduce their partial dot
 //     products with wave shuffles;
-//   * MFMA path (bf16, dense over a tier): a wave loads 16-token K tiles straight
-//     into the A-operand layout of v_mfma_f32_16x16x32_bf16, the B operand holds
-//     the query heads of the GQA group (zero-padded to 16 columns), so one K row
-//     read serves all heads of the group at no VALU cost.
+//   * MFMA path (bf16, dense over a tier): a wave loads 16-token K tiles with
+//     coalesced 16-byte loads, passes them through a padded LDS stage into the
+//     A-operand layout of v_mfma_f32_16x16x32_bf16; the B operand holds the query
+//     heads of the GQA group (zero-padded to 16 columns), so one K row read serves
+//     all heads of the group at no VALU cost.
 // After the scores, both paths share the rest: softmax statistics of the split in
 // LDS, a V pass with coalesced 16-byte loads and fp32 FMAs, a reduction through
 // shuffles and LDS, and one partial (m, l, o) per head and split.
