@@ -259,8 +259,8 @@ template <int D> struct Stage {
 
 // Scaled scores of tokens [t0, t0+nt) of (b, kvh) for the G heads of the group, written to
 // s_sc[n][j] (n < G, j < nt rounded up to 16; entries at j >= nt are finite filler).
-template <int D, int G>
-__device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, float (*s_sc)[kMaxChunk], int b,
+template <int D, int G, int LD>
+__device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, float (*s_sc)[LD], int b,
                                             int kvh, int64_t bh0, int t0, int nt)
 {
     using S = Stage<D>;
@@ -302,7 +302,7 @@ template <int D, int G>
 __global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
 {
     __shared__ uint4 s_stage[kWaves * Stage<D>::kWaveVecs];
-    __shared__ __attribute__((aligned(16))) float s_sc[G][kMaxChunk];
+    __shared__ __attribute__((aligned(16))) float s_sc[G][kMaxScoreChunk];
 
     const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int n = tier_len(a.kv, b);
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
     if (t0 >= n) return;
     const int nt = min(a.chunk, n - t0);
     const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
-    mfma_scores<D, G>(a, s_stage, s_sc, b, kvh, bh0, t0, nt);
+    mfma_scores<D, G, kMaxScoreChunk>(a, s_stage, s_sc, b, kvh, bh0, t0, nt);
     __syncthreads();
 
     // coalesced streaming stores, 16 bytes per lane where the row alignment allows it
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
         return;
     }
     const int nt = min(a.chunk, n - t0);
-    mfma_scores<D, G>(a, reinterpret_cast<uint4 *>(s_buf), s_p, b, kvh, bh0, t0, nt);
+    mfma_scores<D, G, kMaxChunk>(a, reinterpret_cast<uint4 *>(s_buf), s_p, b, kvh, bh0, t0, nt);
     __syncthreads();
     split_softmax<G>(s_p, s_m, s_l, nt);
     __syncthreads();

@@ -14,7 +14,16 @@ namespace {
 using namespace hgca;
 
 constexpr size_t kAlign = 256;
-constexpr int kTargetWorkgroups = 2048;          // aim for ~8 workgroups per CU (256 CUs)
+// Workgroups a launch aims for (256 CUs): compile-time tunables, one per streaming pass.
+#ifndef HGCA_TARGET_WGS_DENSE
+#define HGCA_TARGET_WGS_DENSE 1024
+#endif
+#ifndef HGCA_TARGET_WGS_SCORES
+#define HGCA_TARGET_WGS_SCORES 32768
+#endif
+#ifndef HGCA_TARGET_WGS_SPARSE
+#define HGCA_TARGET_WGS_SPARSE 2048
+#endif
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -77,14 +86,14 @@ ShapeDev to_dev(const hgca_shape *s)
 
 // Tokens per split for a set of at most n tokens processed by `units` independent
 // (sequence, head unit) pairs: a multiple of 64 in [kMinChunk, kMaxChunk] that yields
-// roughly kTargetWorkgroups workgroups.
-int pick_chunk(int64_t n, int64_t units)
+// roughly `target` workgroups.
+int pick_chunk(int64_t n, int64_t units, int target, int max_chunk = kMaxChunk)
 {
     if (n <= 0 || units <= 0) return kMinChunk;
-    const int64_t want_splits = std::max<int64_t>(1, kTargetWorkgroups / units);
+    const int64_t want_splits = std::max<int64_t>(1, target / units);
     int64_t chunk = (n + want_splits - 1) / want_splits;
     chunk = (chunk + 63) / 64 * 64;
-    return (int)std::min<int64_t>(kMaxChunk, std::max<int64_t>(kMinChunk, chunk));
+    return (int)std::min<int64_t>(max_chunk, std::max<int64_t>(kMinChunk, chunk));
 }
 
 int n_splits_for(int64_t n, int chunk) { return (int)((n + chunk - 1) / chunk); }
@@ -159,7 +168,7 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     a.sh = to_dev(shape);
     a.q = q;
     a.kv = to_dev(window);
-    a.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads);
+    a.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
     a.part = partials_at(ws, w, n_splits_for(window->cap, a.chunk));
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
@@ -179,7 +188,8 @@ int hgca_pool_scores(const hgca_shape *shape, const void *q, const hgca_kv_view 
     sa.q = q;
     sa.kv = to_dev(pool);
     sa.scores = scores_out;
-    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads);
+    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
+                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
     sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
     return from_hip(launch_scores(shape->dtype, shape->head_dim, sa, static_cast<hipStream_t>(hip_stream)));
 }
@@ -203,7 +213,8 @@ int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_vi
     sa.q = q;
     sa.kv = to_dev(pool);
     sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws) + w.scores);
-    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads);
+    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
+                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
     sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
     if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
 
@@ -242,7 +253,7 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view 
     a.cnt = cnt;
     a.sel_scores = sel_scores;
     a.k_max = k_max;
-    a.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads);
+    a.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
     a.part = partials_at(ws, w, std::max(1, n_splits_for(k_max, a.chunk)));
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;

@@ -9,6 +9,7 @@
 namespace hgca {
 
 constexpr int kMaxChunk = 512;     // tokens of one split (one workgroup) at most
+constexpr int kMaxScoreChunk = 128;   // same for the MFMA score pass, which wants many small workgroups
 constexpr int kMinChunk = 64;
 
 // Split partials of softmax attention: for every (b, h, split)

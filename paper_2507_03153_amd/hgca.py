@@ -17,7 +17,8 @@ import torch  # noqa: F401  (loads the HIP runtime the library binds to; must pr
 F32, BF16 = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, -1, -2, -3, -4
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhgca.so")
+# HGCA_LIB names another build of the same library (tuning experiments); the default is the in-tree one
+_LIB_PATH = os.environ.get("HGCA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhgca.so")
 
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge")
