@@ -198,6 +198,7 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     bin.inv_w = (mx > mn) ? (float)kBins / (mx - mn) : 0.f;
 
     // ---- pass 1: histogram, threshold bin --------------------------------------------------------------
+#pragma unroll 4
     for (int i = 0; i < steps; ++i) {
         const float4 v = row.at(row.pos(i));
         atomicAdd(&sh.hist[bin(v.x)], 1u);
@@ -213,6 +214,7 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
 
     // ---- pass 2: count the entries above the threshold bin, collect those inside it ---------------------
     uint32_t above = 0;
+#pragma unroll 2
     for (int i = 0; i < steps; ++i) {
         const int t = row.pos(i);
         const float4 v = row.at(t);
@@ -315,6 +317,7 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     uint32_t run_gt = 0, run_eq = 0;             // kept / tied entries before the wave's current step
     for (int i = 0; i < w; ++i) { run_gt += sh.wave_gt[i]; run_eq += sh.wave_eq[i]; }
     const bool pad_ties = thr == -INFINITY;      // only then could padding tie with the threshold
+#pragma unroll 2
     for (int i = 0; i < steps; ++i) {
         const int t = row.pos(i);
         const float4 v = row.at(t);

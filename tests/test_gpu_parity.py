@@ -305,3 +305,23 @@ def test_repeated_runs_are_bitwise_identical(gpu, oracle):
 
 def test_c2_full_size(gpu, oracle):
     run_case(gpu, oracle, wl.CONFIGS["C2"])
+
+
+# ---------------------------------------------------------------- the other benchmark shapes at full size
+
+@pytest.mark.timeout(600)
+def test_c4_full_size_70b_shape(gpu, oracle):
+    """B=4, GQA 8, 128K context: the pool (122880) is longer than the selection's LDS row cache."""
+    run_case(gpu, oracle, wl.CONFIGS["C4"])
+
+
+@pytest.mark.timeout(600)
+def test_c5_full_size_ragged_paged(gpu, oracle):
+    """B=64 ragged lengths, both tiers in 16-token pages, per-sequence budgets of 10 %."""
+    run_case(gpu, oracle, wl.CONFIGS["C5"])
+
+
+@pytest.mark.timeout(900)
+def test_c3_full_size_mha(gpu, oracle):
+    """B=32, 40 MHA heads, 16K context (10.7 GB of KV)."""
+    run_case(gpu, oracle, wl.CONFIGS["C3"])
