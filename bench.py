@@ -3,14 +3,17 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--streams 1|2] [--no-cpu]
 
-A step is one pass of the whole hot path over one batch: hgca_dense_window_attn,
-hgca_select_salient, hgca_sparse_attn and hgca_lse_merge on the 8B-shape 32K-context
+A step is one pass of the whole hot path over one batch: dense window attention,
+salient selection, sparse attention and log-sum-exp merge on the 8B-shape 32K-context
 workload (C2: bf16, B=8, Hq=32, Hkv=8, d=128, window 4096, pool 28672, k=2048) with
 seeded synthetic K/V already resident in HBM.  Steps cycle over L independently drawn
 layers so that consecutive steps do not re-read K/V still held in L2 / Infinity Cache.
 Prints ONE JSON line.
 
-`value` is the full step (selection every step).  In it the selection hands the scores of
+`value` is the full step (selection every step) as hgca_dense_window_attn (result deferred),
+hgca_select_salient, hgca_sparse_attn (result deferred) and hgca_lse_merge_splits, which folds the
+split partials of both parts in one kernel; `four_calls` is the same step with each part folding
+its own splits and hgca_lse_merge joining them.  In both the selection hands the scores of
 the kept entries to the sparse part, which therefore re-reads only V of those entries;
 `algorithmic_bytes_per_step` keeps counting their K rows (the definition of the metric),
 `moved_bytes_per_step` does not.  The `steady` step reuses a selection, as the paper's decode
@@ -47,6 +50,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=4, help="independent KV draws cycled through")
     ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
                     help="2: the dense window part runs on a second stream beside select+sparse")
+    ap.add_argument("--four-calls", action="store_true",
+                    help="headline = the step with per-part outputs and hgca_lse_merge (no deferred results)")
     ap.add_argument("--no-pass-scores", action="store_true",
                     help="sparse part recomputes its scores from K even right after a selection")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -80,31 +85,37 @@ def main() -> int:
     layers = [runner.DeviceLayer.upload(L, dev) for L in host_layers]
     log(f"[bench] {args.layers} layers of C2 generated and uploaded in {time.time() - t0:.1f}s "
         f"({sum(L.kv_bytes() for L in host_layers) / 2**30:.2f} GiB of KV)")
-    step = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, cfg.k, dev, two_streams=(args.streams == 2),
-                             pass_scores=pass_scores)
     main_stream = torch.cuda.current_stream()
-    prepared = [step.prepare(L) for L in layers]               # arguments marshalled once per layer
+    steps_by_tail = {fused: runner.HybridStep(layers[0].shape, cfg.W, cfg.P, cfg.k, dev,
+                                              two_streams=(args.streams == 2), pass_scores=pass_scores,
+                                              fused_tail=fused) for fused in (True, False)}
+    prepared_by_tail = {fused: [st.prepare(L) for L in layers] for fused, st in steps_by_tail.items()}
+    step = steps_by_tail[False]                                 # buffers used by the per-call timings below
 
-    def run_steps(n: int, select: bool, first: int = 0) -> None:
-        for i in range(n):
-            prepared[(first + i) % len(prepared)](select)
+    def timed(fused: bool, select: bool):
+        prepared = prepared_by_tail[fused]                      # arguments marshalled once per layer
 
-    def timed(select: bool):
-        run_steps(args.warmup, select)
+        def run_steps(n: int, first: int = 0) -> None:
+            for i in range(n):
+                prepared[(first + i) % len(prepared)](select)
+
+        run_steps(args.warmup)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t_wall = time.perf_counter()
         e0.record(main_stream)
-        run_steps(args.steps, select, args.warmup)
+        run_steps(args.steps, args.warmup)
         e1.record(main_stream)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t_wall) * 1e3 / args.steps
-        return e0.elapsed_time(e1) / args.steps, wall
+        dev_ms = e0.elapsed_time(e1) / args.steps
+        return max(dev_ms, wall), dev_ms, wall                  # host-side launch cost counts too
 
-    full_ms, wall_ms = timed(True)                              # all four calls
-    ms_per_step = max(full_ms, wall_ms)                         # host-side launch cost counts too
-    steady_dev, steady_wall = timed(False)                      # selection reused
-    steady_ms = max(steady_dev, steady_wall)
+    head = not args.four_calls                                  # tail of the headline step
+    ms_per_step, full_ms, wall_ms = timed(head, True)
+    steady_ms, _, _ = timed(head, False)                        # selection reused
+    other_ms, _, _ = timed(not head, True)
+    other_steady_ms, _, _ = timed(not head, False)
 
     # ---- per-call device time: HIP events on the stream the kernels are launched on ---------------------
     def time_call(fn, n=args.steps) -> float:
@@ -161,7 +172,9 @@ def main() -> int:
         "config": {"workload": "C2: Llama-3-8B-like layer, bf16, B=8, Hq=32, Hkv=8, d=128, ctx 32768 "
                                "(window 4096 + pool 28672), per-head top-k 2048; full step = dense + select + "
                                "sparse + merge", "layers_cycled": args.layers, "streams": args.streams,
-                   "select_passes_scores_to_sparse": pass_scores},
+                   "select_passes_scores_to_sparse": pass_scores,
+                   "tail": "hgca_lse_merge_splits over deferred results" if head else
+                           "per-part outputs + hgca_lse_merge"},
         "achieved_hbm_gbps": rate(nbytes["full"], ms_per_step),
         "hbm_frac": rate(nbytes["full"], ms_per_step) / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": nbytes["full"],
@@ -171,6 +184,11 @@ def main() -> int:
                    "achieved_hbm_gbps": rate(nbytes["steady"], steady_ms),
                    "hbm_frac": rate(nbytes["steady"], steady_ms) / HBM_PEAK_GBPS,
                    "algorithmic_bytes_per_step": nbytes["steady"]},
+        ("four_calls" if head else "deferred_tail"): {
+            "ms_per_step": other_ms, "layer_steps_per_s": 1e3 / other_ms,
+            "hbm_frac": rate(nbytes["full"], other_ms) / HBM_PEAK_GBPS,
+            "steady_ms_per_step": other_steady_ms,
+            "steady_hbm_frac": rate(nbytes["steady"], other_steady_ms) / HBM_PEAK_GBPS},
         "per_call_ms": call_ms, "per_call_gbps": call_gbps,
         "device_ms_per_step": full_ms, "wall_ms_per_step": wall_ms,
         "roofline": roof,

@@ -90,7 +90,8 @@ size_t hgca_workspace_bytes(const hgca_shape *shape, int32_t max_window,
 /* GPU-local dense attention (Sec. 3.3 "GPU-local dense attention"; Alg. 2,
  * gpu_attention): softmax attention of each query head over ALL valid tokens
  * of `window`, which the caller has already extended with the token being
- * decoded.  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32). */
+ * decoded.  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32); both NULL defers
+ * the result (see hgca_lse_merge_splits). */
 int hgca_dense_window_attn(const hgca_shape *shape, const void *q,
                            const hgca_kv_view *window,
                            float *o_out, float *lse_out,
@@ -129,7 +130,8 @@ int hgca_select_salient(const hgca_shape *shape, const void *q,
  * cpu_attention): softmax attention of query head (b,h) over pool rows
  * idx[b,h,0 .. cnt[b,h]).  Entries at or beyond cnt[b,h] are ignored; the
  * listed positions must be valid and distinct (a repeated position is counted
- * twice).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32).
+ * twice).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32); both NULL defers
+ * the result (see hgca_lse_merge_splits).
  * sel_scores (optional, NULL for none) is fp32 [B,Hq,k_max] holding the score
  * s_j = sm_scale * <q, k_j> of every listed entry for THIS q, as
  * hgca_select_salient returns it: the scores are then taken as given and the
@@ -141,6 +143,22 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q,
                      const float *sel_scores,
                      float *o_out, float *lse_out,
                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Deferred results.  hgca_dense_window_attn and hgca_sparse_attn are split-K
+ * kernels followed by a small fold of the splits.  Called with o_out == NULL and
+ * lse_out == NULL (both), they skip the fold and leave their split partials in
+ * `ws`; hgca_lse_merge_splits then folds the splits of BOTH parts in one kernel,
+ * which is merge_state (Sec. 3.3 "Merging states") applied to all partial states at
+ * once -- the fusion is associative -- and saves two kernel launches per step.
+ * window_cap and k_max must be the window->cap and k_max of the two deferred calls
+ * (they fix the split counts), ws_dense / ws_sparse the workspaces those calls
+ * used, untouched since; either may be NULL for "no such part".  o_out is
+ * [B,Hq,d] in o_dtype (fp32 or bf16), lse_out [B,Hq] fp32 or NULL. */
+int hgca_lse_merge_splits(const hgca_shape *shape,
+                          int32_t window_cap, const void *ws_dense, size_t ws_dense_bytes,
+                          int32_t k_max, const void *ws_sparse, size_t ws_sparse_bytes,
+                          void *o_out, int32_t o_dtype, float *lse_out,
+                          void *hip_stream);
 
 /* merge_state (Sec. 3.3 "Merging states"): combines two partial results over
  * disjoint key sets into the result of one softmax over their union.  Evaluated

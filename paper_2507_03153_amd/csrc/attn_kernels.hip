@@ -23,7 +23,10 @@ enum Mode { kDense = 0, kGather = 1, kScores = 2, kGatherScored = 3 };   // kGat
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
-constexpr int kUnroll = 4;
+#ifndef HGCA_UNROLL
+#define HGCA_UNROLL 4
+#endif
+constexpr int kUnroll = HGCA_UNROLL;   // 16-byte loads a lane keeps in flight in the K / V passes
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -273,13 +276,19 @@ __device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, f
     load_q_operand<D, G>(a.q, bh0, qb);
 
     const int n_tiles = (nt + 15) / 16;
-    for (int ti = w; ti < n_tiles; ti += kWaves) {
-        uint4 kr[S::kLoads];
+    auto load_tile = [&](int ti, uint4 (&kr)[S::kLoads]) {
 #pragma unroll
         for (int i = 0; i < S::kLoads; ++i) {
             const int j = min(ti * 16 + i * S::kRowsPerLoad + lrow, nt - 1);
             kr[i] = load16_stream(a.kv.k + row_offset<ROW_BYTES>(a.kv, a.sh.n_kv_heads, b, kvh, t0 + j) + 16 * piece);
         }
+    };
+    // the next tile's loads are issued before the current tile goes through LDS and the MFMAs
+    uint4 kr[S::kLoads], kr_next[S::kLoads];
+    if (w < n_tiles) load_tile(w, kr);
+    for (int ti = w; ti < n_tiles; ti += kWaves) {
+        const bool more = ti + kWaves < n_tiles;
+        if (more) load_tile(ti + kWaves, kr_next);
 #pragma unroll
         for (int i = 0; i < S::kLoads; ++i) st[(i * S::kRowsPerLoad + lrow) * S::kRowStride + piece] = kr[i];
         __builtin_amdgcn_wave_barrier();         // same wave writes and reads its stage; LDS keeps wave order
@@ -294,6 +303,10 @@ __device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, f
             const float sc = a.sh.sm_scale;
             *reinterpret_cast<float4 *>(&s_sc[row][ti * 16 + 4 * g]) =
                 make_float4(c[0] * sc, c[1] * sc, c[2] * sc, c[3] * sc);
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < S::kLoads; ++i) kr[i] = kr_next[i];
         }
     }
 }
@@ -365,11 +378,13 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
 
 // ---- combine and merge ------------------------------------------------------------------------------
 
-// Folds the split partials of one (b, h) row: M = max m_s, L = sum l_s e^{m_s-M},
-// O = sum o_s e^{m_s-M} / L, lse = M + ln L.  Thread (sg, c4) sums the splits sg, sg+SG, ... of four
-// adjacent columns; the SG groups are then added through LDS.
-template <int D>
-__global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, float *o, float *lse)
+// Folds split partials of one (b, h) row: M = max m_s, L = sum l_s e^{m_s-M}, O = sum o_s e^{m_s-M} / L,
+// lse = M + ln L.  The splits may come from two partial sets (p and q): folding the splits of the dense
+// window part and of the sparse part in one go is merge_state applied to all of them at once
+// (the fusion is associative).  Thread (sg, c4) sums the splits sg, sg+SG, ... of four adjacent columns;
+// the SG groups are then added through LDS.
+template <int D, bool OUT_BF16>
+__global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse)
 {
     constexpr int C4 = D / 4;                    // threads across the columns (one float4 each)
     constexpr int SG = kBlock / C4;              // split groups
@@ -378,23 +393,25 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, float *o, f
 
     const int64_t row = blockIdx.x;
     const int tid = threadIdx.x, sg = tid / C4, c4 = tid % C4;
-    const float *pm = p.m + row * p.n_splits;
-    const float *pl = p.l + row * p.n_splits;
+    const int np = p.n_splits, n = np + q.n_splits;
+    auto m_of = [&](int s) { return s < np ? p.m[row * np + s] : q.m[row * q.n_splits + (s - np)]; };
+    auto l_of = [&](int s) { return s < np ? p.l[row * np + s] : q.l[row * q.n_splits + (s - np)]; };
+    auto o_of = [&](int s) {
+        const float *base = s < np ? p.o + (row * np + s) * D : q.o + (row * q.n_splits + (s - np)) * D;
+        return *reinterpret_cast<const float4 *>(base + 4 * c4);
+    };
     float M = -INFINITY;
-    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, pm[s]);
-    if (M == -INFINITY) {                        // every split empty (uniform over the workgroup)
-        if (tid < D) o[row * D + tid] = 0.f;
-        if (tid == 0) lse[row] = -INFINITY;
-        return;
-    }
+    for (int s = 0; s < n; ++s) M = fmaxf(M, m_of(s));
     float L = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = sg; s < p.n_splits; s += SG) {
-        const float wgt = expf(pm[s] - M);       // 0 for empty splits (m = -inf)
-        const float4 v = *reinterpret_cast<const float4 *>(p.o + (row * p.n_splits + s) * D + 4 * c4);
-        L = fmaf(pl[s], wgt, L);
-        acc.x = fmaf(v.x, wgt, acc.x); acc.y = fmaf(v.y, wgt, acc.y);
-        acc.z = fmaf(v.z, wgt, acc.z); acc.w = fmaf(v.w, wgt, acc.w);
+    if (M != -INFINITY) {                        // else every split is empty (uniform over the workgroup)
+        for (int s = sg; s < n; s += SG) {
+            const float wgt = expf(m_of(s) - M); // 0 for empty splits (m = -inf)
+            const float4 v = o_of(s);
+            L = fmaf(l_of(s), wgt, L);
+            acc.x = fmaf(v.x, wgt, acc.x); acc.y = fmaf(v.y, wgt, acc.y);
+            acc.z = fmaf(v.z, wgt, acc.z); acc.w = fmaf(v.w, wgt, acc.w);
+        }
     }
     s_acc[sg][c4] = acc;
     if (c4 == 0) s_L[sg] = L;
@@ -408,9 +425,22 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, float *o, f
             t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
             Lt += s_L[g];
         }
-        const float inv = 1.f / Lt;
-        *reinterpret_cast<float4 *>(o + row * D + 4 * tid) = make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
-        if (tid == 0) lse[row] = M + logf(Lt);
+        const float inv = (M != -INFINITY) ? 1.f / Lt : 0.f;
+        const float r[4] = {t.x * inv, t.y * inv, t.z * inv, t.w * inv};
+        if (OUT_BF16) {
+            uint16_t h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t u = __float_as_uint(r[e]);
+                u += 0x7fffu + ((u >> 16) & 1u); // round to nearest even (finite values)
+                h[e] = (uint16_t)(u >> 16);
+            }
+            uint2 packed = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(o) + row * D + 4 * tid) = packed;
+        } else {
+            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(o) + row * D + 4 * tid) = make_float4(r[0], r[1], r[2], r[3]);
+        }
+        if (tid == 0 && lse) lse[row] = (M != -INFINITY) ? M + logf(Lt) : -INFINITY;
     }
 }
 
@@ -547,9 +577,19 @@ hipError_t launch_scores(int dtype, int head_dim, const ScoreArgs &a, hipStream_
 
 hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float *o, float *lse, hipStream_t s)
 {
+    Partials none{};
+    return launch_combine2(head_dim, n_rows, p, none, o, 0, lse, s);
+}
+
+hipError_t launch_combine2(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
+                           float *lse, hipStream_t s)
+{
     if (n_rows == 0) return hipSuccess;
-    if (head_dim == 64) HGCA_LAUNCH((combine_kernel<64>), dim3((unsigned)n_rows), dim3(kBlock), s, p, o, lse);
-    else if (head_dim == 128) HGCA_LAUNCH((combine_kernel<128>), dim3((unsigned)n_rows), dim3(kBlock), s, p, o, lse);
+    const dim3 grid((unsigned)n_rows), block(kBlock);
+    if (head_dim == 64 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<64, false>), grid, block, s, p, q, o, lse);
+    else if (head_dim == 64 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<64, true>), grid, block, s, p, q, o, lse);
+    else if (head_dim == 128 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<128, false>), grid, block, s, p, q, o, lse);
+    else if (head_dim == 128 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<128, true>), grid, block, s, p, q, o, lse);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

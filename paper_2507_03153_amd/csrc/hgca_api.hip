@@ -159,7 +159,8 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     if (rc != HGCA_OK) return rc;
     if (shape->batch == 0) return HGCA_OK;       // nothing to do
     if ((rc = check_view(window, true)) != HGCA_OK) return rc;
-    if (!q || !o_out || !lse_out || !aligned16(q) || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    const bool deferred = !o_out && !lse_out;    // leave the split partials in ws for hgca_lse_merge_splits
+    if (!q || !aligned16(q) || (!deferred && (!o_out || !lse_out || !aligned16(o_out)))) return HGCA_ERR_INVALID_ARG;
     const WsLayout w = layout(shape, window->cap, 0);
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -172,6 +173,7 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     a.part = partials_at(ws, w, n_splits_for(window->cap, a.chunk));
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
+    if (deferred) return HGCA_OK;
     return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
 }
 
@@ -239,7 +241,8 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view 
     if (rc != HGCA_OK) return rc;
     if (shape->batch == 0) return HGCA_OK;
     if ((rc = check_view(pool, true)) != HGCA_OK) return rc;
-    if (!q || !o_out || !lse_out || !aligned16(q) || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    const bool deferred = !o_out && !lse_out;
+    if (!q || !aligned16(q) || (!deferred && (!o_out || !lse_out || !aligned16(o_out)))) return HGCA_ERR_INVALID_ARG;
     if (k_max < 0 || !cnt || (k_max > 0 && !idx)) return HGCA_ERR_INVALID_ARG;
     const WsLayout w = layout(shape, k_max, 0);
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
@@ -257,7 +260,36 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view 
     a.part = partials_at(ws, w, std::max(1, n_splits_for(k_max, a.chunk)));
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
+    if (deferred) return HGCA_OK;
     return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
+}
+
+int hgca_lse_merge_splits(const hgca_shape *shape, int32_t window_cap, const void *ws_dense, size_t ws_dense_bytes,
+                          int32_t k_max, const void *ws_sparse, size_t ws_sparse_bytes, void *o_out, int32_t o_dtype,
+                          float *lse_out, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (o_dtype != HGCA_F32 && o_dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return HGCA_OK;
+    if (window_cap < 0 || k_max < 0 || !o_out || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    // the same layouts and split counts the two deferred calls used
+    Partials pd{}, ps{};
+    if (ws_dense) {
+        const WsLayout w = layout(shape, window_cap, 0);
+        if (ws_dense_bytes < w.total || !aligned16(ws_dense)) return HGCA_ERR_WORKSPACE;
+        const int chunk = pick_chunk(window_cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
+        pd = partials_at(const_cast<void *>(ws_dense), w, n_splits_for(window_cap, chunk));
+    }
+    if (ws_sparse) {
+        const WsLayout w = layout(shape, k_max, 0);
+        if (ws_sparse_bytes < w.total || !aligned16(ws_sparse)) return HGCA_ERR_WORKSPACE;
+        const int chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
+        ps = partials_at(const_cast<void *>(ws_sparse), w, std::max(1, n_splits_for(k_max, chunk)));
+    }
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    return from_hip(launch_combine2(shape->head_dim, rows, pd, ps, o_out, o_dtype, lse_out,
+                                    static_cast<hipStream_t>(hip_stream)));
 }
 
 int hgca_lse_merge(const hgca_shape *shape, const float *o_a, const float *lse_a, const float *o_b,

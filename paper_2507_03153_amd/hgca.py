@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, -1, -2, -3,
 _LIB_PATH = os.environ.get("HGCA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhgca.so")
 
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
-           "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge")
+           "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge")
 
 
 class Shape(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_select_salient.argtypes = [ps, vp, pk, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         L.hgca_sparse_attn.restype = ctypes.c_int
         L.hgca_sparse_attn.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.hgca_lse_merge_splits.restype = ctypes.c_int
+        L.hgca_lse_merge_splits.argtypes = [ps, i32, vp, sz, i32, vp, sz, vp, i32, vp, vp]
         L.hgca_lse_merge.restype = ctypes.c_int
         L.hgca_lse_merge.argtypes = [ps, vp, vp, vp, vp, vp, i32, vp, vp]
         _lib = L
@@ -144,7 +146,8 @@ def alloc_workspace(shape: Shape, max_window: int, max_pool: int, k_max: int, de
 
 
 def dense_window_attn(shape: Shape, q, window: Tier, o_out, lse_out, ws, stream=None) -> None:
-    for t in (q, o_out, lse_out, ws):
+    """o_out = lse_out = None defers the result: the split partials stay in ws for lse_merge_splits."""
+    for t in (q, ws) + (() if o_out is None else (o_out, lse_out)):
         _require_gpu(t)
     kv = window.view()
     _check(lib().hgca_dense_window_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out), _ptr(lse_out),
@@ -179,12 +182,24 @@ def select_salient(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out,
 def sparse_attn(shape: Shape, q, pool: Tier, idx, cnt, k_max: int, o_out, lse_out, ws, stream=None,
                 sel_scores=None) -> None:
     """sel_scores: scores of the listed entries for this q (from select_salient); K is then not re-read."""
-    for t in (q, idx, cnt, o_out, lse_out, ws) + (() if sel_scores is None else (sel_scores,)):
+    for t in (q, idx, cnt, ws) + (() if sel_scores is None else (sel_scores,)) + \
+            (() if o_out is None else (o_out, lse_out)):
         _require_gpu(t)
     kv = pool.view()
     _check(lib().hgca_sparse_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
                                   _ptr(sel_scores), _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
            "hgca_sparse_attn")
+
+
+def lse_merge_splits(shape: Shape, window_cap: int, ws_dense, k_max: int, ws_sparse, o_out, lse_out=None,
+                     stream=None) -> None:
+    """Folds the deferred split partials of a dense and a sparse call into the final O (and lse)."""
+    for t in (o_out,) + tuple(x for x in (ws_dense, ws_sparse, lse_out) if x is not None):
+        _require_gpu(t)
+    nb = lambda w: 0 if w is None else w.numel()
+    _check(lib().hgca_lse_merge_splits(ctypes.byref(shape), int(window_cap), _ptr(ws_dense), nb(ws_dense), int(k_max),
+                                       _ptr(ws_sparse), nb(ws_sparse), _ptr(o_out), _dtype_code(o_out),
+                                       _ptr(lse_out), _stream(stream)), "hgca_lse_merge_splits")
 
 
 def lse_merge(shape: Shape, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None) -> None:

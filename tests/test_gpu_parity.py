@@ -149,6 +149,22 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
         o_h, l_h, _, _ = oracle.hybrid_step(L.q, tw, tp, L.k, L.k_max, L.scale)
         # an entry swapped inside the tie band changes O by at most its softmax weight times |dv|
         assert_partial("hybrid", step.o, step.lse, o_h, l_h, tol if n_band else min(tol, tight))
+
+        say("  whole step, results deferred and all splits folded by lse_merge_splits")
+        fused = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max, fused_tail=True)
+        fused.o.fill_(float("nan"))
+        fused.lse.fill_(float("nan"))
+        fused.run(D, select=True)
+        torch.cuda.synchronize()
+        assert_partial("hybrid, fused tail", fused.o, fused.lse, o_h, l_h, tol if n_band else min(tol, tight))
+        assert torch.equal(fused.idx, step.idx)
+        if fused.o.numel():
+            finite = torch.isfinite(step.lse)
+            assert float((fused.o - step.o).abs().max()) <= 2e-6
+            assert float((fused.lse[finite] - step.lse[finite]).abs().max()) <= 4e-6 if finite.any() else True
+        fused.run(D, select=False)                             # reused selection: K and V gathered
+        torch.cuda.synchronize()
+        assert_partial("steady, fused tail", fused.o, fused.lse, o_h, l_h, tol if n_band else min(tol, tight))
     return step, D, L
 
 
@@ -284,6 +300,33 @@ def test_merge_alone_in_place_and_bf16_output(gpu, oracle):
     assert err16 <= 2e-2
     # bf16 output is the round-to-nearest-even of the fp32 result
     assert torch.equal(out16, da.to(torch.bfloat16))
+
+
+def test_merge_splits_bf16_output_and_one_sided(gpu, oracle):
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=900, P=2000, k=300)
+    L = wl.make_layer(cfg)
+    D = runner.DeviceLayer.upload(L)
+    say("\n[case] lse_merge_splits: bf16 output, one-sided folds")
+    f32 = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max, fused_tail=True)
+    b16 = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max, fused_tail=True, out_dtype=torch.bfloat16)
+    f32.run(D)
+    b16.run(D)
+    torch.cuda.synchronize()
+    assert torch.equal(b16.o, f32.o.to(torch.bfloat16))       # round-to-nearest-even of the fp32 result
+    assert torch.equal(b16.lse, f32.lse)
+    # dense part alone and sparse part alone through the same fold
+    o, lse = torch.empty_like(f32.o), torch.empty_like(f32.lse)
+    hgca.lse_merge_splits(D.shape, L.window.cap, f32.ws_dense, 0, None, o, lse)
+    torch.cuda.synchronize()
+    o_ref, l_ref = oracle.attend_all(L.q, otier(oracle, L.window), L.scale)
+    assert_partial("dense via merge_splits", o, lse, o_ref, l_ref, TIGHT["bf16"])
+    hgca.lse_merge_splits(D.shape, 0, None, L.k_max, f32.ws_sparse, o, None)
+    std = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max)   # the sparse part folded by its own call
+    std.run(D)
+    torch.cuda.synchronize()
+    assert torch.equal(std.idx, f32.idx)
+    assert float((o - std.o_s).abs().max()) <= 2e-6
 
 
 def test_repeated_runs_are_bitwise_identical(gpu, oracle):
