@@ -181,11 +181,19 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
         return;
     }
     const int nt = min(a.chunk, n - t0);         // 1 .. chunk tokens in this split
-    const int32_t *idx_row = GATHER ? a.idx + bh0 * a.k_max + t0 : nullptr;
-
-    if (MODE == kGatherScored) {                 // the caller already holds the scores of the listed entries
-        const float *given = a.sel_scores + bh0 * a.k_max + t0;
-        for (int j = tid; j < nt; j += kBlock) s_p[0][j] = given[j];
+    // gather: the split's index list is read once, coalesced, so that the row loads of the K and V
+    // passes do not each wait for an index load first
+    __shared__ int32_t s_idx[GATHER ? kMaxChunk : 1];
+    const int32_t *idx_row = nullptr;
+    if (GATHER) {
+        const int32_t *listed = a.idx + bh0 * a.k_max + t0;
+        for (int j = tid; j < nt; j += kBlock) s_idx[j] = listed[j];
+        if (MODE == kGatherScored) {             // the caller already holds the scores of the listed entries
+            const float *given = a.sel_scores + bh0 * a.k_max + t0;
+            for (int j = tid; j < nt; j += kBlock) s_p[0][j] = given[j];
+        }
+        __syncthreads();
+        idx_row = s_idx;
     }
     float qf[NH][EPL];
     if (MODE != kGatherScored) {
