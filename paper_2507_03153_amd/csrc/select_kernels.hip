@@ -102,8 +102,9 @@ __device__ __forceinline__ void locate_rank(SelShared &sh, int nb, uint32_t k_re
 
 struct Binning {
     float lo, inv_w;
+    __device__ __forceinline__ float scaled(float s) const { return (s - lo) * inv_w; }
     __device__ __forceinline__ int operator()(float s) const {   // -inf (padding) and NaN land in bin 0
-        return max(0, min(kBins - 1, (int)((s - lo) * inv_w)));
+        return max(0, min(kBins - 1, (int)scaled(s)));
     }
 };
 
@@ -213,21 +214,23 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     __syncthreads();
 
     // ---- pass 2: count the entries above the threshold bin, collect those inside it ---------------------
+    // bin(s) > tb and bin(s) == tb are decided on the scaled score itself (two float compares against
+    // the bin's edges give the same answer as the truncation and clamps of the histogram pass; the
+    // topmost bin has no upper edge, padding and NaN fail both compares)
+    const float edge_lo = (float)tb, edge_hi = (tb == kBins - 1) ? INFINITY : (float)(tb + 1);
     uint32_t above = 0;
-#pragma unroll 2
     for (int i = 0; i < steps; ++i) {
         const int t = row.pos(i);
         const float4 v = row.at(t);
         const float s[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int bn = bin(s[e]);
-            above += bn > tb;
-            if (bn == tb) {
-                if (t + e < n) {                 // padding shares bin 0 with the lowest scores
-                    const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
-                    if (slot < (uint32_t)kMaxCand) { sh.cand_score[slot] = s[e]; sh.cand_idx[slot] = t + e; }
-                }
+            const float x = bin.scaled(s[e]);
+            const bool over = x >= edge_hi;
+            above += over;
+            if (x >= edge_lo && !over) {
+                const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
+                if (slot < (uint32_t)kMaxCand) { sh.cand_score[slot] = s[e]; sh.cand_idx[slot] = t + e; }
             }
         }
     }
@@ -314,10 +317,39 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     const bool staged = k <= kBins;
     int32_t *dst = staged ? reinterpret_cast<int32_t *>(sh.hist) : out;
     float *sel = a.sel_scores ? a.sel_scores + (int64_t)blockIdx.x * a.k_max : nullptr;
-    uint32_t run_gt = 0, run_eq = 0;             // kept / tied entries before the wave's current step
-    for (int i = 0; i < w; ++i) { run_gt += sh.wave_gt[i]; run_eq += sh.wave_eq[i]; }
+    uint32_t run_gt = 0, run_eq = 0, all_eq = 0; // kept / tied entries before the wave's current step
+    for (int i = 0; i < kSelWaves; ++i) {
+        if (i < w) { run_gt += sh.wave_gt[i]; run_eq += sh.wave_eq[i]; }
+        all_eq += sh.wave_eq[i];
+    }
     const bool pad_ties = thr == -INFINITY;      // only then could padding tie with the threshold
-#pragma unroll 2
+    if (need_eq == all_eq && !pad_ties) {
+        // Usual case: no tie is cut by the budget, so an entry is kept iff its score is >= T, and one
+        // lane mask per score gives its place.
+        uint32_t run = run_gt + run_eq;
+        for (int i = 0; i < steps; ++i) {
+            const int t = row.pos(i);
+            const float4 v = row.at(t);
+            const float s[4] = {v.x, v.y, v.z, v.w};
+            bool keep[4];
+            uint32_t before = run;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                keep[e] = s[e] >= thr;
+                const unsigned long long m = __ballot(keep[e]);
+                before += lanes_below(m);
+                run += __popcll(m);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (keep[e]) {
+                    dst[before] = t + e;
+                    if (sel) sel[before] = s[e];
+                }
+                before += keep[e];
+            }
+        }
+    } else
     for (int i = 0; i < steps; ++i) {
         const int t = row.pos(i);
         const float4 v = row.at(t);
