@@ -38,6 +38,18 @@ METRIC = "hybrid decode-attn layer-steps/s + achieved HBM GB/s vs peak (8B shape
 MEASURED_TRAFFIC_BYTES = None
 
 
+WORKLOADS = {
+    "C2": "C2: Llama-3-8B-like layer, bf16, B=8, Hq=32, Hkv=8, d=128, ctx 32768 (window 4096 + pool 28672), "
+          "per-head top-k 2048",
+    "C3": "C3: OPT-13B-like MHA layer, bf16, B=32, Hq=Hkv=40, d=128, ctx 16384 (window 2048 + pool 14336), "
+          "per-head top-k 1024",
+    "C4": "C4: Llama-3-70B-like layer, bf16, B=4, Hq=64, Hkv=8, d=128, ctx 131072 (window 8192 + pool 122880), "
+          "per-head top-k 4096",
+    "C5": "C5: ragged large batch, bf16, B=64, Hq=32, Hkv=8, d=128, lengths U[2048,16384], window 2048, "
+          "top-k 10 % of the pool, both tiers in 16-token pages",
+}
+
+
 def log(msg: str) -> None:
     print(msg, file=sys.stderr, flush=True)
 
@@ -48,6 +60,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layers", type=int, default=4, help="independent KV draws cycled through")
+    ap.add_argument("--config", default="C2", choices=("C2", "C3", "C4", "C5"),
+                    help="workload; C2 is the one the metric is quoted on (the others are for comparison)")
     ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
                     help="2: the dense window part runs on a second stream beside select+sparse")
     ap.add_argument("--four-calls", action="store_true",
@@ -73,20 +87,22 @@ def main() -> int:
     if args.copy_calibration:
         return copy_calibration(torch, dev)
 
-    cfg = wl.CONFIGS["C2"]
+    cfg = wl.CONFIGS[args.config]
     w_lens, p_lens, k = wl.seq_lengths(cfg)
     nbytes = wl.step_bytes(cfg, w_lens, p_lens, k)
-    k_gather = nbytes["sparse"] - 4 * cfg.B * cfg.Hq * cfg.k    # K+V rows of the kept entries
+    k_sum = int(np.minimum(np.full(cfg.B, k) if np.isscalar(k) else k, p_lens).sum())   # kept entries per head
+    k_gather = nbytes["sparse"] - 4 * cfg.Hq * k_sum            # K+V rows of the kept entries
     pass_scores = not args.no_pass_scores
     moved_full = nbytes["full"] - (k_gather // 2 if pass_scores else 0)
 
     t0 = time.time()
     host_layers = [wl.make_layer(cfg, layer) for layer in range(args.layers)]
     layers = [runner.DeviceLayer.upload(L, dev) for L in host_layers]
-    log(f"[bench] {args.layers} layers of C2 generated and uploaded in {time.time() - t0:.1f}s "
+    log(f"[bench] {args.layers} layers of {cfg.name} generated and uploaded in {time.time() - t0:.1f}s "
         f"({sum(L.kv_bytes() for L in host_layers) / 2**30:.2f} GiB of KV)")
     main_stream = torch.cuda.current_stream()
-    steps_by_tail = {fused: runner.HybridStep(layers[0].shape, cfg.W, cfg.P, cfg.k, dev,
+    k_max = layers[0].k_max
+    steps_by_tail = {fused: runner.HybridStep(layers[0].shape, cfg.W, cfg.P, k_max, dev,
                                               two_streams=(args.streams == 2), pass_scores=pass_scores,
                                               fused_tail=fused) for fused in (True, False)}
     prepared_by_tail = {fused: [st.prepare(L) for L in layers] for fused, st in steps_by_tail.items()}
@@ -136,17 +152,17 @@ def main() -> int:
     calls = {
         "dense_window_attn": lambda L: hgca.dense_window_attn(sh, L.q, L.window, step.o_w, step.lse_w, step.ws_dense),
         "pool_scores": lambda L: hgca.pool_scores(sh, L.q, L.pool, scores_buf),
-        "select_salient": lambda L: hgca.select_salient(sh, L.q, L.pool, L.k, cfg.k, step.idx, step.cnt,
+        "select_salient": lambda L: hgca.select_salient(sh, L.q, L.pool, L.k, k_max, step.idx, step.cnt,
                                                         step.ws_sparse, sel_scores_out=step.sel_scores),
-        "sparse_attn": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, cfg.k, step.o_s, step.lse_s,
+        "sparse_attn": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, k_max, step.o_s, step.lse_s,
                                                   step.ws_sparse),
-        "sparse_attn_given_scores": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, cfg.k, step.o_s,
+        "sparse_attn_given_scores": lambda L: hgca.sparse_attn(sh, L.q, L.pool, step.idx, step.cnt, k_max, step.o_s,
                                                                step.lse_s, step.ws_sparse,
                                                                sel_scores=step.sel_scores),
         "lse_merge": lambda L: hgca.lse_merge(sh, step.o_s, step.lse_s, step.o_w, step.lse_w, step.o, step.lse),
     }
     call_ms = {name: time_call(fn) for name, fn in calls.items()}
-    call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": cfg.B * cfg.Hkv * cfg.P * cfg.d * 2,
+    call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": int(p_lens.sum()) * cfg.Hkv * cfg.d * cfg.elem_bytes,
                   "select_salient": nbytes["select"], "sparse_attn": nbytes["sparse"],
                   "sparse_attn_given_scores": nbytes["sparse"] - k_gather // 2}
     call_gbps = {n: call_bytes[n] / (call_ms[n] * 1e-3) / 1e9 for n in call_bytes}
@@ -169,9 +185,8 @@ def main() -> int:
         "metric": METRIC, "value": 1e3 / ms_per_step, "unit": "layer-steps/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "C2: Llama-3-8B-like layer, bf16, B=8, Hq=32, Hkv=8, d=128, ctx 32768 "
-                               "(window 4096 + pool 28672), per-head top-k 2048; full step = dense + select + "
-                               "sparse + merge", "layers_cycled": args.layers, "streams": args.streams,
+        "config": {"workload": WORKLOADS[args.config] + "; full step = dense + select + sparse + merge",
+                   "layers_cycled": args.layers, "streams": args.streams,
                    "select_passes_scores_to_sparse": pass_scores,
                    "tail": "hgca_lse_merge_splits over deferred results" if head else
                            "per-part outputs + hgca_lse_merge"},
@@ -212,12 +227,13 @@ def copy_calibration(torch, dev) -> int:
 
 
 def cpu_baseline(L, target_s: float) -> dict:
-    """The fp64 oracle as it stands, timed on this machine's host cores: whole C2 layer-steps (dense, select,
-    sparse, merge for all 8 sequences and 32 heads) repeated until about `target_s` seconds have gone."""
+    """The fp64 oracle as it stands, timed on this machine's host cores: whole layer-steps of the workload
+    (dense, select, sparse, merge for all sequences and heads) repeated until about `target_s` seconds
+    have gone."""
     import oracle
 
     def tier(t):
-        return oracle.Tier(t.k, t.v, t.cap)
+        return oracle.Tier(t.k, t.v, t.cap, t.seq_lens, t.block_table, t.block_size)
 
     def one_step():
         t0 = time.perf_counter()
@@ -229,7 +245,7 @@ def cpu_baseline(L, target_s: float) -> dict:
         times.append(one_step())
     mean = sum(times) / len(times)
     return {"value": 1.0 / mean, "unit": "layer-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{len(times)} whole C2 layer-steps on layer 0 ({sum(times):.1f}s of fp64 oracle time, "
+            "sample": f"{len(times)} whole {L.cfg.name} layer-steps on layer 0 ({sum(times):.1f}s of fp64 oracle time, "
                       f"OpenMP over (batch, head))"}
 
 

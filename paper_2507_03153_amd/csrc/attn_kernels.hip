@@ -343,11 +343,9 @@ __global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
         const int g = i / n4, j = 4 * (i % n4);
         const float4 v = *reinterpret_cast<const float4 *>(&s_sc[g][j]);
         float *o = out + g * cap + j;
-        if (vec_ok && j + 3 < nt) {
-            __builtin_nontemporal_store(v.x, o);
-            __builtin_nontemporal_store(v.y, o + 1);
-            __builtin_nontemporal_store(v.z, o + 2);
-            __builtin_nontemporal_store(v.w, o + 3);
+        if (vec_ok && j + 3 < nt) {              // one 16-byte streaming store
+            const floatx4 vv = {v.x, v.y, v.z, v.w};
+            __builtin_nontemporal_store(vv, reinterpret_cast<floatx4 *>(o));
         } else {
             if (j < nt) o[0] = v.x;
             if (j + 1 < nt) o[1] = v.y;
