@@ -270,7 +270,7 @@ template <int D> struct Stage {
 
 // Scaled scores of tokens [t0, t0+nt) of (b, kvh) for the G heads of the group, written to
 // s_sc[n][j] (n < G, j < nt rounded up to 16; entries at j >= nt are finite filler).
-template <int D, int G, int LD>
+template <int D, int G, int LD, int NW = kWaves>
 __device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, float (*s_sc)[LD], int b,
                                             int kvh, int64_t bh0, int t0, int nt)
 {
@@ -294,9 +294,9 @@ __device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, f
     // the next tile's loads are issued before the current tile goes through LDS and the MFMAs
     uint4 kr[S::kLoads], kr_next[S::kLoads];
     if (w < n_tiles) load_tile(w, kr);
-    for (int ti = w; ti < n_tiles; ti += kWaves) {
-        const bool more = ti + kWaves < n_tiles;
-        if (more) load_tile(ti + kWaves, kr_next);
+    for (int ti = w; ti < n_tiles; ti += NW) {
+        const bool more = ti + NW < n_tiles;
+        if (more) load_tile(ti + NW, kr_next);
 #pragma unroll
         for (int i = 0; i < S::kLoads; ++i) st[(i * S::kRowsPerLoad + lrow) * S::kRowStride + piece] = kr[i];
         __builtin_amdgcn_wave_barrier();         // same wave writes and reads its stage; LDS keeps wave order
@@ -319,10 +319,16 @@ __device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, f
     }
 }
 
+#ifndef HGCA_SCORE_WAVES
+#define HGCA_SCORE_WAVES 4
+#endif
+constexpr int kScoreWaves = HGCA_SCORE_WAVES;    // waves per workgroup of the score pass
+constexpr int kScoreBlock = kScoreWaves * kWave;
+
 template <int D, int G>
-__global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
+__global__ __launch_bounds__(kScoreBlock) void pool_scores_mfma_kernel(KernelArgs a)
 {
-    __shared__ uint4 s_stage[kWaves * Stage<D>::kWaveVecs];
+    __shared__ uint4 s_stage[kScoreWaves * Stage<D>::kWaveVecs];
     __shared__ __attribute__((aligned(16))) float s_sc[G][kMaxScoreChunk];
 
     const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -331,7 +337,7 @@ __global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
     if (t0 >= n) return;
     const int nt = min(a.chunk, n - t0);
     const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
-    mfma_scores<D, G, kMaxScoreChunk>(a, s_stage, s_sc, b, kvh, bh0, t0, nt);
+    mfma_scores<D, G, kMaxScoreChunk, kScoreWaves>(a, s_stage, s_sc, b, kvh, bh0, t0, nt);
     __syncthreads();
 
     // coalesced streaming stores, 16 bytes per lane where the row alignment allows it
@@ -339,7 +345,7 @@ __global__ __launch_bounds__(kBlock) void pool_scores_mfma_kernel(KernelArgs a)
     float *out = a.scores + bh0 * cap + t0;
     const bool vec_ok = (cap % 4) == 0;
     const int n4 = (nt + 3) / 4;
-    for (int i = threadIdx.x; i < G * n4; i += kBlock) {
+    for (int i = threadIdx.x; i < G * n4; i += kScoreBlock) {
         const int g = i / n4, j = 4 * (i % n4);
         const float4 v = *reinterpret_cast<const float4 *>(&s_sc[g][j]);
         float *o = out + g * cap + j;
@@ -503,7 +509,7 @@ hipError_t launch_mfma_group(const KernelArgs &ka, int g, dim3 grid, hipStream_t
 {
 #define HGCA_MFMA_CASE(G)                                                                           \
     case G:                                                                                         \
-        if (MODE == kScores) HGCA_LAUNCH((pool_scores_mfma_kernel<D, G>), grid, dim3(kBlock), s, ka); \
+        if (MODE == kScores) HGCA_LAUNCH((pool_scores_mfma_kernel<D, G>), grid, dim3(kScoreBlock), s, ka); \
         else HGCA_LAUNCH((dense_attn_mfma_kernel<D, G>), grid, dim3(kBlock), s, ka);                \
         break;
     switch (g) {
