@@ -46,6 +46,45 @@ struct KernelArgs {
 
 // ---- pieces shared by all split kernels ---------------------------------------------------
 
+// Where the rows of a split live: the number of the [d] row (counted over the whole K or V buffer of
+// the tier) of the split's j-th token.  A dense split of a contiguous tier is plain arithmetic; paged
+// tiers and index lists get a table in LDS, filled once per workgroup, so that neither the block table
+// nor the index list is in the dependency chain of every row load of the K and V passes.
+struct RowMap {
+    const uint32_t *table;   // LDS; nullptr => row = base + j
+    uint32_t base;
+    __device__ __forceinline__ uint32_t operator()(int j) const { return table ? table[j] : base + (uint32_t)j; }
+};
+
+// `listed` (gather only) points at the split's first index.  Contains a barrier iff a table is filled;
+// the condition is uniform over the workgroup.
+template <bool GATHER, int BLOCK>
+__device__ __forceinline__ RowMap make_row_map(uint32_t *s_row, const KvDev &kv, int n_kv_heads, int b, int kvh,
+                                               int t0, int nt, const int32_t *listed)
+{
+    RowMap m;
+    if (!GATHER && kv.block_table == nullptr) {
+        m.table = nullptr;
+        m.base = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + t0);
+        return m;
+    }
+    for (int j = threadIdx.x; j < nt; j += BLOCK) {
+        const int32_t tok = GATHER ? listed[j] : t0 + j;
+        uint32_t row;
+        if (kv.block_table) {
+            const int32_t blk = kv.block_table[(int64_t)b * kv.max_blocks + tok / kv.block_size];
+            row = (uint32_t)(((int64_t)blk * n_kv_heads + kvh) * kv.block_size + tok % kv.block_size);
+        } else {
+            row = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + tok);
+        }
+        s_row[j] = row;
+    }
+    __syncthreads();
+    m.table = s_row;
+    m.base = 0;
+    return m;
+}
+
 template <int D, int NH>
 __device__ __forceinline__ void write_empty_partial(const Partials &part, int64_t bh0, int split)
 {
@@ -83,17 +122,15 @@ __device__ __forceinline__ void split_softmax(float (*s_p)[kMaxChunk], float *s_
 template <typename T, int D, int NH, bool GATHER>
 __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[kMaxChunk],
                                            float (*s_red)[NH][D], const float *s_m, const float *s_l,
-                                           int b, int kvh, int64_t bh0, int split, int t0, int nt,
-                                           const int32_t *idx_row)
+                                           int64_t bh0, int split, int nt, const RowMap &rows)
 {
     constexpr int EPL = Elem<T>::kPerLoad;       // elements per lane per load
     constexpr int LPR = D / EPL;                 // lanes per row
     constexpr int RPW = kWave / LPR;             // rows per wave per load
     constexpr int RPI = kWaves * RPW;            // rows per workgroup iteration
-    constexpr int ROW_BYTES = D * (int)sizeof(T);
+    constexpr size_t ROW_BYTES = D * sizeof(T);
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
     const int r = lane / LPR, c = lane % LPR;
-    const int Hkv = a.sh.n_kv_heads;
 
     float acc[NH][EPL];
 #pragma unroll
@@ -106,8 +143,7 @@ __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[kMa
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int j = min(base + u * RPI + w * RPW + r, nt - 1);
-            const int32_t tok = GATHER ? idx_row[j] : t0 + j;
-            vr[u] = load16_stream(a.kv.v + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
+            vr[u] = load16_stream(a.kv.v + rows(j) * ROW_BYTES + c * 16);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -158,9 +194,10 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
     constexpr int LPR = D / EPL;
     constexpr int RPW = kWave / LPR;
     constexpr int RPI = kWaves * RPW;
-    constexpr int ROW_BYTES = D * (int)sizeof(T);
+    constexpr size_t ROW_BYTES = D * sizeof(T);
 
     __shared__ float s_p[NH][kMaxChunk];         // scores of the split, then weights
+    __shared__ uint32_t s_row[kMaxChunk];
     __shared__ float s_red[kWaves][NH][D];
     __shared__ float s_m[NH], s_l[NH];
 
@@ -181,20 +218,12 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
         return;
     }
     const int nt = min(a.chunk, n - t0);         // 1 .. chunk tokens in this split
-    // gather: the split's index list is read once, coalesced, so that the row loads of the K and V
-    // passes do not each wait for an index load first
-    __shared__ int32_t s_idx[GATHER ? kMaxChunk : 1];
-    const int32_t *idx_row = nullptr;
-    if (GATHER) {
-        const int32_t *listed = a.idx + bh0 * a.k_max + t0;
-        for (int j = tid; j < nt; j += kBlock) s_idx[j] = listed[j];
-        if (MODE == kGatherScored) {             // the caller already holds the scores of the listed entries
-            const float *given = a.sel_scores + bh0 * a.k_max + t0;
-            for (int j = tid; j < nt; j += kBlock) s_p[0][j] = given[j];
-        }
-        __syncthreads();
-        idx_row = s_idx;
+    if (MODE == kGatherScored) {                 // the caller already holds the scores of the listed entries
+        const float *given = a.sel_scores + bh0 * a.k_max + t0;
+        for (int j = tid; j < nt; j += kBlock) s_p[0][j] = given[j];
     }
+    const RowMap rows = make_row_map<GATHER, kBlock>(s_row, a.kv, Hkv, b, kvh, t0, nt,
+                                                     GATHER ? a.idx + bh0 * a.k_max + t0 : nullptr);
     float qf[NH][EPL];
     if (MODE != kGatherScored) {
 #pragma unroll
@@ -208,8 +237,7 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int j = min(base + u * RPI + w * RPW + r, nt - 1);
-            const int32_t tok = GATHER ? idx_row[j] : t0 + j;
-            kr[u] = load16_stream(a.kv.k + row_offset<ROW_BYTES>(a.kv, Hkv, b, kvh, tok) + c * 16);
+            kr[u] = load16_stream(a.kv.k + rows(j) * ROW_BYTES + c * 16);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -238,7 +266,7 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 
     split_softmax<NH>(s_p, s_m, s_l, nt);
     __syncthreads();
-    value_pass<T, D, NH, GATHER>(a, s_p, s_red, s_m, s_l, b, kvh, bh0, split, t0, nt, idx_row);
+    value_pass<T, D, NH, GATHER>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows);
 }
 
 // ---- MFMA path (bf16 K/V, dense over a tier) -------------------------------------------------
@@ -271,11 +299,11 @@ template <int D> struct Stage {
 // Scaled scores of tokens [t0, t0+nt) of (b, kvh) for the G heads of the group, written to
 // s_sc[n][j] (n < G, j < nt rounded up to 16; entries at j >= nt are finite filler).
 template <int D, int G, int LD, int NW = kWaves>
-__device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, float (*s_sc)[LD], int b,
-                                            int kvh, int64_t bh0, int t0, int nt)
+__device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, float (*s_sc)[LD], int64_t bh0,
+                                            int nt, const RowMap &rows)
 {
     using S = Stage<D>;
-    constexpr int ROW_BYTES = D * 2;
+    constexpr size_t ROW_BYTES = D * 2;
     const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int lrow = lane / S::kPieces, piece = lane % S::kPieces;   // role while loading
     const int row = lane % 16, g = lane / 16;                        // role as A operand / C result
@@ -288,7 +316,7 @@ __device__ __forceinline__ void mfma_scores(const KernelArgs &a, uint4 *stage, f
 #pragma unroll
         for (int i = 0; i < S::kLoads; ++i) {
             const int j = min(ti * 16 + i * S::kRowsPerLoad + lrow, nt - 1);
-            kr[i] = load16_stream(a.kv.k + row_offset<ROW_BYTES>(a.kv, a.sh.n_kv_heads, b, kvh, t0 + j) + 16 * piece);
+            kr[i] = load16_stream(a.kv.k + rows(j) * ROW_BYTES + 16 * piece);
         }
     };
     // the next tile's loads are issued before the current tile goes through LDS and the MFMAs
@@ -330,6 +358,7 @@ __global__ __launch_bounds__(kScoreBlock) void pool_scores_mfma_kernel(KernelArg
 {
     __shared__ uint4 s_stage[kScoreWaves * Stage<D>::kWaveVecs];
     __shared__ __attribute__((aligned(16))) float s_sc[G][kMaxScoreChunk];
+    __shared__ uint32_t s_row[kMaxScoreChunk];
 
     const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int n = tier_len(a.kv, b);
@@ -337,7 +366,8 @@ __global__ __launch_bounds__(kScoreBlock) void pool_scores_mfma_kernel(KernelArg
     if (t0 >= n) return;
     const int nt = min(a.chunk, n - t0);
     const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
-    mfma_scores<D, G, kMaxScoreChunk, kScoreWaves>(a, s_stage, s_sc, b, kvh, bh0, t0, nt);
+    const RowMap rows = make_row_map<false, kScoreBlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nt, nullptr);
+    mfma_scores<D, G, kMaxScoreChunk, kScoreWaves>(a, s_stage, s_sc, bh0, nt, rows);
     __syncthreads();
 
     // coalesced streaming stores, 16 bytes per lane where the row alignment allows it
@@ -370,6 +400,7 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
     __shared__ __attribute__((aligned(16))) char s_buf[kStageBytes > kRedBytes ? kStageBytes : kRedBytes];
     __shared__ __attribute__((aligned(16))) float s_p[G][kMaxChunk];
     __shared__ float s_m[G], s_l[G];
+    __shared__ uint32_t s_row[kMaxChunk];
 
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
@@ -380,12 +411,12 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
         return;
     }
     const int nt = min(a.chunk, n - t0);
-    mfma_scores<D, G, kMaxChunk>(a, reinterpret_cast<uint4 *>(s_buf), s_p, b, kvh, bh0, t0, nt);
+    const RowMap rows = make_row_map<false, kBlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nt, nullptr);
+    mfma_scores<D, G, kMaxChunk>(a, reinterpret_cast<uint4 *>(s_buf), s_p, bh0, nt, rows);
     __syncthreads();
     split_softmax<G>(s_p, s_m, s_l, nt);
     __syncthreads();
-    value_pass<bf16_t, D, G, false>(a, s_p, reinterpret_cast<float (*)[G][D]>(s_buf), s_m, s_l, b, kvh, bh0, split,
-                                    t0, nt, nullptr);
+    value_pass<bf16_t, D, G, false>(a, s_p, reinterpret_cast<float (*)[G][D]>(s_buf), s_m, s_l, bh0, split, nt, rows);
 }
 
 // ---- combine and merge ------------------------------------------------------------------------------

@@ -48,17 +48,6 @@ __device__ __forceinline__ int32_t tier_len(const KvDev &kv, int b) {
     return kv.seq_lens ? min(max(kv.seq_lens[b], 0), kv.cap) : kv.cap;   // never beyond the buffer
 }
 
-// Byte offset of row (b, kvh, t) inside a tier's k or v buffer.
-template <int kRowBytes>
-__device__ __forceinline__ size_t row_offset(const KvDev &kv, int n_kv_heads, int b, int kvh, int32_t t) {
-    if (kv.block_table) {
-        const int32_t blk = kv.block_table[(size_t)b * kv.max_blocks + t / kv.block_size];
-        const int32_t slot = t % kv.block_size;
-        return (((size_t)blk * n_kv_heads + kvh) * kv.block_size + slot) * kRowBytes;
-    }
-    return (((size_t)b * n_kv_heads + kvh) * kv.cap + t) * kRowBytes;
-}
-
 __device__ __forceinline__ uint4 load16(const char *p) {
     return *reinterpret_cast<const uint4 *>(p);
 }
