@@ -27,7 +27,8 @@
  *    physical block block_table[b * max_blocks + t / block_size], slot
  *    t % block_size.  Valid tokens of sequence b are [0, seq_lens[b]) (all `cap`
  *    when seq_lens is NULL).  The order of tokens inside a tier does not matter
- *    to the result (softmax attention is a function of the key set).
+ *    to the result (softmax attention is a function of the key set).  A tier
+ *    holds fewer than 2^32 rows (B*Hkv*cap, or n_blocks*Hkv*block_size).
  *  - Scores are s_j = sm_scale * <q, k_j>; lse is the natural log of sum e^{s_j}.
  *  - Partial outputs are fp32: O [B, Hq, d], lse [B, Hq].  An empty set gives
  *    O = 0 and lse = -inf.

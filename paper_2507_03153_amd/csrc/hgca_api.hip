@@ -44,10 +44,12 @@ int check_shape(const hgca_shape *s)
     return HGCA_OK;
 }
 
-int check_view(const hgca_kv_view *v, bool need_v)
+int check_view(const hgca_shape *s, const hgca_kv_view *v, bool need_v)
 {
     if (!v) return HGCA_ERR_INVALID_ARG;
     if (v->cap < 0) return HGCA_ERR_INVALID_ARG;
+    // rows of a tier are numbered with 32 bits inside the kernels
+    if (!v->block_table && (int64_t)s->batch * s->n_kv_heads * v->cap >= (int64_t(1) << 32)) return HGCA_ERR_UNSUPPORTED;
     if (v->cap > 0) {
         if (!v->k || !aligned16(v->k)) return HGCA_ERR_INVALID_ARG;
         if (need_v && (!v->v || !aligned16(v->v))) return HGCA_ERR_INVALID_ARG;
@@ -158,7 +160,7 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
     if (shape->batch == 0) return HGCA_OK;       // nothing to do
-    if ((rc = check_view(window, true)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, window, true)) != HGCA_OK) return rc;
     const bool deferred = !o_out && !lse_out;    // leave the split partials in ws for hgca_lse_merge_splits
     if (!q || !aligned16(q) || (!deferred && (!o_out || !lse_out || !aligned16(o_out)))) return HGCA_ERR_INVALID_ARG;
     const WsLayout w = layout(shape, window->cap, 0);
@@ -183,7 +185,7 @@ int hgca_pool_scores(const hgca_shape *shape, const void *q, const hgca_kv_view 
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
     if (shape->batch == 0) return HGCA_OK;
-    if ((rc = check_view(pool, false)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, pool, false)) != HGCA_OK) return rc;
     if (!q || !aligned16(q) || (pool->cap > 0 && (!scores_out || !aligned16(scores_out)))) return HGCA_ERR_INVALID_ARG;
     ScoreArgs sa{};
     sa.sh = to_dev(shape);
@@ -203,7 +205,7 @@ int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_vi
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
     if (shape->batch == 0) return HGCA_OK;
-    if ((rc = check_view(pool, false)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, pool, false)) != HGCA_OK) return rc;
     if (!q || !aligned16(q) || !cnt_out || k_max < 0 || (k_max > 0 && !idx_out)) return HGCA_ERR_INVALID_ARG;
     if (!k_per_seq && (k_uniform < 0 || std::min(k_uniform, pool->cap) > k_max)) return HGCA_ERR_INVALID_ARG;
     const WsLayout w = layout(shape, 0, pool->cap);
@@ -240,7 +242,7 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view 
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
     if (shape->batch == 0) return HGCA_OK;
-    if ((rc = check_view(pool, true)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, pool, true)) != HGCA_OK) return rc;
     const bool deferred = !o_out && !lse_out;
     if (!q || !aligned16(q) || (!deferred && (!o_out || !lse_out || !aligned16(o_out)))) return HGCA_ERR_INVALID_ARG;
     if (k_max < 0 || !cnt || (k_max > 0 && !idx)) return HGCA_ERR_INVALID_ARG;

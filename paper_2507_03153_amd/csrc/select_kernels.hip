@@ -428,14 +428,11 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s)
     // rows whose padded length fits are cached in LDS (dynamic, beyond the 64 KiB default limit)
     const int seg = ((a.kv.cap + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
     const int cache_floats = kSelWaves * seg <= kMaxCacheFloats ? kSelWaves * seg : 0;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kMaxCacheFloats * (int)sizeof(float));
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per process (thread-safe static initialisation): lift the dynamic LDS limit of the kernel
+    static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                          kMaxCacheFloats * (int)sizeof(float));
+    if (attr_rc != hipSuccess) return attr_rc;
     hipLaunchKernelGGL(select_topk_kernel, dim3((unsigned)rows), dim3(kSelBlock),
                        (size_t)cache_floats * sizeof(float), s, a, cache_floats);
     return hipGetLastError();
