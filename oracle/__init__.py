@@ -56,7 +56,8 @@ def lib():
         _lib = ctypes.CDLL(build())
         for name in ("oracle_scores", "oracle_attend_all", "oracle_attend_indexed",
                      "oracle_attend_union", "oracle_select", "oracle_merge",
-                     "oracle_hybrid_step", "oracle_num_threads"):
+                     "oracle_hybrid_step", "oracle_num_threads", "oracle_window_weights",
+                     "oracle_maw_update", "oracle_threshold_select"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -214,3 +215,44 @@ def hybrid_step(q, window: Tier, pool: Tier, k, k_max: int, scale: float, idx=No
                                     _ptr(k_arr), k_uni, int(k_max), int(do_select), _ptr(idx), _ptr(cnt),
                                     _ptr(o), _ptr(lse)), "hybrid_step")
     return o, lse, idx, cnt
+
+
+def window_weights(q, tier: Tier, scale: float) -> np.ndarray:
+    """A_gpu: softmax weights of the query over the window, [B,Hq,cap], zero beyond each length."""
+    sh, kv = _shape(q, tier, scale), _kv(tier, q.shape[0])
+    a = np.empty((q.shape[0], q.shape[1], tier.cap), dtype=np.float64)
+    _check(lib().oracle_window_weights(ctypes.byref(sh), _ptr(q), ctypes.byref(kv), _ptr(a)), "window_weights")
+    return a
+
+
+def _row_lens(lens, shape):
+    """Per-sequence lengths [B] -> per-row lengths [B*Hq] (or None)."""
+    if lens is None:
+        return None
+    return np.ascontiguousarray(np.repeat(np.asarray(lens, np.int32), shape[1]))
+
+
+def maw_update(maw, a, alpha: float, lens=None, n_new: int = 0) -> np.ndarray:
+    """maw, a: [B,Hq,cap] float64; returns the updated moving average (a new array)."""
+    maw = np.array(maw, dtype=np.float64, order="C")
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    assert maw.shape == a.shape and maw.ndim == 3
+    rl = _row_lens(lens, maw.shape)
+    _check(lib().oracle_maw_update(ctypes.c_int64(maw.shape[0] * maw.shape[1]), int(maw.shape[2]), _ptr(rl),
+                                   int(n_new), ctypes.c_double(alpha), _ptr(maw), _ptr(a)), "maw_update")
+    return maw
+
+
+def threshold_select(w, beta: float, size, k_max: int, lens=None, normalised: bool = False):
+    """w: [B,Hq,cap] float64; size: int or per-sequence int array [B].  Returns idx, cnt (, w_norm)."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    B, Hq, cap = w.shape
+    rl = _row_lens(lens, w.shape)
+    sizes, size_uni = (None, int(size)) if np.isscalar(size) else (_row_lens(size, w.shape), 0)
+    idx = np.empty((B, Hq, k_max), dtype=np.int32)
+    cnt = np.empty((B, Hq), dtype=np.int32)
+    wn = np.empty((B, Hq, k_max), dtype=np.float64) if normalised else None
+    _check(lib().oracle_threshold_select(ctypes.c_int64(B * Hq), int(cap), _ptr(rl), _ptr(sizes), size_uni,
+                                         ctypes.c_double(beta), _ptr(w), int(k_max), _ptr(idx), _ptr(cnt),
+                                         _ptr(wn)), "threshold_select")
+    return (idx, cnt, wn) if normalised else (idx, cnt)

@@ -292,3 +292,86 @@ int oracle_hybrid_step(const oracle_shape *sh, const void *q,
     free(o_g); free(o_c); free(l_g); free(l_c);
     return rc;
 }
+
+/* ---- the paper's own sparsifier (Alg. 1; Sec. 3.2.2) ---------------------- */
+
+/* A = softmax(S) of Sec. 2.1 for the dense window: the A_gpu that Alg. 2's
+ * gpu_attention returns.  a is [B, Hq, cap]; positions >= len_b are set to 0. */
+int oracle_window_weights(const oracle_shape *sh, const void *q,
+                          const oracle_kv *kv, double *a)
+{
+    if (!shape_ok(sh) || !q || !kv || !a) return -1;
+    long n_bh = (long)sh->batch * sh->n_q_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < n_bh; ++bh) {
+        int b = (int)(bh / sh->n_q_heads), h = (int)(bh % sh->n_q_heads);
+        int32_t n = seq_len(kv, b);
+        double *row = a + (size_t)bh * kv->cap;
+        double m = -INFINITY, l = 0.0;
+        for (int32_t t = 0; t < n; ++t) {
+            row[t] = score_of(sh, q, kv, b, h, t);
+            if (row[t] > m) m = row[t];
+        }
+        for (int32_t t = 0; t < n; ++t) l += exp(row[t] - m);
+        for (int32_t t = 0; t < n; ++t) row[t] = exp(row[t] - m) / l;
+        for (int32_t t = n; t < kv->cap; ++t) row[t] = 0.0;
+    }
+    return 0;
+}
+
+/* Alg. 1: A_maw <- (1 - alpha) * A_maw + alpha * A_gpu for every GPU-resident
+ * entry of every head.  maw and a are [rows, cap]; lens[r] entries of row r are
+ * valid; the last n_new valid entries of a row have no history yet and take
+ * their first observed weight (a reading: the paper does not say). */
+int oracle_maw_update(int64_t rows, int32_t cap, const int32_t *lens,
+                      int32_t n_new, double alpha, double *maw, const double *a)
+{
+    if (rows < 0 || cap < 0 || n_new < 0 || !maw || !a) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        int32_t n = lens ? lens[r] : cap;
+        for (int32_t t = 0; t < n; ++t) {
+            size_t i = (size_t)r * cap + t;
+            maw[i] = (t >= n - n_new) ? a[i] : (1.0 - alpha) * maw[i] + alpha * a[i];
+        }
+    }
+    return 0;
+}
+
+/* Sec. 3.2.2: an entry is salient for a head iff its weight exceeds beta / size
+ * (strictly), size being the number of entries the weights were taken over.
+ * w is [rows, cap]; kept positions go to idx [rows, k_max] in ascending order
+ * (-1 padded; if more than k_max pass, the first k_max in position order are
+ * kept), their count to cnt [rows].  w_norm (optional, [rows, k_max]) receives
+ * the kept weights re-normalised to sum to 1 per row, as the paper does after
+ * selection. */
+int oracle_threshold_select(int64_t rows, int32_t cap, const int32_t *lens,
+                            const int32_t *sizes, int32_t size_uniform,
+                            double beta, const double *w, int32_t k_max,
+                            int32_t *idx, int32_t *cnt, double *w_norm)
+{
+    if (rows < 0 || cap < 0 || k_max < 0 || !w || !idx || !cnt) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        int32_t n = lens ? lens[r] : cap;
+        int32_t size = sizes ? sizes[r] : size_uniform;
+        double thr = beta / (double)size;
+        int32_t kept = 0;
+        double sum = 0.0;
+        for (int32_t t = 0; t < n && kept < k_max; ++t) {
+            double x = w[(size_t)r * cap + t];
+            if (x > thr) {
+                idx[(size_t)r * k_max + kept] = t;
+                if (w_norm) w_norm[(size_t)r * k_max + kept] = x;
+                sum += x;
+                ++kept;
+            }
+        }
+        for (int32_t j = kept; j < k_max; ++j) {
+            idx[(size_t)r * k_max + j] = -1;
+            if (w_norm) w_norm[(size_t)r * k_max + j] = 0.0;
+        }
+        if (w_norm)
+            for (int32_t j = 0; j < kept; ++j) w_norm[(size_t)r * k_max + j] /= sum;
+        cnt[r] = kept;
+    }
+    return 0;
+}

@@ -20,7 +20,10 @@
  *     paper describes in Sec. 2.2: the k entries with the largest attention
  *     score of the current query;
  *   - merge_state: z = e^{lse_c} + e^{lse_g},
- *     O = (e^{lse_c} O_cpu + e^{lse_g} O_gpu) / z   (Sec. 3.3, merge equations).
+ *     O = (e^{lse_c} O_cpu + e^{lse_g} O_gpu) / z   (Sec. 3.3, merge equations);
+ *   - the paper's own sparsifier: the window's attention weights A_gpu, their
+ *     moving average (Alg. 1: A_maw <- (1-alpha) A_maw + alpha A_gpu) and the
+ *     per-head threshold rule "keep iff weight > beta / size" (Sec. 3.2.2).
  *
  * Readings taken where the paper is silent:
  *   - scores are scaled, s_j = scale * <q, k_j>, scale is an argument;
@@ -120,6 +123,28 @@ int oracle_hybrid_step(const oracle_shape *sh, const void *q,
                        const int32_t *k_per_seq, int32_t k_uniform,
                        int32_t k_max, int select, int32_t *idx, int32_t *cnt,
                        double *o, double *lse);
+
+/* ---- the paper's own sparsifier (Alg. 1; Sec. 3.2.2) ---- */
+
+/* A_gpu of Alg. 2: softmax weights of the query over the dense window,
+ * a is [B, Hq, cap], zero at positions >= len_b. */
+int oracle_window_weights(const oracle_shape *sh, const void *q,
+                          const oracle_kv *kv, double *a);
+
+/* Alg. 1: A_maw <- (1-alpha) A_maw + alpha A_gpu, rows = B*Hq of [cap] entries,
+ * lens per ROW (NULL => cap); the last n_new valid entries of a row take their
+ * first observed weight. */
+int oracle_maw_update(int64_t rows, int32_t cap, const int32_t *lens,
+                      int32_t n_new, double alpha, double *maw, const double *a);
+
+/* Sec. 3.2.2: keep iff w > beta / size (strict); sizes per ROW or uniform.
+ * idx [rows, k_max] ascending, -1 padded (first k_max passing entries if more
+ * pass), cnt [rows]; w_norm optional [rows, k_max]: kept weights re-normalised
+ * to sum to 1 per row. */
+int oracle_threshold_select(int64_t rows, int32_t cap, const int32_t *lens,
+                            const int32_t *sizes, int32_t size_uniform,
+                            double beta, const double *w, int32_t k_max,
+                            int32_t *idx, int32_t *cnt, double *w_norm);
 
 /* Number of OpenMP threads the (batch, head) loop will use. */
 int oracle_num_threads(void);
