@@ -173,6 +173,52 @@ int hgca_lse_merge(const hgca_shape *shape,
                    void *o_out, int32_t o_dtype, float *lse_out,
                    void *hip_stream);
 
+/* ---- The paper's own sparsifier: attention weights of the window, their
+ * moving average, and the beta/size threshold rule (Alg. 1; Sec. 3.2.2). ---- */
+
+/* hgca_dense_window_attn that also returns A_gpu (Alg. 2, gpu_attention returns
+ * O_gpu, lse_g and A_gpu): a_out is fp32 [B,Hq,window->cap] and receives the
+ * softmax weight e^{s_j - lse_g} of every valid window token (Sec. 2.1,
+ * A = softmax(S)) and 0 at positions >= seq_lens[b].  o_out and lse_out are
+ * required (the result cannot be deferred). */
+int hgca_dense_window_attn_weights(const hgca_shape *shape, const void *q,
+                                   const hgca_kv_view *window,
+                                   float *o_out, float *lse_out, float *a_out,
+                                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Moving average of attention weights (Alg. 1, the A_maw update; Sec. 3.1):
+ * a_maw <- (1 - alpha) * a_maw + alpha * a_gpu on the first seq_lens[b] entries
+ * of every (b, h) row (all `cap` entries if seq_lens is NULL); a_maw and a_gpu
+ * are device fp32 [B,Hq,cap], a_maw is updated in place, entries beyond the
+ * length are left untouched.  The last n_new valid entries of a row (the tokens
+ * appended since the previous update: 1 per decode step) have no history and
+ * are set to a_gpu, their first observed weight.  0 <= alpha <= 1.  Only batch
+ * and n_q_heads of `shape` are used. */
+int hgca_maw_update(const hgca_shape *shape, float *a_maw, const float *a_gpu,
+                    const int32_t *seq_lens, int32_t cap, int32_t n_new,
+                    float alpha, void *hip_stream);
+
+/* Per-head threshold rule (Sec. 3.2.2; Alg. 1, ids <- A > beta / A.size):
+ * entry j of row (b, h) is salient iff weights[b,h,j] > beta / size_b
+ * (strictly), size_b = size_per_seq[b] (device [B]) if given, else
+ * size_uniform (> 0): the number of entries the weights were taken over.
+ * The comparison is made in fp64 on the exactly widened fp32 weight.  weights
+ * is device fp32 [B,Hq,cap]; the first seq_lens[b] entries of a row are
+ * examined (all if seq_lens is NULL).  idx_out [B,Hq,k_max] receives the
+ * salient positions in ascending order, padded with -1, cnt_out [B,Hq] their
+ * number; if more than k_max entries pass, the first k_max in position order
+ * are kept and cnt_out is k_max (pass k_max = cap to rule that out).
+ * w_norm_out (optional, NULL to skip) is fp32 [B,Hq,k_max] and receives the
+ * kept weights re-normalised to sum to 1 per row, 0 in the padding.  The result
+ * feeds hgca_sparse_attn as idx / cnt.  Only batch and n_q_heads of `shape` are
+ * used. */
+int hgca_threshold_select(const hgca_shape *shape, const float *weights,
+                          const int32_t *seq_lens, int32_t cap,
+                          const int32_t *size_per_seq, int32_t size_uniform,
+                          double beta, int32_t k_max,
+                          int32_t *idx_out, int32_t *cnt_out, float *w_norm_out,
+                          void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -185,6 +185,17 @@ __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[kMa
     }
 }
 
+// Scaled scores of the split to a.scores[b, h, t0 .. t0+nt) for the NH heads of the workgroup.
+template <int NH>
+__device__ __forceinline__ void store_split_scores(const KernelArgs &a, const float (*s_p)[kMaxChunk], int64_t bh0,
+                                                   int t0, int nt)
+{
+    for (int i = threadIdx.x; i < NH * nt; i += kBlock) {
+        const int g = i / nt, j = i % nt;
+        a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
+    }
+}
+
 // ---- VALU path -----------------------------------------------------------------------------
 
 template <typename T, int D, int NH, int MODE>
@@ -256,13 +267,8 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
     }
     __syncthreads();
 
-    if (MODE == kScores) {
-        for (int i = tid; i < NH * nt; i += kBlock) {
-            const int g = i / nt, j = i % nt;
-            a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
-        }
-        return;
-    }
+    if (MODE == kScores || (MODE == kDense && a.scores)) store_split_scores<NH>(a, s_p, bh0, t0, nt);
+    if (MODE == kScores) return;
 
     split_softmax<NH>(s_p, s_m, s_l, nt);
     __syncthreads();
@@ -414,6 +420,7 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
     const RowMap rows = make_row_map<false, kBlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nt, nullptr);
     mfma_scores<D, G, kMaxChunk>(a, reinterpret_cast<uint4 *>(s_buf), s_p, bh0, nt, rows);
     __syncthreads();
+    if (a.scores) store_split_scores<G>(a, s_p, bh0, t0, nt);
     split_softmax<G>(s_p, s_m, s_l, nt);
     __syncthreads();
     value_pass<bf16_t, D, G, false>(a, s_p, reinterpret_cast<float (*)[G][D]>(s_buf), s_m, s_l, bh0, split, nt, rows);
@@ -575,7 +582,7 @@ KernelArgs to_kernel_args(const AttnArgs &a)
     ka.k_max = a.k_max;
     ka.chunk = a.chunk;
     ka.part = a.part;
-    ka.scores = nullptr;
+    ka.scores = a.raw_scores;
     return ka;
 }
 

@@ -154,8 +154,10 @@ size_t hgca_workspace_bytes(const hgca_shape *shape, int32_t max_window, int32_t
     return layout(shape, std::max(max_window, k_max), max_pool).total;
 }
 
-int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
-                           float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
+namespace {
+
+int dense_window(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out, float *lse_out,
+                 float *a_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
@@ -163,6 +165,7 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     if ((rc = check_view(shape, window, true)) != HGCA_OK) return rc;
     const bool deferred = !o_out && !lse_out;    // leave the split partials in ws for hgca_lse_merge_splits
     if (!q || !aligned16(q) || (!deferred && (!o_out || !lse_out || !aligned16(o_out)))) return HGCA_ERR_INVALID_ARG;
+    if (a_out && deferred) return HGCA_ERR_INVALID_ARG;   // the weights need the window's own lse
     const WsLayout w = layout(shape, window->cap, 0);
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -173,10 +176,66 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
     a.kv = to_dev(window);
     a.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
     a.part = partials_at(ws, w, n_splits_for(window->cap, a.chunk));
+    a.raw_scores = a_out;
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
     if (deferred) return HGCA_OK;
-    return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
+    if ((rc = from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s))) != HGCA_OK) return rc;
+    if (!a_out) return HGCA_OK;
+    return from_hip(launch_window_weights(a_out, lse_out, window->seq_lens, rows, shape->n_q_heads, window->cap, s));
+}
+
+}  // namespace
+
+int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
+                           float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return dense_window(shape, q, window, o_out, lse_out, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int hgca_dense_window_attn_weights(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
+                                   float *lse_out, float *a_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!a_out && window && window->cap > 0) return HGCA_ERR_INVALID_ARG;
+    return dense_window(shape, q, window, o_out, lse_out, a_out, ws, ws_bytes, hip_stream);
+}
+
+int hgca_maw_update(const hgca_shape *shape, float *a_maw, const float *a_gpu, const int32_t *seq_lens, int32_t cap,
+                    int32_t n_new, float alpha, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (cap < 0 || n_new < 0 || !(alpha >= 0.f && alpha <= 1.f)) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0 || cap == 0) return HGCA_OK;
+    if (!a_maw || !a_gpu) return HGCA_ERR_INVALID_ARG;
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    return from_hip(launch_maw_update(a_maw, a_gpu, seq_lens, rows, shape->n_q_heads, cap, n_new, alpha,
+                                      static_cast<hipStream_t>(hip_stream)));
+}
+
+int hgca_threshold_select(const hgca_shape *shape, const float *weights, const int32_t *seq_lens, int32_t cap,
+                          const int32_t *size_per_seq, int32_t size_uniform, double beta, int32_t k_max,
+                          int32_t *idx_out, int32_t *cnt_out, float *w_norm_out, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (cap < 0 || k_max < 0 || !(beta >= 0.0) || (!size_per_seq && size_uniform <= 0)) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return HGCA_OK;
+    if (!cnt_out || (k_max > 0 && !idx_out) || (cap > 0 && !weights)) return HGCA_ERR_INVALID_ARG;
+    ThresholdArgs a{};
+    a.w = weights;
+    a.seq_lens = seq_lens;
+    a.sizes = size_per_seq;
+    a.beta = beta;
+    a.size_uniform = size_uniform;
+    a.n_q_heads = shape->n_q_heads;
+    a.cap = cap;
+    a.k_max = k_max;
+    a.idx = idx_out;
+    a.cnt = cnt_out;
+    a.w_norm = k_max > 0 ? w_norm_out : nullptr;
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    return from_hip(launch_threshold_select(a, rows, static_cast<hipStream_t>(hip_stream)));
 }
 
 int hgca_pool_scores(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, float *scores_out,

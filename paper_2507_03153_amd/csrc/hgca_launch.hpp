@@ -31,6 +31,7 @@ struct AttnArgs {
     int32_t k_max;
     int32_t chunk;         // tokens per split
     Partials part;
+    float *raw_scores;     // dense only, optional: [B, Hq, cap], receives the scaled score of every valid token
 };
 
 // dtype: 0 fp32, 1 bf16; head_dim 64|128.  Dense handles the `group` query heads
@@ -67,5 +68,26 @@ struct SelectArgs {
     float *sel_scores;     // optional [B, Hq, k_max]: score of every kept entry, in idx order
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t s);
+
+// ---- attention weights, their moving average, threshold rule ----
+
+// a [n_rows, cap] holds scaled scores on entry and softmax weights e^{s - lse} on exit (0 beyond the length).
+hipError_t launch_window_weights(float *a, const float *lse, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
+                                 int32_t cap, hipStream_t s);
+
+hipError_t launch_maw_update(float *maw, const float *a_gpu, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
+                             int32_t cap, int32_t n_new, float alpha, hipStream_t s);
+
+struct ThresholdArgs {
+    const float *w;            // [B*Hq, cap]
+    const int32_t *seq_lens;   // [B] or null
+    const int32_t *sizes;      // [B] or null
+    double beta;
+    int32_t size_uniform, n_q_heads, cap, k_max;
+    int32_t *idx;              // [B*Hq, k_max]
+    int32_t *cnt;              // [B*Hq]
+    float *w_norm;             // optional [B*Hq, k_max]
+};
+hipError_t launch_threshold_select(const ThresholdArgs &a, int64_t n_rows, hipStream_t s);
 
 }  // namespace hgca

@@ -1,0 +1,166 @@
+// The paper's own sparsifier (Alg. 1; Sec. 3.2.2): attention weights of the dense window,
+// their moving average, and the per-head threshold rule "keep iff weight > beta / size".
+//
+// All three are streaming passes over [B*Hq, cap] fp32 rows, a few MB per layer-step: one
+// load and at most one store per element, coalesced, no reuse.
+#include "hgca_launch.hpp"
+
+namespace hgca {
+
+namespace {
+
+constexpr int kRowBlock = 256;
+constexpr int kRowWaves = kRowBlock / kWave;
+constexpr int kPerThread = 4;                    // elements a thread handles per step
+constexpr int kRowStep = kRowBlock * kPerThread;
+
+__device__ __forceinline__ int32_t row_len(const int32_t *seq_lens, int b, int32_t cap) {
+    return seq_lens ? min(max(seq_lens[b], 0), cap) : cap;
+}
+
+// a[row, j] holds the scaled score s_j on entry; on exit the softmax weight e^{s_j - lse_row}
+// (Sec. 2.1, A = softmax(S)) for j < len and 0 beyond.
+__global__ __launch_bounds__(kRowBlock) void window_weights_kernel(float *a, const float *lse, const int32_t *seq_lens,
+                                                                   int32_t n_q_heads, int32_t cap)
+{
+    const int64_t row = blockIdx.y;
+    const int n = row_len(seq_lens, (int)(row / n_q_heads), cap);
+    const float L = lse[row];
+    float *p = a + row * cap;
+    const int j0 = blockIdx.x * kRowStep + threadIdx.x;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int j = j0 + e * kRowBlock;
+        if (j < cap) p[j] = j < n ? expf(p[j] - L) : 0.f;
+    }
+}
+
+// Alg. 1: A_maw <- (1 - alpha) A_maw + alpha A_gpu on the valid entries of every row; the last
+// n_new valid entries have no history and take their first observed weight.
+__global__ __launch_bounds__(kRowBlock) void maw_update_kernel(float *maw, const float *a_gpu, const int32_t *seq_lens,
+                                                               int32_t n_q_heads, int32_t cap, int32_t n_new,
+                                                               float alpha)
+{
+    const int64_t row = blockIdx.y;
+    const int n = row_len(seq_lens, (int)(row / n_q_heads), cap);
+    const int first_new = n - min(n_new, n);
+    float *m = maw + row * cap;
+    const float *a = a_gpu + row * cap;
+    const float keep = 1.f - alpha;
+    const int j0 = blockIdx.x * kRowStep + threadIdx.x;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int j = j0 + e * kRowBlock;
+        if (j < n) {
+            const float x = a[j];
+            m[j] = j >= first_new ? x : fmaf(alpha, x, keep * m[j]);
+        }
+    }
+}
+
+// Number of lanes below this one whose bit is set in `mask`.
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// One workgroup per (sequence, query head) row.  The row is walked in steps of 1024 entries;
+// sub-round e of a step covers entries [e*256, e*256+256) so that loads are coalesced and the
+// output order is the position order.  The comparison is done in fp64 on the exactly widened
+// weight, i.e. with the threshold beta / size at full precision.
+__global__ __launch_bounds__(kRowBlock) void threshold_select_kernel(ThresholdArgs a)
+{
+    __shared__ int s_cnt[2][kPerThread][kRowWaves];   // double-buffered: one barrier per step
+    __shared__ float s_sum[kRowWaves];
+
+    const int64_t row = blockIdx.x;
+    const int b = (int)(row / a.n_q_heads);
+    const int n = row_len(a.seq_lens, b, a.cap);
+    const int size = a.sizes ? a.sizes[b] : a.size_uniform;
+    const double thr = a.beta / (double)size;
+    const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
+    const float *wr = a.w + row * a.cap;
+    int32_t *idx = a.idx + row * a.k_max;
+    float *wn = a.w_norm ? a.w_norm + row * a.k_max : nullptr;
+
+    int base = 0;                                 // entries kept so far (uniform over the workgroup)
+    float my_sum = 0.f;
+    int buf = 0;
+    for (int t0 = 0; t0 < n && base < a.k_max; t0 += kRowStep, buf ^= 1) {
+        float x[kPerThread];
+        bool keep[kPerThread];
+        int below[kPerThread];
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) {
+            const int t = t0 + e * kRowBlock + tid;
+            x[e] = t < n ? wr[t] : 0.f;
+            keep[e] = t < n && (double)x[e] > thr;
+            const uint64_t mask = __ballot(keep[e]);
+            below[e] = lanes_below(mask);
+            if (lane == 0) s_cnt[buf][e][w] = __popcll(mask);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) {
+            int before = 0, total = 0;
+#pragma unroll
+            for (int v = 0; v < kRowWaves; ++v) {
+                const int c = s_cnt[buf][e][v];
+                before += v < w ? c : 0;
+                total += c;
+            }
+            const int pos = base + before + below[e];
+            if (keep[e] && pos < a.k_max) {
+                idx[pos] = t0 + e * kRowBlock + tid;
+                if (wn) wn[pos] = x[e];
+                my_sum += x[e];
+            }
+            base += total;
+        }
+    }
+    const int kept = min(base, a.k_max);
+    for (int j = kept + tid; j < a.k_max; j += kRowBlock) {
+        idx[j] = -1;
+        if (wn) wn[j] = 0.f;
+    }
+    if (tid == 0) a.cnt[row] = kept;
+    if (!wn) return;
+
+    // re-normalise the kept weights to sum to 1 (fixed reduction order: deterministic)
+    my_sum = wave_sum(my_sum);
+    if (lane == 0) s_sum[w] = my_sum;
+    __syncthreads();                              // also orders the wn stores above before the loads below
+    float sum = 0.f;
+#pragma unroll
+    for (int v = 0; v < kRowWaves; ++v) sum += s_sum[v];
+    for (int j = tid; j < kept; j += kRowBlock) wn[j] = wn[j] / sum;
+}
+
+}  // namespace
+
+hipError_t launch_window_weights(float *a, const float *lse, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
+                                 int32_t cap, hipStream_t s)
+{
+    if (n_rows == 0 || cap == 0) return hipSuccess;
+    dim3 grid((cap + kRowStep - 1) / kRowStep, (unsigned)n_rows);
+    hipLaunchKernelGGL(window_weights_kernel, grid, dim3(kRowBlock), 0, s, a, lse, seq_lens, n_q_heads, cap);
+    return hipGetLastError();
+}
+
+hipError_t launch_maw_update(float *maw, const float *a_gpu, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
+                             int32_t cap, int32_t n_new, float alpha, hipStream_t s)
+{
+    if (n_rows == 0 || cap == 0) return hipSuccess;
+    dim3 grid((cap + kRowStep - 1) / kRowStep, (unsigned)n_rows);
+    hipLaunchKernelGGL(maw_update_kernel, grid, dim3(kRowBlock), 0, s, maw, a_gpu, seq_lens, n_q_heads, cap, n_new,
+                       alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_threshold_select(const ThresholdArgs &a, int64_t n_rows, hipStream_t s)
+{
+    if (n_rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(threshold_select_kernel, dim3((unsigned)n_rows), dim3(kRowBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace hgca

@@ -21,7 +21,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, -1, -2, -3,
 _LIB_PATH = os.environ.get("HGCA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhgca.so")
 
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
-           "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge")
+           "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
+           "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select")
 
 
 class Shape(ctypes.Structure):
@@ -70,6 +71,12 @@ def lib() -> ctypes.CDLL:
         L.hgca_lse_merge_splits.argtypes = [ps, i32, vp, sz, i32, vp, sz, vp, i32, vp, vp]
         L.hgca_lse_merge.restype = ctypes.c_int
         L.hgca_lse_merge.argtypes = [ps, vp, vp, vp, vp, vp, i32, vp, vp]
+        L.hgca_dense_window_attn_weights.restype = ctypes.c_int
+        L.hgca_dense_window_attn_weights.argtypes = [ps, vp, pk, vp, vp, vp, vp, sz, vp]
+        L.hgca_maw_update.restype = ctypes.c_int
+        L.hgca_maw_update.argtypes = [ps, vp, vp, vp, i32, i32, ctypes.c_float, vp]
+        L.hgca_threshold_select.restype = ctypes.c_int
+        L.hgca_threshold_select.argtypes = [ps, vp, vp, i32, vp, i32, ctypes.c_double, i32, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -207,3 +214,36 @@ def lse_merge(shape: Shape, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=
         _require_gpu(t)
     _check(lib().hgca_lse_merge(ctypes.byref(shape), _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b), _ptr(o_out),
                                 _dtype_code(o_out), _ptr(lse_out), _stream(stream)), "hgca_lse_merge")
+
+
+def dense_window_attn_weights(shape: Shape, q, window: Tier, o_out, lse_out, a_out, ws, stream=None) -> None:
+    """Dense window attention that also returns the window's softmax weights a_out [B,Hq,cap] (fp32)."""
+    for t in (q, ws, o_out, lse_out, a_out):
+        _require_gpu(t)
+    kv = window.view()
+    _check(lib().hgca_dense_window_attn_weights(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out),
+                                                _ptr(lse_out), _ptr(a_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_dense_window_attn_weights")
+
+
+def maw_update(shape: Shape, a_maw, a_gpu, seq_lens, cap: int, n_new: int, alpha: float, stream=None) -> None:
+    """a_maw <- (1 - alpha) a_maw + alpha a_gpu in place; the last n_new valid entries take a_gpu."""
+    for t in (a_maw, a_gpu) + (() if seq_lens is None else (seq_lens,)):
+        _require_gpu(t)
+    _check(lib().hgca_maw_update(ctypes.byref(shape), _ptr(a_maw), _ptr(a_gpu), _ptr(seq_lens), int(cap), int(n_new),
+                                 float(alpha), _stream(stream)), "hgca_maw_update")
+
+
+def threshold_select(shape: Shape, weights, seq_lens, cap: int, size, beta: float, k_max: int, idx_out, cnt_out,
+                     w_norm_out=None, stream=None) -> None:
+    """size: int (uniform) or int32 GPU tensor [B]: the number of entries the weights were taken over."""
+    for t in (weights, idx_out, cnt_out) + tuple(x for x in (seq_lens, w_norm_out) if x is not None):
+        _require_gpu(t)
+    if isinstance(size, torch.Tensor):
+        _require_gpu(size)
+        size_ptr, size_uni = _ptr(size), 0
+    else:
+        size_ptr, size_uni = None, int(size)
+    _check(lib().hgca_threshold_select(ctypes.byref(shape), _ptr(weights), _ptr(seq_lens), int(cap), size_ptr,
+                                       size_uni, float(beta), int(k_max), _ptr(idx_out), _ptr(cnt_out),
+                                       _ptr(w_norm_out), _stream(stream)), "hgca_threshold_select")

@@ -139,3 +139,38 @@ def test_binding_refuses_cpu_tensors(hg):
     q = torch.zeros(1, 4, 64)
     with pytest.raises(ValueError):
         hg.make_shape(q, 4, 0.125)
+
+
+def test_sparsifier_entry_points_reject_bad_arguments(hg):
+    L = hg.lib()
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    view = _view(hg)
+    byref = ctypes.byref
+    # the weights cannot be produced without the window's own result
+    assert L.hgca_dense_window_attn_weights(byref(sh), FAKE, byref(view), None, None, FAKE, FAKE, 1 << 40, None) \
+        == hg.ERR_INVALID_ARG
+    assert L.hgca_dense_window_attn_weights(byref(sh), FAKE, byref(view), FAKE, FAKE, None, FAKE, 1 << 40, None) \
+        == hg.ERR_INVALID_ARG
+    assert L.hgca_dense_window_attn_weights(byref(sh), FAKE, byref(view), FAKE, FAKE, FAKE, FAKE, 16, None) \
+        == hg.ERR_WORKSPACE
+    # moving average: alpha in [0, 1], sizes non-negative, pointers present
+    for alpha in (-0.1, 1.5, float("nan")):
+        assert L.hgca_maw_update(byref(sh), FAKE, FAKE, None, 64, 1, alpha, None) == hg.ERR_INVALID_ARG
+    assert L.hgca_maw_update(byref(sh), FAKE, FAKE, None, -1, 1, 0.5, None) == hg.ERR_INVALID_ARG
+    assert L.hgca_maw_update(byref(sh), FAKE, FAKE, None, 64, -1, 0.5, None) == hg.ERR_INVALID_ARG
+    assert L.hgca_maw_update(byref(sh), None, FAKE, None, 64, 1, 0.5, None) == hg.ERR_INVALID_ARG
+    assert L.hgca_maw_update(byref(sh), FAKE, None, None, 64, 1, 0.5, None) == hg.ERR_INVALID_ARG
+    assert L.hgca_maw_update(byref(sh), None, None, None, 0, 1, 0.5, None) == hg.OK       # nothing to do
+    # threshold rule
+    def thr(w=FAKE, cap=64, sizes=None, size=64, beta=1.0, k_max=64, idx=FAKE, cnt=FAKE):
+        return L.hgca_threshold_select(byref(sh), w, None, cap, sizes, size, beta, k_max, idx, cnt, None, None)
+    assert thr(size=0) == hg.ERR_INVALID_ARG
+    assert thr(beta=-1.0) == hg.ERR_INVALID_ARG
+    assert thr(beta=float("nan")) == hg.ERR_INVALID_ARG
+    assert thr(k_max=-1) == hg.ERR_INVALID_ARG
+    assert thr(cap=-1) == hg.ERR_INVALID_ARG
+    assert thr(w=None) == hg.ERR_INVALID_ARG
+    assert thr(idx=None) == hg.ERR_INVALID_ARG
+    assert thr(cnt=None) == hg.ERR_INVALID_ARG
+    empty = hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088)
+    assert L.hgca_threshold_select(byref(empty), None, None, 64, None, 64, 1.0, 64, None, None, None, None) == hg.OK

@@ -1,0 +1,253 @@
+"""Parity of the paper-literal sparsifier (window attention weights A_gpu, their moving average,
+the beta/size threshold rule; paper Alg. 1, Alg. 2, Sec. 3.2.2) with the fp64 CPU oracle, through
+the C ABI.
+
+Bars:
+  * attention weights: 2e-6 absolute for fp32 inputs, 2e-5 for bf16 inputs (weights are <= 1; the
+    path accumulates exact bf16 products in fp32), rows sum to 1 within 1e-5;
+  * moving average: 1e-6 absolute (one fp32 multiply-add per entry);
+  * threshold rule on the SAME fp32 weights: bit-exact positions and counts (both sides compare the
+    exactly widened weight with beta/size in fp64); re-normalised weights 1e-6;
+  * the chained decode loop (weights -> moving average -> threshold): positions exact outside a band
+    of 1e-5 relative to the threshold, where the two sides' rounding may differ.
+"""
+import sys
+
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from paper_2507_03153_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+W_TOL = {"f32": 2e-6, "bf16": 2e-5}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2507_03153_amd import hgca, runner
+    hgca.lib()
+    return torch, hgca, runner
+
+
+def otier(oracle, t):
+    return oracle.Tier(t.k, t.v, t.cap, t.seq_lens, t.block_table, t.block_size)
+
+
+def window_weights_case(gpu, oracle, cfg):
+    torch, hgca, runner = gpu
+    say(f"\n[case] window weights {cfg.name} dtype={cfg.dtype} B={cfg.B} Hq={cfg.Hq} Hkv={cfg.Hkv} d={cfg.d} "
+        f"W={cfg.W} ragged={cfg.ragged} block={cfg.block_size}")
+    L = wl.make_layer(cfg)
+    D = runner.DeviceLayer.upload(L)
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    ws = hgca.alloc_workspace(D.shape, cfg.W, 0, 0, "cuda:0")
+    o, lse = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32), torch.empty(cfg.B, cfg.Hq, **f32)
+    o2, lse2 = torch.empty_like(o), torch.empty_like(lse)
+    a = torch.full((cfg.B, cfg.Hq, max(cfg.W, 1)), float("nan"), **f32)
+    hgca.dense_window_attn_weights(D.shape, D.q, D.window, o, lse, a, ws)
+    hgca.dense_window_attn(D.shape, D.q, D.window, o2, lse2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)       # the extra output changes nothing else
+    a = a.double().cpu().numpy()[:, :, :cfg.W]
+    a_ref = oracle.window_weights(L.q, otier(oracle, L.window), L.scale)
+    err = np.max(np.abs(a - a_ref)) if a.size else 0.0
+    say(f"    max|dA|={err:.3e} (tol {W_TOL[cfg.dtype]:g})")
+    assert err <= W_TOL[cfg.dtype]
+    lens = L.window.lens(cfg.B)
+    for b in range(cfg.B):
+        assert np.all(a[b, :, lens[b]:] == 0.0)                # zero beyond the length, NaN prefill gone
+        if lens[b]:
+            assert np.max(np.abs(a[b, :, :lens[b]].sum(-1) - 1.0)) <= 1e-5
+    return a_ref
+
+
+@pytest.mark.parametrize("kw", [
+    dict(B=2, Hq=8, Hkv=2, W=700, P=64, k=8),
+    dict(B=3, Hq=4, Hkv=4, W=130, P=64, k=8),
+    dict(B=1, Hq=16, Hkv=2, W=1100, P=64, k=8),
+    dict(B=2, Hq=4, Hkv=2, d=64, W=333, P=64, k=8),
+    dict(B=2, Hq=8, Hkv=2, W=1, P=64, k=8),
+    dict(B=2, Hq=8, Hkv=2, W=0, P=64, k=8),
+], ids=["gqa4", "mha", "gqa8", "gqa2_d64", "W1", "W0"])
+def test_window_weights_bf16(gpu, oracle, kw):
+    window_weights_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], **kw))
+
+
+def test_window_weights_fp32(gpu, oracle):
+    window_weights_case(gpu, oracle, wl.CONFIGS["C1"])
+    window_weights_case(gpu, oracle, wl.scaled(wl.CONFIGS["C1"], B=2, Hq=8, Hkv=2, d=128, W=300, P=64, k=8))
+
+
+def test_window_weights_ragged_paged_with_empty_sequences(gpu, oracle):
+    window_weights_case(gpu, oracle, wl.scaled(wl.CONFIGS["C5"], B=6, Hq=8, Hkv=2, W=256, P=1792, ragged=(100, 2048)))
+    window_weights_case(gpu, oracle, wl.scaled(wl.CONFIGS["C5"], B=6, Hq=8, Hkv=2, W=256, P=1792, ragged=(200, 2048),
+                                               block_size=0))
+
+
+def test_window_weights_full_size_c2(gpu, oracle):
+    window_weights_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], P=64, k=8))
+
+
+# ------------------------------------------------------------------------ moving average
+
+@pytest.mark.parametrize("B,Hq,cap,n_new,alpha", [
+    (2, 8, 700, 1, 0.25), (3, 4, 1024, 0, 0.5), (2, 2, 5, 9, 0.1), (1, 4, 4097, 3, 1.0), (2, 4, 64, 1, 0.0),
+    (8, 32, 4096, 1, 0.3),
+])
+def test_maw_update_matches_oracle(gpu, oracle, B, Hq, cap, n_new, alpha):
+    torch, hgca, _ = gpu
+    say(f"\n[case] maw_update B={B} Hq={Hq} cap={cap} n_new={n_new} alpha={alpha}")
+    rng = np.random.default_rng(100 + cap)
+    maw0 = softmax(rng.standard_normal((B, Hq, cap)), axis=-1).astype(np.float32)
+    a = softmax(2.0 * rng.standard_normal((B, Hq, cap)), axis=-1).astype(np.float32)
+    lens = rng.integers(0, cap + 1, B).astype(np.int32)
+    lens[0] = cap
+    sh = hgca.Shape(hgca.BF16, B, Hq, Hq, 128, 1.0)
+    for use_lens in (True, False):
+        m = torch.from_numpy(maw0).cuda()
+        hgca.maw_update(sh, m, torch.from_numpy(a).cuda(), torch.from_numpy(lens).cuda() if use_lens else None,
+                        cap, n_new, alpha)
+        torch.cuda.synchronize()
+        m = m.cpu().numpy()
+        ref = oracle.maw_update(maw0, a, alpha, lens=lens if use_lens else None, n_new=n_new)
+        assert np.max(np.abs(m - ref)) <= 1e-6
+        if use_lens:
+            for b in range(B):                                 # beyond the length: bit-identical to the input
+                assert np.array_equal(m[b, :, lens[b]:], maw0[b, :, lens[b]:])
+                first_new = max(lens[b] - n_new, 0)            # first observations are copied, not blended
+                assert np.array_equal(m[b, :, first_new:lens[b]], a[b, :, first_new:lens[b]])
+
+
+# ------------------------------------------------------------------------ threshold rule
+
+def threshold_case(gpu, oracle, w, beta, size, k_max, lens=None):
+    torch, hgca, _ = gpu
+    B, Hq, cap = w.shape
+    sh = hgca.Shape(hgca.BF16, B, Hq, Hq, 128, 1.0)
+    dev = "cuda:0"
+    idx = torch.full((B, Hq, max(k_max, 1)), -7, dtype=torch.int32, device=dev)
+    cnt = torch.full((B, Hq), -7, dtype=torch.int32, device=dev)
+    wn = torch.full((B, Hq, max(k_max, 1)), float("nan"), dtype=torch.float32, device=dev)
+    size_arg = size if np.isscalar(size) else torch.from_numpy(np.asarray(size, np.int32)).to(dev)
+    lens_arg = None if lens is None else torch.from_numpy(lens).to(dev)
+    w_dev = torch.from_numpy(w).to(dev) if w.size else torch.empty(B, Hq, 1, dtype=torch.float32, device=dev)
+    hgca.threshold_select(sh, w_dev, lens_arg, cap, size_arg, beta, k_max, idx, cnt, wn)
+    idx2 = torch.full_like(idx, -7)
+    cnt2 = torch.full_like(cnt, -7)
+    hgca.threshold_select(sh, w_dev, lens_arg, cap, size_arg, beta, k_max, idx2, cnt2, None)
+    torch.cuda.synchronize()
+    idx_ref, cnt_ref, wn_ref = oracle.threshold_select(w, beta, size, k_max, lens=lens, normalised=True)
+    idx, cnt, wn = idx.cpu().numpy()[:, :, :k_max], cnt.cpu().numpy(), wn.cpu().numpy()[:, :, :k_max]
+    assert np.array_equal(cnt, cnt_ref)
+    assert np.array_equal(idx, idx_ref)
+    assert np.array_equal(idx2.cpu().numpy()[:, :, :k_max], idx_ref) and np.array_equal(cnt2.cpu().numpy(), cnt_ref)
+    assert np.max(np.abs(wn - wn_ref), initial=0.0) <= 1e-6
+    return cnt_ref
+
+
+@pytest.mark.parametrize("B,Hq,cap,beta,sharp", [
+    (2, 8, 700, 1.0, 3.0), (3, 4, 1023, 0.5, 1.0), (1, 4, 5000, 1.0, 6.0), (2, 2, 1, 0.5, 1.0), (2, 4, 257, 0.0, 1.0),
+    (8, 32, 4096, 1.0, 4.0),
+])
+def test_threshold_select_is_exact_on_the_same_weights(gpu, oracle, B, Hq, cap, beta, sharp):
+    say(f"\n[case] threshold_select B={B} Hq={Hq} cap={cap} beta={beta}")
+    rng = np.random.default_rng(200 + cap)
+    w = softmax(sharp * rng.standard_normal((B, Hq, cap)), axis=-1).astype(np.float32)
+    cnt = threshold_case(gpu, oracle, w, beta, cap, cap)
+    say(f"    kept per head: min {cnt.min()} mean {cnt.mean():.1f} max {cnt.max()} of {cap}")
+    # ragged rows, per-sequence sizes, and a budget smaller than what passes
+    lens = rng.integers(0, cap + 1, B).astype(np.int32)
+    lens[-1] = 0
+    sizes = np.maximum(lens, 1).astype(np.int32)
+    threshold_case(gpu, oracle, w, beta, sizes, cap, lens=lens)
+    threshold_case(gpu, oracle, w, beta * 0.5, cap, max(int(cnt.max()) // 2, 1))
+    threshold_case(gpu, oracle, w, beta, cap, 0)
+
+
+def test_threshold_is_strict_and_handles_all_or_nothing(gpu, oracle):
+    say("\n[case] threshold_select: weights equal to the threshold, all kept, none kept")
+    w = np.full((2, 4, 2048), 1.0 / 2048, np.float32)          # 2^-11 is exact: equal to beta/size at beta = 1
+    assert threshold_case(gpu, oracle, w, 1.0, 2048, 2048).max() == 0
+    assert threshold_case(gpu, oracle, w, 0.999, 2048, 2048).min() == 2048
+    assert threshold_case(gpu, oracle, w, 1.0, 4096, 2048).min() == 2048   # size is an argument, not the row length
+    w[:, :, 1000] = np.float32(1.0 / 2048) + np.float32(2.0 ** -34)        # one ulp above the threshold
+    cnt = threshold_case(gpu, oracle, w, 1.0, 2048, 2048)
+    assert cnt.min() == 1 and cnt.max() == 1
+
+
+# ------------------------------------------------------------------------ the chain, over decode steps
+
+def test_decode_steps_maw_then_threshold_then_sparse_attention(gpu, oracle):
+    """Alg. 1 over a few decode steps: every step the window grows by one token, A_gpu updates the moving
+    average, and at the end the oldest l_evict entries are filtered by MAW > beta / window size; the
+    kept entries are then attended sparsely (Alg. 2, cpu_attention).  Both sides run the whole chain
+    on their own from the same seeded inputs."""
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=1200, P=64, k=8)
+    steps, alpha, beta, l_evict = 5, 0.3, 1.0, 512
+    say(f"\n[case] decode loop: {steps} steps, alpha={alpha}, beta={beta}, evict {l_evict} of {cfg.W}")
+    L = wl.make_layer(cfg)
+    tw = otier(oracle, L.window)
+    D = runner.DeviceLayer.upload(L)
+    dev = "cuda:0"
+    f32 = dict(dtype=torch.float32, device=dev)
+    ws = hgca.alloc_workspace(D.shape, cfg.W, 0, l_evict, dev)
+    o, lse = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32), torch.empty(cfg.B, cfg.Hq, **f32)
+    a_gpu = torch.empty(cfg.B, cfg.Hq, cfg.W, **f32)
+    maw = torch.zeros(cfg.B, cfg.Hq, cfg.W, **f32)
+    maw_ref = np.zeros((cfg.B, cfg.Hq, cfg.W))
+    base = np.array([cfg.W - steps, cfg.W - steps - 300], np.int32)   # window lengths before the first step
+    for t in range(steps):
+        lens = (base + t + 1).astype(np.int32)
+        q_t = wl.make_layer(cfg, layer=t + 1).q                 # a fresh seeded query per step
+        n_new = int(lens.max()) if t == 0 else 1               # first step: every entry is a first observation
+        D.window.seq_lens = torch.from_numpy(lens).to(dev)
+        hgca.dense_window_attn_weights(D.shape, runner._to_gpu(q_t, dev), D.window, o, lse, a_gpu, ws)
+        hgca.maw_update(D.shape, maw, a_gpu, D.window.seq_lens, cfg.W, n_new, alpha)
+        tw.seq_lens = lens
+        a_ref = oracle.window_weights(q_t, tw, L.scale)
+        maw_ref = oracle.maw_update(maw_ref, a_ref, alpha, lens=lens, n_new=n_new)
+    torch.cuda.synchronize()
+    err = np.max(np.abs(maw.double().cpu().numpy() - maw_ref))
+    say(f"    max|dMAW| after {steps} steps = {err:.3e}")
+    assert err <= W_TOL["bf16"]
+
+    evict = np.full(cfg.B, l_evict, np.int32)
+    idx = torch.empty(cfg.B, cfg.Hq, l_evict, dtype=torch.int32, device=dev)
+    cnt = torch.empty(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
+    hgca.threshold_select(D.shape, maw, torch.from_numpy(evict).to(dev), cfg.W, D.window.seq_lens, beta, l_evict,
+                          idx, cnt)
+    torch.cuda.synchronize()
+    idx_ref, cnt_ref = oracle.threshold_select(maw_ref, beta, lens, l_evict, lens=evict)
+    idx_g, cnt_g = idx.cpu().numpy(), cnt.cpu().numpy()
+    say(f"    kept per head: min {cnt_ref.min()} mean {cnt_ref.mean():.1f} max {cnt_ref.max()} of {l_evict}")
+    assert 0 < cnt_ref.min() and cnt_ref.max() < l_evict
+    differing = 0
+    for b in range(cfg.B):
+        thr = beta / lens[b]
+        for h in range(cfg.Hq):
+            got = set(idx_g[b, h, :cnt_g[b, h]].tolist())
+            want = set(idx_ref[b, h, :cnt_ref[b, h]].tolist())
+            assert np.all(np.diff(idx_g[b, h, :cnt_g[b, h]]) > 0) and np.all(idx_g[b, h, cnt_g[b, h]:] == -1)
+            for j in got ^ want:                               # only entries within rounding of the threshold
+                assert abs(maw_ref[b, h, j] - thr) <= 1e-5 * thr
+                differing += 1
+    say(f"    entries decided differently inside the rounding band: {differing}")
+
+    # the salient entries of the evicted block, attended sparsely with the last query
+    o_s, lse_s = torch.empty_like(o), torch.empty_like(lse)
+    hgca.sparse_attn(D.shape, runner._to_gpu(q_t, dev), D.window, idx, cnt, l_evict, o_s, lse_s, ws)
+    torch.cuda.synchronize()
+    if differing == 0:
+        o_ref, l_ref = oracle.attend_indexed(q_t, tw, idx_ref, cnt_ref, L.scale)
+        assert np.max(np.abs(o_s.double().cpu().numpy() - o_ref)) <= 2e-4
+        assert np.max(np.abs(lse_s.double().cpu().numpy() - l_ref)) <= 2e-4
