@@ -149,6 +149,10 @@ def main() -> int:
 
     scores_buf = torch.empty(cfg.B, cfg.Hq, cfg.P, dtype=torch.float32, device=dev)
     sh = layers[0].shape
+    a_gpu = torch.zeros(cfg.B, cfg.Hq, cfg.W, dtype=torch.float32, device=dev)
+    a_maw = torch.zeros_like(a_gpu)
+    thr_idx = torch.empty(cfg.B, cfg.Hq, cfg.W, dtype=torch.int32, device=dev)
+    thr_cnt = torch.empty(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
     calls = {
         "dense_window_attn": lambda L: hgca.dense_window_attn(sh, L.q, L.window, step.o_w, step.lse_w, step.ws_dense),
         "pool_scores": lambda L: hgca.pool_scores(sh, L.q, L.pool, scores_buf),
@@ -160,11 +164,21 @@ def main() -> int:
                                                                step.lse_s, step.ws_sparse,
                                                                sel_scores=step.sel_scores),
         "lse_merge": lambda L: hgca.lse_merge(sh, step.o_s, step.lse_s, step.o_w, step.lse_w, step.o, step.lse),
+        # the paper's own sparsifier (Alg. 1): window weights, their moving average, the beta/size rule
+        "dense_window_attn_weights": lambda L: hgca.dense_window_attn_weights(sh, L.q, L.window, step.o_w, step.lse_w,
+                                                                              a_gpu, step.ws_dense),
+        "maw_update": lambda L: hgca.maw_update(sh, a_maw, a_gpu, L.window.seq_lens, cfg.W, 1, 0.3),
+        "threshold_select": lambda L: hgca.threshold_select(sh, a_maw, L.window.seq_lens, cfg.W, cfg.W, 1.0, cfg.W,
+                                                            thr_idx, thr_cnt),
     }
     call_ms = {name: time_call(fn) for name, fn in calls.items()}
     call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": int(p_lens.sum()) * cfg.Hkv * cfg.d * cfg.elem_bytes,
                   "select_salient": nbytes["select"], "sparse_attn": nbytes["sparse"],
-                  "sparse_attn_given_scores": nbytes["sparse"] - k_gather // 2}
+                  "sparse_attn_given_scores": nbytes["sparse"] - k_gather // 2,
+                  # weights: one fp32 per (head, window token) written as a score, then read and rewritten
+                  "dense_window_attn_weights": nbytes["dense"] + 3 * 4 * cfg.Hq * int(w_lens.sum()),
+                  "maw_update": 3 * 4 * cfg.Hq * int(w_lens.sum()),
+                  "threshold_select": 4 * cfg.Hq * int(w_lens.sum())}
     call_gbps = {n: call_bytes[n] / (call_ms[n] * 1e-3) / 1e9 for n in call_bytes}
     log("[bench] per call (ms, moved GB/s): " + ", ".join(
         f"{n}={call_ms[n]:.4f}" + (f"/{call_gbps[n]:.0f}" if n in call_gbps else "") for n in call_ms))

@@ -127,6 +127,20 @@ int hgca_select_salient(const hgca_shape *shape, const void *q,
                         float *sel_scores_out,
                         void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The second pass of hgca_select_salient on scores the caller supplies (Sec.
+ * 3.2.2: the sparsifier ranks entries by a per-head relevance value, which may
+ * as well be the moving average of attention weights that hgca_maw_update
+ * keeps): per (b, h) row of scores (device fp32 [B,Hq,cap], 16-byte aligned,
+ * finite values; with infinities or NaN the selection is unspecified) keep the k_b = min(k, len_b) largest of the first len_b =
+ * seq_lens[b] entries (all `cap` if seq_lens is NULL).  Tie rule, budgets,
+ * k_max, idx_out, cnt_out and sel_scores_out as in hgca_select_salient.  Only
+ * batch and n_q_heads of `shape` are used. */
+int hgca_select_topk(const hgca_shape *shape, const float *scores,
+                     const int32_t *seq_lens, int32_t cap,
+                     const int32_t *k_per_seq, int32_t k_uniform,
+                     int32_t k_max, int32_t *idx_out, int32_t *cnt_out,
+                     float *sel_scores_out, void *hip_stream);
+
 /* Per-head sparse attention (Sec. 3.3 "CPU-local sparse attention"; Alg. 2,
  * cpu_attention): softmax attention of query head (b,h) over pool rows
  * idx[b,h,0 .. cnt[b,h]).  Entries at or beyond cnt[b,h] are ignored; the

@@ -57,7 +57,7 @@ def lib():
         for name in ("oracle_scores", "oracle_attend_all", "oracle_attend_indexed",
                      "oracle_attend_union", "oracle_select", "oracle_merge",
                      "oracle_hybrid_step", "oracle_num_threads", "oracle_window_weights",
-                     "oracle_maw_update", "oracle_threshold_select"):
+                     "oracle_maw_update", "oracle_threshold_select", "oracle_select_given"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -256,3 +256,16 @@ def threshold_select(w, beta: float, size, k_max: int, lens=None, normalised: bo
                                          ctypes.c_double(beta), _ptr(w), int(k_max), _ptr(idx), _ptr(cnt),
                                          _ptr(wn)), "threshold_select")
     return (idx, cnt, wn) if normalised else (idx, cnt)
+
+
+def select_given(scores, k, k_max: int, lens=None):
+    """Top-k per (b, h) row of caller-supplied scores [B,Hq,cap]; k: int or per-sequence array [B]."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    B, Hq, cap = scores.shape
+    rl = _row_lens(lens, scores.shape)
+    k_rows, k_uni = (None, int(k)) if np.isscalar(k) else (_row_lens(k, scores.shape), 0)
+    idx = np.empty((B, Hq, k_max), dtype=np.int32)
+    cnt = np.empty((B, Hq), dtype=np.int32)
+    _check(lib().oracle_select_given(ctypes.c_int64(B * Hq), int(cap), _ptr(rl), _ptr(k_rows), k_uni, int(k_max),
+                                     _ptr(scores), _ptr(idx), _ptr(cnt)), "select_given")
+    return idx, cnt

@@ -248,6 +248,32 @@ int oracle_select(const oracle_shape *sh, const void *q, const oracle_kv *pool,
     return bad ? -2 : 0;
 }
 
+/* The same ranking on scores the caller supplies (for instance moving averages
+ * of attention weights): rows of [cap] doubles, lens / k per ROW. */
+int oracle_select_given(int64_t rows, int32_t cap, const int32_t *lens,
+                        const int32_t *k_per_row, int32_t k_uniform, int32_t k_max,
+                        const double *scores, int32_t *idx, int32_t *cnt)
+{
+    if (rows < 0 || cap < 0 || k_max < 0 || !scores || !idx || !cnt) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        int32_t n = lens ? lens[r] : cap;
+        int32_t k = k_per_row ? k_per_row[r] : k_uniform;
+        if (k > n) k = n;
+        if (k > k_max) k = k_max;
+        if (k < 0) k = 0;
+        int32_t *out = idx + (size_t)r * k_max;
+        scored *all = (scored *)malloc(((size_t)n + 1) * sizeof *all);
+        for (int32_t t = 0; t < n; ++t) { all[t].s = scores[(size_t)r * cap + t]; all[t].t = t; }
+        qsort(all, (size_t)n, sizeof *all, by_score_desc_then_pos);
+        for (int32_t j = 0; j < k; ++j) out[j] = all[j].t;
+        qsort(out, (size_t)k, sizeof *out, by_int32);
+        for (int32_t j = k; j < k_max; ++j) out[j] = -1;
+        cnt[r] = k;
+        free(all);
+    }
+    return 0;
+}
+
 int oracle_merge(int64_t n_rows, int32_t d,
                  const double *o_a, const double *lse_a,
                  const double *o_b, const double *lse_b,

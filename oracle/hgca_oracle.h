@@ -109,6 +109,12 @@ int oracle_select(const oracle_shape *sh, const void *q, const oracle_kv *pool,
                   const int32_t *k_per_seq, int32_t k_uniform, int32_t k_max,
                   int round_scores_to_f32, int32_t *idx, int32_t *cnt);
 
+/* The same ranking (score descending, lower position first on ties, output
+ * ascending) on caller-supplied scores [rows, cap]; lens and k per ROW. */
+int oracle_select_given(int64_t rows, int32_t cap, const int32_t *lens,
+                        const int32_t *k_per_row, int32_t k_uniform, int32_t k_max,
+                        const double *scores, int32_t *idx, int32_t *cnt);
+
 /* merge_state on n_rows independent (batch, head) rows of width d. */
 int oracle_merge(int64_t n_rows, int32_t d,
                  const double *o_a, const double *lse_a,

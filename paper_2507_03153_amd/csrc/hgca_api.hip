@@ -294,6 +294,30 @@ int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_vi
     return from_hip(launch_select(se, s));
 }
 
+int hgca_select_topk(const hgca_shape *shape, const float *scores, const int32_t *seq_lens, int32_t cap,
+                     const int32_t *k_per_seq, int32_t k_uniform, int32_t k_max, int32_t *idx_out, int32_t *cnt_out,
+                     float *sel_scores_out, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (cap < 0 || k_max < 0) return HGCA_ERR_INVALID_ARG;
+    if (!k_per_seq && (k_uniform < 0 || std::min(k_uniform, cap) > k_max)) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return HGCA_OK;
+    if (!cnt_out || (k_max > 0 && !idx_out) || (cap > 0 && (!scores || !aligned16(scores)))) return HGCA_ERR_INVALID_ARG;
+    SelectArgs se{};
+    se.sh = to_dev(shape);
+    se.kv.seq_lens = seq_lens;
+    se.kv.cap = cap;
+    se.scores = scores;
+    se.k_per_seq = k_per_seq;
+    se.k_uniform = k_uniform;
+    se.k_max = k_max;
+    se.idx = idx_out;
+    se.cnt = cnt_out;
+    se.sel_scores = sel_scores_out;
+    return from_hip(launch_select(se, static_cast<hipStream_t>(hip_stream)));
+}
+
 int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *idx,
                      const int32_t *cnt, int32_t k_max, const float *sel_scores, float *o_out, float *lse_out,
                      void *ws, size_t ws_bytes, void *hip_stream)

@@ -22,7 +22,7 @@ _LIB_PATH = os.environ.get("HGCA_LIB") or os.path.join(os.path.dirname(os.path.a
 
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
-           "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select")
+           "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk")
 
 
 class Shape(ctypes.Structure):
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_lse_merge.argtypes = [ps, vp, vp, vp, vp, vp, i32, vp, vp]
         L.hgca_dense_window_attn_weights.restype = ctypes.c_int
         L.hgca_dense_window_attn_weights.argtypes = [ps, vp, pk, vp, vp, vp, vp, sz, vp]
+        L.hgca_select_topk.restype = ctypes.c_int
+        L.hgca_select_topk.argtypes = [ps, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
         L.hgca_maw_update.restype = ctypes.c_int
         L.hgca_maw_update.argtypes = [ps, vp, vp, vp, i32, i32, ctypes.c_float, vp]
         L.hgca_threshold_select.restype = ctypes.c_int
@@ -247,3 +249,18 @@ def threshold_select(shape: Shape, weights, seq_lens, cap: int, size, beta: floa
     _check(lib().hgca_threshold_select(ctypes.byref(shape), _ptr(weights), _ptr(seq_lens), int(cap), size_ptr,
                                        size_uni, float(beta), int(k_max), _ptr(idx_out), _ptr(cnt_out),
                                        _ptr(w_norm_out), _stream(stream)), "hgca_threshold_select")
+
+
+def select_topk(shape: Shape, scores, seq_lens, cap: int, k, k_max: int, idx_out, cnt_out, sel_scores_out=None,
+                stream=None) -> None:
+    """Per-head top-k of caller-supplied fp32 scores [B,Hq,cap]; k: int or int32 GPU tensor [B]."""
+    for t in (scores, idx_out, cnt_out) + tuple(x for x in (seq_lens, sel_scores_out) if x is not None):
+        _require_gpu(t)
+    if isinstance(k, torch.Tensor):
+        _require_gpu(k)
+        k_ptr, k_uni = _ptr(k), 0
+    else:
+        k_ptr, k_uni = None, int(k)
+    _check(lib().hgca_select_topk(ctypes.byref(shape), _ptr(scores), _ptr(seq_lens), int(cap), k_ptr, k_uni, int(k_max),
+                                  _ptr(idx_out), _ptr(cnt_out), _ptr(sel_scores_out), _stream(stream)),
+           "hgca_select_topk")

@@ -174,3 +174,18 @@ def test_sparsifier_entry_points_reject_bad_arguments(hg):
     assert thr(cnt=None) == hg.ERR_INVALID_ARG
     empty = hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088)
     assert L.hgca_threshold_select(byref(empty), None, None, 64, None, 64, 1.0, 64, None, None, None, None) == hg.OK
+
+
+def test_select_topk_rejects_bad_arguments(hg):
+    L = hg.lib()
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+
+    def topk(scores=FAKE, cap=64, k=8, k_max=8, idx=FAKE, cnt=FAKE):
+        return L.hgca_select_topk(ctypes.byref(sh), scores, None, cap, None, k, k_max, idx, cnt, None, None)
+    assert topk(scores=None) == hg.ERR_INVALID_ARG
+    assert topk(scores=ODD) == hg.ERR_INVALID_ARG
+    assert topk(cap=-1) == hg.ERR_INVALID_ARG
+    assert topk(k=-1) == hg.ERR_INVALID_ARG
+    assert topk(k=9) == hg.ERR_INVALID_ARG                     # budget beyond the row length of idx_out
+    assert topk(idx=None) == hg.ERR_INVALID_ARG
+    assert topk(cnt=None) == hg.ERR_INVALID_ARG

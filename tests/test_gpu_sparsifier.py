@@ -251,3 +251,41 @@ def test_decode_steps_maw_then_threshold_then_sparse_attention(gpu, oracle):
         o_ref, l_ref = oracle.attend_indexed(q_t, tw, idx_ref, cnt_ref, L.scale)
         assert np.max(np.abs(o_s.double().cpu().numpy() - o_ref)) <= 2e-4
         assert np.max(np.abs(lse_s.double().cpu().numpy() - l_ref)) <= 2e-4
+
+
+# ------------------------------------------------------------------------ top-k on supplied scores
+
+@pytest.mark.parametrize("B,Hq,cap,k,kind", [
+    (2, 8, 700, 100, "normal"), (2, 4, 4097, 512, "maw"), (1, 4, 33000, 1200, "maw"), (3, 2, 64, 64, "coarse"),
+    (8, 32, 4096, 409, "maw"),
+])
+def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kind):
+    torch, hgca, _ = gpu
+    say(f"\n[case] select_topk B={B} Hq={Hq} cap={cap} k={k} scores={kind}")
+    rng = np.random.default_rng(300 + cap)
+    z = rng.standard_normal((B, Hq, cap))
+    if kind == "maw":                                           # weights of a peaked softmax: many tiny values, exact zeros
+        s = softmax(12.0 * z, axis=-1).astype(np.float32)
+        s[s < 1e-12] = 0.0
+    elif kind == "coarse":
+        s = np.round(z, 1).astype(np.float32)                   # plenty of exact ties
+    else:
+        s = z.astype(np.float32)
+    lens = rng.integers(0, cap + 1, B).astype(np.int32)
+    lens[0] = cap
+    sh = hgca.Shape(hgca.BF16, B, Hq, Hq, 128, 1.0)
+    dev = "cuda:0"
+    s_dev = torch.from_numpy(s).to(dev)
+    for use_lens in (False, True):
+        idx = torch.full((B, Hq, k), -7, dtype=torch.int32, device=dev)
+        cnt = torch.full((B, Hq), -7, dtype=torch.int32, device=dev)
+        sel = torch.full((B, Hq, k), float("nan"), dtype=torch.float32, device=dev)
+        hgca.select_topk(sh, s_dev, torch.from_numpy(lens).to(dev) if use_lens else None, cap, k, k, idx, cnt, sel)
+        torch.cuda.synchronize()
+        idx_ref, cnt_ref = oracle.select_given(s, k, k, lens=lens if use_lens else None)
+        idx, cnt, sel = idx.cpu().numpy(), cnt.cpu().numpy(), sel.cpu().numpy()
+        assert np.array_equal(cnt, cnt_ref)
+        assert np.array_equal(idx, idx_ref)
+        kept = np.arange(k)[None, None, :] < cnt[:, :, None]
+        want = np.take_along_axis(s, np.where(kept, idx, 0).astype(np.int64), axis=2)
+        assert np.array_equal(sel[kept], want[kept])            # the kept entries' own scores, bit for bit

@@ -173,3 +173,38 @@ def test_peaked_head_keeps_fewer_than_flat_head(oracle):
     w = np.stack([softmax(8.0 * z), softmax(0.5 * z)])[None]
     _, cnt = oracle.threshold_select(w, 1.0, 256, 256)
     assert 0 < cnt[0, 0] < cnt[0, 1] < 256
+
+
+# ------------------------------------------------------------ top-k on supplied scores
+
+def test_select_given_matches_stable_argsort_and_the_scoring_select(oracle):
+    rng = np.random.default_rng(13)
+    B, Hq, cap = 3, 4, 61
+    s = np.round(rng.standard_normal((B, Hq, cap)), 1)            # rounded: plenty of exact ties
+    lens = np.array([61, 17, 0], np.int32)
+    ks = np.array([10, 30, 5], np.int32)
+    idx, cnt = oracle.select_given(s, ks, 32, lens=lens)
+    for b in range(B):
+        kb = min(ks[b], lens[b])
+        for h in range(Hq):
+            order = np.argsort(-s[b, h, :lens[b]], kind="stable")[:kb]   # stable: lower position first on ties
+            assert cnt[b, h] == kb
+            assert idx[b, h, :kb].tolist() == sorted(order.tolist())
+            assert np.all(idx[b, h, kb:] == -1)
+    # fed the oracle's own scores it reproduces the scoring selection
+    q, K = rand(rng, 2, 4, 8), rand(rng, 2, 2, 40, 8)
+    t = tier(oracle, K, K)
+    sc = oracle.scores(q, t, 0.4)
+    i1, c1 = oracle.select(q, t, 7, 7, 0.4, round_scores_to_f32=False)
+    i2, c2 = oracle.select_given(sc, 7, 7)
+    assert np.array_equal(i1, i2) and np.array_equal(c1, c2)
+
+
+def test_select_given_hand_worked(oracle):
+    s = np.array([[[0.1, 0.7, 0.7, -1.0, 0.3]]])
+    idx, cnt = oracle.select_given(s, 2, 3)
+    assert idx[0, 0].tolist() == [1, 2, -1] and cnt[0, 0] == 2
+    idx, cnt = oracle.select_given(s, 1, 1)
+    assert idx[0, 0].tolist() == [1]                              # tie: the lower position is kept
+    idx, cnt = oracle.select_given(s, 3, 3)
+    assert idx[0, 0].tolist() == [1, 2, 4]
