@@ -24,8 +24,11 @@
  *    Query head h reads KV head h / (Hq / Hkv).
  *  - A KV tier (`hgca_kv_view`) is contiguous, k/v = [B, Hkv, cap, d], or paged,
  *    k/v = [n_blocks, Hkv, block_size, d] with logical token t of sequence b in
- *    physical block block_table[b * max_blocks + t / block_size], slot
- *    t % block_size.  Valid tokens of sequence b are [0, seq_lens[b]) (all `cap`
+ *    physical block block_table[b * max_blocks + first_block[b] + t / block_size]
+ *    (first_block = NULL counts as 0), slot t % block_size; the caller guarantees
+ *    that the entries a sequence's valid tokens reach lie inside its table row.
+ *    Two tiers may share one table: the window and the older pool of a sequence
+ *    are then two ranges of the same list of blocks (see hgca_cache_state).  Valid tokens of sequence b are [0, seq_lens[b]) (all `cap`
  *    when seq_lens is NULL).  The order of tokens inside a tier does not matter
  *    to the result (softmax attention is a function of the key set).  A tier
  *    holds fewer than 2^32 rows (B*Hkv*cap, or n_blocks*Hkv*block_size).
@@ -77,6 +80,8 @@ typedef struct {
     int32_t cap;                  /* capacity in tokens per sequence (logical)         */
     int32_t block_size;           /* paged only: tokens per block, a multiple of 16    */
     int32_t max_blocks;           /* paged only: row length of block_table             */
+    const int32_t *first_block;   /* paged only, device [B] or NULL (= 0): the tier    */
+                                  /* starts at entry first_block[b] of its table row   */
 } hgca_kv_view;
 
 /* Text for a status code (static storage). */
@@ -232,6 +237,71 @@ int hgca_threshold_select(const hgca_shape *shape, const float *weights,
                           double beta, int32_t k_max,
                           int32_t *idx_out, int32_t *cnt_out, float *w_norm_out,
                           void *hip_stream);
+
+/* ---- KV manager across decode steps (Alg. 1; Sec. 3.2.1 retention and
+ * offload, Sec. 3.2.2 sparsification). ----
+ *
+ * In the paper the recent window is a circular buffer of fixed-size blocks in
+ * GPU memory and evicted blocks are copied to host memory.  Here both tiers are
+ * ranges of ONE per-sequence list of blocks in HBM: row b of `block_table`
+ * names, in arrival order, the physical blocks of sequence b; the older pool is
+ * its first first_win_block[b] blocks, the window the blocks after them.
+ * Evicting the oldest window block therefore moves a boundary and copies no KV
+ * row.  Views for the attention calls:
+ *   window = { k_blocks, v_blocks, win_lens,  block_table, cap = win_blocks *
+ *              block_size, block_size, max_blocks, first_block = first_win_block }
+ *   pool   = { k_blocks, v_blocks, pool_lens, block_table, cap = pool_cap,
+ *              block_size, max_blocks, first_block = NULL }
+ * All pointers are device memory owned by the caller; the struct itself is host
+ * memory read during the call.  Arrays marked (rw) are updated by the calls. */
+typedef struct {
+    void          *k_blocks, *v_blocks; /* [n_blocks, Hkv, block_size, d], dtype of the shape (rw) */
+    const int32_t *block_table;         /* [B, max_blocks]: blocks of each sequence, oldest first   */
+    int32_t       *first_win_block;     /* [B] (rw) first window block = number of pool blocks      */
+    int32_t       *win_lens;            /* [B] (rw) tokens in the window                            */
+    int32_t       *pool_lens;           /* [B] (rw) tokens in the pool = first_win_block*block_size */
+    float         *a_maw;               /* [B, Hq, win_blocks*block_size] (rw) moving average of    */
+                                        /* attention weights, by window position                    */
+    int32_t       *ctx_idx;             /* [B, Hq, k_max] (rw) salient pool positions, ascending    */
+    int32_t       *ctx_cnt;             /* [B, Hq] (rw) their number                                */
+    float         *a_evicted;           /* optional [B, Hq, pool_cap] (rw): moving average of every */
+                                        /* evicted entry at its pool position; NULL to skip         */
+    int32_t       *plan;                /* [B, 4] scratch of hgca_kv_evict                          */
+    int32_t       *status;              /* [1] (rw) sticky HGCA_CACHE_* bits, 0 = consistent        */
+    int32_t block_size;                 /* tokens per block, a multiple of 16                       */
+    int32_t max_blocks;                 /* row length of block_table                                */
+    int32_t win_blocks;                 /* blk_num of Alg. 1: l_max = win_blocks * block_size       */
+    int32_t k_max;                      /* row length of ctx_idx                                    */
+    int32_t pool_cap;                   /* capacity of the pool view and row length of a_evicted    */
+} hgca_cache_state;
+
+enum {
+    HGCA_CACHE_WINDOW_FULL = 1,   /* append on a window that already holds l_max tokens: token dropped  */
+    HGCA_CACHE_CONTEXT_FULL = 2,  /* append beyond the last block of the table row: token dropped        */
+    HGCA_CACHE_LIST_FULL = 4      /* more salient entries than k_max: the later ones were not listed     */
+};
+
+/* Insert the new token's KV entry (Alg. 1, KV_gpu.add(KV_in); Alg. 2 does it
+ * before gpu_attention so that the window includes the token being decoded):
+ * k_in, v_in are [B, Hkv, d] in shape.dtype, 16-byte aligned; the rows go to
+ * window position win_lens[b], then win_lens[b] grows by one.  `active`
+ * (device [B] or NULL = all) masks sequences that receive no token.  A full
+ * window or table row sets a status bit and drops the token (call hgca_kv_evict
+ * after every step and it cannot happen before the context is exhausted). */
+int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache,
+                   const void *k_in, const void *v_in, const int32_t *active,
+                   void *hip_stream);
+
+/* Eviction and sparsification of Alg. 1, per sequence, decided on the device:
+ * if l_cur = win_lens[b] >= l_max, the oldest l_evict = ceil((l_cur - l_max + 1)
+ * / block_size) * block_size window entries (the printed formula has l_max and
+ * l_cur swapped) become the newest pool entries; for every head the evicted
+ * entries with a_maw > beta / l_cur (strictly; fp64 comparison; A_gpu.size =
+ * l_cur) are appended to ctx_idx as pool positions and the rest of the a_maw row
+ * shifts down by l_evict (vacated entries become 0).  Call it after
+ * hgca_maw_update of the step.  Sequences below l_max are left untouched. */
+int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
+                  double beta, void *hip_stream);
 
 #ifdef __cplusplus
 }

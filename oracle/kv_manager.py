@@ -12,6 +12,8 @@ State (names as in Alg. 1):
     KV_ctx   per head, the salient offloaded entries; kept here as positions into
              KV_cpu (the paper copies them to per-head contiguous storage, which
              holds the same entries)                                ctx[h] = int array
+    A_evict  the moving averages that travelled with the evicted entries (Sec. 3.2.1:
+             the MAW is transferred alongside the KV block)         A_cpu_maw [Hq, m]
 
 One decode step (Alg. 2, then Alg. 1):
     KV_gpu' = concat(KV_gpu, KV_in);  O_gpu, lse_g, A_gpu = attention(q, KV_gpu')
@@ -72,6 +74,7 @@ class KvManager:
         self.K_cpu = np.zeros((0, Hkv, d))
         self.V_cpu = np.zeros((0, Hkv, d))
         self.ctx = [np.zeros(0, dtype=np.int64) for _ in range(Hq)]
+        self.A_cpu_maw = np.zeros((Hq, 0))
 
     # ---- Alg. 2, decode branch ---------------------------------------------------------------
     def hybrid_attention(self, q: np.ndarray, k_in: np.ndarray, v_in: np.ndarray):
@@ -108,6 +111,7 @@ class KvManager:
         for h in range(self.Hq):
             ids = np.nonzero(A_evict[h] > self.beta / l_cur)[0]
             self.ctx[h] = np.concatenate([self.ctx[h], base + ids])
+        self.A_cpu_maw = np.concatenate([self.A_cpu_maw, A_evict], axis=1)
         self.K_cpu = np.concatenate([self.K_cpu, K_evict])
         self.V_cpu = np.concatenate([self.V_cpu, V_evict])
         return l_evict

@@ -1,0 +1,75 @@
+"""Plumbing for the KV manager calls: owns the device buffers of one layer's cache state (block pool,
+block table, window / pool lengths, moving averages, per-head salient lists) and enqueues the calls of
+one decode step in the order of the paper's Alg. 2 (attention) and Alg. 1 (management).  Nothing here
+computes: every step is a libhgca call."""
+from __future__ import annotations
+
+import torch
+
+from . import hgca
+
+
+class LayerCache:
+    """Cache state of one attention layer for a batch of B sequences.
+
+    Sequence b owns the blocks block_table[b, :] (here simply b*max_blocks + j); its pool is the first
+    first_win_block[b] of them, its window the following ones."""
+
+    def __init__(self, dtype, B: int, Hq: int, Hkv: int, d: int, block_size: int, win_blocks: int, max_blocks: int,
+                 k_max: int, sm_scale: float, device="cuda:0", keep_evicted_maw: bool = False):
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.B, self.Hq, self.Hkv, self.d = B, Hq, Hkv, d
+        self.block_size, self.win_blocks, self.max_blocks, self.k_max = block_size, win_blocks, max_blocks, k_max
+        self.win_cap = win_blocks * block_size
+        self.pool_cap = max_blocks * block_size
+        self.k_blocks = torch.zeros(B * max_blocks, Hkv, block_size, d, dtype=dtype, device=device)
+        self.v_blocks = torch.zeros_like(self.k_blocks)
+        self.block_table = torch.arange(B * max_blocks, **i32).reshape(B, max_blocks).contiguous()
+        self.first_win_block = torch.zeros(B, **i32)
+        self.win_lens = torch.zeros(B, **i32)
+        self.pool_lens = torch.zeros(B, **i32)
+        self.a_maw = torch.zeros(B, Hq, self.win_cap, **f32)
+        self.ctx_idx = torch.full((B, Hq, max(k_max, 1)), -1, **i32)
+        self.ctx_cnt = torch.zeros(B, Hq, **i32)
+        self.a_evicted = torch.zeros(B, Hq, self.pool_cap, **f32) if keep_evicted_maw else None
+        self.plan = torch.zeros(B, 4, **i32)
+        self.status = torch.zeros(1, **i32)
+        q_like = torch.empty(B, Hq, d, dtype=dtype, device=device)
+        self.shape = hgca.make_shape(q_like, Hkv, sm_scale)
+        p = lambda t: None if t is None else t.data_ptr()
+        self.state = hgca.CacheState(p(self.k_blocks), p(self.v_blocks), p(self.block_table), p(self.first_win_block),
+                                     p(self.win_lens), p(self.pool_lens), p(self.a_maw), p(self.ctx_idx),
+                                     p(self.ctx_cnt), p(self.a_evicted), p(self.plan), p(self.status),
+                                     block_size, max_blocks, win_blocks, k_max, self.pool_cap)
+        self.window = hgca.Tier(self.k_blocks, self.v_blocks, self.win_cap, self.win_lens, self.block_table,
+                                block_size, self.first_win_block)
+        self.pool = hgca.Tier(self.k_blocks, self.v_blocks, self.pool_cap, self.pool_lens, self.block_table,
+                              block_size, None)
+        # per-step outputs and scratch
+        self.o_w, self.lse_w = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
+        self.o_s, self.lse_s = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
+        self.o, self.lse = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
+        self.a_gpu = torch.zeros(B, Hq, self.win_cap, **f32)
+        self.ws_dense = hgca.alloc_workspace(self.shape, self.win_cap, 0, 0, device)
+        self.ws_sparse = hgca.alloc_workspace(self.shape, 0, 0, k_max, device)
+
+    def append(self, k_in, v_in, active=None) -> None:
+        hgca.kv_append(self.shape, self.state, k_in, v_in, active)
+
+    def attend(self, q) -> None:
+        """Alg. 2, decode branch, on a window that already holds the token being decoded."""
+        sh = self.shape
+        hgca.dense_window_attn_weights(sh, q, self.window, self.o_w, self.lse_w, self.a_gpu, self.ws_dense)
+        hgca.sparse_attn(sh, q, self.pool, self.ctx_idx, self.ctx_cnt, self.k_max, self.o_s, self.lse_s, self.ws_sparse)
+        hgca.lse_merge(sh, self.o_s, self.lse_s, self.o_w, self.lse_w, self.o, self.lse)
+
+    def manage(self, alpha: float, beta: float, n_new: int = 1) -> None:
+        """Alg. 1: moving-average update, then eviction and sparsification where a window is full."""
+        hgca.maw_update(self.shape, self.a_maw, self.a_gpu, self.win_lens, self.win_cap, n_new, alpha)
+        hgca.kv_evict(self.shape, self.state, beta)
+
+    def decode_step(self, q, k_in, v_in, alpha: float, beta: float) -> None:
+        self.append(k_in, v_in)
+        self.attend(q)
+        self.manage(alpha, beta)

@@ -68,11 +68,13 @@ __device__ __forceinline__ RowMap make_row_map(uint32_t *s_row, const KvDev &kv,
         m.base = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + t0);
         return m;
     }
+    const int32_t *blocks = nullptr;             // the sequence's table row, from the tier's first block on
+    if (kv.block_table) blocks = kv.block_table + (int64_t)b * kv.max_blocks + (kv.first_block ? kv.first_block[b] : 0);
     for (int j = threadIdx.x; j < nt; j += BLOCK) {
         const int32_t tok = GATHER ? listed[j] : t0 + j;
         uint32_t row;
-        if (kv.block_table) {
-            const int32_t blk = kv.block_table[(int64_t)b * kv.max_blocks + tok / kv.block_size];
+        if (blocks) {
+            const int32_t blk = blocks[tok / kv.block_size];
             row = (uint32_t)(((int64_t)blk * n_kv_heads + kvh) * kv.block_size + tok % kv.block_size);
         } else {
             row = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + tok);

@@ -1,0 +1,132 @@
+// KV manager (Alg. 1) for tiers that live in one block pool in HBM: a sequence's KV entries sit in
+// fixed-size blocks listed, in arrival order, in one row of a block table; the older pool is the
+// first `first_win_block` blocks of the row and the recent window the blocks after them.  Inserting
+// a token writes one K and one V row; evicting the oldest window block moves the boundary: no KV row
+// is copied.  What does move is the per-entry moving average of attention weights, which is kept
+// per window position: the evicted entries' averages are thresholded (Sec. 3.2.2) into the per-head
+// lists of salient pool positions and the rest of the row shifts down.
+#include "hgca_launch.hpp"
+#include "threshold_compact.hpp"
+
+namespace hgca {
+
+namespace {
+
+// One workgroup per sequence: the token's K and V rows of every KV head go to slot len % block_size of
+// window block len / block_size; then the length grows by one.
+__global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const char *k_in, const char *v_in,
+                                                              const int32_t *active, int32_t n_kv_heads,
+                                                              int32_t row_bytes)
+{
+    const int b = blockIdx.x;
+    if (active && !active[b]) return;
+    const int len = c.win_lens[b];
+    const int blk_i = c.first_win_block[b] + len / c.block_size;
+    if (len < 0 || len >= c.win_blocks * c.block_size || blk_i >= c.max_blocks) {   // uniform over the workgroup
+        if (threadIdx.x == 0) atomicOr(c.status, len >= c.win_blocks * c.block_size ? kCacheWindowFull : kCacheContextFull);
+        return;
+    }
+    const int64_t blk = c.block_table[(int64_t)b * c.max_blocks + blk_i];
+    const int slot = len % c.block_size;
+    const int pieces = row_bytes / 16;                         // 16-byte pieces of one row
+    for (int i = threadIdx.x; i < n_kv_heads * pieces; i += kRowBlock) {
+        const int kvh = i / pieces, p = i % pieces;
+        const int64_t dst = ((blk * n_kv_heads + kvh) * c.block_size + slot) * row_bytes + 16 * p;
+        const int64_t src = ((int64_t)b * n_kv_heads + kvh) * row_bytes + 16 * p;
+        *reinterpret_cast<uint4 *>(c.k_blocks + dst) = *reinterpret_cast<const uint4 *>(k_in + src);
+        *reinterpret_cast<uint4 *>(c.v_blocks + dst) = *reinterpret_cast<const uint4 *>(v_in + src);
+    }
+    __syncthreads();                                           // every thread has read `len` by now
+    if (threadIdx.x == 0) c.win_lens[b] = len + 1;
+}
+
+// One thread per sequence decides the eviction (Alg. 1: if l_cur >= l_max, the smallest whole number of
+// blocks that brings the window below l_max), records what the row kernel needs, and moves the boundary.
+__global__ void evict_plan_kernel(CacheDev c, int32_t batch)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    const int l_cur = c.win_lens[b], l_max = c.win_blocks * c.block_size;
+    int n_ev = 0;
+    if (l_cur >= l_max) n_ev = min((l_cur - l_max + c.block_size) / c.block_size, l_cur / c.block_size);
+    const int l_ev = n_ev * c.block_size;
+    const int p_len = c.pool_lens[b];
+    c.plan[4 * b + 0] = l_ev;
+    c.plan[4 * b + 1] = l_cur;
+    c.plan[4 * b + 2] = p_len;
+    c.plan[4 * b + 3] = 0;
+    if (n_ev == 0) return;
+    c.first_win_block[b] += n_ev;
+    c.win_lens[b] = l_cur - l_ev;
+    c.pool_lens[b] = p_len + l_ev;
+}
+
+// One workgroup per (sequence, query head) row of a sequence that evicts: the evicted entries whose moving
+// average exceeds beta / l_cur join the head's list of salient pool positions (appended in position order),
+// optionally the evicted averages are saved at their pool positions, and the row shifts down by l_evict.
+__global__ __launch_bounds__(kRowBlock) void evict_rows_kernel(CacheDev c, int32_t n_q_heads, double beta)
+{
+    __shared__ CompactShared s_compact;
+    const int64_t row = blockIdx.x;
+    const int b = (int)(row / n_q_heads), tid = threadIdx.x;
+    const int l_ev = c.plan[4 * b + 0];
+    if (l_ev == 0) return;
+    const int l_cur = c.plan[4 * b + 1], p_old = c.plan[4 * b + 2];
+    const int win_cap = c.win_blocks * c.block_size;
+    float *maw = c.a_maw + row * win_cap;
+
+    const int start = min(max(c.ctx_cnt[row], 0), c.k_max);
+    float unused = 0.f;
+    const int total = threshold_compact(s_compact, maw, l_ev, beta / (double)l_cur, c.ctx_idx + row * c.k_max, start,
+                                        c.k_max, p_old, nullptr, unused);
+    if (tid == 0) {
+        c.ctx_cnt[row] = min(total, c.k_max);
+        if (total > c.k_max) atomicOr(c.status, kCacheListFull);
+    }
+    if (c.a_evicted) {
+        float *dst = c.a_evicted + row * (int64_t)c.pool_cap + p_old;
+        for (int j = tid; j < l_ev && p_old + j < c.pool_cap; j += kRowBlock) dst[j] = maw[j];
+    }
+    __syncthreads();                                           // the evicted averages have been read
+
+    // shift down: a step reads [t0 + l_ev, ...) which no earlier step has written (they wrote below t0)
+    const int n_stay = l_cur - l_ev;
+    for (int t0 = 0; t0 < l_cur; t0 += kRowStep) {
+        float x[kPerThread];
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) {
+            const int j = t0 + e * kRowBlock + tid;
+            x[e] = j < n_stay ? maw[j + l_ev] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) {
+            const int j = t0 + e * kRowBlock + tid;
+            if (j < l_cur) maw[j] = x[e];                      // entries [n_stay, l_cur) become 0
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
+                            int32_t n_kv_heads, int32_t row_bytes, hipStream_t s)
+{
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(kv_append_kernel, dim3(batch), dim3(kRowBlock), 0, s, c, static_cast<const char *>(k_in),
+                       static_cast<const char *>(v_in), active, n_kv_heads, row_bytes);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s)
+{
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(evict_plan_kernel, dim3((batch + 63) / 64), dim3(64), 0, s, c, batch);
+    hipError_t rc = hipGetLastError();
+    if (rc != hipSuccess) return rc;
+    hipLaunchKernelGGL(evict_rows_kernel, dim3((unsigned)((int64_t)batch * n_q_heads)), dim3(kRowBlock), 0, s, c,
+                       n_q_heads, beta);
+    return hipGetLastError();
+}
+
+}  // namespace hgca

@@ -69,6 +69,7 @@ KvDev to_dev(const hgca_kv_view *v)
     d.v = static_cast<const char *>(v->v);
     d.seq_lens = v->seq_lens;
     d.block_table = v->block_table;
+    d.first_block = v->block_table ? v->first_block : nullptr;
     d.cap = v->cap;
     d.block_size = v->block_table ? v->block_size : 1;
     d.max_blocks = v->block_table ? v->max_blocks : 0;
@@ -390,6 +391,67 @@ int hgca_lse_merge(const hgca_shape *shape, const float *o_a, const float *lse_a
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     return from_hip(launch_merge(shape->head_dim, rows, o_a, lse_a, o_b, lse_b, o_out, o_dtype, lse_out,
                                  static_cast<hipStream_t>(hip_stream)));
+}
+
+namespace {
+
+int check_cache(const hgca_shape *shape, const hgca_cache_state *c, CacheDev *out)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (!c) return HGCA_ERR_INVALID_ARG;
+    if (c->block_size <= 0 || c->max_blocks <= 0 || c->win_blocks <= 0 || c->win_blocks > c->max_blocks || c->k_max < 0 ||
+        c->pool_cap < 0)
+        return HGCA_ERR_INVALID_ARG;
+    if (c->block_size % 16 != 0) return HGCA_ERR_UNSUPPORTED;
+    if (shape->batch > 0 &&
+        (!c->k_blocks || !c->v_blocks || !aligned16(c->k_blocks) || !aligned16(c->v_blocks) || !c->block_table ||
+         !c->first_win_block || !c->win_lens || !c->pool_lens || !c->a_maw || !c->ctx_cnt || !c->plan || !c->status ||
+         (c->k_max > 0 && !c->ctx_idx)))
+        return HGCA_ERR_INVALID_ARG;
+    out->k_blocks = static_cast<char *>(c->k_blocks);
+    out->v_blocks = static_cast<char *>(c->v_blocks);
+    out->block_table = c->block_table;
+    out->first_win_block = c->first_win_block;
+    out->win_lens = c->win_lens;
+    out->pool_lens = c->pool_lens;
+    out->a_maw = c->a_maw;
+    out->ctx_idx = c->ctx_idx;
+    out->ctx_cnt = c->ctx_cnt;
+    out->plan = c->plan;
+    out->status = c->status;
+    out->a_evicted = c->a_evicted;
+    out->block_size = c->block_size;
+    out->max_blocks = c->max_blocks;
+    out->win_blocks = c->win_blocks;
+    out->k_max = c->k_max;
+    out->pool_cap = c->pool_cap;
+    return HGCA_OK;
+}
+
+}  // namespace
+
+int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache, const void *k_in, const void *v_in,
+                   const int32_t *active, void *hip_stream)
+{
+    CacheDev c{};
+    int rc = check_cache(shape, cache, &c);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if (!k_in || !v_in || !aligned16(k_in) || !aligned16(v_in)) return HGCA_ERR_INVALID_ARG;
+    const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
+    return from_hip(launch_kv_append(c, k_in, v_in, active, shape->batch, shape->n_kv_heads, row_bytes,
+                                     static_cast<hipStream_t>(hip_stream)));
+}
+
+int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache, double beta, void *hip_stream)
+{
+    CacheDev c{};
+    int rc = check_cache(shape, cache, &c);
+    if (rc != HGCA_OK) return rc;
+    if (!(beta >= 0.0)) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return HGCA_OK;
+    return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, static_cast<hipStream_t>(hip_stream)));
 }
 
 }  // extern "C"

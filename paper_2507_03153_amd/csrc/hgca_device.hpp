@@ -15,6 +15,7 @@ struct KvDev {
     const char *k, *v;
     const int32_t *seq_lens;
     const int32_t *block_table;
+    const int32_t *first_block;     // paged only: per-sequence offset into the table row, or null
     int32_t cap, block_size, max_blocks;
 };
 

@@ -90,4 +90,22 @@ struct ThresholdArgs {
 };
 hipError_t launch_threshold_select(const ThresholdArgs &a, int64_t n_rows, hipStream_t s);
 
+// ---- KV manager over a block pool (mirrors hgca_cache_state; all pointers device memory) ----
+
+constexpr int32_t kCacheWindowFull = 1, kCacheContextFull = 2, kCacheListFull = 4;   // sticky bits of *status
+
+struct CacheDev {
+    char *k_blocks, *v_blocks;
+    const int32_t *block_table;
+    int32_t *first_win_block, *win_lens, *pool_lens;
+    float *a_maw;
+    int32_t *ctx_idx, *ctx_cnt, *plan, *status;
+    float *a_evicted;          // optional [B*Hq, pool_cap]
+    int32_t block_size, max_blocks, win_blocks, k_max, pool_cap;
+};
+
+hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
+                            int32_t n_kv_heads, int32_t row_bytes, hipStream_t s);
+hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s);
+
 }  // namespace hgca

@@ -4,19 +4,11 @@
 // All three are streaming passes over [B*Hq, cap] fp32 rows, a few MB per layer-step: one
 // load and at most one store per element, coalesced, no reuse.
 #include "hgca_launch.hpp"
+#include "threshold_compact.hpp"
 
 namespace hgca {
 
 namespace {
-
-constexpr int kRowBlock = 256;
-constexpr int kRowWaves = kRowBlock / kWave;
-constexpr int kPerThread = 4;                    // elements a thread handles per step
-constexpr int kRowStep = kRowBlock * kPerThread;
-
-__device__ __forceinline__ int32_t row_len(const int32_t *seq_lens, int b, int32_t cap) {
-    return seq_lens ? min(max(seq_lens[b], 0), cap) : cap;
-}
 
 // a[row, j] holds the scaled score s_j on entry; on exit the softmax weight e^{s_j - lse_row}
 // (Sec. 2.1, A = softmax(S)) for j < len and 0 beyond.
@@ -58,18 +50,11 @@ __global__ __launch_bounds__(kRowBlock) void maw_update_kernel(float *maw, const
     }
 }
 
-// Number of lanes below this one whose bit is set in `mask`.
-__device__ __forceinline__ int lanes_below(uint64_t mask) {
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
-
-// One workgroup per (sequence, query head) row.  The row is walked in steps of 1024 entries;
-// sub-round e of a step covers entries [e*256, e*256+256) so that loads are coalesced and the
-// output order is the position order.  The comparison is done in fp64 on the exactly widened
-// weight, i.e. with the threshold beta / size at full precision.
+// One workgroup per (sequence, query head) row: the salient positions in ascending order, -1 padding,
+// their count, and optionally the kept weights re-normalised to sum to 1.
 __global__ __launch_bounds__(kRowBlock) void threshold_select_kernel(ThresholdArgs a)
 {
-    __shared__ int s_cnt[2][kPerThread][kRowWaves];   // double-buffered: one barrier per step
+    __shared__ CompactShared s_compact;
     __shared__ float s_sum[kRowWaves];
 
     const int64_t row = blockIdx.x;
@@ -78,46 +63,12 @@ __global__ __launch_bounds__(kRowBlock) void threshold_select_kernel(ThresholdAr
     const int size = a.sizes ? a.sizes[b] : a.size_uniform;
     const double thr = a.beta / (double)size;
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
-    const float *wr = a.w + row * a.cap;
     int32_t *idx = a.idx + row * a.k_max;
     float *wn = a.w_norm ? a.w_norm + row * a.k_max : nullptr;
 
-    int base = 0;                                 // entries kept so far (uniform over the workgroup)
     float my_sum = 0.f;
-    int buf = 0;
-    for (int t0 = 0; t0 < n && base < a.k_max; t0 += kRowStep, buf ^= 1) {
-        float x[kPerThread];
-        bool keep[kPerThread];
-        int below[kPerThread];
-#pragma unroll
-        for (int e = 0; e < kPerThread; ++e) {
-            const int t = t0 + e * kRowBlock + tid;
-            x[e] = t < n ? wr[t] : 0.f;
-            keep[e] = t < n && (double)x[e] > thr;
-            const uint64_t mask = __ballot(keep[e]);
-            below[e] = lanes_below(mask);
-            if (lane == 0) s_cnt[buf][e][w] = __popcll(mask);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < kPerThread; ++e) {
-            int before = 0, total = 0;
-#pragma unroll
-            for (int v = 0; v < kRowWaves; ++v) {
-                const int c = s_cnt[buf][e][v];
-                before += v < w ? c : 0;
-                total += c;
-            }
-            const int pos = base + before + below[e];
-            if (keep[e] && pos < a.k_max) {
-                idx[pos] = t0 + e * kRowBlock + tid;
-                if (wn) wn[pos] = x[e];
-                my_sum += x[e];
-            }
-            base += total;
-        }
-    }
-    const int kept = min(base, a.k_max);
+    const int passing = threshold_compact(s_compact, a.w + row * a.cap, n, thr, idx, 0, a.k_max, 0, wn, my_sum);
+    const int kept = min(passing, a.k_max);
     for (int j = kept + tid; j < a.k_max; j += kRowBlock) {
         idx[j] = -1;
         if (wn) wn[j] = 0.f;

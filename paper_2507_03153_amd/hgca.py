@@ -22,7 +22,9 @@ _LIB_PATH = os.environ.get("HGCA_LIB") or os.path.join(os.path.dirname(os.path.a
 
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
-           "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk")
+           "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
+           "hgca_kv_append", "hgca_kv_evict")
+CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
 class Shape(ctypes.Structure):
@@ -33,7 +35,14 @@ class Shape(ctypes.Structure):
 class KvView(ctypes.Structure):
     _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
                 ("block_table", ctypes.c_void_p), ("cap", ctypes.c_int32), ("block_size", ctypes.c_int32),
-                ("max_blocks", ctypes.c_int32)]
+                ("max_blocks", ctypes.c_int32), ("first_block", ctypes.c_void_p)]
+
+
+class CacheState(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("k_blocks", "v_blocks", "block_table", "first_win_block", "win_lens",
+                                               "pool_lens", "a_maw", "ctx_idx", "ctx_cnt", "a_evicted", "plan",
+                                               "status")] + \
+               [(n, ctypes.c_int32) for n in ("block_size", "max_blocks", "win_blocks", "k_max", "pool_cap")]
 
 
 class HgcaError(RuntimeError):
@@ -75,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.hgca_dense_window_attn_weights.argtypes = [ps, vp, pk, vp, vp, vp, vp, sz, vp]
         L.hgca_select_topk.restype = ctypes.c_int
         L.hgca_select_topk.argtypes = [ps, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
+        L.hgca_kv_append.restype = ctypes.c_int
+        L.hgca_kv_append.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp]
+        L.hgca_kv_evict.restype = ctypes.c_int
+        L.hgca_kv_evict.argtypes = [ps, ctypes.POINTER(CacheState), ctypes.c_double, vp]
         L.hgca_maw_update.restype = ctypes.c_int
         L.hgca_maw_update.argtypes = [ps, vp, vp, vp, i32, i32, ctypes.c_float, vp]
         L.hgca_threshold_select.restype = ctypes.c_int
@@ -101,14 +114,15 @@ class Tier:
     seq_lens: Optional[torch.Tensor] = None      # int32 [B]
     block_table: Optional[torch.Tensor] = None   # int32 [B,max_blocks]
     block_size: int = 0
+    first_block: Optional[torch.Tensor] = None   # int32 [B]: the tier starts at this entry of its table row
 
     def view(self) -> KvView:
-        for t in (self.k, self.v, self.seq_lens, self.block_table):
+        for t in (self.k, self.v, self.seq_lens, self.block_table, self.first_block):
             if t is not None:
                 _require_gpu(t)
         mb = 0 if self.block_table is None else int(self.block_table.shape[1])
         return KvView(_ptr(self.k), _ptr(self.v), _ptr(self.seq_lens), _ptr(self.block_table),
-                      int(self.cap), int(self.block_size), mb)
+                      int(self.cap), int(self.block_size), mb, _ptr(self.first_block))
 
 
 def _require_gpu(t: torch.Tensor) -> None:
@@ -264,3 +278,17 @@ def select_topk(shape: Shape, scores, seq_lens, cap: int, k, k_max: int, idx_out
     _check(lib().hgca_select_topk(ctypes.byref(shape), _ptr(scores), _ptr(seq_lens), int(cap), k_ptr, k_uni, int(k_max),
                                   _ptr(idx_out), _ptr(cnt_out), _ptr(sel_scores_out), _stream(stream)),
            "hgca_select_topk")
+
+
+def kv_append(shape: Shape, cache: CacheState, k_in, v_in, active=None, stream=None) -> None:
+    """Writes the new token's K/V rows [B,Hkv,d] at the end of every (active) sequence's window."""
+    for t in (k_in, v_in) + (() if active is None else (active,)):
+        _require_gpu(t)
+    _check(lib().hgca_kv_append(ctypes.byref(shape), ctypes.byref(cache), _ptr(k_in), _ptr(v_in), _ptr(active),
+                                _stream(stream)), "hgca_kv_append")
+
+
+def kv_evict(shape: Shape, cache: CacheState, beta: float, stream=None) -> None:
+    """Sequences whose window reached l_max hand their oldest block(s) to the pool and sparsify them."""
+    _check(lib().hgca_kv_evict(ctypes.byref(shape), ctypes.byref(cache), float(beta), _stream(stream)),
+           "hgca_kv_evict")

@@ -49,7 +49,7 @@ ODD = ctypes.c_void_p(0x10004)
 
 
 def _view(hg, cap=64, k=FAKE, v=FAKE, table=None, bs=0, mb=0):
-    return hg.KvView(k, v, None, table, cap, bs, mb)
+    return hg.KvView(k, v, None, table, cap, bs, mb, None)
 
 
 def _dense(hg, sh, view, q=FAKE, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40):
@@ -189,3 +189,35 @@ def test_select_topk_rejects_bad_arguments(hg):
     assert topk(k=9) == hg.ERR_INVALID_ARG                     # budget beyond the row length of idx_out
     assert topk(idx=None) == hg.ERR_INVALID_ARG
     assert topk(cnt=None) == hg.ERR_INVALID_ARG
+
+
+def test_kv_manager_entry_points_reject_bad_arguments(hg):
+    L = hg.lib()
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    p = 0x10000
+
+    def state(**kw):
+        f = dict(k_blocks=p, v_blocks=p, block_table=p, first_win_block=p, win_lens=p, pool_lens=p, a_maw=p,
+                 ctx_idx=p, ctx_cnt=p, a_evicted=None, plan=p, status=p,
+                 block_size=16, max_blocks=8, win_blocks=4, k_max=64, pool_cap=128)
+        f.update(kw)
+        return hg.CacheState(**f)
+
+    def append(st, k=FAKE, v=FAKE):
+        return L.hgca_kv_append(ctypes.byref(sh), ctypes.byref(st), k, v, None, None)
+
+    def evict(st, beta=1.0):
+        return L.hgca_kv_evict(ctypes.byref(sh), ctypes.byref(st), beta, None)
+    for bad in (dict(block_size=0), dict(win_blocks=0), dict(win_blocks=9), dict(max_blocks=0), dict(k_max=-1),
+                dict(pool_cap=-1), dict(k_blocks=None), dict(v_blocks=0x10004), dict(block_table=None),
+                dict(win_lens=None), dict(a_maw=None), dict(ctx_idx=None), dict(plan=None), dict(status=None)):
+        assert append(state(**bad)) == hg.ERR_INVALID_ARG, bad
+        assert evict(state(**bad)) == hg.ERR_INVALID_ARG, bad
+    assert append(state(block_size=24)) == hg.ERR_UNSUPPORTED
+    assert append(state(), k=None) == hg.ERR_INVALID_ARG
+    assert append(state(), v=ODD) == hg.ERR_INVALID_ARG
+    assert evict(state(), beta=-0.5) == hg.ERR_INVALID_ARG
+    assert evict(state(), beta=float("nan")) == hg.ERR_INVALID_ARG
+    assert L.hgca_kv_append(ctypes.byref(sh), None, FAKE, FAKE, None, None) == hg.ERR_INVALID_ARG
+    empty = hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088)
+    assert L.hgca_kv_evict(ctypes.byref(empty), ctypes.byref(state(k_blocks=None)), 1.0, None) == hg.OK
