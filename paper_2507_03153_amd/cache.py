@@ -16,11 +16,13 @@ class LayerCache:
     first_win_block[b] of them, its window the following ones."""
 
     def __init__(self, dtype, B: int, Hq: int, Hkv: int, d: int, block_size: int, win_blocks: int, max_blocks: int,
-                 k_max: int, sm_scale: float, device="cuda:0", keep_evicted_maw: bool = False):
+                 k_max: int, sm_scale: float, device="cuda:0", keep_evicted_maw: bool = False,
+                 fused_tail: bool = True):
         i32 = dict(dtype=torch.int32, device=device)
         f32 = dict(dtype=torch.float32, device=device)
         self.B, self.Hq, self.Hkv, self.d = B, Hq, Hkv, d
         self.block_size, self.win_blocks, self.max_blocks, self.k_max = block_size, win_blocks, max_blocks, k_max
+        self.fused_tail = fused_tail      # one fold of all split partials instead of sparse fold + merge
         self.win_cap = win_blocks * block_size
         self.pool_cap = max_blocks * block_size
         self.k_blocks = torch.zeros(B * max_blocks, Hkv, block_size, d, dtype=dtype, device=device)
@@ -61,8 +63,13 @@ class LayerCache:
         """Alg. 2, decode branch, on a window that already holds the token being decoded."""
         sh = self.shape
         hgca.dense_window_attn_weights(sh, q, self.window, self.o_w, self.lse_w, self.a_gpu, self.ws_dense)
-        hgca.sparse_attn(sh, q, self.pool, self.ctx_idx, self.ctx_cnt, self.k_max, self.o_s, self.lse_s, self.ws_sparse)
-        hgca.lse_merge(sh, self.o_s, self.lse_s, self.o_w, self.lse_w, self.o, self.lse)
+        if self.fused_tail:        # the window's split partials are still in ws_dense: fold them with the sparse ones
+            hgca.sparse_attn(sh, q, self.pool, self.ctx_idx, self.ctx_cnt, self.k_max, None, None, self.ws_sparse)
+            hgca.lse_merge_splits(sh, self.win_cap, self.ws_dense, self.k_max, self.ws_sparse, self.o, self.lse)
+        else:
+            hgca.sparse_attn(sh, q, self.pool, self.ctx_idx, self.ctx_cnt, self.k_max, self.o_s, self.lse_s,
+                             self.ws_sparse)
+            hgca.lse_merge(sh, self.o_s, self.lse_s, self.o_w, self.lse_w, self.o, self.lse)
 
     def manage(self, alpha: float, beta: float, n_new: int = 1) -> None:
         """Alg. 1: moving-average update, then eviction and sparsification where a window is full."""

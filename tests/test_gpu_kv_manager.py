@@ -45,7 +45,7 @@ def make_tokens(seed, T, B, Hq, Hkv, d, boost=3.0):
 
 
 def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, prefill, steps, alpha, beta, seed,
-             expect_list_full=False):
+             expect_list_full=False, fused_tail=True):
     torch, hgca, runner, cache = gpu
     dev = "cuda:0"
     T = max(prefill) + steps
@@ -55,7 +55,7 @@ def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, pref
     qf, kf, vf = (wl.bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
     scale = 1.0 / np.sqrt(d)
     C = cache.LayerCache(torch.bfloat16, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, scale, dev,
-                         keep_evicted_maw=True)
+                         keep_evicted_maw=True, fused_tail=fused_tail)
     mgr = [KvManager(Hq, Hkv, d, win_blocks, block_size, alpha, beta, scale) for _ in range(B)]
 
     # prefill: sequence b starts with prefill[b] < l_max window entries whose moving average is 1/prefill[b]
@@ -140,7 +140,7 @@ def test_decode_loop_ragged_windows_gqa4(gpu):
 
 def test_decode_loop_mha_head_dim_64_blocks_of_32(gpu):
     _, _, status = run_loop(gpu, B=2, Hq=4, Hkv=4, d=64, block_size=32, win_blocks=3, max_blocks=8, k_max=256,
-                            prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12)
+                            prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12, fused_tail=False)
     assert status == 0
 
 
@@ -177,3 +177,34 @@ def test_status_bits_for_full_list_full_window_and_full_context(gpu):
     torch.cuda.synchronize()
     assert int(C.status.cpu()[0]) & hgca.CACHE_CONTEXT_FULL
     assert int(C.pool_lens.cpu()[0]) + int(C.win_lens.cpu()[0]) == 64     # nothing written beyond the row
+
+
+def test_graph_replay_of_the_decode_step_equals_eager(gpu):
+    """The decode step takes every decision on the device, so one captured launch sequence serves every step.
+    Each replay is checked against an eager twin fed the same tokens, with eager work and synchronisation
+    between the replays, across two evictions."""
+    torch, hgca, runner, cache = gpu
+    B, Hq, Hkv, d, bs, wb = 2, 8, 2, 128, 16, 2
+    say("\n[case] HIP graph replay of the decode step vs eager")
+    qb, kb, vb = make_tokens(21, 60, B, Hq, Hkv, d)
+    dev = "cuda:0"
+    mk = lambda: cache.LayerCache(torch.bfloat16, B, Hq, Hkv, d, bs, wb, 8, 96, 1.0 / np.sqrt(d), dev)
+    E, G = mk(), mk()
+    q, k, v = (runner._to_gpu(x[0], dev).clone() for x in (qb, kb, vb))        # static inputs of the graph
+    side = torch.cuda.Stream(device=dev)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                # capture on a non-default stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            G.decode_step(q, k, v, 0.3, 1.0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert int(G.win_lens.cpu()[0]) == 0                         # capturing executes nothing
+    for t in range(60):
+        q.copy_(runner._to_gpu(qb[t], dev)); k.copy_(runner._to_gpu(kb[t], dev)); v.copy_(runner._to_gpu(vb[t], dev))
+        graph.replay()
+        E.decode_step(q, k, v, 0.3, 1.0)
+        torch.cuda.synchronize()
+        for name in ("o", "lse", "a_maw", "ctx_idx", "ctx_cnt", "win_lens", "pool_lens", "first_win_block"):
+            assert torch.equal(getattr(E, name), getattr(G, name)), f"step {t}: {name} differs"
+    assert int(G.pool_lens.cpu()[0]) == 32 and int(G.status.cpu()[0]) == 0
