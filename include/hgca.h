@@ -303,6 +303,37 @@ int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache,
 int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
                   double beta, void *hip_stream);
 
+/* ---- Append stage (Sec. 2.1: N incoming tokens, Q in R^{h x N x d}; Alg. 2,
+ * append branch).  bf16 only (both contractions run on the matrix cores). ----
+ *
+ * q is [B, N, Hq, d].  Attention of all N queries over one tier; the two parts
+ * of the hybrid step are two calls (the window with causal_tail = 1, the
+ * complete older pool with causal_tail = 0) whose results hgca_lse_merge
+ * combines with a shape whose batch is B*N.
+ * causal_tail != 0: the tier's last N valid tokens are the incoming tokens
+ * themselves and attention among them is causal: query i (0-based) sees tokens
+ * [0, seq_lens[b] - N + i + 1).  causal_tail == 0: every query sees every valid
+ * token.  o_out is fp32 [B, N, Hq, d], lse_out fp32 [B, N, Hq]; a query that
+ * sees nothing gives O = 0, lse = -inf.  ws needs hgca_append_workspace_bytes
+ * (shape, n_q, tier->cap) bytes.  n_q <= 4096. */
+size_t hgca_append_workspace_bytes(const hgca_shape *shape, int32_t n_q,
+                                   int32_t max_tokens);
+int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q,
+                     const hgca_kv_view *tier, int32_t causal_tail,
+                     float *o_out, float *lse_out,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/* A_gpu / A_cpu of the append branch (Alg. 2 returns them; Alg. 1 re-evaluates
+ * the salient set with ids = A_cpu > beta / A_cpu.size): one weight per head
+ * and entry, the average over the N queries of the part's own softmax weights,
+ * a_out[b,h,t] = (1/N) * sum_i e^{s_it - lse[b,i,h]} over the queries i that
+ * see t, where lse is the lse_out of hgca_append_attn on the same tier (same q,
+ * n_q, causal_tail).  a_out is fp32 [B, Hq, tier->cap], 0 at t >= seq_lens[b].
+ * Only tier->k is read. */
+int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q,
+                        const hgca_kv_view *tier, int32_t causal_tail,
+                        const float *lse, float *a_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -454,4 +454,112 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache, double
     return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, static_cast<hipStream_t>(hip_stream)));
 }
 
+namespace {
+
+// Split size of the append-stage attention: enough workgroups to fill the GPU, few enough splits that the
+// per-row partials stay small beside the K/V traffic.
+int append_want_splits(const hgca_shape *s, int32_t n_q)
+{
+    const int64_t n_qb = ((int64_t)n_q * group_of(s) + 127) / 128;
+    const int64_t units = std::max<int64_t>(1, (int64_t)s->batch * s->n_kv_heads * n_qb);
+    return (int)std::max<int64_t>(1, 1024 / units);
+}
+
+int append_chunk(const hgca_shape *s, int32_t n_q, int64_t cap)
+{
+    const int want = append_want_splits(s, n_q);
+    int64_t chunk = (std::max<int64_t>(cap, 1) + want - 1) / want;
+    chunk = (chunk + 31) / 32 * 32;
+    return (int)std::min<int64_t>(kMaxAppendChunk, std::max<int64_t>(kMinChunk, chunk));
+}
+
+struct AppendWs {
+    size_t o, m, l, total;
+    int max_splits;
+};
+
+AppendWs append_layout(const hgca_shape *s, int32_t n_q, int64_t max_tokens)
+{
+    AppendWs w{};
+    w.max_splits = std::max(append_want_splits(s, n_q), n_splits_for(std::max<int64_t>(max_tokens, 1), kMaxAppendChunk));
+    const size_t rows = (size_t)s->batch * n_q * s->n_q_heads;
+    size_t at = 0;
+    w.o = at; at += align_up(rows * w.max_splits * s->head_dim * sizeof(float));
+    w.m = at; at += align_up(rows * w.max_splits * sizeof(float));
+    w.l = at; at += align_up(rows * w.max_splits * sizeof(float));
+    w.total = std::max<size_t>(at, kAlign);
+    return w;
+}
+
+int check_append(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier, bool need_v)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (n_q < 0 || n_q > 4096) return HGCA_ERR_INVALID_ARG;
+    if (shape->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;      // the MFMA path is bf16 only
+    if ((rc = check_view(shape, tier, need_v)) != HGCA_OK) return rc;
+    if (shape->batch > 0 && n_q > 0 && (!q || !aligned16(q))) return HGCA_ERR_INVALID_ARG;
+    return HGCA_OK;
+}
+
+}  // namespace
+
+size_t hgca_append_workspace_bytes(const hgca_shape *shape, int32_t n_q, int32_t max_tokens)
+{
+    if (check_shape(shape) != HGCA_OK || n_q < 0 || max_tokens < 0) return 0;
+    return append_layout(shape, n_q, max_tokens).total;
+}
+
+int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier,
+                     int32_t causal_tail, float *o_out, float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_append(shape, q, n_q, tier, true);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0 || n_q == 0) return HGCA_OK;
+    if (!o_out || !lse_out || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    const AppendWs w = append_layout(shape, n_q, tier->cap);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    AppendArgs a{};
+    a.sh = to_dev(shape);
+    a.q = q;
+    a.kv = to_dev(tier);
+    a.n_q = n_q;
+    a.causal_tail = causal_tail ? 1 : 0;
+    a.chunk = append_chunk(shape, n_q, tier->cap);
+    char *base = static_cast<char *>(ws);
+    a.part.o = reinterpret_cast<float *>(base + w.o);
+    a.part.m = reinterpret_cast<float *>(base + w.m);
+    a.part.l = reinterpret_cast<float *>(base + w.l);
+    a.part.n_splits = std::max(1, n_splits_for(tier->cap, a.chunk));
+    if (a.part.n_splits > w.max_splits) return HGCA_ERR_WORKSPACE;
+    if ((rc = from_hip(launch_append_attn(shape->head_dim, a, s))) != HGCA_OK) return rc;
+    const int64_t rows = (int64_t)shape->batch * n_q * shape->n_q_heads;
+    return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
+}
+
+int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier,
+                        int32_t causal_tail, const float *lse, float *a_out, void *hip_stream)
+{
+    int rc = check_append(shape, q, n_q, tier, false);
+    if (rc != HGCA_OK) return rc;
+    if (n_q == 0) return HGCA_ERR_INVALID_ARG;       // an average over no query is undefined
+    if (shape->batch == 0 || tier->cap == 0) return HGCA_OK;
+    if (!lse || !a_out) return HGCA_ERR_INVALID_ARG;
+    AppendArgs a{};
+    a.sh = to_dev(shape);
+    a.q = q;
+    a.kv = to_dev(tier);
+    a.n_q = n_q;
+    a.causal_tail = causal_tail ? 1 : 0;
+    a.lse = lse;
+    a.a_out = a_out;
+    const int64_t units = (int64_t)shape->batch * shape->n_kv_heads;
+    a.chunk = 512;
+    while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < 2048) a.chunk /= 2;
+    return from_hip(launch_append_weights(shape->head_dim, a, n_splits_for(tier->cap, a.chunk),
+                                          static_cast<hipStream_t>(hip_stream)));
+}
+
 }  // extern "C"

@@ -90,6 +90,24 @@ struct ThresholdArgs {
 };
 hipError_t launch_threshold_select(const ThresholdArgs &a, int64_t n_rows, hipStream_t s);
 
+// ---- append stage: N queries per sequence over one tier (bf16, MFMA) ----
+
+constexpr int kMaxAppendChunk = 4096;   // tokens of one split of the append-stage attention at most
+
+struct AppendArgs {
+    ShapeDev sh;
+    const void *q;             // [B, N, Hq, d] bf16
+    KvDev kv;
+    int32_t n_q;               // N
+    int32_t causal_tail;       // 1: the tier's last N valid tokens are the queries' own; query i sees tokens < len-N+i+1
+    int32_t chunk;             // tokens per split (attention) or per workgroup (weights), a multiple of 32
+    Partials part;             // attention: rows are (b, query, head)
+    const float *lse;          // weights: [B, N, Hq], the tier's log-sum-exp per query and head
+    float *a_out;              // weights: [B, Hq, cap]
+};
+hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s);
+hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks, hipStream_t s);
+
 // ---- KV manager over a block pool (mirrors hgca_cache_state; all pointers device memory) ----
 
 constexpr int32_t kCacheWindowFull = 1, kCacheContextFull = 2, kCacheListFull = 4;   // sticky bits of *status

@@ -1,0 +1,52 @@
+// Row addressing of a split, shared by the attention kernels.
+#pragma once
+
+#include "hgca_device.hpp"
+
+namespace hgca {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Where the rows of a split live: the number of the [d] row (counted over the whole K or V buffer of
+// the tier) of the split's j-th token.  A dense split of a contiguous tier is plain arithmetic; paged
+// tiers and index lists get a table in LDS, filled once per workgroup, so that neither the block table
+// nor the index list is in the dependency chain of every row load of the K and V passes.
+struct RowMap {
+    const uint32_t *table;   // LDS; nullptr => row = base + j
+    uint32_t base;
+    __device__ __forceinline__ uint32_t operator()(int j) const { return table ? table[j] : base + (uint32_t)j; }
+};
+
+// `listed` (gather only) points at the split's first index.  Contains a barrier iff a table is filled;
+// the condition is uniform over the workgroup.
+template <bool GATHER, int BLOCK>
+__device__ __forceinline__ RowMap make_row_map(uint32_t *s_row, const KvDev &kv, int n_kv_heads, int b, int kvh,
+                                               int t0, int nt, const int32_t *listed)
+{
+    RowMap m;
+    if (!GATHER && kv.block_table == nullptr) {
+        m.table = nullptr;
+        m.base = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + t0);
+        return m;
+    }
+    const int32_t *blocks = nullptr;             // the sequence's table row, from the tier's first block on
+    if (kv.block_table) blocks = kv.block_table + (int64_t)b * kv.max_blocks + (kv.first_block ? kv.first_block[b] : 0);
+    for (int j = threadIdx.x; j < nt; j += BLOCK) {
+        const int32_t tok = GATHER ? listed[j] : t0 + j;
+        uint32_t row;
+        if (blocks) {
+            const int32_t blk = blocks[tok / kv.block_size];
+            row = (uint32_t)(((int64_t)blk * n_kv_heads + kvh) * kv.block_size + tok % kv.block_size);
+        } else {
+            row = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + tok);
+        }
+        s_row[j] = row;
+    }
+    __syncthreads();
+    m.table = s_row;
+    m.base = 0;
+    return m;
+}
+
+}  // namespace hgca

@@ -23,7 +23,8 @@ _LIB_PATH = os.environ.get("HGCA_LIB") or os.path.join(os.path.dirname(os.path.a
 EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn",
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
-           "hgca_kv_append", "hgca_kv_evict")
+           "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
+           "hgca_append_weights")
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -84,6 +85,12 @@ def lib() -> ctypes.CDLL:
         L.hgca_dense_window_attn_weights.argtypes = [ps, vp, pk, vp, vp, vp, vp, sz, vp]
         L.hgca_select_topk.restype = ctypes.c_int
         L.hgca_select_topk.argtypes = [ps, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
+        L.hgca_append_workspace_bytes.restype = sz
+        L.hgca_append_workspace_bytes.argtypes = [ps, i32, i32]
+        L.hgca_append_attn.restype = ctypes.c_int
+        L.hgca_append_attn.argtypes = [ps, vp, i32, pk, i32, vp, vp, vp, sz, vp]
+        L.hgca_append_weights.restype = ctypes.c_int
+        L.hgca_append_weights.argtypes = [ps, vp, i32, pk, i32, vp, vp, vp]
         L.hgca_kv_append.restype = ctypes.c_int
         L.hgca_kv_append.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp]
         L.hgca_kv_evict.restype = ctypes.c_int
@@ -292,3 +299,29 @@ def kv_evict(shape: Shape, cache: CacheState, beta: float, stream=None) -> None:
     """Sequences whose window reached l_max hand their oldest block(s) to the pool and sparsify them."""
     _check(lib().hgca_kv_evict(ctypes.byref(shape), ctypes.byref(cache), float(beta), _stream(stream)),
            "hgca_kv_evict")
+
+
+def append_workspace(shape: Shape, n_q: int, max_tokens: int, device) -> torch.Tensor:
+    n = int(lib().hgca_append_workspace_bytes(ctypes.byref(shape), int(n_q), int(max_tokens)))
+    if n == 0:
+        raise HgcaError(ERR_INVALID_ARG, "hgca_append_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def append_attn(shape: Shape, q, tier: Tier, causal_tail: bool, o_out, lse_out, ws, stream=None) -> None:
+    """q [B,N,Hq,d] bf16; o_out [B,N,Hq,d], lse_out [B,N,Hq] fp32."""
+    for t in (q, o_out, lse_out, ws):
+        _require_gpu(t)
+    kv = tier.view()
+    _check(lib().hgca_append_attn(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), int(causal_tail),
+                                  _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_append_attn")
+
+
+def append_weights(shape: Shape, q, tier: Tier, causal_tail: bool, lse, a_out, stream=None) -> None:
+    """Query-averaged softmax weights of the tier, a_out [B,Hq,cap] fp32; lse from append_attn on the same tier."""
+    for t in (q, lse, a_out):
+        _require_gpu(t)
+    kv = tier.view()
+    _check(lib().hgca_append_weights(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), int(causal_tail),
+                                     _ptr(lse), _ptr(a_out), _stream(stream)), "hgca_append_weights")

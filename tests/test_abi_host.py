@@ -221,3 +221,33 @@ def test_kv_manager_entry_points_reject_bad_arguments(hg):
     assert L.hgca_kv_append(ctypes.byref(sh), None, FAKE, FAKE, None, None) == hg.ERR_INVALID_ARG
     empty = hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088)
     assert L.hgca_kv_evict(ctypes.byref(empty), ctypes.byref(state(k_blocks=None)), 1.0, None) == hg.OK
+
+
+def test_append_entry_points_reject_bad_arguments(hg):
+    L = hg.lib()
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    view = _view(hg)
+    byref = ctypes.byref
+    assert hg.lib().hgca_append_workspace_bytes(byref(sh), 32, 4096) > 0
+    assert hg.lib().hgca_append_workspace_bytes(byref(sh), -1, 4096) == 0
+    assert hg.lib().hgca_append_workspace_bytes(byref(hg.Shape(hg.BF16, 2, 8, 3, 128, 1.0)), 4, 64) == 0
+
+    def attn(shape=sh, q=FAKE, n_q=4, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40):
+        return L.hgca_append_attn(byref(shape), q, n_q, byref(view), 1, o, lse, ws, ws_bytes, None)
+    assert attn(q=None) == hg.ERR_INVALID_ARG
+    assert attn(q=ODD) == hg.ERR_INVALID_ARG
+    assert attn(n_q=-1) == hg.ERR_INVALID_ARG
+    assert attn(n_q=5000) == hg.ERR_INVALID_ARG
+    assert attn(o=None) == hg.ERR_INVALID_ARG
+    assert attn(lse=None) == hg.ERR_INVALID_ARG
+    assert attn(ws=None) == hg.ERR_WORKSPACE
+    assert attn(ws_bytes=64) == hg.ERR_WORKSPACE
+    assert attn(shape=hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)) == hg.ERR_UNSUPPORTED      # bf16 only
+    assert attn(n_q=0) == hg.OK                                                          # nothing to do
+
+    def weights(q=FAKE, n_q=4, lse=FAKE, a=FAKE):
+        return L.hgca_append_weights(byref(sh), q, n_q, byref(view), 0, lse, a, None)
+    assert weights(q=None) == hg.ERR_INVALID_ARG
+    assert weights(n_q=0) == hg.ERR_INVALID_ARG
+    assert weights(lse=None) == hg.ERR_INVALID_ARG
+    assert weights(a=None) == hg.ERR_INVALID_ARG

@@ -1,0 +1,185 @@
+"""Parity of the append stage (N queries per sequence; paper Sec. 2.1 and Alg. 2, append branch) with the
+numpy fp64 oracle, through the C ABI: causal attention over the window, attention over the complete older
+pool, their merge, the query-averaged weights of each part, and the re-evaluation threshold on A_cpu.
+
+Bars (bf16 inputs; scores accumulate exact products in fp32; the probabilities enter the second
+contraction as a high and a low bf16 part): lse within 2e-5, O within 2e-4 (the stated bar is 2e-2),
+averaged weights within 2e-5 and summing to 1 within 1e-4."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import append_stage as ap
+from paper_2507_03153_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2507_03153_amd import hgca, runner
+    hgca.lib()
+    return torch, hgca, runner
+
+
+def make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens):
+    rng = np.random.default_rng(seed)
+    bits = lambda *s: wl.f32_to_bf16_bits(rng.standard_normal(s).astype(np.float32))
+    q, Kw, Vw, Kp, Vp = bits(B, N, Hq, d), bits(B, Hkv, W, d), bits(B, Hkv, W, d), bits(B, Hkv, max(P, 1), d), \
+        bits(B, Hkv, max(P, 1), d)
+    # a few pool keys lean towards the first query of each head's group so that some weights stand out
+    qf = wl.bf16_bits_to_f32(q)
+    for b in range(B):
+        for kvh in range(Hkv):
+            for j in range(0, P, 37):
+                kf = wl.bf16_bits_to_f32(Kp[b, kvh, j]) + 0.6 * qf[b, 0, kvh * (Hq // Hkv)]
+                Kp[b, kvh, j] = wl.f32_to_bf16_bits(kf.astype(np.float32))
+    w_lens = np.full(B, W, np.int32) if w_lens is None else np.asarray(w_lens, np.int32)
+    p_lens = np.full(B, P, np.int32) if p_lens is None else np.asarray(p_lens, np.int32)
+    return q, Kw, Vw, w_lens, Kp, Vp, p_lens
+
+
+def to_paged(runner, hgca, torch, K, V, lens, cap, block, seed, dev):
+    """The same logical tier in shuffled 16-token blocks, addressed through a table row that starts at a
+    per-sequence offset (first_block)."""
+    B, Hkv, _, d = K.shape
+    nb = (cap + block - 1) // block
+    rng = np.random.default_rng(seed)
+    first = rng.integers(0, 3, B).astype(np.int32)
+    table = np.full((B, nb + 3), 0, np.int32)
+    perm = rng.permutation(B * nb).astype(np.int32)
+    kb = np.zeros((B * nb, Hkv, block, d), K.dtype)
+    vb = np.zeros_like(kb)
+    for b in range(B):
+        for j in range(nb):
+            blk = perm[b * nb + j]
+            table[b, first[b] + j] = blk
+            n = min(block, cap - j * block)
+            kb[blk, :, :n] = K[b, :, j * block:j * block + n]
+            vb[blk, :, :n] = V[b, :, j * block:j * block + n]
+    g = lambda a: runner._to_gpu(a, dev)
+    return hgca.Tier(g(kb), g(vb), cap, g(lens), g(table), block, g(first))
+
+
+def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=False):
+    torch, hgca, runner = gpu
+    dev = "cuda:0"
+    say(f"\n[case] append N={N} B={B} Hq={Hq} Hkv={Hkv} d={d} W={W} P={P} w_lens={w_lens} p_lens={p_lens} paged={paged}")
+    q, Kw, Vw, wl_, Kp, Vp, pl_ = make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens)
+    scale = 1.0 / np.sqrt(d)
+    f = lambda x: wl.bf16_bits_to_f32(x).astype(np.float64)
+    o_g, l_g, A_g = ap.part_attention(f(q), f(Kw), f(Vw), wl_, scale, True)
+    o_c, l_c, A_c = ap.part_attention(f(q), f(Kp), f(Vp), pl_, scale, False)
+    o_ref, l_ref = ap.merge_state(o_c, l_c, o_g, l_g)
+
+    g = lambda a: runner._to_gpu(a, dev)
+    qd = g(q)
+    if paged:
+        win = to_paged(runner, hgca, torch, Kw, Vw, wl_, W, 16, seed + 1, dev)
+        pool = to_paged(runner, hgca, torch, Kp, Vp, pl_, max(P, 1), 16, seed + 2, dev)
+        pool.cap = P
+    else:
+        win = hgca.Tier(g(Kw), g(Vw), W, g(wl_))
+        pool = hgca.Tier(g(Kp), g(Vp), P, g(pl_))
+    shape = hgca.Shape(hgca.BF16, B, Hq, Hkv, d, scale)
+    f32 = dict(dtype=torch.float32, device=dev)
+    ws = hgca.append_workspace(shape, N, max(W, P), dev)
+    ow, lw = torch.full((B, N, Hq, d), float("nan"), **f32), torch.full((B, N, Hq), float("nan"), **f32)
+    op, lp = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
+    hgca.append_attn(shape, qd, win, True, ow, lw, ws)
+    hgca.append_attn(shape, qd, pool, False, op, lp, ws)
+    o, lse = torch.empty_like(ow), torch.empty_like(lw)
+    merged_shape = hgca.Shape(hgca.BF16, B * N, Hq, Hkv, d, scale)
+    hgca.lse_merge(merged_shape, op, lp, ow, lw, o, lse)
+    a_gpu = torch.full((B, Hq, W), float("nan"), **f32)
+    a_cpu = torch.full((B, Hq, max(P, 1)), float("nan"), **f32)
+    hgca.append_weights(shape, qd, win, True, lw, a_gpu)
+    hgca.append_weights(shape, qd, pool, False, lp, a_cpu)
+    torch.cuda.synchronize()
+
+    def check(name, o_t, l_t, o_r, l_r):
+        o_t, l_t = o_t.double().cpu().numpy(), l_t.double().cpu().numpy()
+        empty = np.isneginf(l_r)
+        assert np.array_equal(np.isneginf(l_t), empty), f"{name}: empty sets differ"
+        assert np.all(np.isfinite(o_t)) and np.all(o_t[empty] == 0)
+        err_l = np.max(np.abs(l_t[~empty] - l_r[~empty]), initial=0.0)
+        err_o = np.max(np.abs(o_t - o_r), initial=0.0)
+        say(f"    {name}: max|dO|={err_o:.2e} max|dlse|={err_l:.2e}")
+        assert err_l <= 2e-5 and err_o <= 2e-4, f"{name}: dO={err_o} dlse={err_l}"
+    check("window (causal)", ow, lw, o_g, l_g)
+    check("pool", op, lp, o_c, l_c)
+    check("merged", o, lse, o_ref, l_ref)
+
+    for name, a_t, A, lens, cap in (("A_gpu", a_gpu, A_g, wl_, W), ("A_cpu", a_cpu, A_c, pl_, P)):
+        a_t = a_t.double().cpu().numpy()[:, :, :cap]
+        a_r = A.mean(axis=2)
+        err = np.max(np.abs(a_t - a_r), initial=0.0)
+        say(f"    {name}: max|dA|={err:.2e}")
+        assert err <= 2e-5
+        for b in range(B):
+            assert np.all(a_t[b, :, lens[b]:] == 0.0)
+            if lens[b] and (name == "A_cpu" or lens[b] >= N):
+                assert np.max(np.abs(a_t[b, :, :lens[b]].sum(-1) - 1.0)) <= 1e-4
+    return shape, a_cpu, A_c.mean(axis=2), pl_
+
+
+@pytest.mark.parametrize("kw", [
+    dict(B=2, N=5, Hq=8, Hkv=2, d=128, W=100, P=333),                       # one partly filled row tile
+    dict(B=2, N=32, Hq=8, Hkv=2, d=128, W=700, P=1500),                      # 128 rows: every wave two tiles
+    dict(B=1, N=40, Hq=8, Hkv=2, d=128, W=300, P=900),                       # 160 rows: two query blocks
+    dict(B=3, N=7, Hq=4, Hkv=4, d=128, W=130, P=257),                        # MHA
+    dict(B=1, N=16, Hq=16, Hkv=2, d=128, W=96, P=640),                       # GQA 8
+    dict(B=2, N=9, Hq=4, Hkv=2, d=64, W=333, P=1111),                        # head_dim 64
+    dict(B=1, N=1, Hq=8, Hkv=2, d=128, W=64, P=200),                         # a single query: the decode step
+], ids=["n5", "n32", "n40_two_blocks", "mha", "gqa8", "d64", "n1"])
+def test_append_shapes(gpu, kw):
+    run_case(gpu, 31, **kw)
+
+
+def test_append_ragged_and_degenerate_lengths(gpu):
+    # a window that holds only the incoming tokens, an empty pool, a window shorter than the chunk tail
+    run_case(gpu, 32, B=4, N=6, Hq=8, Hkv=2, d=128, W=200, P=500, w_lens=(200, 6, 37, 150), p_lens=(500, 0, 1, 33))
+    run_case(gpu, 33, B=2, N=12, Hq=8, Hkv=2, d=128, W=64, P=0, w_lens=(64, 12))
+
+
+def test_append_paged_tiers_with_first_block_offsets(gpu):
+    run_case(gpu, 34, B=3, N=10, Hq=8, Hkv=2, d=128, W=208, P=1000, w_lens=(208, 100, 10), p_lens=(1000, 17, 640),
+             paged=True)
+
+
+def test_append_long_pool_many_splits_and_row_table_refills(gpu):
+    run_case(gpu, 35, B=1, N=32, Hq=8, Hkv=2, d=128, W=256, P=9000)
+
+
+def test_reevaluation_threshold_on_a_cpu(gpu, oracle):
+    """Alg. 1, append: ids = A_cpu > beta / A_cpu.size; both sides threshold their own A_cpu, entries within
+    rounding of the threshold may differ."""
+    torch, hgca, runner = gpu
+    shape, a_cpu, a_ref, p_lens = run_case(gpu, 36, B=2, N=16, Hq=8, Hkv=2, d=128, W=128, P=2000, p_lens=(2000, 1234))
+    P = a_ref.shape[2]
+    idx = torch.empty(2, 8, P, dtype=torch.int32, device="cuda:0")
+    cnt = torch.empty(2, 8, dtype=torch.int32, device="cuda:0")
+    lens_d = torch.from_numpy(p_lens).to("cuda:0")
+    hgca.threshold_select(shape, a_cpu, lens_d, P, lens_d, 1.0, P, idx, cnt)
+    torch.cuda.synchronize()
+    idx_ref, cnt_ref = oracle.threshold_select(a_ref, 1.0, p_lens, P, lens=p_lens)
+    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    differing = 0
+    for b in range(2):
+        thr = 1.0 / p_lens[b]
+        for h in range(8):
+            got, want = set(idx[b, h, :cnt[b, h]].tolist()), set(idx_ref[b, h, :cnt_ref[b, h]].tolist())
+            for j in got ^ want:
+                assert abs(a_ref[b, h, j] - thr) <= 1e-4 * thr
+                differing += 1
+    say(f"    kept per head {cnt_ref.min()}..{cnt_ref.max()} of {p_lens.tolist()}; decided differently inside the "
+        f"rounding band: {differing}")
+    assert 0 < cnt_ref.min() and cnt_ref.max() < p_lens.min()
