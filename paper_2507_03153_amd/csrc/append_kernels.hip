@@ -3,14 +3,15 @@
 // v_mfma_f32_16x16x32_bf16.
 //
 // Work unit: one workgroup = one split of the tokens of one (sequence, KV head) and up to 128 query
-// rows (a row = one query x one head of the GQA group, query-major).  The four waves own disjoint
-// 16-row tiles (wave w: tiles w and w+4), so nothing is reduced across waves; all 256 threads stage
-// the K and V rows of a 32-token step into LDS with coalesced 16-byte loads (next step's loads in
-// flight during the current step's arithmetic, double-buffered stage, one barrier per step).
+// rows (a row = one query x one head of the GQA group, query-major).  Each of the eight waves owns
+// one 16-row tile, so nothing is reduced across waves; all 512 threads stage the K and V rows of a
+// 32-token step into LDS with coalesced 16-byte loads.  The loads of the next TWO steps are in flight
+// during a step's arithmetic (two register sets, parked into a double-buffered LDS stage, one barrier
+// per step): with two workgroups per CU that keeps 64 KB per CU on its way from HBM.
 //
 // Orientation (per 16-row tile, per step):
 //   S^T[token, row]  = K[token, :] . Q[row, :]        A = K tile (LDS, padded rows), B = Q (registers)
-//   O^T[dcol, row]  += V^T[dcol, token] . P^T[token, row]   A = V^T (LDS, read 2 bytes at a time), B = P
+//   O^T[dcol, row]  += V^T[dcol, token] . P^T[token, row]   A = V^T (LDS transpose reads of the rows), B = P
 // In both results a lane's column is the query row lane%16, so the running maximum, the running sum
 // and the rescaling factor of a row live in the lanes that hold its scores AND its output columns:
 // the online softmax needs two shuffles per row statistic and no LDS.  The probabilities go from
@@ -24,24 +25,32 @@ namespace hgca {
 
 namespace {
 
-constexpr int kABlock = 256;
+constexpr int kABlock = 512;
 constexpr int kAWaves = kABlock / kWave;
 constexpr int kStepTokens = 32;
-constexpr int kRowsPerBlock = 128;               // query rows per workgroup = 8 tiles of 16
-constexpr int kTilesPerWave = kRowsPerBlock / 16 / kAWaves;
+constexpr int kRowsPerBlock = 128;               // query rows per workgroup = 8 tiles of 16, one per wave
+static_assert(kRowsPerBlock == 16 * kAWaves, "one row tile per wave");
 constexpr int kSub = kMaxChunk;                  // tokens per refill of the row table
 
 template <int D> struct AStage {
     static constexpr int kPieces = D / 8;                        // 16-byte pieces per row
     static constexpr int kKStride = kPieces + 1;                 // K row stride in uint4 (conflict-free b128 reads)
-    static constexpr int kVStride = D * 2 + 8;                   // V row stride in bytes (conflict-free 2-byte reads)
-    static constexpr int kLoads = kStepTokens * kPieces / kABlock;   // 16-byte loads per thread, step and tensor
+    static constexpr int kVStride = D * 2 + 32;                  // V row stride in bytes: 4 consecutive rows x 32 bytes
+                                                                 // cover all banks (transpose reads of a lane group)
+    static constexpr int kTotal = kStepTokens * kPieces;         // 16-byte pieces of a step, per tensor
+    static constexpr int kLoads = (kTotal + kABlock - 1) / kABlock;  // loads per thread, step and tensor
 };
 
-__device__ __forceinline__ uint32_t bf16_rne(float x) {          // finite x
-    uint32_t u = __float_as_uint(x);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+
+// LDS transpose read of 16-bit elements (ds_read_b64_tr_b16): inside a 16-lane group, lane i receives as its
+// element e the element i % 4 of the four that lane 4e + i/4 points at.  So if lane j of a group points at
+// columns 4(j%4) .. 4(j%4)+3 of row j/4 of a row-major tile, lane i ends up with column i of rows 0..3:
+// the 8-tokens-of-one-column slice an MFMA operand needs, straight from the rows as they were loaded.
+__device__ __forceinline__ short4v lds_read_tr16(const char *p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (short4v __attribute__((address_space(3))) *)(const_cast<char *>(p)));
 }
 
 // Token of the step that contraction index 8*g + i stands for in lane group g: the lane's own score
@@ -85,6 +94,7 @@ struct StepLoader {
 #pragma unroll
         for (int u = 0; u < S::kLoads; ++u) {
             const int p = threadIdx.x + kABlock * u, trow = p / S::kPieces, piece = p % S::kPieces;
+            if (p >= S::kTotal) break;
             const int j = min(step * kStepTokens + trow, nsub - 1);
             const size_t off = rows(j) * ROW_BYTES + 16 * piece;
             kr[u] = load16_stream(kv.k + off);
@@ -95,12 +105,9 @@ struct StepLoader {
 #pragma unroll
         for (int u = 0; u < S::kLoads; ++u) {
             const int p = threadIdx.x + kABlock * u, trow = p / S::kPieces, piece = p % S::kPieces;
+            if (p >= S::kTotal) break;
             s_k[trow * S::kKStride + piece] = kr[u];
-            if (WITH_V) {
-                char *dst = s_v + trow * S::kVStride + 16 * piece;
-                *reinterpret_cast<uint2 *>(dst) = make_uint2(vr[u].x, vr[u].y);
-                *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(vr[u].z, vr[u].w);
-            }
+            if (WITH_V) *reinterpret_cast<uint4 *>(s_v + trow * S::kVStride + 16 * piece) = vr[u];
         }
     }
 };
@@ -127,8 +134,34 @@ __device__ __forceinline__ void tile_scores(const uint4 *s_k, const bf16x8 (&qop
     }
 }
 
+// Runs `body(stage, step)` for every 32-token step of a sub-chunk with the loads of the next two steps in
+// flight: two register sets (even and odd steps), each parked into its own LDS stage right before use.
+// A stage written in step s is read in step s and rewritten in step s + 2; the barrier of step s + 1 lies
+// between, so one barrier per step orders everything.
+template <int D, bool WITH_V, typename Body>
+__device__ __forceinline__ void for_each_step(const KvDev &kv, const RowMap &rows, int nsub, uint4 (*s_k)[kStepTokens * AStage<D>::kKStride],
+                                              char (*s_v)[kStepTokens * AStage<D>::kVStride], Body body)
+{
+    const int steps = (nsub + kStepTokens - 1) / kStepTokens;
+    StepLoader<D, WITH_V> even, odd;
+    even.fetch(kv, rows, 0, nsub);
+    if (steps > 1) odd.fetch(kv, rows, 1, nsub);
+    for (int s = 0; s < steps; s += 2) {
+        even.park(s_k[0], WITH_V ? s_v[0] : nullptr);
+        if (s + 2 < steps) even.fetch(kv, rows, s + 2, nsub);
+        __syncthreads();
+        body(0, s);
+        if (s + 1 < steps) {                     // uniform over the workgroup
+            odd.park(s_k[1], WITH_V ? s_v[1] : nullptr);
+            if (s + 3 < steps) odd.fetch(kv, rows, s + 3, nsub);
+            __syncthreads();
+            body(1, s + 1);
+        }
+    }
+}
+
 template <int D, int G, bool SPLIT_P>
-__global__ __launch_bounds__(kABlock) void append_attn_kernel(AppendArgs a)
+__global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
 {
     using S = AStage<D>;
     constexpr int DT = D / 16;
@@ -143,111 +176,81 @@ __global__ __launch_bounds__(kABlock) void append_attn_kernel(AppendArgs a)
     const int t0 = split * a.chunk;
     const int nt_total = min(a.chunk, len - t0);                 // <= 0: nothing of this split is valid
 
-    RowInfo ri[kTilesPerWave];
-    int vis[kTilesPerWave];                                      // tokens [0, vis) of the tier are visible to the row
-    bf16x8 qop[kTilesPerWave][D / 32];
-    float m[kTilesPerWave], l[kTilesPerWave];
-    floatx4 acc[kTilesPerWave][DT];
+    const int tile_row0 = qb * kRowsPerBlock + w * 16;           // first row of the wave's tile
+    const bool tile_live = tile_row0 < a.n_q * G;                // uniform over the wave
+    const RowInfo ri = row_info<G>(a, b, kvh, tile_row0 + n);
+    // tokens [0, vis) of the tier are visible to the row
+    const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
+    bf16x8 qop[D / 32];
+    load_q_tile<D>(a, ri, g, qop);
+    float m = -INFINITY, l = 0.f;
+    floatx4 acc[DT];
 #pragma unroll
-    for (int rt = 0; rt < kTilesPerWave; ++rt) {
-        ri[rt] = row_info<G>(a, b, kvh, qb * kRowsPerBlock + (w + kAWaves * rt) * 16 + n);
-        vis[rt] = !ri[rt].valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri[rt].query + 1, 0), len) : len;
-        load_q_tile<D>(a, ri[rt], g, qop[rt]);
-        m[rt] = -INFINITY;
-        l[rt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) acc[rt][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int dt = 0; dt < DT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    StepLoader<D, true> ld;
     for (int sub0 = 0; sub0 < nt_total; sub0 += kSub) {
         const int nsub = min(kSub, nt_total - sub0);
         __syncthreads();                         // the previous table and stages are no longer in use
         const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
-        const int steps = (nsub + kStepTokens - 1) / kStepTokens;
-        ld.fetch(a.kv, rows, 0, nsub);
-        for (int s = 0; s < steps; ++s) {
-            const int buf = s & 1;
-            ld.park(s_k[buf], s_v[buf]);
-            if (s + 1 < steps) ld.fetch(a.kv, rows, s + 1, nsub);
-            __syncthreads();
-
-            // V^T operands of the step (shared by the wave's row tiles): 8 tokens of one output column
-            bf16x8 vop[DT];
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                uint32_t wd[4];
-#pragma unroll
-                for (int i = 0; i < 8; i += 2) {
-                    const uint32_t lo = *reinterpret_cast<const uint16_t *>(s_v[buf] + step_token(g, i) * S::kVStride + (dt * 16 + n) * 2);
-                    const uint32_t hi = *reinterpret_cast<const uint16_t *>(s_v[buf] + step_token(g, i + 1) * S::kVStride + (dt * 16 + n) * 2);
-                    wd[i / 2] = lo | (hi << 16);
-                }
-                vop[dt] = __builtin_bit_cast(bf16x8, make_uint4(wd[0], wd[1], wd[2], wd[3]));
-            }
-
+        for_each_step<D, true>(a.kv, rows, nsub, s_k, s_v, [&](int buf, int s) {
+            if (!tile_live) return;
             const int step0 = t0 + sub0 + s * kStepTokens;       // tier position of the step's first token
             const int in_split = nsub - s * kStepTokens;         // tokens of the step that belong to this split
+            float sv[8];
+            tile_scores<D>(s_k[buf], qop, a.sh.sm_scale, min(in_split, vis - step0), sv);
+            float mx = sv[0];
 #pragma unroll
-            for (int rt = 0; rt < kTilesPerWave; ++rt) {
-                if (qb * kRowsPerBlock + (w + kAWaves * rt) * 16 >= a.n_q * G) continue;   // uniform over the wave
-                float sv[8];
-                tile_scores<D>(s_k[buf], qop[rt], a.sh.sm_scale, min(in_split, vis[rt] - step0), sv);
-                float mx = sv[0];
+            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(m, mx);
+            float p[8], ps = 0.f;
 #pragma unroll
-                for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
-                mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-                mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-                const float m_new = fmaxf(m[rt], mx);
-                float p[8], ps = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    p[e] = (m_new == -INFINITY) ? 0.f : __expf(sv[e] - m_new);   // masked scores give 0
-                    ps += p[e];
-                }
-                ps += __shfl_xor(ps, 16, kWave);
-                ps += __shfl_xor(ps, 32, kWave);
-                const float corr = (m[rt] == -INFINITY) ? 0.f : __expf(m[rt] - m_new);
-                l[rt] = l[rt] * corr + ps;
-                m[rt] = m_new;
-                if (__any(corr != 1.f)) {
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) acc[rt][dt] *= corr;
-                }
-                uint32_t hi[8], lo[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    hi[e] = bf16_rne(p[e]);
-                    if (SPLIT_P) lo[e] = bf16_rne(p[e] - __uint_as_float(hi[e] << 16));
-                }
-                const bf16x8 ph = __builtin_bit_cast(bf16x8, make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16),
-                                                                        hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)));
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-                    acc[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[dt], ph, acc[rt][dt], 0, 0, 0);
-                if (SPLIT_P) {
-                    const bf16x8 pl = __builtin_bit_cast(bf16x8, make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16),
-                                                                            lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)));
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
-                        acc[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[dt], pl, acc[rt][dt], 0, 0, 0);
-                }
+            for (int e = 0; e < 8; ++e) {
+                p[e] = (m_new == -INFINITY) ? 0.f : __expf(sv[e] - m_new);   // masked scores give 0
+                ps += p[e];
             }
-        }
+            ps += __shfl_xor(ps, 16, kWave);
+            ps += __shfl_xor(ps, 32, kWave);
+            const float corr = (m == -INFINITY) ? 0.f : __expf(m - m_new);
+            l = l * corr + ps;
+            m = m_new;
+            if (__any(corr != 1.f)) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) acc[dt] *= corr;
+            }
+            bf16x8 ph, pl;                       // round to nearest even; the low part carries the rounding error
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                ph[e] = (__bf16)p[e];
+                pl[e] = SPLIT_P ? (__bf16)(p[e] - (float)ph[e]) : (__bf16)0.f;
+            }
+            // O^T += V^T P^T, one 16-column tile of the output at a time.  The V^T operand (8 tokens of one column
+            // per lane) comes from two transpose reads: lane j of a group points at columns 4(j%4).. of the row of
+            // contraction index j/4 (first read) and 4 + j/4 (second read).
+            const char *v_lo = s_v[buf] + step_token(g, n / 4) * S::kVStride + 8 * (n % 4);
+            const char *v_hi = s_v[buf] + step_token(g, 4 + n / 4) * S::kVStride + 8 * (n % 4);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const short4v a0 = lds_read_tr16(v_lo + 32 * dt), a1 = lds_read_tr16(v_hi + 32 * dt);
+                const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                const bf16x8 vop = __builtin_bit_cast(bf16x8, both);
+                acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, ph, acc[dt], 0, 0, 0);
+                if (SPLIT_P) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pl, acc[dt], 0, 0, 0);
+            }
+        });
     }
 
     // partial of every valid row: lane (n, g) holds output columns dt*16 + 4g .. +3 of row n
-#pragma unroll
-    for (int rt = 0; rt < kTilesPerWave; ++rt) {
-        if (!ri[rt].valid) continue;
-        const int64_t at = ri[rt].out_row * a.part.n_splits + split;
+    if (ri.valid) {
+        const int64_t at = ri.out_row * a.part.n_splits + split;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
             *reinterpret_cast<float4 *>(a.part.o + at * D + dt * 16 + 4 * g) =
-                make_float4(acc[rt][dt][0], acc[rt][dt][1], acc[rt][dt][2], acc[rt][dt][3]);
+                make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]);
         if (g == 0) {
-            a.part.m[at] = m[rt];
-            a.part.l[at] = l[rt];
+            a.part.m[at] = m;
+            a.part.l[at] = l;
         }
     }
 }
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     using S = AStage<D>;
     __shared__ uint4 s_k[2][kStepTokens * S::kKStride];
     __shared__ uint32_t s_row[kSub];
-    __shared__ float s_part[kAWaves][G][kStepTokens];
+    __shared__ float s_part[2][kAWaves][G][kStepTokens];         // per stage: read after the next step's barrier
     __shared__ float s_out[G][kSub];
 
     const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -274,39 +277,32 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     if (nsub > 0) {
         __syncthreads();
         const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nsub, nullptr);
-        const int steps = (nsub + kStepTokens - 1) / kStepTokens;
         const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
-        StepLoader<D, false> ld;
         for (int qb = 0; qb < n_qb; ++qb) {
-            RowInfo ri[kTilesPerWave];
-            int vis[kTilesPerWave];
-            float lse[kTilesPerWave];
-            bf16x8 qop[kTilesPerWave][D / 32];
+            const RowInfo ri = row_info<G>(a, b, kvh, qb * kRowsPerBlock + w * 16 + n);
+            const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
+            const float lse = ri.valid ? a.lse[ri.out_row] : -INFINITY;
+            bf16x8 qop[D / 32];
+            load_q_tile<D>(a, ri, g, qop);
+            int pending = -1;                    // step whose per-wave sums wait in s_part[pending & 1]
+            // add the waves' sums of a finished step into the output row (one thread per entry: fixed order)
+            auto fold = [&](int step) {
+                for (int i = tid; i < G * kStepTokens; i += kABlock) {
+                    const int gh = i / kStepTokens, tok = i % kStepTokens;
+                    float v = 0.f;
 #pragma unroll
-            for (int rt = 0; rt < kTilesPerWave; ++rt) {
-                ri[rt] = row_info<G>(a, b, kvh, qb * kRowsPerBlock + (w + kAWaves * rt) * 16 + n);
-                vis[rt] = !ri[rt].valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri[rt].query + 1, 0), len) : len;
-                lse[rt] = ri[rt].valid ? a.lse[ri[rt].out_row] : -INFINITY;
-                load_q_tile<D>(a, ri[rt], g, qop[rt]);
-            }
-            __syncthreads();                     // stages of the previous query block are no longer in use
-            ld.fetch(a.kv, rows, 0, nsub);
-            for (int s = 0; s < steps; ++s) {
-                const int buf = s & 1;
-                ld.park(s_k[buf], nullptr);
-                if (s + 1 < steps) ld.fetch(a.kv, rows, s + 1, nsub);
-                __syncthreads();
-                const int step0 = t0 + s * kStepTokens, in_split = nsub - s * kStepTokens;
-                float sum[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) sum[e] = 0.f;
-#pragma unroll
-                for (int rt = 0; rt < kTilesPerWave; ++rt) {
-                    float sv[8];
-                    tile_scores<D>(s_k[buf], qop[rt], a.sh.sm_scale, min(in_split, vis[rt] - step0), sv);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) sum[e] += (lse[rt] == -INFINITY) ? 0.f : expf(sv[e] - lse[rt]);
+                    for (int ww = 0; ww < kAWaves; ++ww) v += s_part[step & 1][ww][gh][tok];
+                    s_out[gh][step * kStepTokens + tok] += v;
                 }
+            };
+            __syncthreads();                     // stages and sums of the previous query block are no longer in use
+            for_each_step<D, false>(a.kv, rows, nsub, s_k, static_cast<char (*)[kStepTokens * S::kVStride]>(nullptr),
+                                    [&](int buf, int s) {
+                if (pending >= 0) fold(pending);                 // written before the barrier that preceded this call
+                float sv[8], sum[8];
+                tile_scores<D>(s_k[buf], qop, a.sh.sm_scale, min(nsub - s * kStepTokens, vis - (t0 + s * kStepTokens)), sv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum[e] = (lse == -INFINITY) ? 0.f : expf(sv[e] - lse);
                 // add the rows of the same head: columns n, n + G, n + 2G, ... of the 16-lane group
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -315,17 +311,12 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
                 }
                 if (n < G) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) s_part[w][n][16 * (e / 4) + 4 * g + (e % 4)] = sum[e];
+                    for (int e = 0; e < 8; ++e) s_part[s & 1][w][n][16 * (e / 4) + 4 * g + (e % 4)] = sum[e];
                 }
-                __syncthreads();
-                for (int i = tid; i < G * kStepTokens; i += kABlock) {
-                    const int gh = i / kStepTokens, tok = i % kStepTokens;
-                    float v = 0.f;
-#pragma unroll
-                    for (int ww = 0; ww < kAWaves; ++ww) v += s_part[ww][gh][tok];
-                    s_out[gh][s * kStepTokens + tok] += v;       // one thread per entry: fixed order
-                }
-            }
+                pending = s;
+            });
+            __syncthreads();
+            if (pending >= 0) fold(pending);
         }
     }
     __syncthreads();
