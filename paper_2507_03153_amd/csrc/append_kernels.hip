@@ -5,9 +5,12 @@
 // Work unit: one workgroup = one split of the tokens of one (sequence, KV head) and up to 128 query
 // rows (a row = one query x one head of the GQA group, query-major).  Each of the eight waves owns
 // one 16-row tile, so nothing is reduced across waves; all 512 threads stage the K and V rows of a
-// 32-token step into LDS with coalesced 16-byte loads.  The loads of the next TWO steps are in flight
-// during a step's arithmetic (two register sets, parked into a double-buffered LDS stage, one barrier
-// per step): with two workgroups per CU that keeps 64 KB per CU on its way from HBM.
+// 64-token step into LDS with coalesced 16-byte loads.  The next step's loads are in flight during a
+// step's arithmetic (registers, parked into a double-buffered LDS stage, one barrier per step); two
+// workgroups share a CU, so 64 KB per CU are on their way from HBM while 16 waves do arithmetic.
+// A step is 64 tokens rather than 32 because the softmax of a step is one dependent chain (scores,
+// row maximum, exponentials, row sum, rounding, second contraction): four score tiles per chain give
+// the wave independent work to overlap it with.
 //
 // Orientation (per 16-row tile, per step):
 //   S^T[token, row]  = K[token, :] . Q[row, :]        A = K tile (LDS, padded rows), B = Q (registers)
@@ -27,7 +30,8 @@ namespace {
 
 constexpr int kABlock = 512;
 constexpr int kAWaves = kABlock / kWave;
-constexpr int kStepTokens = 32;
+constexpr int kStepBlocks = 2;                   // 32-token contraction blocks per step
+constexpr int kStepTokens = 32 * kStepBlocks;
 constexpr int kRowsPerBlock = 128;               // query rows per workgroup = 8 tiles of 16, one per wave
 static_assert(kRowsPerBlock == 16 * kAWaves, "one row tile per wave");
 constexpr int kSub = kMaxChunk;                  // tokens per refill of the row table
@@ -53,9 +57,15 @@ __device__ __forceinline__ short4v lds_read_tr16(const char *p) {
         (short4v __attribute__((address_space(3))) *)(const_cast<char *>(p)));
 }
 
-// Token of the step that contraction index 8*g + i stands for in lane group g: the lane's own score
-// registers hold tokens 4g..4g+3 of the step's first 16-token tile and of its second one.
-__device__ __forceinline__ int step_token(int g, int i) { return i < 4 ? 4 * g + i : 16 + 4 * g + (i - 4); }
+// Token of a 32-token block that contraction index 8*g + i stands for in lane group g: the lane's own score
+// registers hold tokens 4g..4g+3 of the block's first 16-token tile and of its second one.
+__device__ __forceinline__ int block_token(int g, int i) { return i < 4 ? 4 * g + i : 16 + 4 * g + (i - 4); }
+
+// The value of the lane ROT places further on in the same row of 16 lanes (DPP row_ror).
+template <int ROT>
+__device__ __forceinline__ float row_rotate(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + ROT, 0xf, 0xf, true));
+}
 
 // Row bookkeeping of one 16-row tile for this lane (column n = lane % 16).
 struct RowInfo {
@@ -83,7 +93,7 @@ __device__ __forceinline__ void load_q_tile(const AppendArgs &a, const RowInfo &
     }
 }
 
-// Stages the K (and V) rows of 32-token steps: global -> registers -> LDS, one step ahead.
+// Stages the K (and V) rows of a step: global -> registers -> LDS, one step ahead.
 template <int D, bool WITH_V>
 struct StepLoader {
     using S = AStage<D>;
@@ -112,51 +122,43 @@ struct StepLoader {
     }
 };
 
-// Scaled, masked scores of one 16-row tile for the step's 32 tokens: sv[4*tt + r] belongs to step token
-// 16*tt + 4*g + r and query row lane % 16.  Tokens at or beyond `limit` (counted from the step's first
-// token) read -inf.
-template <int D>
+// Scaled scores of one 16-row tile for the step's tokens: sv[8*kb + 4*tt + r] belongs to step token
+// 32*kb + 16*tt + 4*g + r and query row lane % 16.  With MASK, tokens at or beyond `limit` (counted from the
+// step's first token) read -inf.
+template <int D, bool MASK>
 __device__ __forceinline__ void tile_scores(const uint4 *s_k, const bf16x8 (&qop)[D / 32], float scale, int limit,
-                                            float (&sv)[8])
+                                            float (&sv)[8 * kStepBlocks])
 {
     using S = AStage<D>;
     const int lane = threadIdx.x % kWave, n = lane % 16, g = lane / 16;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
+    for (int t = 0; t < 2 * kStepBlocks; ++t) {  // 16-token tiles of the step
         floatx4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
-            const uint4 ka = s_k[(tt * 16 + n) * S::kKStride + 4 * kk + g];
+            const uint4 ka = s_k[(t * 16 + n) * S::kKStride + 4 * kk + g];
             c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qop[kk], c, 0, 0, 0);
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sv[4 * tt + r] = (16 * tt + 4 * g + r < limit) ? c[r] * scale : -INFINITY;
+        for (int r = 0; r < 4; ++r) sv[4 * t + r] = (!MASK || 16 * t + 4 * g + r < limit) ? c[r] * scale : -INFINITY;
     }
 }
 
-// Runs `body(stage, step)` for every 32-token step of a sub-chunk with the loads of the next two steps in
-// flight: two register sets (even and odd steps), each parked into its own LDS stage right before use.
-// A stage written in step s is read in step s and rewritten in step s + 2; the barrier of step s + 1 lies
-// between, so one barrier per step orders everything.
+// Runs `body(stage, step)` for every step of a sub-chunk with the next step's loads in flight.  A stage
+// written in step s is read in step s and rewritten in step s + 2; the barrier of step s + 1 lies between,
+// so one barrier per step orders everything.
 template <int D, bool WITH_V, typename Body>
 __device__ __forceinline__ void for_each_step(const KvDev &kv, const RowMap &rows, int nsub, uint4 (*s_k)[kStepTokens * AStage<D>::kKStride],
                                               char (*s_v)[kStepTokens * AStage<D>::kVStride], Body body)
 {
     const int steps = (nsub + kStepTokens - 1) / kStepTokens;
-    StepLoader<D, WITH_V> even, odd;
-    even.fetch(kv, rows, 0, nsub);
-    if (steps > 1) odd.fetch(kv, rows, 1, nsub);
-    for (int s = 0; s < steps; s += 2) {
-        even.park(s_k[0], WITH_V ? s_v[0] : nullptr);
-        if (s + 2 < steps) even.fetch(kv, rows, s + 2, nsub);
+    StepLoader<D, WITH_V> ld;
+    ld.fetch(kv, rows, 0, nsub);
+    for (int s = 0; s < steps; ++s) {
+        ld.park(s_k[s & 1], WITH_V ? s_v[s & 1] : nullptr);
+        if (s + 1 < steps) ld.fetch(kv, rows, s + 1, nsub);
         __syncthreads();
-        body(0, s);
-        if (s + 1 < steps) {                     // uniform over the workgroup
-            odd.park(s_k[1], WITH_V ? s_v[1] : nullptr);
-            if (s + 3 < steps) odd.fetch(kv, rows, s + 3, nsub);
-            __syncthreads();
-            body(1, s + 1);
-        }
+        body(s & 1, s);
     }
 }
 
@@ -165,6 +167,7 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
 {
     using S = AStage<D>;
     constexpr int DT = D / 16;
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     __shared__ uint4 s_k[2][kStepTokens * S::kKStride];
     __shared__ __attribute__((aligned(16))) char s_v[2][kStepTokens * S::kVStride];
     __shared__ uint32_t s_row[kSub];
@@ -181,62 +184,76 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
     const RowInfo ri = row_info<G>(a, b, kvh, tile_row0 + n);
     // tokens [0, vis) of the tier are visible to the row
     const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
+    int vis_min = vis;                           // over the rows of the tile: steps below it need no mask
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) vis_min = min(vis_min, __shfl_xor(vis_min, off, kWave));
     bf16x8 qop[D / 32];
     load_q_tile<D>(a, ri, g, qop);
+    // scores are kept in units of ln 2 (the exponentials are then bare v_exp_f32)
+    const float scale2 = a.sh.sm_scale * kLog2e;
     float m = -INFINITY, l = 0.f;
     floatx4 acc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int sub0 = 0; sub0 < nt_total; sub0 += kSub) {
-        const int nsub = min(kSub, nt_total - sub0);
+    // a paged tier needs a row table in LDS, refilled every kSub tokens (which drains the load pipeline);
+    // a contiguous tier is plain arithmetic and takes the whole split in one pass
+    const int sub_len = a.kv.block_table ? kSub : max(nt_total, 1);
+    for (int sub0 = 0; sub0 < nt_total; sub0 += sub_len) {
+        const int nsub = min(sub_len, nt_total - sub0);
         __syncthreads();                         // the previous table and stages are no longer in use
         const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
         for_each_step<D, true>(a.kv, rows, nsub, s_k, s_v, [&](int buf, int s) {
             if (!tile_live) return;
             const int step0 = t0 + sub0 + s * kStepTokens;       // tier position of the step's first token
             const int in_split = nsub - s * kStepTokens;         // tokens of the step that belong to this split
-            float sv[8];
-            tile_scores<D>(s_k[buf], qop, a.sh.sm_scale, min(in_split, vis - step0), sv);
+            float sv[8 * kStepBlocks];
+            if (min(in_split, vis_min - step0) >= kStepTokens)   // uniform over the wave: every token visible to every row
+                tile_scores<D, false>(s_k[buf], qop, scale2, 0, sv);
+            else
+                tile_scores<D, true>(s_k[buf], qop, scale2, min(in_split, vis - step0), sv);
             float mx = sv[0];
 #pragma unroll
-            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+            for (int e = 1; e < 8 * kStepBlocks; ++e) mx = fmaxf(mx, sv[e]);
             mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
             const float m_new = fmaxf(m, mx);
-            float p[8], ps = 0.f;
+            float ps = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                p[e] = (m_new == -INFINITY) ? 0.f : __expf(sv[e] - m_new);   // masked scores give 0
-                ps += p[e];
+            for (int e = 0; e < 8 * kStepBlocks; ++e) {          // sv becomes the probabilities; masked scores give 0
+                sv[e] = (m_new == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv[e] - m_new);
+                ps += sv[e];
             }
             ps += __shfl_xor(ps, 16, kWave);
             ps += __shfl_xor(ps, 32, kWave);
-            const float corr = (m == -INFINITY) ? 0.f : __expf(m - m_new);
+            const float corr = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_new);
             l = l * corr + ps;
             m = m_new;
             if (__any(corr != 1.f)) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) acc[dt] *= corr;
             }
-            bf16x8 ph, pl;                       // round to nearest even; the low part carries the rounding error
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                ph[e] = (__bf16)p[e];
-                pl[e] = SPLIT_P ? (__bf16)(p[e] - (float)ph[e]) : (__bf16)0.f;
-            }
-            // O^T += V^T P^T, one 16-column tile of the output at a time.  The V^T operand (8 tokens of one column
-            // per lane) comes from two transpose reads: lane j of a group points at columns 4(j%4).. of the row of
-            // contraction index j/4 (first read) and 4 + j/4 (second read).
-            const char *v_lo = s_v[buf] + step_token(g, n / 4) * S::kVStride + 8 * (n % 4);
-            const char *v_hi = s_v[buf] + step_token(g, 4 + n / 4) * S::kVStride + 8 * (n % 4);
+            for (int kb = 0; kb < kStepBlocks; ++kb) {
+                bf16x8 ph, pl;                   // round to nearest even; the low part carries the rounding error
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const short4v a0 = lds_read_tr16(v_lo + 32 * dt), a1 = lds_read_tr16(v_hi + 32 * dt);
-                const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-                const bf16x8 vop = __builtin_bit_cast(bf16x8, both);
-                acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, ph, acc[dt], 0, 0, 0);
-                if (SPLIT_P) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pl, acc[dt], 0, 0, 0);
+                for (int e = 0; e < 8; ++e) {
+                    ph[e] = (__bf16)sv[8 * kb + e];
+                    pl[e] = SPLIT_P ? (__bf16)(sv[8 * kb + e] - (float)ph[e]) : (__bf16)0.f;
+                }
+                // O^T += V^T P^T, one 16-column tile of the output at a time.  The V^T operand (8 tokens of one column
+                // per lane) comes from two transpose reads: lane j of a group points at columns 4(j%4).. of the row of
+                // contraction index j/4 (first read) and 4 + j/4 (second read).
+                const char *v_lo = s_v[buf] + (32 * kb + block_token(g, n / 4)) * S::kVStride + 8 * (n % 4);
+                const char *v_hi = s_v[buf] + (32 * kb + block_token(g, 4 + n / 4)) * S::kVStride + 8 * (n % 4);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const short4v a0 = lds_read_tr16(v_lo + 32 * dt), a1 = lds_read_tr16(v_hi + 32 * dt);
+                    const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                    const bf16x8 vop = __builtin_bit_cast(bf16x8, both);
+                    acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, ph, acc[dt], 0, 0, 0);
+                    if (SPLIT_P) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pl, acc[dt], 0, 0, 0);
+                }
             }
         });
     }
@@ -249,14 +266,16 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
             *reinterpret_cast<float4 *>(a.part.o + at * D + dt * 16 + 4 * g) =
                 make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]);
         if (g == 0) {
-            a.part.m[at] = m;
+            a.part.m[at] = m * kLn2;             // back to natural units (-inf stays -inf)
             a.part.l[at] = l;
         }
     }
 }
 
 // Query-averaged softmax weights of a tier: a_out[b, h, t] = (1/N) sum_i e^{s_it - lse_i} over the queries i
-// that see token t (lse_i is the tier's own log-sum-exp for query i), 0 beyond the length.
+// that see token t (lse_i is the tier's own log-sum-exp for query i), 0 beyond the length.  One workgroup
+// owns a_out[b, heads of kvh, t0 .. t0 + chunk): every step the waves' sums go through LDS to one thread
+// per entry, which writes (first block of 128 query rows) or adds to (further blocks) the entry.
 template <int D, int G>
 __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
 {
@@ -264,54 +283,58 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     __shared__ uint4 s_k[2][kStepTokens * S::kKStride];
     __shared__ uint32_t s_row[kSub];
     __shared__ float s_part[2][kAWaves][G][kStepTokens];         // per stage: read after the next step's barrier
-    __shared__ float s_out[G][kSub];
 
     const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave, n = lane % 16, g = lane / 16;
     const int len = tier_len(a.kv, b);
-    const int t0 = chunk_id * a.chunk;                           // a.chunk <= kSub
+    const int t0 = chunk_id * a.chunk;
     const int n_here = min(a.chunk, a.kv.cap - t0);              // entries of a_out this workgroup writes
-    const int nsub = min(a.chunk, len - t0);                     // valid tokens among them
-    for (int i = tid; i < G * kSub; i += kABlock) (&s_out[0][0])[i] = 0.f;
+    const int nt_total = min(a.chunk, len - t0);                 // valid tokens among them (may be <= 0)
+    const float inv_n = 1.f / (float)a.n_q;
+    constexpr float kLog2e = 1.4426950408889634f;
+    const float scale2 = a.sh.sm_scale * kLog2e;
+    float *out = a.a_out + ((int64_t)b * a.sh.n_q_heads + kvh * G) * a.kv.cap + t0;
 
-    if (nsub > 0) {
-        __syncthreads();
-        const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nsub, nullptr);
-        const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
-        for (int qb = 0; qb < n_qb; ++qb) {
-            const RowInfo ri = row_info<G>(a, b, kvh, qb * kRowsPerBlock + w * 16 + n);
-            const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
-            const float lse = ri.valid ? a.lse[ri.out_row] : -INFINITY;
-            bf16x8 qop[D / 32];
-            load_q_tile<D>(a, ri, g, qop);
+    const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int sub_len = a.kv.block_table ? kSub : max(nt_total, 1);
+    for (int qb = 0; qb < n_qb && nt_total > 0; ++qb) {
+        const RowInfo ri = row_info<G>(a, b, kvh, qb * kRowsPerBlock + w * 16 + n);
+        const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
+        const float lse2 = (ri.valid ? a.lse[ri.out_row] : -INFINITY) * kLog2e;   // in units of ln 2, like the scores
+        bf16x8 qop[D / 32];
+        load_q_tile<D>(a, ri, g, qop);
+        for (int sub0 = 0; sub0 < nt_total; sub0 += sub_len) {
+            const int nsub = min(sub_len, nt_total - sub0);
+            __syncthreads();                     // table, stages and sums of the previous pass are no longer in use
+            const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
             int pending = -1;                    // step whose per-wave sums wait in s_part[pending & 1]
-            // add the waves' sums of a finished step into the output row (one thread per entry: fixed order)
-            auto fold = [&](int step) {
+            auto fold = [&](int step) {          // one thread per entry, waves added in a fixed order
                 for (int i = tid; i < G * kStepTokens; i += kABlock) {
-                    const int gh = i / kStepTokens, tok = i % kStepTokens;
+                    const int gh = i / kStepTokens, tok = sub0 + step * kStepTokens + i % kStepTokens;
+                    if (tok >= nt_total) continue;
                     float v = 0.f;
 #pragma unroll
-                    for (int ww = 0; ww < kAWaves; ++ww) v += s_part[step & 1][ww][gh][tok];
-                    s_out[gh][step * kStepTokens + tok] += v;
+                    for (int ww = 0; ww < kAWaves; ++ww) v += s_part[step & 1][ww][gh][i % kStepTokens];
+                    float *dst = out + (int64_t)gh * a.kv.cap + tok;
+                    *dst = qb == 0 ? v * inv_n : fmaf(v, inv_n, *dst);
                 }
             };
-            __syncthreads();                     // stages and sums of the previous query block are no longer in use
             for_each_step<D, false>(a.kv, rows, nsub, s_k, static_cast<char (*)[kStepTokens * S::kVStride]>(nullptr),
                                     [&](int buf, int s) {
                 if (pending >= 0) fold(pending);                 // written before the barrier that preceded this call
-                float sv[8], sum[8];
-                tile_scores<D>(s_k[buf], qop, a.sh.sm_scale, min(nsub - s * kStepTokens, vis - (t0 + s * kStepTokens)), sv);
+                float sv[8 * kStepBlocks];
+                const int step0 = sub0 + s * kStepTokens;
+                tile_scores<D, true>(s_k[buf], qop, scale2, min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sum[e] = (lse == -INFINITY) ? 0.f : expf(sv[e] - lse);
-                // add the rows of the same head: columns n, n + G, n + 2G, ... of the 16-lane group
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-#pragma unroll
-                    for (int off = G; off < 16; off <<= 1) sum[e] += __shfl_xor(sum[e], off, kWave);
-                }
-                if (n < G) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) s_part[s & 1][w][n][16 * (e / 4) + 4 * g + (e % 4)] = sum[e];
+                for (int e = 0; e < 8 * kStepBlocks; ++e) {
+                    float x = (lse2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv[e] - lse2);
+                    // add the rows of the same head: columns n, n + G, n + 2G, ... of the 16-lane row, by rotating
+                    // the row (DPP row_ror) by 8, 4, ... G lanes
+                    if (G <= 8) x += row_rotate<8>(x);
+                    if (G <= 4) x += row_rotate<4>(x);
+                    if (G <= 2) x += row_rotate<2>(x);
+                    if (G <= 1) x += row_rotate<1>(x);
+                    if (n < G) s_part[s & 1][w][n][16 * (e / 4) + 4 * g + (e % 4)] = x;
                 }
                 pending = s;
             });
@@ -319,11 +342,10 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
             if (pending >= 0) fold(pending);
         }
     }
-    __syncthreads();
-    const float inv_n = 1.f / (float)a.n_q;
+    // entries beyond the sequence's length
     for (int i = tid; i < G * n_here; i += kABlock) {
         const int gh = i / n_here, j = i % n_here;
-        a.a_out[((int64_t)b * a.sh.n_q_heads + kvh * G + gh) * a.kv.cap + t0 + j] = j < nsub ? s_out[gh][j] * inv_n : 0.f;
+        if (j >= nt_total) out[(int64_t)gh * a.kv.cap + j] = 0.f;
     }
 }
 

@@ -469,7 +469,7 @@ int append_chunk(const hgca_shape *s, int32_t n_q, int64_t cap)
 {
     const int want = append_want_splits(s, n_q);
     int64_t chunk = (std::max<int64_t>(cap, 1) + want - 1) / want;
-    chunk = (chunk + 31) / 32 * 32;
+    chunk = (chunk + 63) / 64 * 64;
     return (int)std::min<int64_t>(kMaxAppendChunk, std::max<int64_t>(kMinChunk, chunk));
 }
 
@@ -556,8 +556,8 @@ int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, con
     a.lse = lse;
     a.a_out = a_out;
     const int64_t units = (int64_t)shape->batch * shape->n_kv_heads;
-    a.chunk = 512;
-    while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < 2048) a.chunk /= 2;
+    a.chunk = 2048;                                  // tokens per workgroup, halved until the GPU is filled
+    while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < 1024) a.chunk /= 2;
     return from_hip(launch_append_weights(shape->head_dim, a, n_splits_for(tier->cap, a.chunk),
                                           static_cast<hipStream_t>(hip_stream)));
 }
