@@ -226,6 +226,7 @@ def main() -> int:
     }
     if args.config == "C2" and not args.no_decode_loop:
         out["paper_literal_decode"] = decode_loop_timing(torch, hgca, cfg, layers[0], k_max, dev)
+        out["append_stage"] = append_stage_timing(torch, hgca, cfg, layers[0], dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host_layers[0], args.cpu_seconds)
     print(json.dumps(out), flush=True)
@@ -303,6 +304,53 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
             "bytes_per_step": int(moved), "hbm_frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "calls_per_step": "kv_append, dense_window_attn_weights, sparse_attn (deferred), lse_merge_splits, "
                               "maw_update, kv_evict"}
+
+
+def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20) -> dict:
+    """The append branch (N incoming tokens per sequence) on the workload's tensors: causal attention over the
+    window (whose last N tokens stand for the incoming ones), attention over the COMPLETE pool, merge, and the
+    query-averaged weights of both parts (what the KV manager's re-evaluation thresholds).  Both contractions run on
+    the matrix cores, so the figure is set beside the MFMA peak as well as the HBM peak."""
+    B, Hq, Hkv, d, W, P = cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.W, cfg.P
+    g = torch.Generator(device="cpu").manual_seed(7)
+    q = torch.randn(B, n_q, Hq, d, generator=g).to(torch.bfloat16).to(dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    ws = hgca.append_workspace(L.shape, n_q, max(W, P), dev)
+    ow, lw = torch.empty(B, n_q, Hq, d, **f32), torch.empty(B, n_q, Hq, **f32)
+    op, lp = torch.empty_like(ow), torch.empty_like(lw)
+    o, lse = torch.empty_like(ow), torch.empty_like(lw)
+    a_gpu, a_cpu = torch.empty(B, Hq, W, **f32), torch.empty(B, Hq, P, **f32)
+    merged = hgca.Shape(L.shape.dtype, B * n_q, Hq, Hkv, d, L.shape.sm_scale)
+    stream = torch.cuda.current_stream()
+    calls = {
+        "append_attn_window": lambda: hgca.append_attn(L.shape, q, L.window, True, ow, lw, ws),
+        "append_attn_pool": lambda: hgca.append_attn(L.shape, q, L.pool, False, op, lp, ws),
+        "lse_merge": lambda: hgca.lse_merge(merged, op, lp, ow, lw, o, lse),
+        "append_weights_window": lambda: hgca.append_weights(L.shape, q, L.window, True, lw, a_gpu),
+        "append_weights_pool": lambda: hgca.append_weights(L.shape, q, L.pool, False, lp, a_cpu),
+    }
+    ms = {}
+    for name, fn in calls.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms[name] = e0.elapsed_time(e1) / reps
+    elem = 2
+    kv_bytes = 2 * B * Hkv * (W + P) * d * elem                 # K and V of both tiers, once per KV head
+    flops = 4.0 * B * Hq * n_q * (W + P) * d                    # QK^T and PV, 2 flops per multiply-add (causal skip ignored)
+    attn_ms = ms["append_attn_window"] + ms["append_attn_pool"] + ms["lse_merge"]
+    return {"n_q": n_q, "per_call_ms": ms, "attention_ms": attn_ms, "with_weights_ms": sum(ms.values()),
+            "tokens_per_s": B * n_q / (attn_ms * 1e-3),
+            "kv_bytes": kv_bytes, "hbm_frac": kv_bytes / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "tflops": flops / (attn_ms * 1e-3) / 1e12, "mfma_frac_bf16": flops / (attn_ms * 1e-3) / 2.5e15,
+            "note": "probabilities enter the second contraction as a high and a low bf16 part, so the matrix cores "
+                    "execute 1.5x the counted flops"}
 
 
 def copy_calibration(torch, dev) -> int:
