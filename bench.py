@@ -302,8 +302,7 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
     return {"ms_per_step": ms, "layer_steps_per_s": 1e3 / ms, "graph_replay_ms_per_step": graph_ms, "steps": n_steps, "evictions": n_steps // block_size,
             "block_size": block_size, "salient_per_head": kept, "cache_status": status,
             "bytes_per_step": int(moved), "hbm_frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "calls_per_step": "kv_append, dense_window_attn_weights, sparse_attn (deferred), lse_merge_splits, "
-                              "maw_update, kv_evict"}
+            "calls_per_step": "kv_append, dense_window_attn_maw, sparse_attn (deferred), lse_merge_splits, kv_evict"}
 
 
 def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20) -> dict:

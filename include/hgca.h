@@ -205,6 +205,17 @@ int hgca_dense_window_attn_weights(const hgca_shape *shape, const void *q,
                                    float *o_out, float *lse_out, float *a_out,
                                    void *ws, size_t ws_bytes, void *hip_stream);
 
+/* hgca_dense_window_attn_weights followed by hgca_maw_update(a_maw, a_out,
+ * window->seq_lens, window->cap, n_new, alpha) in the same kernels (Alg. 2's
+ * gpu_attention, then the first statement of Alg. 1): one launch and one pass
+ * over the weights fewer per decode step.  a_maw is fp32 [B,Hq,window->cap],
+ * updated in place; results are identical to the two separate calls. */
+int hgca_dense_window_attn_maw(const hgca_shape *shape, const void *q,
+                               const hgca_kv_view *window,
+                               float *o_out, float *lse_out, float *a_out,
+                               float *a_maw, int32_t n_new, float alpha,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Moving average of attention weights (Alg. 1, the A_maw update; Sec. 3.1):
  * a_maw <- (1 - alpha) * a_maw + alpha * a_gpu on the first seq_lens[b] entries
  * of every (b, h) row (all `cap` entries if seq_lens is NULL); a_maw and a_gpu

@@ -59,10 +59,15 @@ class LayerCache:
     def append(self, k_in, v_in, active=None) -> None:
         hgca.kv_append(self.shape, self.state, k_in, v_in, active)
 
-    def attend(self, q) -> None:
-        """Alg. 2, decode branch, on a window that already holds the token being decoded."""
+    def attend(self, q, alpha=None, n_new: int = 1) -> None:
+        """Alg. 2, decode branch, on a window that already holds the token being decoded.  With `alpha` the
+        moving-average update of Alg. 1 rides along with the window's weights."""
         sh = self.shape
-        hgca.dense_window_attn_weights(sh, q, self.window, self.o_w, self.lse_w, self.a_gpu, self.ws_dense)
+        if alpha is None:
+            hgca.dense_window_attn_weights(sh, q, self.window, self.o_w, self.lse_w, self.a_gpu, self.ws_dense)
+        else:
+            hgca.dense_window_attn_maw(sh, q, self.window, self.o_w, self.lse_w, self.a_gpu, self.a_maw, n_new, alpha,
+                                       self.ws_dense)
         if self.fused_tail:        # the window's split partials are still in ws_dense: fold them with the sparse ones
             hgca.sparse_attn(sh, q, self.pool, self.ctx_idx, self.ctx_cnt, self.k_max, None, None, self.ws_sparse)
             hgca.lse_merge_splits(sh, self.win_cap, self.ws_dense, self.k_max, self.ws_sparse, self.o, self.lse)
@@ -71,12 +76,14 @@ class LayerCache:
                              self.ws_sparse)
             hgca.lse_merge(sh, self.o_s, self.lse_s, self.o_w, self.lse_w, self.o, self.lse)
 
-    def manage(self, alpha: float, beta: float, n_new: int = 1) -> None:
-        """Alg. 1: moving-average update, then eviction and sparsification where a window is full."""
-        hgca.maw_update(self.shape, self.a_maw, self.a_gpu, self.win_lens, self.win_cap, n_new, alpha)
+    def manage(self, alpha: float, beta: float, n_new: int = 1, maw_done: bool = False) -> None:
+        """Alg. 1: moving-average update (unless `attend` did it), then eviction and sparsification where a
+        window is full."""
+        if not maw_done:
+            hgca.maw_update(self.shape, self.a_maw, self.a_gpu, self.win_lens, self.win_cap, n_new, alpha)
         hgca.kv_evict(self.shape, self.state, beta)
 
-    def decode_step(self, q, k_in, v_in, alpha: float, beta: float) -> None:
+    def decode_step(self, q, k_in, v_in, alpha: float, beta: float, fused_maw: bool = True) -> None:
         self.append(k_in, v_in)
-        self.attend(q)
-        self.manage(alpha, beta)
+        self.attend(q, alpha if fused_maw else None)
+        self.manage(alpha, beta, maw_done=fused_maw)

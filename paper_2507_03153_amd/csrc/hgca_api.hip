@@ -158,7 +158,7 @@ size_t hgca_workspace_bytes(const hgca_shape *shape, int32_t max_window, int32_t
 namespace {
 
 int dense_window(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out, float *lse_out,
-                 float *a_out, void *ws, size_t ws_bytes, void *hip_stream)
+                 float *a_out, float *a_maw, int32_t n_new, float alpha, void *ws, size_t ws_bytes, void *hip_stream)
 {
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
@@ -183,7 +183,8 @@ int dense_window(const hgca_shape *shape, const void *q, const hgca_kv_view *win
     if (deferred) return HGCA_OK;
     if ((rc = from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s))) != HGCA_OK) return rc;
     if (!a_out) return HGCA_OK;
-    return from_hip(launch_window_weights(a_out, lse_out, window->seq_lens, rows, shape->n_q_heads, window->cap, s));
+    return from_hip(launch_window_weights(a_out, lse_out, window->seq_lens, rows, shape->n_q_heads, window->cap, a_maw,
+                                          n_new, alpha, s));
 }
 
 }  // namespace
@@ -191,14 +192,23 @@ int dense_window(const hgca_shape *shape, const void *q, const hgca_kv_view *win
 int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
                            float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    return dense_window(shape, q, window, o_out, lse_out, nullptr, ws, ws_bytes, hip_stream);
+    return dense_window(shape, q, window, o_out, lse_out, nullptr, nullptr, 0, 0.f, ws, ws_bytes, hip_stream);
 }
 
 int hgca_dense_window_attn_weights(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
                                    float *lse_out, float *a_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     if (!a_out && window && window->cap > 0) return HGCA_ERR_INVALID_ARG;
-    return dense_window(shape, q, window, o_out, lse_out, a_out, ws, ws_bytes, hip_stream);
+    return dense_window(shape, q, window, o_out, lse_out, a_out, nullptr, 0, 0.f, ws, ws_bytes, hip_stream);
+}
+
+int hgca_dense_window_attn_maw(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
+                               float *lse_out, float *a_out, float *a_maw, int32_t n_new, float alpha, void *ws,
+                               size_t ws_bytes, void *hip_stream)
+{
+    if (window && window->cap > 0 && (!a_out || !a_maw)) return HGCA_ERR_INVALID_ARG;
+    if (n_new < 0 || !(alpha >= 0.f && alpha <= 1.f)) return HGCA_ERR_INVALID_ARG;
+    return dense_window(shape, q, window, o_out, lse_out, a_out, a_maw, n_new, alpha, ws, ws_bytes, hip_stream);
 }
 
 int hgca_maw_update(const hgca_shape *shape, float *a_maw, const float *a_gpu, const int32_t *seq_lens, int32_t cap,

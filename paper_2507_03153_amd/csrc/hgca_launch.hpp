@@ -71,9 +71,10 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s);
 
 // ---- attention weights, their moving average, threshold rule ----
 
-// a [n_rows, cap] holds scaled scores on entry and softmax weights e^{s - lse} on exit (0 beyond the length).
+// a [n_rows, cap] holds scaled scores on entry and softmax weights e^{s - lse} on exit (0 beyond the length);
+// maw (optional, [n_rows, cap]) receives the moving-average update with those weights in the same pass.
 hipError_t launch_window_weights(float *a, const float *lse, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
-                                 int32_t cap, hipStream_t s);
+                                 int32_t cap, float *maw, int32_t n_new, float alpha, hipStream_t s);
 
 hipError_t launch_maw_update(float *maw, const float *a_gpu, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
                              int32_t cap, int32_t n_new, float alpha, hipStream_t s);

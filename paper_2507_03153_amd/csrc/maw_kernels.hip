@@ -11,19 +11,27 @@ namespace hgca {
 namespace {
 
 // a[row, j] holds the scaled score s_j on entry; on exit the softmax weight e^{s_j - lse_row}
-// (Sec. 2.1, A = softmax(S)) for j < len and 0 beyond.
+// (Sec. 2.1, A = softmax(S)) for j < len and 0 beyond.  With maw != nullptr the same pass applies
+// Alg. 1's moving-average update to maw[row, j] (see maw_update_kernel).
 __global__ __launch_bounds__(kRowBlock) void window_weights_kernel(float *a, const float *lse, const int32_t *seq_lens,
-                                                                   int32_t n_q_heads, int32_t cap)
+                                                                   int32_t n_q_heads, int32_t cap, float *maw,
+                                                                   int32_t n_new, float alpha)
 {
     const int64_t row = blockIdx.y;
     const int n = row_len(seq_lens, (int)(row / n_q_heads), cap);
-    const float L = lse[row];
+    const int first_new = n - min(n_new, n);
+    const float L = lse[row], keep = 1.f - alpha;
     float *p = a + row * cap;
+    float *m = maw ? maw + row * cap : nullptr;
     const int j0 = blockIdx.x * kRowStep + threadIdx.x;
 #pragma unroll
     for (int e = 0; e < kPerThread; ++e) {
         const int j = j0 + e * kRowBlock;
-        if (j < cap) p[j] = j < n ? expf(p[j] - L) : 0.f;
+        if (j < cap) {
+            const float x = j < n ? expf(p[j] - L) : 0.f;
+            p[j] = x;
+            if (m && j < n) m[j] = j >= first_new ? x : fmaf(alpha, x, keep * m[j]);
+        }
     }
 }
 
@@ -89,11 +97,12 @@ __global__ __launch_bounds__(kRowBlock) void threshold_select_kernel(ThresholdAr
 }  // namespace
 
 hipError_t launch_window_weights(float *a, const float *lse, const int32_t *seq_lens, int64_t n_rows, int32_t n_q_heads,
-                                 int32_t cap, hipStream_t s)
+                                 int32_t cap, float *maw, int32_t n_new, float alpha, hipStream_t s)
 {
     if (n_rows == 0 || cap == 0) return hipSuccess;
     dim3 grid((cap + kRowStep - 1) / kRowStep, (unsigned)n_rows);
-    hipLaunchKernelGGL(window_weights_kernel, grid, dim3(kRowBlock), 0, s, a, lse, seq_lens, n_q_heads, cap);
+    hipLaunchKernelGGL(window_weights_kernel, grid, dim3(kRowBlock), 0, s, a, lse, seq_lens, n_q_heads, cap, maw, n_new,
+                       alpha);
     return hipGetLastError();
 }
 

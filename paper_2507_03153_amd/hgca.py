@@ -24,7 +24,7 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
-           "hgca_append_weights")
+           "hgca_append_weights", "hgca_dense_window_attn_maw")
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_kv_append.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp]
         L.hgca_kv_evict.restype = ctypes.c_int
         L.hgca_kv_evict.argtypes = [ps, ctypes.POINTER(CacheState), ctypes.c_double, vp]
+        L.hgca_dense_window_attn_maw.restype = ctypes.c_int
+        L.hgca_dense_window_attn_maw.argtypes = [ps, vp, pk, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         L.hgca_maw_update.restype = ctypes.c_int
         L.hgca_maw_update.argtypes = [ps, vp, vp, vp, i32, i32, ctypes.c_float, vp]
         L.hgca_threshold_select.restype = ctypes.c_int
@@ -325,3 +327,14 @@ def append_weights(shape: Shape, q, tier: Tier, causal_tail: bool, lse, a_out, s
     kv = tier.view()
     _check(lib().hgca_append_weights(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), int(causal_tail),
                                      _ptr(lse), _ptr(a_out), _stream(stream)), "hgca_append_weights")
+
+
+def dense_window_attn_maw(shape: Shape, q, window: Tier, o_out, lse_out, a_out, a_maw, n_new: int, alpha: float, ws,
+                          stream=None) -> None:
+    """dense_window_attn_weights and maw_update(a_maw, a_out, ...) in one call."""
+    for t in (q, ws, o_out, lse_out, a_out, a_maw):
+        _require_gpu(t)
+    kv = window.view()
+    _check(lib().hgca_dense_window_attn_maw(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out), _ptr(lse_out),
+                                            _ptr(a_out), _ptr(a_maw), int(n_new), float(alpha), _ptr(ws), ws.numel(),
+                                            _stream(stream)), "hgca_dense_window_attn_maw")

@@ -45,7 +45,7 @@ def make_tokens(seed, T, B, Hq, Hkv, d, boost=3.0):
 
 
 def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, prefill, steps, alpha, beta, seed,
-             expect_list_full=False, fused_tail=True):
+             expect_list_full=False, fused_tail=True, fused_maw=True):
     torch, hgca, runner, cache = gpu
     dev = "cuda:0"
     T = max(prefill) + steps
@@ -75,7 +75,8 @@ def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, pref
     differing, worst_o, worst_l, evictions = 0, 0.0, 0.0, 0
     for s in range(steps):
         t = max(prefill) + s
-        C.decode_step(runner._to_gpu(qb[t], dev), runner._to_gpu(kb[t], dev), runner._to_gpu(vb[t], dev), alpha, beta)
+        C.decode_step(runner._to_gpu(qb[t], dev), runner._to_gpu(kb[t], dev), runner._to_gpu(vb[t], dev), alpha, beta,
+                      fused_maw=fused_maw)
         torch.cuda.synchronize()
         o_g, l_g = C.o.double().cpu().numpy(), C.lse.double().cpu().numpy()
         cnt_g, idx_g = C.ctx_cnt.cpu().numpy(), C.ctx_idx.cpu().numpy()
@@ -140,7 +141,8 @@ def test_decode_loop_ragged_windows_gqa4(gpu):
 
 def test_decode_loop_mha_head_dim_64_blocks_of_32(gpu):
     _, _, status = run_loop(gpu, B=2, Hq=4, Hkv=4, d=64, block_size=32, win_blocks=3, max_blocks=8, k_max=256,
-                            prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12, fused_tail=False)
+                            prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12, fused_tail=False,
+                            fused_maw=False)
     assert status == 0
 
 

@@ -289,3 +289,31 @@ def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kin
         kept = np.arange(k)[None, None, :] < cnt[:, :, None]
         want = np.take_along_axis(s, np.where(kept, idx, 0).astype(np.int64), axis=2)
         assert np.array_equal(sel[kept], want[kept])            # the kept entries' own scores, bit for bit
+
+
+def test_dense_with_moving_average_equals_the_two_calls(gpu, oracle):
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C5"], B=4, Hq=8, Hkv=2, W=256, P=1792, ragged=(100, 2048))
+    say("\n[case] dense_window_attn_maw vs dense_window_attn_weights + maw_update")
+    L = wl.make_layer(cfg)
+    D = runner.DeviceLayer.upload(L)
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    ws = hgca.alloc_workspace(D.shape, cfg.W, 0, 0, "cuda:0")
+    g = torch.Generator(device="cpu").manual_seed(3)
+    maw0 = torch.rand(cfg.B, cfg.Hq, cfg.W, generator=g).cuda()
+    outs = []
+    for fused in (False, True):
+        o, lse = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32), torch.empty(cfg.B, cfg.Hq, **f32)
+        a, maw = torch.empty(cfg.B, cfg.Hq, cfg.W, **f32), maw0.clone()
+        if fused:
+            hgca.dense_window_attn_maw(D.shape, D.q, D.window, o, lse, a, maw, 2, 0.3, ws)
+        else:
+            hgca.dense_window_attn_weights(D.shape, D.q, D.window, o, lse, a, ws)
+            hgca.maw_update(D.shape, maw, a, D.window.seq_lens, cfg.W, 2, 0.3)
+        torch.cuda.synchronize()
+        outs.append((o, lse, a, maw))
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
+    a_ref = oracle.window_weights(L.q, otier(oracle, L.window), L.scale)
+    ref = oracle.maw_update(maw0.double().cpu().numpy(), a_ref, 0.3, lens=L.window.seq_lens, n_new=2)
+    assert np.max(np.abs(outs[1][3].double().cpu().numpy() - ref)) <= W_TOL["bf16"]
