@@ -155,6 +155,8 @@ def main() -> int:
     a_maw = torch.zeros_like(a_gpu)
     thr_idx = torch.empty(cfg.B, cfg.Hq, cfg.W, dtype=torch.int32, device=dev)
     thr_cnt = torch.empty(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
+    g_idx = torch.full((cfg.B, cfg.Hkv, max(k_max, 1)), -1, dtype=torch.int32, device=dev)
+    g_cnt = torch.zeros(cfg.B, cfg.Hkv, dtype=torch.int32, device=dev)
     calls = {
         "dense_window_attn": lambda L: hgca.dense_window_attn(sh, L.q, L.window, step.o_w, step.lse_w, step.ws_dense),
         "pool_scores": lambda L: hgca.pool_scores(sh, L.q, L.pool, scores_buf),
@@ -172,6 +174,11 @@ def main() -> int:
         "maw_update": lambda L: hgca.maw_update(sh, a_maw, a_gpu, L.window.seq_lens, cfg.W, 1, 0.3),
         "threshold_select": lambda L: hgca.threshold_select(sh, a_maw, L.window.seq_lens, cfg.W, cfg.W, 1.0, cfg.W,
                                                             thr_idx, thr_cnt),
+        # group-shared lists under GQA (Sec. 3.3, merged heads): one list per KV head
+        "select_salient_grouped": lambda L: hgca.select_salient_grouped(sh, L.q, L.pool, L.k, k_max, g_idx, g_cnt,
+                                                                        step.ws_sparse),
+        "sparse_attn_grouped": lambda L: hgca.sparse_attn_grouped(sh, L.q, L.pool, g_idx, g_cnt, k_max, step.o_s,
+                                                                  step.lse_s, step.ws_sparse),
     }
     call_ms = {name: time_call(fn) for name, fn in calls.items()}
     call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": int(p_lens.sum()) * cfg.Hkv * cfg.d * cfg.elem_bytes,
@@ -180,7 +187,11 @@ def main() -> int:
                   # weights: one fp32 per (head, window token) written as a score, then read and rewritten
                   "dense_window_attn_weights": nbytes["dense"] + 3 * 4 * cfg.Hq * int(w_lens.sum()),
                   "maw_update": 3 * 4 * cfg.Hq * int(w_lens.sum()),
-                  "threshold_select": 4 * cfg.Hq * int(w_lens.sum())}
+                  "threshold_select": 4 * cfg.Hq * int(w_lens.sum()),
+                  # K of the pool once per KV head + one fp32 score per (KV head, token) written and read
+                  "select_salient_grouped": int(p_lens.sum()) * cfg.Hkv * (cfg.d * cfg.elem_bytes + 8),
+                  # K and V rows of the kept entries once per KV head
+                  "sparse_attn_grouped": 2 * cfg.Hkv * k_sum * cfg.d * cfg.elem_bytes}
     call_gbps = {n: call_bytes[n] / (call_ms[n] * 1e-3) / 1e9 for n in call_bytes}
     log("[bench] per call (ms, moved GB/s): " + ", ".join(
         f"{n}={call_ms[n]:.4f}" + (f"/{call_gbps[n]:.0f}" if n in call_gbps else "") for n in call_ms))

@@ -249,6 +249,44 @@ int hgca_threshold_select(const hgca_shape *shape, const float *weights,
                           int32_t *idx_out, int32_t *cnt_out, float *w_norm_out,
                           void *hip_stream);
 
+/* ---- Group-shared salient lists for grouped-query attention (Sec. 3.3, "CPU-local
+ * sparse attention": adjacent heads are merged into one sparse attention task and
+ * the per-head sparsification is relaxed: a merged head may be padded with
+ * entries that do not meet its own criterion).  The heads of a GQA group read the
+ * same K/V rows, so the merge unit here is the group: ONE list of pool positions
+ * per KV head, idx [B,Hkv,k_max] / cnt [B,Hkv], attended by every head of the
+ * group; the sparse part then reads each listed row once per group instead of
+ * once per head. ---- */
+
+/* Group budget: per (b, KV head) the k_b entries with the largest group score,
+ * the group score of an entry being the maximum over the group's heads of
+ * s_j = sm_scale * <q_h, k_j>.  Budgets, tie rule, k_max and outputs as in
+ * hgca_select_salient, with Hkv rows per sequence instead of Hq. */
+int hgca_select_salient_grouped(const hgca_shape *shape, const void *q,
+                                const hgca_kv_view *pool,
+                                const int32_t *k_per_seq, int32_t k_uniform,
+                                int32_t k_max, int32_t *idx_out, int32_t *cnt_out,
+                                void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Union: per (b, KV head) the ascending union of the lists idx [B,Hq,k_max] /
+ * cnt [B,Hq] of the group's heads (nothing a head selected is lost).  Positions
+ * lie in [0, n_positions), n_positions <= 2^19.  idx_out is [B,Hkv,k_max_out],
+ * -1 padded, cnt_out [B,Hkv]; a union longer than k_max_out is cut (lowest
+ * positions kept) and bit 0 of *status (device int32, optional) is set. */
+int hgca_union_lists(const hgca_shape *shape, const int32_t *idx, const int32_t *cnt,
+                     int32_t k_max, int32_t n_positions,
+                     int32_t *idx_out, int32_t *cnt_out, int32_t k_max_out,
+                     int32_t *status, void *hip_stream);
+
+/* hgca_sparse_attn with one list per KV head: query head (b,h) attends to pool
+ * rows idx[b, h/G, 0 .. cnt[b, h/G]).  Outputs, deferral and workspace as in
+ * hgca_sparse_attn (k_max fixes the split count the same way). */
+int hgca_sparse_attn_grouped(const hgca_shape *shape, const void *q,
+                             const hgca_kv_view *pool,
+                             const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                             float *o_out, float *lse_out,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+
 /* ---- KV manager across decode steps (Alg. 1; Sec. 3.2.1 retention and
  * offload, Sec. 3.2.2 sparsification). ----
  *

@@ -20,7 +20,8 @@ namespace hgca {
 
 namespace {
 
-enum Mode { kDense = 0, kGather = 1, kScores = 2, kGatherScored = 3 };   // kGatherScored: scores are given
+// kGatherScored: scores are given; kGatherGroup: one index list per KV head, shared by the NH heads of its group
+enum Mode { kDense = 0, kGather = 1, kScores = 2, kGatherScored = 3, kGatherGroup = 4 };
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
@@ -41,6 +42,7 @@ struct KernelArgs {
     int32_t chunk;
     Partials part;
     float *scores;
+    int32_t group_max;     // score pass: write one row per KV head, the maximum over the group's heads
 };
 
 // ---- pieces shared by all split kernels ---------------------------------------------------
@@ -150,6 +152,15 @@ template <int NH>
 __device__ __forceinline__ void store_split_scores(const KernelArgs &a, const float (*s_p)[kMaxChunk], int64_t bh0,
                                                    int t0, int nt)
 {
+    if (a.group_max) {                           // one row per KV head: row index bh0 / NH (bh0 is the group's first head)
+        for (int j = threadIdx.x; j < nt; j += kBlock) {
+            float v = s_p[0][j];
+#pragma unroll
+            for (int g = 1; g < NH; ++g) v = fmaxf(v, s_p[g][j]);
+            a.scores[(bh0 / NH) * (int64_t)a.kv.cap + t0 + j] = v;
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < NH * nt; i += kBlock) {
         const int g = i / nt, j = i % nt;
         a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
@@ -174,14 +185,16 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 
     const int split = blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
     const int Hq = a.sh.n_q_heads, Hkv = a.sh.n_kv_heads;
-    constexpr bool GATHER = MODE == kGather || MODE == kGatherScored;
-    const int kvh = GATHER ? unit / a.sh.group : unit;
-    const int h0 = GATHER ? unit : unit * NH;                     // first of the NH heads handled
+    constexpr bool GATHER = MODE == kGather || MODE == kGatherScored || MODE == kGatherGroup;
+    constexpr bool PER_HEAD_LIST = MODE == kGather || MODE == kGatherScored;
+    const int kvh = PER_HEAD_LIST ? unit / a.sh.group : unit;
+    const int h0 = PER_HEAD_LIST ? unit : unit * NH;             // first of the NH heads handled
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
     const int r = lane / LPR, c = lane % LPR;
 
     const int64_t bh0 = (int64_t)b * Hq + h0;
-    const int n = GATHER ? min(a.cnt[bh0], a.k_max) : tier_len(a.kv, b);
+    const int64_t list = PER_HEAD_LIST ? bh0 : (int64_t)b * Hkv + unit;      // row of idx / cnt
+    const int n = GATHER ? min(a.cnt[list], a.k_max) : tier_len(a.kv, b);
     const int t0 = split * a.chunk;
 
     if (t0 >= n) {                               // empty split (uniform over the workgroup)
@@ -194,7 +207,7 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
         for (int j = tid; j < nt; j += kBlock) s_p[0][j] = given[j];
     }
     const RowMap rows = make_row_map<GATHER, kBlock>(s_row, a.kv, Hkv, b, kvh, t0, nt,
-                                                     GATHER ? a.idx + bh0 * a.k_max + t0 : nullptr);
+                                                     GATHER ? a.idx + list * a.k_max + t0 : nullptr);
     float qf[NH][EPL];
     if (MODE != kGatherScored) {
 #pragma unroll
@@ -338,12 +351,20 @@ __global__ __launch_bounds__(kScoreBlock) void pool_scores_mfma_kernel(KernelArg
 
     // coalesced streaming stores, 16 bytes per lane where the row alignment allows it
     const int64_t cap = a.kv.cap;
-    float *out = a.scores + bh0 * cap + t0;
     const bool vec_ok = (cap % 4) == 0;
     const int n4 = (nt + 3) / 4;
-    for (int i = threadIdx.x; i < G * n4; i += kScoreBlock) {
+    const int n_out = a.group_max ? 1 : G;       // rows written: one per KV head, or one per head
+    float *out = a.scores + (a.group_max ? bh0 / G : bh0) * cap + t0;
+    for (int i = threadIdx.x; i < n_out * n4; i += kScoreBlock) {
         const int g = i / n4, j = 4 * (i % n4);
-        const float4 v = *reinterpret_cast<const float4 *>(&s_sc[g][j]);
+        float4 v = *reinterpret_cast<const float4 *>(&s_sc[g][j]);
+        if (a.group_max) {
+#pragma unroll
+            for (int gg = 1; gg < G; ++gg) {
+                const float4 u = *reinterpret_cast<const float4 *>(&s_sc[gg][j]);
+                v = make_float4(fmaxf(v.x, u.x), fmaxf(v.y, u.y), fmaxf(v.z, u.z), fmaxf(v.w, u.w));
+            }
+        }
         float *o = out + g * cap + j;
         if (vec_ok && j + 3 < nt) {              // one 16-byte streaming store
             const floatx4 vv = {v.x, v.y, v.z, v.w};
@@ -555,9 +576,31 @@ hipError_t launch_attn_partial_dense(int dtype, int head_dim, const AttnArgs &a,
     return launch_tier_pass<kDense>(dtype, head_dim, to_kernel_args(a), grid, s);
 }
 
+template <typename T, int D>
+hipError_t launch_gather_group(const KernelArgs &ka, int nh, dim3 grid, hipStream_t s)
+{
+    switch (nh) {
+    case 1: HGCA_LAUNCH((attn_split_kernel<T, D, 1, kGatherGroup>), grid, dim3(kBlock), s, ka); break;
+    case 2: HGCA_LAUNCH((attn_split_kernel<T, D, 2, kGatherGroup>), grid, dim3(kBlock), s, ka); break;
+    case 4: HGCA_LAUNCH((attn_split_kernel<T, D, 4, kGatherGroup>), grid, dim3(kBlock), s, ka); break;
+    case 8: HGCA_LAUNCH((attn_split_kernel<T, D, 8, kGatherGroup>), grid, dim3(kBlock), s, ka); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_partial_gather(int dtype, int head_dim, const AttnArgs &a, hipStream_t s)
 {
     if (a.sh.batch == 0 || a.part.n_splits == 0) return hipSuccess;
+    if (a.grouped) {                             // one list per KV head: a workgroup serves the whole group
+        dim3 grid(a.part.n_splits, a.sh.n_kv_heads, a.sh.batch);
+        const KernelArgs ka = to_kernel_args(a);
+        if (dtype == 0 && head_dim == 64) return launch_gather_group<float, 64>(ka, a.sh.group, grid, s);
+        if (dtype == 0 && head_dim == 128) return launch_gather_group<float, 128>(ka, a.sh.group, grid, s);
+        if (dtype == 1 && head_dim == 64) return launch_gather_group<bf16_t, 64>(ka, a.sh.group, grid, s);
+        if (dtype == 1 && head_dim == 128) return launch_gather_group<bf16_t, 128>(ka, a.sh.group, grid, s);
+        return hipErrorInvalidValue;
+    }
     dim3 grid(a.part.n_splits, a.sh.n_q_heads, a.sh.batch);
     const KernelArgs ka = to_kernel_args(a);
 #define HGCA_GATHER_CASE(T, D)                                                                              \
@@ -581,6 +624,7 @@ hipError_t launch_scores(int dtype, int head_dim, const ScoreArgs &a, hipStream_
     ka.kv = a.kv;
     ka.chunk = a.chunk;
     ka.scores = a.scores;
+    ka.group_max = a.group_max;
     dim3 grid(a.n_chunks, a.sh.n_kv_heads, a.sh.batch);
     return launch_tier_pass<kScores>(dtype, head_dim, ka, grid, s);
 }

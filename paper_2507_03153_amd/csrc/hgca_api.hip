@@ -360,6 +360,89 @@ int hgca_sparse_attn(const hgca_shape *shape, const void *q, const hgca_kv_view 
     return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
 }
 
+int hgca_select_salient_grouped(const hgca_shape *shape, const void *q, const hgca_kv_view *pool,
+                                const int32_t *k_per_seq, int32_t k_uniform, int32_t k_max, int32_t *idx_out,
+                                int32_t *cnt_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(shape, pool, false)) != HGCA_OK) return rc;
+    if (!q || !aligned16(q) || !cnt_out || k_max < 0 || (k_max > 0 && !idx_out)) return HGCA_ERR_INVALID_ARG;
+    if (!k_per_seq && (k_uniform < 0 || std::min(k_uniform, pool->cap) > k_max)) return HGCA_ERR_INVALID_ARG;
+    const WsLayout w = layout(shape, 0, pool->cap);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    ScoreArgs sa{};
+    sa.sh = to_dev(shape);
+    sa.q = q;
+    sa.kv = to_dev(pool);
+    sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws) + w.scores);    // [B, Hkv, cap] of the region
+    sa.group_max = 1;
+    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
+                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+    sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
+    if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
+
+    SelectArgs se{};
+    se.sh = sa.sh;
+    se.sh.n_q_heads = shape->n_kv_heads;         // one row of scores and one list per KV head
+    se.kv = sa.kv;
+    se.scores = sa.scores;
+    se.k_per_seq = k_per_seq;
+    se.k_uniform = k_uniform;
+    se.k_max = k_max;
+    se.idx = idx_out;
+    se.cnt = cnt_out;
+    return from_hip(launch_select(se, s));
+}
+
+int hgca_union_lists(const hgca_shape *shape, const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                     int32_t n_positions, int32_t *idx_out, int32_t *cnt_out, int32_t k_max_out, int32_t *status,
+                     void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (k_max < 0 || k_max_out < 0 || n_positions < 0 || n_positions > (1 << 19)) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return HGCA_OK;
+    if (!cnt || !cnt_out || (k_max > 0 && !idx) || (k_max_out > 0 && !idx_out)) return HGCA_ERR_INVALID_ARG;
+    return from_hip(launch_union_lists(idx, cnt, k_max, shape->batch, shape->n_q_heads, shape->n_kv_heads, n_positions,
+                                       idx_out, cnt_out, k_max_out, status, static_cast<hipStream_t>(hip_stream)));
+}
+
+int hgca_sparse_attn_grouped(const hgca_shape *shape, const void *q, const hgca_kv_view *pool, const int32_t *idx,
+                             const int32_t *cnt, int32_t k_max, float *o_out, float *lse_out, void *ws,
+                             size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(shape, pool, true)) != HGCA_OK) return rc;
+    const bool deferred = !o_out && !lse_out;
+    if (!q || !aligned16(q) || (!deferred && (!o_out || !lse_out || !aligned16(o_out)))) return HGCA_ERR_INVALID_ARG;
+    if (k_max < 0 || !cnt || (k_max > 0 && !idx)) return HGCA_ERR_INVALID_ARG;
+    const WsLayout w = layout(shape, k_max, 0);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    AttnArgs a{};
+    a.sh = to_dev(shape);
+    a.q = q;
+    a.kv = to_dev(pool);
+    a.idx = idx;
+    a.cnt = cnt;
+    a.k_max = k_max;
+    a.grouped = 1;
+    // same split size as hgca_sparse_attn (hgca_lse_merge_splits derives the split count from k_max alone)
+    a.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
+    a.part = partials_at(ws, w, std::max(1, n_splits_for(k_max, a.chunk)));
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, a, s))) != HGCA_OK) return rc;
+    if (deferred) return HGCA_OK;
+    return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
+}
+
 int hgca_lse_merge_splits(const hgca_shape *shape, int32_t window_cap, const void *ws_dense, size_t ws_dense_bytes,
                           int32_t k_max, const void *ws_sparse, size_t ws_sparse_bytes, void *o_out, int32_t o_dtype,
                           float *lse_out, void *hip_stream)

@@ -32,6 +32,7 @@ struct AttnArgs {
     int32_t chunk;         // tokens per split
     Partials part;
     float *raw_scores;     // dense only, optional: [B, Hq, cap], receives the scaled score of every valid token
+    int32_t grouped;       // gather only: idx is [B, Hkv, k_max], cnt [B, Hkv]; the heads of a group share the list
 };
 
 // dtype: 0 fp32, 1 bf16; head_dim 64|128.  Dense handles the `group` query heads
@@ -51,9 +52,10 @@ struct ScoreArgs {
     ShapeDev sh;
     const void *q;
     KvDev kv;
-    float *scores;         // [B, Hq, cap] fp32
+    float *scores;         // [B, Hq, cap] fp32, or [B, Hkv, cap] with group_max
     int32_t chunk;
     int32_t n_chunks;
+    int32_t group_max;     // write the maximum over the heads of each group instead of every head's score
 };
 hipError_t launch_scores(int dtype, int head_dim, const ScoreArgs &a, hipStream_t s);
 
@@ -68,6 +70,12 @@ struct SelectArgs {
     float *sel_scores;     // optional [B, Hq, k_max]: score of every kept entry, in idx order
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t s);
+
+// Union of the index lists of the heads of each group: idx [B, Hq, k_max] / cnt [B, Hq] -> out [B, Hkv, k_max_out]
+// ascending, -1 padded, out_cnt [B, Hkv].  Positions must lie in [0, n_positions).
+hipError_t launch_union_lists(const int32_t *idx, const int32_t *cnt, int32_t k_max, int32_t batch, int32_t n_q_heads,
+                              int32_t n_kv_heads, int32_t n_positions, int32_t *out, int32_t *out_cnt,
+                              int32_t k_max_out, int32_t *status, hipStream_t s);
 
 // ---- attention weights, their moving average, threshold rule ----
 

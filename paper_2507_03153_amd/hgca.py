@@ -24,7 +24,8 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
-           "hgca_append_weights", "hgca_dense_window_attn_maw")
+           "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
+           "hgca_sparse_attn_grouped")
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -95,6 +96,12 @@ def lib() -> ctypes.CDLL:
         L.hgca_kv_append.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp]
         L.hgca_kv_evict.restype = ctypes.c_int
         L.hgca_kv_evict.argtypes = [ps, ctypes.POINTER(CacheState), ctypes.c_double, vp]
+        L.hgca_select_salient_grouped.restype = ctypes.c_int
+        L.hgca_select_salient_grouped.argtypes = [ps, vp, pk, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.hgca_union_lists.restype = ctypes.c_int
+        L.hgca_union_lists.argtypes = [ps, vp, vp, i32, i32, vp, vp, i32, vp, vp]
+        L.hgca_sparse_attn_grouped.restype = ctypes.c_int
+        L.hgca_sparse_attn_grouped.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
         L.hgca_dense_window_attn_maw.restype = ctypes.c_int
         L.hgca_dense_window_attn_maw.argtypes = [ps, vp, pk, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         L.hgca_maw_update.restype = ctypes.c_int
@@ -338,3 +345,37 @@ def dense_window_attn_maw(shape: Shape, q, window: Tier, o_out, lse_out, a_out, 
     _check(lib().hgca_dense_window_attn_maw(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out), _ptr(lse_out),
                                             _ptr(a_out), _ptr(a_maw), int(n_new), float(alpha), _ptr(ws), ws.numel(),
                                             _stream(stream)), "hgca_dense_window_attn_maw")
+
+
+def select_salient_grouped(shape: Shape, q, pool: Tier, k, k_max: int, idx_out, cnt_out, ws, stream=None) -> None:
+    """One list per KV head (idx_out [B,Hkv,k_max], cnt_out [B,Hkv]): top-k of the maximum score over the group."""
+    for t in (q, idx_out, cnt_out, ws):
+        _require_gpu(t)
+    kv = pool.view()
+    if isinstance(k, torch.Tensor):
+        _require_gpu(k)
+        k_ptr, k_uni = _ptr(k), 0
+    else:
+        k_ptr, k_uni = None, int(k)
+    _check(lib().hgca_select_salient_grouped(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), k_ptr, k_uni, int(k_max),
+                                             _ptr(idx_out), _ptr(cnt_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_select_salient_grouped")
+
+
+def union_lists(shape: Shape, idx, cnt, k_max: int, n_positions: int, idx_out, cnt_out, k_max_out: int, status=None,
+                stream=None) -> None:
+    """Per KV head, the ascending union of its heads' lists."""
+    for t in (idx, cnt, idx_out, cnt_out) + (() if status is None else (status,)):
+        _require_gpu(t)
+    _check(lib().hgca_union_lists(ctypes.byref(shape), _ptr(idx), _ptr(cnt), int(k_max), int(n_positions), _ptr(idx_out),
+                                  _ptr(cnt_out), int(k_max_out), _ptr(status), _stream(stream)), "hgca_union_lists")
+
+
+def sparse_attn_grouped(shape: Shape, q, pool: Tier, idx, cnt, k_max: int, o_out, lse_out, ws, stream=None) -> None:
+    """sparse_attn with idx [B,Hkv,k_max], cnt [B,Hkv]: the heads of a group share the list."""
+    for t in (q, idx, cnt, ws) + (() if o_out is None else (o_out, lse_out)):
+        _require_gpu(t)
+    kv = pool.view()
+    _check(lib().hgca_sparse_attn_grouped(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
+                                          _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_sparse_attn_grouped")

@@ -251,3 +251,35 @@ def test_append_entry_points_reject_bad_arguments(hg):
     assert weights(n_q=0) == hg.ERR_INVALID_ARG
     assert weights(lse=None) == hg.ERR_INVALID_ARG
     assert weights(a=None) == hg.ERR_INVALID_ARG
+
+
+def test_grouped_entry_points_reject_bad_arguments(hg):
+    L = hg.lib()
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    view = _view(hg)
+    byref = ctypes.byref
+
+    def sel(q=FAKE, k=8, k_max=8, idx=FAKE, cnt=FAKE, ws=FAKE, ws_bytes=1 << 40):
+        return L.hgca_select_salient_grouped(byref(sh), q, byref(view), None, k, k_max, idx, cnt, ws, ws_bytes, None)
+    assert sel(q=None) == hg.ERR_INVALID_ARG
+    assert sel(k=9) == hg.ERR_INVALID_ARG
+    assert sel(idx=None) == hg.ERR_INVALID_ARG
+    assert sel(cnt=None) == hg.ERR_INVALID_ARG
+    assert sel(ws_bytes=16) == hg.ERR_WORKSPACE
+
+    def uni(idx=FAKE, cnt=FAKE, k_max=8, n_pos=64, out=FAKE, out_cnt=FAKE, k_out=32):
+        return L.hgca_union_lists(byref(sh), idx, cnt, k_max, n_pos, out, out_cnt, k_out, None, None)
+    assert uni(idx=None) == hg.ERR_INVALID_ARG
+    assert uni(cnt=None) == hg.ERR_INVALID_ARG
+    assert uni(out=None) == hg.ERR_INVALID_ARG
+    assert uni(n_pos=-1) == hg.ERR_INVALID_ARG
+    assert uni(n_pos=(1 << 19) + 1) == hg.ERR_INVALID_ARG
+    assert uni(k_max=-1) == hg.ERR_INVALID_ARG
+
+    def att(q=FAKE, idx=FAKE, cnt=FAKE, k_max=8, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40):
+        return L.hgca_sparse_attn_grouped(byref(sh), q, byref(view), idx, cnt, k_max, o, lse, ws, ws_bytes, None)
+    assert att(q=ODD) == hg.ERR_INVALID_ARG
+    assert att(idx=None) == hg.ERR_INVALID_ARG
+    assert att(cnt=None) == hg.ERR_INVALID_ARG
+    assert att(o=None) == hg.ERR_INVALID_ARG                   # one output without the other
+    assert att(ws=None) == hg.ERR_WORKSPACE
