@@ -45,22 +45,6 @@ template <int D> struct AStage {
     static constexpr int kLoads = (kTotal + kABlock - 1) / kABlock;  // loads per thread, step and tensor
 };
 
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef short short8v __attribute__((ext_vector_type(8)));
-
-// LDS transpose read of 16-bit elements (ds_read_b64_tr_b16): inside a 16-lane group, lane i receives as its
-// element e the element i % 4 of the four that lane 4e + i/4 points at.  So if lane j of a group points at
-// columns 4(j%4) .. 4(j%4)+3 of row j/4 of a row-major tile, lane i ends up with column i of rows 0..3:
-// the 8-tokens-of-one-column slice an MFMA operand needs, straight from the rows as they were loaded.
-__device__ __forceinline__ short4v lds_read_tr16(const char *p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (short4v __attribute__((address_space(3))) *)(const_cast<char *>(p)));
-}
-
-// Token of a 32-token block that contraction index 8*g + i stands for in lane group g: the lane's own score
-// registers hold tokens 4g..4g+3 of the block's first 16-token tile and of its second one.
-__device__ __forceinline__ int block_token(int g, int i) { return i < 4 ? 4 * g + i : 16 + 4 * g + (i - 4); }
-
 // The value of the lane ROT places further on in the same row of 16 lanes (DPP row_ror).
 template <int ROT>
 __device__ __forceinline__ float row_rotate(float x) {

@@ -378,13 +378,99 @@ __global__ __launch_bounds__(kScoreBlock) void pool_scores_mfma_kernel(KernelArg
     }
 }
 
+// Heads per group from which the V pass of the dense kernel runs on the matrix cores.  With 8 heads the VALU pass
+// (G fused multiply-adds per loaded element) is bound by instruction issue (2.8 TB/s measured, 3.6 with MFMA);
+// with 4 heads and fewer the VALU pass keeps up with HBM and needs less LDS (measured 31.2 against 32.3 us on C2).
+#ifndef HGCA_DENSE_PV_MFMA_FROM
+#define HGCA_DENSE_PV_MFMA_FROM 8
+#endif
+constexpr int kPvPad = 32;                       // bytes of padding per V row in the stage (conflict-free transpose reads)
+
+// V pass on the matrix cores: O^T[dcol, head] += V^T[dcol, token] . P^T[token, head] in 32-token blocks, one wave
+// per block.  The block's V rows are parked in a wave-private LDS stage as loaded (row-major) and come back
+// through transpose reads as the A operand; the weights of the block (fp32 in s_p) are rounded to a high and a
+// low bf16 part for the B operand (column = head, zero beyond the group).
+template <int D, int G>
+__device__ __forceinline__ void value_pass_mfma(const KernelArgs &a, float (*s_p)[kMaxChunk], char *stage,
+                                                float (*s_red)[G][D], const float *s_m, const float *s_l, int64_t bh0,
+                                                int split, int nt, const RowMap &rows)
+{
+    constexpr int DT = D / 16, PIECES = D / 8, VS = D * 2 + kPvPad, LOADS = 32 * PIECES / kWave;
+    constexpr size_t ROW_BYTES = D * 2;
+    const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave, n = lane % 16, g = lane / 16;
+    char *st = stage + w * (32 * VS);
+    floatx4 acc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int n_blocks = (nt + 31) / 32;
+    auto load_block = [&](int blk, uint4 (&vr)[LOADS]) {
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) {
+            const int p = lane + kWave * u, trow = p / PIECES, piece = p % PIECES;
+            vr[u] = load16_stream(a.kv.v + rows(min(blk * 32 + trow, nt - 1)) * ROW_BYTES + 16 * piece);
+        }
+    };
+    uint4 vr[LOADS];
+    if (w < n_blocks) load_block(w, vr);
+    for (int blk = w; blk < n_blocks; blk += kWaves) {
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) {
+            const int p = lane + kWave * u, trow = p / PIECES, piece = p % PIECES;
+            *reinterpret_cast<uint4 *>(st + trow * VS + 16 * piece) = vr[u];
+        }
+        if (blk + kWaves < n_blocks) load_block(blk + kWaves, vr);
+        __builtin_amdgcn_wave_barrier();
+        bf16x8 ph, pl;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = blk * 32 + block_token(g, i);
+            const float p = (n < G && j < nt) ? s_p[n < G ? n : 0][j] : 0.f;
+            ph[i] = (__bf16)p;
+            pl[i] = (__bf16)(p - (float)ph[i]);
+        }
+        const char *v_lo = st + block_token(g, n / 4) * VS + 8 * (n % 4);
+        const char *v_hi = st + block_token(g, 4 + n / 4) * VS + 8 * (n % 4);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const short4v a0 = lds_read_tr16(v_lo + 32 * dt), a1 = lds_read_tr16(v_hi + 32 * dt);
+            const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+            const bf16x8 vop = __builtin_bit_cast(bf16x8, both);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, ph, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pl, acc[dt], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();                             // every wave is done with its stage: the reduction reuses the space
+    if (n < G) {                                 // lane (head n, group g) holds output columns dt*16 + 4g .. +3
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            *reinterpret_cast<float4 *>(&s_red[w][n][dt * 16 + 4 * g]) =
+                make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]);
+    }
+    __syncthreads();
+    for (int i = tid; i < G * D; i += kBlock) {
+        const int gg = i / D, col = i % D;
+        float v = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) v += s_red[ww][gg][col];
+        a.part.o[((bh0 + gg) * a.part.n_splits + split) * D + col] = v;
+    }
+    if (tid < G) {
+        a.part.m[(bh0 + tid) * a.part.n_splits + split] = s_m[tid];
+        a.part.l[(bh0 + tid) * a.part.n_splits + split] = s_l[tid];
+    }
+}
+
 template <int D, int G>
 __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
 {
-    // the K stage is dead once the scores are in s_p; the output reduction reuses its space
+    // the K stage is dead once the scores are in s_p; the V stage and the output reduction reuse its space
     constexpr int kStageBytes = kWaves * Stage<D>::kWaveVecs * 16;
-    constexpr int kRedBytes = kWaves * G * D * 4;
-    __shared__ __attribute__((aligned(16))) char s_buf[kStageBytes > kRedBytes ? kStageBytes : kRedBytes];
+    constexpr bool kPvMfma = G >= HGCA_DENSE_PV_MFMA_FROM;
+    constexpr int kVStageBytes = kPvMfma ? kWaves * 32 * (D * 2 + kPvPad) : 0;
+    constexpr int kRedBytes = kWaves * G * D * 4 + kVStageBytes;
+    constexpr int kBufBytes = kStageBytes > kRedBytes ? kStageBytes : kRedBytes;
+    __shared__ __attribute__((aligned(16))) char s_buf[kBufBytes];
     __shared__ __attribute__((aligned(16))) float s_p[G][kMaxChunk];
     __shared__ float s_m[G], s_l[G];
     __shared__ uint32_t s_row[kMaxChunk];
@@ -404,7 +490,11 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
     if (a.scores) store_split_scores<G>(a, s_p, bh0, t0, nt);
     split_softmax<G>(s_p, s_m, s_l, nt);
     __syncthreads();
-    value_pass<bf16_t, D, G, false>(a, s_p, reinterpret_cast<float (*)[G][D]>(s_buf), s_m, s_l, bh0, split, nt, rows);
+    if (kPvMfma)                                 // V stage first, reduction area behind it
+        value_pass_mfma<D, G>(a, s_p, s_buf, reinterpret_cast<float (*)[G][D]>(s_buf + kVStageBytes), s_m, s_l, bh0, split,
+                              nt, rows);
+    else
+        value_pass<bf16_t, D, G, false>(a, s_p, reinterpret_cast<float (*)[G][D]>(s_buf), s_m, s_l, bh0, split, nt, rows);
 }
 
 // ---- combine and merge ------------------------------------------------------------------------------

@@ -26,7 +26,10 @@ namespace {
 
 constexpr int kSelBlock = 1024;
 constexpr int kSelWaves = kSelBlock / kWave;
-constexpr int kBins = 4096;
+#ifndef HGCA_SEL_BINS
+#define HGCA_SEL_BINS 4096
+#endif
+constexpr int kBins = HGCA_SEL_BINS;
 constexpr int kBinsPerThread = kBins / kSelBlock;
 constexpr int kMaxCand = kSelBlock;              // one candidate per thread in the exact ranking
 constexpr int kStep = 4 * kWave;                 // scores a wave handles per step
