@@ -45,10 +45,13 @@ __device__ __forceinline__ float key_to_score(uint32_t key) {
     return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
+static_assert(kBins >= 2 * kMaxCand, "the candidate lists live in the histogram's space");
 struct SelShared {
-    alignas(16) uint32_t hist[kBins];            // reused as the output staging area of the compaction
-    float cand_score[kMaxCand];
-    int32_t cand_idx[kMaxCand];
+    // The histogram is dead once the threshold bin is located; the candidate lists of the exact ranking then
+    // take its first 2 * kMaxCand words, and after the ranking the whole array stages the output of the compaction.
+    alignas(16) uint32_t hist[kBins];
+    __device__ __forceinline__ float *cand_score() { return reinterpret_cast<float *>(hist); }
+    __device__ __forceinline__ int32_t *cand_idx() { return reinterpret_cast<int32_t *>(hist + kMaxCand); }
     uint32_t scan_scratch[kSelWaves];
     float wave_min[kSelWaves], wave_max[kSelWaves];
     uint32_t wave_gt[kSelWaves], wave_eq[kSelWaves];
@@ -129,13 +132,24 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
 }
 
 // The padded row: wave w owns the positions [w*seg, (w+1)*seg), seg a multiple of kStep; in step i a
-// lane holds the 4 scores at w*seg + kStep*i + 4*lane.  Positions >= n hold -inf.
+// lane holds the 4 scores at w*seg + kStep*i + 4*lane.  Positions >= n hold -inf.  The row is padded to a
+// whole number of segments (not of workgroups of segments): waves whose segment lies beyond it have no steps.
+// Positions per wave, and the padded length of a row of n scores.
+__host__ __device__ inline int segment_length(int n) { return ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep; }
+__host__ __device__ inline int padded_length(int n) {
+    const int seg = segment_length(n);
+    return seg ? (n + seg - 1) / seg * seg : 0;
+}
+
 template <bool CACHED>
 struct Row {
     const float *sc, *cache;
     bool sc_vec;
     int n, seg;
-    __device__ __forceinline__ int steps() const { return seg / kStep; }
+    __device__ __forceinline__ int padded() const { return (n + seg - 1) / seg * seg; }
+    __device__ __forceinline__ int steps() const {             // uniform over a wave
+        return (int)(threadIdx.x / kWave) * seg < padded() ? seg / kStep : 0;
+    }
     __device__ __forceinline__ int pos(int i) const {
         return (int)(threadIdx.x / kWave) * seg + kStep * i + 4 * (int)(threadIdx.x % kWave);
     }
@@ -155,8 +169,8 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     row.cache = cache;
     row.sc_vec = (a.kv.cap & 3) == 0;            // rows start 16-byte aligned
     row.n = n;
-    row.seg = ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
-    const int padded = kSelWaves * row.seg;      // >= n
+    row.seg = segment_length(n);
+    const int padded = row.padded();             // >= n, <= kSelWaves * seg
     const int steps = row.steps();
 
     // ---- pass 0: range of the row; the padded row goes to LDS ---------------------------------------
@@ -233,7 +247,7 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
             above += over;
             if (x >= edge_lo && !over) {
                 const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
-                if (slot < (uint32_t)kMaxCand) { sh.cand_score[slot] = s[e]; sh.cand_idx[slot] = t + e; }
+                if (slot < (uint32_t)kMaxCand) { sh.cand_score()[slot] = s[e]; sh.cand_idx()[slot] = t + e; }
             }
         }
     }
@@ -247,13 +261,13 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         float my_s = 0.f;
         int32_t my_idx = 0;
         if ((uint32_t)tid < n_cand) {
-            my_s = sh.cand_score[tid];
-            my_idx = sh.cand_idx[tid];
+            my_s = sh.cand_score()[tid];
+            my_idx = sh.cand_idx()[tid];
             uint32_t gt = 0, eq_lower = 0;
             for (uint32_t j = 0; j < n_cand; ++j) {
-                const float sj = sh.cand_score[j];
+                const float sj = sh.cand_score()[j];
                 gt += sj > my_s;
-                eq_lower += (sj == my_s) && (sh.cand_idx[j] < my_idx);
+                eq_lower += (sj == my_s) && (sh.cand_idx()[j] < my_idx);
             }
             if (gt + eq_lower == k_rem - 1) { sh.found[0] = __float_as_uint(my_s); sh.found[1] = k_rem - gt; }
         }
@@ -417,8 +431,7 @@ __global__ __launch_bounds__(kSelBlock) void select_topk_kernel(SelectArgs a, in
         }
         return;
     }
-    const int seg = ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
-    if (kSelWaves * seg <= cache_floats) select_row<true>(a, sh, s_cache, sc, out, n, k);
+    if (padded_length(n) <= cache_floats) select_row<true>(a, sh, s_cache, sc, out, n, k);
     else select_row<false>(a, sh, s_cache, sc, out, n, k);
 }
 
@@ -429,8 +442,8 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s)
     const int64_t rows = (int64_t)a.sh.batch * a.sh.n_q_heads;
     if (rows == 0) return hipSuccess;
     // rows whose padded length fits are cached in LDS (dynamic, beyond the 64 KiB default limit)
-    const int seg = ((a.kv.cap + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
-    const int cache_floats = kSelWaves * seg <= kMaxCacheFloats ? kSelWaves * seg : 0;
+    // (the padded length grows with n in steps, so the capacity's padded length covers every row)
+    const int cache_floats = padded_length(a.kv.cap) <= kMaxCacheFloats ? padded_length(a.kv.cap) : 0;
     // once per process (thread-safe static initialisation): lift the dynamic LDS limit of the kernel
     static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel),
                                                           hipFuncAttributeMaxDynamicSharedMemorySize,
