@@ -35,7 +35,7 @@ METRIC = "hybrid decode-attn layer-steps/s + achieved HBM GB/s vs peak (8B shape
 
 # HBM bytes per launch of the pool-score kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
 # scaled by the same counters on a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = 499_731_046
+MEASURED_TRAFFIC_BYTES = 495_292_337
 
 
 WORKLOADS = {
