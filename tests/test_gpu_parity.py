@@ -368,3 +368,38 @@ def test_c5_full_size_ragged_paged(gpu, oracle):
 def test_c3_full_size_mha(gpu, oracle):
     """B=32, 40 MHA heads, 16K context (10.7 GB of KV)."""
     run_case(gpu, oracle, wl.CONFIGS["C3"])
+
+
+# ---------------------------------------------------------------- seeded sweep over small random shapes
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        G = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        d = int(rng.choice([64, 128]))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        W = int(rng.choice([0, 1, 17, 64, 255, 256, 257, 600]))
+        P = int(rng.choice([0, 1, 63, 64, 65, 1000, 2049, 3000]))
+        k = int(rng.integers(0, max(P, 1) + 1)) if rng.random() < 0.7 else int(rng.choice([0, 1, P, P + 5]))
+        kw = dict(B=int(rng.integers(1, 4)), Hq=G * Hkv, Hkv=Hkv, d=d, W=W, P=P, k=k)
+        mode = rng.random()
+        if mode < 0.3 and W >= 16 and P >= 16:                 # ragged paged, blocks of 16
+            kw.update(ragged=(int(W // 2), W + P), k_frac=0.1, block_size=16)
+        elif mode < 0.5 and W >= 16 and P >= 16:               # ragged contiguous
+            kw.update(ragged=(int(W // 3), W + P), k_frac=0.25, block_size=0)
+        out.append((f"s{i}_{dtype}_g{G}_d{d}_W{W}_P{P}_k{k}", dtype, kw))
+    return out
+
+
+@pytest.mark.parametrize("name,dtype,kw", _random_shapes(24, 2507), ids=lambda x: x if isinstance(x, str) else None)
+def test_seeded_sweep_of_small_shapes(gpu, oracle, name, dtype, kw):
+    base = wl.CONFIGS["C1" if dtype == "f32" else ("C5" if "ragged" in kw else "C2")]
+    run_case(gpu, oracle, wl.scaled(base, **kw))
+
+
+@pytest.mark.parametrize("P", [33791, 33792, 33793], ids=["below", "at", "above"])
+def test_pool_lengths_around_the_lds_cache_limit(gpu, oracle, P):
+    """33 792 scores are the longest row the selection keeps in LDS: the row before, at and after the switch."""
+    run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], B=1, Hq=2, Hkv=1, W=32, P=P, k=700), check_end_to_end=False)
