@@ -106,11 +106,11 @@ struct StepLoader {
     }
 };
 
-// Scaled scores of one 16-row tile for the step's tokens: sv[8*kb + 4*tt + r] belongs to step token
-// 32*kb + 16*tt + 4*g + r and query row lane % 16.  With MASK, tokens at or beyond `limit` (counted from the
-// step's first token) read -inf.
+// Raw scores <q, k> (no softmax scale yet) of one 16-row tile for the step's tokens: sv[8*kb + 4*tt + r] belongs
+// to step token 32*kb + 16*tt + 4*g + r and query row lane % 16.  With MASK, tokens at or beyond `limit` (counted
+// from the step's first token) read -inf.
 template <int D, bool MASK>
-__device__ __forceinline__ void tile_scores(const uint4 *s_k, const bf16x8 (&qop)[D / 32], float scale, int limit,
+__device__ __forceinline__ void tile_scores(const uint4 *s_k, const bf16x8 (&qop)[D / 32], int limit,
                                             float (&sv)[8 * kStepBlocks])
 {
     using S = AStage<D>;
@@ -124,7 +124,7 @@ __device__ __forceinline__ void tile_scores(const uint4 *s_k, const bf16x8 (&qop
             c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qop[kk], c, 0, 0, 0);
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sv[4 * t + r] = (!MASK || 16 * t + 4 * g + r < limit) ? c[r] * scale : -INFINITY;
+        for (int r = 0; r < 4; ++r) sv[4 * t + r] = (!MASK || 16 * t + 4 * g + r < limit) ? c[r] : -INFINITY;
     }
 }
 
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
 {
     using S = AStage<D>;
     constexpr int DT = D / 16;
-    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    constexpr float kLog2e = 1.4426950408889634f;
     __shared__ uint4 s_k[2][kStepTokens * S::kKStride];
     __shared__ __attribute__((aligned(16))) char s_v[2][kStepTokens * S::kVStride];
     __shared__ uint32_t s_row[kSub];
@@ -173,7 +173,9 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
     for (int off = 1; off < 16; off <<= 1) vis_min = min(vis_min, __shfl_xor(vis_min, off, kWave));
     bf16x8 qop[D / 32];
     load_q_tile<D>(a, ri, g, qop);
-    // scores are kept in units of ln 2 (the exponentials are then bare v_exp_f32)
+    // The running maximum m is kept on the RAW scores (the softmax scale is positive, so the order is the same) and
+    // the scale, in units of ln 2, is applied inside the exponent: e^{scale (s - m)} = 2^{fma(s, scale2, -m scale2)},
+    // one fused multiply-add and one bare v_exp_f32 per score.
     const float scale2 = a.sh.sm_scale * kLog2e;
     float m = -INFINITY, l = 0.f;
     floatx4 acc[DT];
@@ -193,24 +195,26 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
             const int in_split = nsub - s * kStepTokens;         // tokens of the step that belong to this split
             float sv[8 * kStepBlocks];
             if (min(in_split, vis_min - step0) >= kStepTokens)   // uniform over the wave: every token visible to every row
-                tile_scores<D, false>(s_k[buf], qop, scale2, 0, sv);
+                tile_scores<D, false>(s_k[buf], qop, 0, sv);
             else
-                tile_scores<D, true>(s_k[buf], qop, scale2, min(in_split, vis - step0), sv);
+                tile_scores<D, true>(s_k[buf], qop, min(in_split, vis - step0), sv);
             float mx = sv[0];
 #pragma unroll
             for (int e = 1; e < 8 * kStepBlocks; ++e) mx = fmaxf(mx, sv[e]);
             mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
             const float m_new = fmaxf(m, mx);
+            // a row that has seen nothing yet keeps m = -inf: shift by 0 then, every exponent is -inf and gives 0
+            const float shift = (m_new == -INFINITY) ? 0.f : -m_new * scale2;
             float ps = 0.f;
 #pragma unroll
             for (int e = 0; e < 8 * kStepBlocks; ++e) {          // sv becomes the probabilities; masked scores give 0
-                sv[e] = (m_new == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv[e] - m_new);
+                sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], scale2, shift));
                 ps += sv[e];
             }
             ps += __shfl_xor(ps, 16, kWave);
             ps += __shfl_xor(ps, 32, kWave);
-            const float corr = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_new);
+            const float corr = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(fmaf(m, scale2, shift));
             l = l * corr + ps;
             m = m_new;
             if (__any(corr != 1.f)) {
@@ -230,13 +234,26 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
                 // contraction index j/4 (first read) and 4 + j/4 (second read).
                 const char *v_lo = s_v[buf] + (32 * kb + block_token(g, n / 4)) * S::kVStride + 8 * (n % 4);
                 const char *v_hi = s_v[buf] + (32 * kb + block_token(g, 4 + n / 4)) * S::kVStride + 8 * (n % 4);
+                // column tiles in groups of kPvGroup: the group's high-part products first, then its low-part ones, so
+                // that two MFMAs on the same accumulator are kPvGroup instructions apart
+                constexpr int kPvGroup = 4;
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const short4v a0 = lds_read_tr16(v_lo + 32 * dt), a1 = lds_read_tr16(v_hi + 32 * dt);
-                    const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-                    const bf16x8 vop = __builtin_bit_cast(bf16x8, both);
-                    acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, ph, acc[dt], 0, 0, 0);
-                    if (SPLIT_P) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pl, acc[dt], 0, 0, 0);
+                for (int dt0 = 0; dt0 < DT; dt0 += kPvGroup) {
+                    bf16x8 vop[kPvGroup];
+#pragma unroll
+                    for (int u = 0; u < kPvGroup; ++u) {
+                        const short4v a0 = lds_read_tr16(v_lo + 32 * (dt0 + u)), a1 = lds_read_tr16(v_hi + 32 * (dt0 + u));
+                        const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                        vop[u] = __builtin_bit_cast(bf16x8, both);
+                    }
+#pragma unroll
+                    for (int u = 0; u < kPvGroup; ++u)
+                        acc[dt0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[u], ph, acc[dt0 + u], 0, 0, 0);
+                    if (SPLIT_P) {
+#pragma unroll
+                        for (int u = 0; u < kPvGroup; ++u)
+                            acc[dt0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[u], pl, acc[dt0 + u], 0, 0, 0);
+                    }
                 }
             }
         });
@@ -250,7 +267,7 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
             *reinterpret_cast<float4 *>(a.part.o + at * D + dt * 16 + 4 * g) =
                 make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]);
         if (g == 0) {
-            a.part.m[at] = m * kLn2;             // back to natural units (-inf stays -inf)
+            a.part.m[at] = m * a.sh.sm_scale;    // the maximum of the scaled scores (-inf stays -inf)
             a.part.l[at] = l;
         }
     }
@@ -284,7 +301,10 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     for (int qb = 0; qb < n_qb && nt_total > 0; ++qb) {
         const RowInfo ri = row_info<G>(a, b, kvh, qb * kRowsPerBlock + w * 16 + n);
         const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
-        const float lse2 = (ri.valid ? a.lse[ri.out_row] : -INFINITY) * kLog2e;   // in units of ln 2, like the scores
+        // minus the row's lse in units of ln 2; a row that sees nothing has lse = -inf and only masked (-inf) scores,
+        // which a shift of 0 turns into weights 0
+        const float row_lse = ri.valid ? a.lse[ri.out_row] : -INFINITY;
+        const float neg_lse2 = (row_lse == -INFINITY) ? 0.f : -row_lse * kLog2e;
         bf16x8 qop[D / 32];
         load_q_tile<D>(a, ri, g, qop);
         for (int sub0 = 0; sub0 < nt_total; sub0 += sub_len) {
@@ -308,10 +328,10 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
                 if (pending >= 0) fold(pending);                 // written before the barrier that preceded this call
                 float sv[8 * kStepBlocks];
                 const int step0 = sub0 + s * kStepTokens;
-                tile_scores<D, true>(s_k[buf], qop, scale2, min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
+                tile_scores<D, true>(s_k[buf], qop, min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
 #pragma unroll
                 for (int e = 0; e < 8 * kStepBlocks; ++e) {
-                    float x = (lse2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv[e] - lse2);
+                    float x = __builtin_amdgcn_exp2f(fmaf(sv[e], scale2, neg_lse2));
                     // add the rows of the same head: columns n, n + G, n + 2G, ... of the 16-lane row, by rotating
                     // the row (DPP row_ror) by 8, 4, ... G lanes
                     if (G <= 8) x += row_rotate<8>(x);
