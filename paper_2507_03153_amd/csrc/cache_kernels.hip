@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kRowBlock) void evict_rows_kernel(CacheDev c, int32
 
     const int start = min(max(c.ctx_cnt[row], 0), c.k_max);
     float unused = 0.f;
-    const int total = threshold_compact(s_compact, maw, l_ev, beta / (double)l_cur, c.ctx_idx + row * c.k_max, start,
+    const int total = threshold_compact<false>(s_compact, maw, l_ev, beta / (double)l_cur, c.ctx_idx + row * c.k_max, start,
                                         c.k_max, p_old, nullptr, unused);
     if (tid == 0) {
         c.ctx_cnt[row] = min(total, c.k_max);

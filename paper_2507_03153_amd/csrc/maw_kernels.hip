@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kRowBlock) void threshold_select_kernel(ThresholdAr
     float *wn = a.w_norm ? a.w_norm + row * a.k_max : nullptr;
 
     float my_sum = 0.f;
-    const int passing = threshold_compact(s_compact, a.w + row * a.cap, n, thr, idx, 0, a.k_max, 0, wn, my_sum);
+    const int passing = threshold_compact<true>(s_compact, a.w + row * a.cap, n, thr, idx, 0, a.k_max, 0, wn, my_sum);
     const int kept = min(passing, a.k_max);
     for (int j = kept + tid; j < a.k_max; j += kRowBlock) {
         idx[j] = -1;

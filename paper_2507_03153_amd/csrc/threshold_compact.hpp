@@ -29,15 +29,17 @@ struct CompactShared {
 // position order.  Entry j passes iff (double)wr[j] > thr: the comparison is made in fp64 on the exactly
 // widened weight.  The r-th passing entry goes to out[start + r] = j + value_offset (and its weight to
 // wn[start + r] if wn != nullptr) as long as start + r < k_max.  Returns start + the number of passing
-// entries seen (uniform over the workgroup; may exceed k_max: the walk stops once the list is full).
-// my_sum accumulates the weights this thread stored.
+// entries seen (uniform over the workgroup; may exceed k_max).  With STOP_WHEN_FULL the walk ends once the list
+// is full (the return value is then only a lower bound of the count); without it the whole row is examined, so
+// that the caller learns whether anything was left out.  my_sum accumulates the weights this thread stored.
+template <bool STOP_WHEN_FULL>
 __device__ __forceinline__ int threshold_compact(CompactShared &sh, const float *wr, int n, double thr, int32_t *out,
                                                  int start, int k_max, int value_offset, float *wn, float &my_sum)
 {
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
     int base = start;
     int buf = 0;
-    for (int t0 = 0; t0 < n && base < k_max; t0 += kRowStep, buf ^= 1) {
+    for (int t0 = 0; t0 < n && (!STOP_WHEN_FULL || base < k_max); t0 += kRowStep, buf ^= 1) {
         float x[kPerThread];
         bool keep[kPerThread];
         int below[kPerThread];

@@ -210,3 +210,22 @@ def test_graph_replay_of_the_decode_step_equals_eager(gpu):
         for name in ("o", "lse", "a_maw", "ctx_idx", "ctx_cnt", "win_lens", "pool_lens", "first_win_block"):
             assert torch.equal(getattr(E, name), getattr(G, name)), f"step {t}: {name} differs"
     assert int(G.pool_lens.cpu()[0]) == 32 and int(G.status.cpu()[0]) == 0
+
+
+def test_full_list_is_flagged_even_when_it_was_exactly_full_before(gpu):
+    """The salient list fills exactly to k_max without overflow at one eviction; the next eviction finds salient
+    entries it cannot list and must say so."""
+    torch, hgca, runner, cache = gpu
+    say("\n[case] list exactly full, then one more salient entry")
+    C = cache.LayerCache(torch.bfloat16, 1, 2, 1, 128, 16, 1, 4, 16, 0.1)       # window of one block, list of 16
+    tok = torch.ones(1, 1, 128, dtype=torch.bfloat16, device="cuda:0")
+    q = torch.ones(1, 2, 128, dtype=torch.bfloat16, device="cuda:0")
+    for _ in range(16):                                           # first eviction: 16 entries, all salient at beta = 0
+        C.decode_step(q, tok, tok, 0.5, 0.0)
+    torch.cuda.synchronize()
+    assert C.ctx_cnt.cpu().tolist() == [[16, 16]] and int(C.status.cpu()[0]) == 0
+    for _ in range(16):                                           # second eviction: nothing fits any more
+        C.decode_step(q, tok, tok, 0.5, 0.0)
+    torch.cuda.synchronize()
+    assert C.ctx_cnt.cpu().tolist() == [[16, 16]] and int(C.status.cpu()[0]) == hgca.CACHE_LIST_FULL
+    assert int(C.pool_lens.cpu()[0]) == 32
