@@ -35,7 +35,8 @@
  *  - Scores are s_j = sm_scale * <q, k_j>; lse is the natural log of sum e^{s_j}.
  *  - Partial outputs are fp32: O [B, Hq, d], lse [B, Hq].  An empty set gives
  *    O = 0 and lse = -inf.
- *  - q, k, v and O pointers must be 16-byte aligned.  head_dim is 64 or 128.
+ *  - q, k, v and O pointers must be 16-byte aligned.  head_dim is 64 or 128;
+ *    batch and n_q_heads are at most 65 535 each.
  *  - `ws` is scratch the caller provides (split partials, score lists,
  *    histograms); its required size for a call is `hgca_workspace_bytes` with
  *    the maxima of that call.  Its contents are undefined between calls; two

@@ -36,6 +36,8 @@ int check_shape(const hgca_shape *s)
     if (!s) return HGCA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0) return HGCA_ERR_INVALID_ARG;
     if (s->n_q_heads % s->n_kv_heads != 0) return HGCA_ERR_INVALID_ARG;
+    // sequences and heads are grid dimensions y and z of the launches (65 535 at most each)
+    if (s->batch > 65535 || s->n_q_heads > 65535) return HGCA_ERR_UNSUPPORTED;
     if (s->dtype != HGCA_F32 && s->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return HGCA_ERR_UNSUPPORTED;
     const int g = group_of(s);

@@ -17,13 +17,13 @@ __global__ __launch_bounds__(kRowBlock) void window_weights_kernel(float *a, con
                                                                    int32_t n_q_heads, int32_t cap, float *maw,
                                                                    int32_t n_new, float alpha)
 {
-    const int64_t row = blockIdx.y;
+    const int64_t row = blockIdx.x;
     const int n = row_len(seq_lens, (int)(row / n_q_heads), cap);
     const int first_new = n - min(n_new, n);
     const float L = lse[row], keep = 1.f - alpha;
     float *p = a + row * cap;
     float *m = maw ? maw + row * cap : nullptr;
-    const int j0 = blockIdx.x * kRowStep + threadIdx.x;
+    const int j0 = blockIdx.y * kRowStep + threadIdx.x;
 #pragma unroll
     for (int e = 0; e < kPerThread; ++e) {
         const int j = j0 + e * kRowBlock;
@@ -41,13 +41,13 @@ __global__ __launch_bounds__(kRowBlock) void maw_update_kernel(float *maw, const
                                                                int32_t n_q_heads, int32_t cap, int32_t n_new,
                                                                float alpha)
 {
-    const int64_t row = blockIdx.y;
+    const int64_t row = blockIdx.x;
     const int n = row_len(seq_lens, (int)(row / n_q_heads), cap);
     const int first_new = n - min(n_new, n);
     float *m = maw + row * cap;
     const float *a = a_gpu + row * cap;
     const float keep = 1.f - alpha;
-    const int j0 = blockIdx.x * kRowStep + threadIdx.x;
+    const int j0 = blockIdx.y * kRowStep + threadIdx.x;
 #pragma unroll
     for (int e = 0; e < kPerThread; ++e) {
         const int j = j0 + e * kRowBlock;
@@ -100,7 +100,7 @@ hipError_t launch_window_weights(float *a, const float *lse, const int32_t *seq_
                                  int32_t cap, float *maw, int32_t n_new, float alpha, hipStream_t s)
 {
     if (n_rows == 0 || cap == 0) return hipSuccess;
-    dim3 grid((cap + kRowStep - 1) / kRowStep, (unsigned)n_rows);
+    dim3 grid((unsigned)n_rows, (cap + kRowStep - 1) / kRowStep);   // rows in x: no 65 535 limit on them
     hipLaunchKernelGGL(window_weights_kernel, grid, dim3(kRowBlock), 0, s, a, lse, seq_lens, n_q_heads, cap, maw, n_new,
                        alpha);
     return hipGetLastError();
@@ -110,7 +110,7 @@ hipError_t launch_maw_update(float *maw, const float *a_gpu, const int32_t *seq_
                              int32_t cap, int32_t n_new, float alpha, hipStream_t s)
 {
     if (n_rows == 0 || cap == 0) return hipSuccess;
-    dim3 grid((cap + kRowStep - 1) / kRowStep, (unsigned)n_rows);
+    dim3 grid((unsigned)n_rows, (cap + kRowStep - 1) / kRowStep);   // rows in x: no 65 535 limit on them
     hipLaunchKernelGGL(maw_update_kernel, grid, dim3(kRowBlock), 0, s, maw, a_gpu, seq_lens, n_q_heads, cap, n_new,
                        alpha);
     return hipGetLastError();

@@ -28,6 +28,13 @@ def test_every_declared_symbol_is_exported(hg):
         assert getattr(L, name) is not None
 
 
+def test_batch_and_head_count_limits(hg):
+    assert hg.workspace_bytes(hg.Shape(hg.BF16, 65535, 8, 2, 128, 1.0), 16, 16, 4) > 0
+    assert hg.workspace_bytes(hg.Shape(hg.BF16, 65536, 8, 2, 128, 1.0), 16, 16, 4) == 0
+    sh = hg.Shape(hg.BF16, 65536, 8, 2, 128, 1.0)
+    assert hg.lib().hgca_maw_update(ctypes.byref(sh), FAKE, FAKE, None, 64, 1, 0.5, None) == hg.ERR_UNSUPPORTED
+
+
 def test_status_strings(hg):
     texts = {hg.status_string(s) for s in (0, -1, -2, -3, -4)}
     assert len(texts) == 5 and hg.status_string(-99) == "unknown status"
