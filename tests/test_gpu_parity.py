@@ -403,3 +403,36 @@ def test_seeded_sweep_of_small_shapes(gpu, oracle, name, dtype, kw):
 def test_pool_lengths_around_the_lds_cache_limit(gpu, oracle, P):
     """33 792 scores are the longest row the selection keeps in LDS: the row before, at and after the switch."""
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], B=1, Hq=2, Hkv=1, W=32, P=P, k=700), check_end_to_end=False)
+
+
+def test_graph_replay_of_the_whole_step_equals_eager(gpu, oracle):
+    """The library records kernels only (no memset, no allocation), so a step can be captured once and replayed:
+    every replay is compared with the eager result, with eager work and synchronisation in between."""
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=700, P=3001, k=300)
+    say("\n[case] HIP graph replay of the full step")
+    layers = [runner.DeviceLayer.upload(wl.make_layer(cfg, i)) for i in range(3)]
+    eager = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, layers[0].k_max, fused_tail=True)
+    graphed = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, layers[0].k_max, fused_tail=True)
+    L = layers[0]
+    q_static = L.q.clone()                                       # the graph reads its query from here
+    G = runner.DeviceLayer(q_static, L.window, L.pool, L.k, L.k_max, L.shape)
+    side = torch.cuda.Stream(device="cuda:0")
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            graphed.run(G, select=True, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for i in range(4):
+        q_static.copy_(layers[i % 3].q)                          # a different query each time, same KV
+        graph.replay()
+        cur = runner.DeviceLayer(layers[i % 3].q, L.window, L.pool, L.k, L.k_max, L.shape)
+        eager.run(cur, select=True)
+        torch.cuda.synchronize()
+        assert torch.equal(eager.o, graphed.o) and torch.equal(eager.lse, graphed.lse), f"replay {i} differs"
+        assert torch.equal(eager.idx, graphed.idx) and torch.equal(eager.cnt, graphed.cnt)
+    o_ref, l_ref, _, _ = oracle.hybrid_step(wl.make_layer(cfg, 0).q, otier(oracle, wl.make_layer(cfg, 0).window),
+                                            otier(oracle, wl.make_layer(cfg, 0).pool), L.k, L.k_max, cfg.scale)
+    assert_partial("graph replay vs oracle (query of layer 0)", graphed.o, graphed.lse, o_ref, l_ref, TOL["bf16"])
