@@ -133,6 +133,12 @@ def main() -> int:
     ms_per_step, full_ms, wall_ms = timed(head, True)
     steady_ms, _, _ = timed(head, False)                        # selection reused
     other_ms, _, _ = timed(not head, True)
+    one_call_ms = None
+    if pass_scores and args.streams == 1:                       # the same step through hgca_hybrid_decode_step
+        steps_by_tail["one"] = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, k_max, dev, fused_tail=True,
+                                                 one_call=True)
+        prepared_by_tail["one"] = [steps_by_tail["one"].prepare(L) for L in layers]
+        one_call_ms, _, one_call_wall = timed("one", True)
     other_steady_ms, _, _ = timed(not head, False)
 
     # ---- per-call device time: HIP events on the stream the kernels are launched on ---------------------
@@ -231,6 +237,7 @@ def main() -> int:
             "hbm_frac": rate(nbytes["full"], other_ms) / HBM_PEAK_GBPS,
             "steady_ms_per_step": other_steady_ms,
             "steady_hbm_frac": rate(nbytes["steady"], other_steady_ms) / HBM_PEAK_GBPS},
+        "one_call": None if one_call_ms is None else {"ms_per_step": one_call_ms, "wall_ms_per_step": one_call_wall},
         "per_call_ms": call_ms, "per_call_gbps": call_gbps,
         "device_ms_per_step": full_ms, "wall_ms_per_step": wall_ms,
         "roofline": roof,

@@ -181,6 +181,27 @@ int hgca_lse_merge_splits(const hgca_shape *shape,
                           void *o_out, int32_t o_dtype, float *lse_out,
                           void *hip_stream);
 
+/* The whole decode branch of Alg. 2 in one call: dense window part, per-head
+ * top-k selection over the pool with the current query (as
+ * hgca_select_salient), sparse part over the selected entries, merge_state.
+ * Same results as hgca_dense_window_attn + hgca_select_salient +
+ * hgca_sparse_attn (with the selection's scores) + hgca_lse_merge_splits, bit
+ * for bit, for one crossing of the boundary: the kept entries' scores stay in
+ * the workspace and one fold produces O.  idx_out / cnt_out receive
+ * the selection (reusable by later steps through hgca_sparse_attn); o_out is
+ * [B,Hq,d] in o_dtype, lse_out [B,Hq] optional.  ws_dense needs
+ * hgca_workspace_bytes(shape, window->cap, 0, 0), ws_sparse
+ * hgca_workspace_bytes(shape, 0, pool->cap, k_max); they must be different
+ * buffers. */
+int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q,
+                            const hgca_kv_view *window, const hgca_kv_view *pool,
+                            const int32_t *k_per_seq, int32_t k_uniform, int32_t k_max,
+                            int32_t *idx_out, int32_t *cnt_out,
+                            void *o_out, int32_t o_dtype, float *lse_out,
+                            void *ws_dense, size_t ws_dense_bytes,
+                            void *ws_sparse, size_t ws_sparse_bytes,
+                            void *hip_stream);
+
 /* merge_state (Sec. 3.3 "Merging states"): combines two partial results over
  * disjoint key sets into the result of one softmax over their union.  Evaluated
  * with both exponents shifted by max(lse_a, lse_b).  o_out is [B,Hq,d] in

@@ -103,9 +103,9 @@ int pick_chunk(int64_t n, int64_t units, int target, int max_chunk = kMaxChunk)
 
 int n_splits_for(int64_t n, int chunk) { return (int)((n + chunk - 1) / chunk); }
 
-// Workspace layout: [partials o | partials m | partials l | scores].
+// Workspace layout: [partials o | partials m | partials l | scores | scores of the kept entries].
 struct WsLayout {
-    size_t part_o, part_m, part_l, scores, total;
+    size_t part_o, part_m, part_l, scores, sel, total;
 };
 
 WsLayout layout(const hgca_shape *s, int64_t max_attn_tokens, int64_t max_pool)
@@ -118,6 +118,7 @@ WsLayout layout(const hgca_shape *s, int64_t max_attn_tokens, int64_t max_pool)
     w.part_m = at; at += align_up(rows * max_splits * sizeof(float));
     w.part_l = at; at += align_up(rows * max_splits * sizeof(float));
     w.scores = at; at += align_up(rows * (size_t)std::max<int64_t>(max_pool, 0) * sizeof(float));
+    w.sel = at; at += max_pool > 0 ? align_up(rows * (size_t)std::max<int64_t>(max_attn_tokens, 0) * sizeof(float)) : 0;
     w.total = std::max<size_t>(at, kAlign);
     return w;
 }
@@ -471,6 +472,77 @@ int hgca_lse_merge_splits(const hgca_shape *shape, int32_t window_cap, const voi
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     return from_hip(launch_combine2(shape->head_dim, rows, pd, ps, o_out, o_dtype, lse_out,
                                     static_cast<hipStream_t>(hip_stream)));
+}
+
+int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q, const hgca_kv_view *window,
+                            const hgca_kv_view *pool, const int32_t *k_per_seq, int32_t k_uniform, int32_t k_max,
+                            int32_t *idx_out, int32_t *cnt_out, void *o_out, int32_t o_dtype, float *lse_out,
+                            void *ws_dense, size_t ws_dense_bytes, void *ws_sparse, size_t ws_sparse_bytes,
+                            void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (o_dtype != HGCA_F32 && o_dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(shape, window, true)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, pool, true)) != HGCA_OK) return rc;
+    if (!q || !aligned16(q) || !o_out || !aligned16(o_out) || !cnt_out || k_max < 0 || (k_max > 0 && !idx_out))
+        return HGCA_ERR_INVALID_ARG;
+    if (!k_per_seq && (k_uniform < 0 || std::min(k_uniform, pool->cap) > k_max)) return HGCA_ERR_INVALID_ARG;
+    const WsLayout wd = layout(shape, window->cap, 0);
+    const WsLayout wsp = layout(shape, k_max, pool->cap);
+    if (!ws_dense || ws_dense_bytes < wd.total || !aligned16(ws_dense)) return HGCA_ERR_WORKSPACE;
+    if (!ws_sparse || ws_sparse_bytes < wsp.total || !aligned16(ws_sparse)) return HGCA_ERR_WORKSPACE;
+    if (ws_dense == ws_sparse) return HGCA_ERR_WORKSPACE;       // the two parts are live at the same time
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    ScoreArgs sa{};
+    sa.sh = to_dev(shape);
+    sa.q = q;
+    sa.kv = to_dev(pool);
+    sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws_sparse) + wsp.scores);
+    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
+                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+    sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
+
+    AttnArgs da{};
+    da.sh = sa.sh;
+    da.q = q;
+    da.kv = to_dev(window);
+    da.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
+    da.part = partials_at(ws_dense, wd, n_splits_for(window->cap, da.chunk));
+
+    // 1. split kernels of the window part, score pass over the pool (independent of each other)
+    if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
+    if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
+    // 2. per-head top-k; the kept entries' scores stay in the workspace for the sparse part
+    float *sel = k_max > 0 && pool->cap > 0 ? reinterpret_cast<float *>(static_cast<char *>(ws_sparse) + wsp.sel) : nullptr;
+    SelectArgs se{};
+    se.sh = sa.sh;
+    se.kv = sa.kv;
+    se.scores = sa.scores;
+    se.k_per_seq = k_per_seq;
+    se.k_uniform = k_uniform;
+    se.k_max = k_max;
+    se.idx = idx_out;
+    se.cnt = cnt_out;
+    se.sel_scores = sel;
+    if ((rc = from_hip(launch_select(se, s))) != HGCA_OK) return rc;
+    // 3. sparse part on the given scores (V rows only)
+    AttnArgs ga{};
+    ga.sh = sa.sh;
+    ga.q = q;
+    ga.kv = sa.kv;
+    ga.idx = idx_out;
+    ga.cnt = cnt_out;
+    ga.sel_scores = sel;
+    ga.k_max = k_max;
+    ga.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
+    ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(k_max, ga.chunk)));
+    if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
+    // 4. one fold of all split partials = merge_state over all of them
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    return from_hip(launch_combine2(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, s));
 }
 
 int hgca_lse_merge(const hgca_shape *shape, const float *o_a, const float *lse_a, const float *o_b,

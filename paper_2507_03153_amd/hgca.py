@@ -25,7 +25,7 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
-           "hgca_sparse_attn_grouped")
+           "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step")
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -102,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_union_lists.argtypes = [ps, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.hgca_sparse_attn_grouped.restype = ctypes.c_int
         L.hgca_sparse_attn_grouped.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.hgca_hybrid_decode_step.restype = ctypes.c_int
+        L.hgca_hybrid_decode_step.argtypes = [ps, vp, pk, pk, vp, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp]
         L.hgca_dense_window_attn_maw.restype = ctypes.c_int
         L.hgca_dense_window_attn_maw.argtypes = [ps, vp, pk, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         L.hgca_maw_update.restype = ctypes.c_int
@@ -379,3 +381,20 @@ def sparse_attn_grouped(shape: Shape, q, pool: Tier, idx, cnt, k_max: int, o_out
     _check(lib().hgca_sparse_attn_grouped(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
                                           _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
            "hgca_sparse_attn_grouped")
+
+
+def hybrid_decode_step(shape: Shape, q, window: Tier, pool: Tier, k, k_max: int, idx_out, cnt_out, o_out, lse_out,
+                       ws_dense, ws_sparse, stream=None) -> None:
+    """The whole decode step (dense, select, sparse, merge) in one library call."""
+    for t in (q, idx_out, cnt_out, o_out, ws_dense, ws_sparse) + (() if lse_out is None else (lse_out,)):
+        _require_gpu(t)
+    kw, kp = window.view(), pool.view()
+    if isinstance(k, torch.Tensor):
+        _require_gpu(k)
+        k_ptr, k_uni = _ptr(k), 0
+    else:
+        k_ptr, k_uni = None, int(k)
+    _check(lib().hgca_hybrid_decode_step(ctypes.byref(shape), _ptr(q), ctypes.byref(kw), ctypes.byref(kp), k_ptr, k_uni,
+                                         int(k_max), _ptr(idx_out), _ptr(cnt_out), _ptr(o_out), _dtype_code(o_out),
+                                         _ptr(lse_out), _ptr(ws_dense), ws_dense.numel(), _ptr(ws_sparse),
+                                         ws_sparse.numel(), _stream(stream)), "hgca_hybrid_decode_step")

@@ -59,12 +59,15 @@ class HybridStep:
 
     def __init__(self, shape: hgca.Shape, max_window: int, max_pool: int, k_max: int, device="cuda:0",
                  out_dtype=torch.float32, two_streams: bool = False, pass_scores: bool = True,
-                 fused_tail: bool = False):
+                 fused_tail: bool = False, one_call: bool = False):
         B, Hq, d = shape.batch, shape.n_q_heads, shape.head_dim
         f32 = dict(dtype=torch.float32, device=device)
         self.shape, self.k_max, self.device = shape, k_max, device
         self.pass_scores = pass_scores                              # select hands its scores to the sparse part
         self.fused_tail = fused_tail                                # one fold of all splits instead of three kernels
+        self.one_call = one_call                                    # a step with a fresh selection = hgca_hybrid_decode_step
+        if one_call and (two_streams or not fused_tail or not pass_scores):
+            raise ValueError("one_call implies fused_tail and pass_scores on one stream")
         self.o_w, self.lse_w = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
         self.o_s, self.lse_s = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
         self.o = torch.empty(B, Hq, d, dtype=out_dtype, device=device)
@@ -103,9 +106,15 @@ class HybridStep:
         a_splits = (ref(sh), int(L.window.cap), ptr(self.ws_dense), self.ws_dense.numel(), self.k_max,
                     ptr(self.ws_sparse), self.ws_sparse.numel(), ptr(self.o), hgca._dtype_code(self.o),
                     ptr(self.lse), s_main)
+        a_step = (ref(sh), ptr(L.q), ref(win), ref(pool), k_ptr, k_uni, self.k_max, ptr(self.idx), ptr(self.cnt),
+                  ptr(self.o), hgca._dtype_code(self.o), ptr(self.lse), ptr(self.ws_dense), self.ws_dense.numel(),
+                  ptr(self.ws_sparse), self.ws_sparse.numel(), s_main)
         keep = (sh, win, pool, L)                               # the structs must outlive the closure
 
         def run(select: bool = True) -> None:
+            if select and self.one_call:
+                hgca._check(lib.hgca_hybrid_decode_step(*a_step), "hgca_hybrid_decode_step")
+                return
             if self.side is not None:
                 self._fork.record(main)
                 side.wait_event(self._fork)
@@ -126,6 +135,10 @@ class HybridStep:
 
     def run(self, L: DeviceLayer, select: bool = True, stream=None) -> None:
         main = torch.cuda.current_stream() if stream is None else stream
+        if select and self.one_call:
+            hgca.hybrid_decode_step(self.shape, L.q, L.window, L.pool, L.k, self.k_max, self.idx, self.cnt, self.o,
+                                    self.lse, self.ws_dense, self.ws_sparse, main)
+            return
         side = main
         if self.side is not None:
             side = self.side

@@ -110,7 +110,7 @@ def test_select_and_sparse_reject_bad_arguments(hg):
     assert select(q=None) == hg.ERR_INVALID_ARG
     assert select(ws_bytes=1024) == hg.ERR_WORKSPACE
     assert select(view=_view(hg, cap=256, k=None, v=None)) == hg.ERR_INVALID_ARG
-    need = hg.workspace_bytes(sh, 0, 256, 8)
+    need = hg.workspace_bytes(sh, 0, 256, 0)                  # the selection alone keeps no kept-entry scores
     assert select(ws_bytes=need - 1) == hg.ERR_WORKSPACE
 
     def sparse(idx=FAKE, cnt=FAKE, k_max=8, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40, view=v):
@@ -290,3 +290,31 @@ def test_grouped_entry_points_reject_bad_arguments(hg):
     assert att(cnt=None) == hg.ERR_INVALID_ARG
     assert att(o=None) == hg.ERR_INVALID_ARG                   # one output without the other
     assert att(ws=None) == hg.ERR_WORKSPACE
+
+
+def test_hybrid_decode_step_rejects_bad_arguments(hg):
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    win, pool = _view(hg, cap=64), _view(hg, cap=256)
+    WS2 = ctypes.c_void_p(0x40000)
+
+    def step(shape=sh, q=FAKE, w=win, p=pool, k_uni=8, k_max=8, idx=FAKE, cnt=FAKE, o=FAKE, o_dtype=0, wd=FAKE,
+             wd_bytes=1 << 40, wsp=WS2, wsp_bytes=1 << 40):
+        return hg.lib().hgca_hybrid_decode_step(ctypes.byref(shape), q, ctypes.byref(w), ctypes.byref(p), None, k_uni,
+                                                k_max, idx, cnt, o, o_dtype, None, wd, wd_bytes, wsp, wsp_bytes, None)
+
+    assert step(shape=hg.Shape(hg.BF16, 2, 8, 3, 128, 0.088)) == hg.ERR_INVALID_ARG
+    assert step(q=None) == hg.ERR_INVALID_ARG
+    assert step(o=None) == hg.ERR_INVALID_ARG
+    assert step(o_dtype=5) == hg.ERR_UNSUPPORTED
+    assert step(idx=None) == hg.ERR_INVALID_ARG
+    assert step(cnt=None) == hg.ERR_INVALID_ARG
+    assert step(k_uni=9) == hg.ERR_INVALID_ARG                 # k > k_max
+    assert step(k_max=-1) == hg.ERR_INVALID_ARG
+    assert step(w=_view(hg, cap=64, k=None)) == hg.ERR_INVALID_ARG
+    assert step(p=_view(hg, cap=256, v=None)) == hg.ERR_INVALID_ARG
+    assert step(wd=None) == hg.ERR_WORKSPACE
+    assert step(wsp=None) == hg.ERR_WORKSPACE
+    assert step(wsp=FAKE) == hg.ERR_WORKSPACE                  # one buffer for both parts
+    assert step(wd_bytes=hg.workspace_bytes(sh, 64, 0, 0) - 1) == hg.ERR_WORKSPACE
+    assert step(wsp_bytes=hg.workspace_bytes(sh, 0, 256, 8) - 1) == hg.ERR_WORKSPACE
+    assert step(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), q=None, o=None) == hg.OK   # empty batch: nothing to do

@@ -162,6 +162,18 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
             finite = torch.isfinite(step.lse)
             assert float((fused.o - step.o).abs().max()) <= 2e-6
             assert float((fused.lse[finite] - step.lse[finite]).abs().max()) <= 4e-6 if finite.any() else True
+        say("  whole step as one library call")
+        one = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max, fused_tail=True, one_call=True)
+        one.o.fill_(float("nan"))
+        one.lse.fill_(float("nan"))
+        one.idx.fill_(-7)
+        one.cnt.fill_(-7)
+        one.run(D, select=True)
+        torch.cuda.synchronize()
+        assert_partial("hybrid, one call", one.o, one.lse, o_h, l_h, tol if n_band else min(tol, tight))
+        # same kernels on the same data as the separate calls: identical bits
+        assert torch.equal(one.idx[..., :L.k_max], fused.idx[..., :L.k_max]) and torch.equal(one.cnt, fused.cnt)
+        assert torch.equal(one.o, fused.o) and torch.equal(one.lse, fused.lse)
         fused.run(D, select=False)                             # reused selection: K and V gathered
         torch.cuda.synchronize()
         assert_partial("steady, fused tail", fused.o, fused.lse, o_h, l_h, tol if n_band else min(tol, tight))
