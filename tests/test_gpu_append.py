@@ -159,6 +159,64 @@ def test_append_long_pool_many_splits_and_row_table_refills(gpu):
     run_case(gpu, 35, B=1, N=32, Hq=8, Hkv=2, d=128, W=256, P=9000)
 
 
+@pytest.mark.timeout(600)
+def test_append_full_size_c2_sampled(gpu):
+    """The shape and launch configuration bench.py times for the append stage (B=8, N=32, 32 query heads on 8 KV
+    heads, window 4096, pool 28672); the oracle computes sampled (sequence, head) pairs: all N queries of the pair
+    and its two query-averaged weight rows."""
+    torch, hgca, runner = gpu
+    dev = "cuda:0"
+    c2 = wl.CONFIGS["C2"]
+    B, N, Hq, Hkv, d, W, P = c2.B, 32, c2.Hq, c2.Hkv, c2.d, c2.W, c2.P
+    G = Hq // Hkv
+    say(f"\n[case] append full size N={N} B={B} Hq={Hq} Hkv={Hkv} d={d} W={W} P={P}")
+    q, Kw, Vw, wl_, Kp, Vp, pl_ = make_inputs(41, B, N, Hq, Hkv, d, W, P, None, None)
+    wl_[1], pl_[1] = W - 1000, P - 5001                         # one sequence with ragged tails in both tiers
+    scale = 1.0 / np.sqrt(d)
+    g = lambda a: runner._to_gpu(a, dev)
+    qd = g(q)
+    win, pool = hgca.Tier(g(Kw), g(Vw), W, g(wl_)), hgca.Tier(g(Kp), g(Vp), P, g(pl_))
+    shape = hgca.Shape(hgca.BF16, B, Hq, Hkv, d, scale)
+    f32 = dict(dtype=torch.float32, device=dev)
+    ws = hgca.append_workspace(shape, N, max(W, P), dev)
+    ow, lw = torch.full((B, N, Hq, d), float("nan"), **f32), torch.full((B, N, Hq), float("nan"), **f32)
+    op, lp = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
+    hgca.append_attn(shape, qd, win, True, ow, lw, ws)
+    hgca.append_attn(shape, qd, pool, False, op, lp, ws)
+    o, lse = torch.empty_like(ow), torch.empty_like(lw)
+    hgca.lse_merge(hgca.Shape(hgca.BF16, B * N, Hq, Hkv, d, scale), op, lp, ow, lw, o, lse)
+    a_gpu, a_cpu = torch.full((B, Hq, W), float("nan"), **f32), torch.full((B, Hq, P), float("nan"), **f32)
+    hgca.append_weights(shape, qd, win, True, lw, a_gpu)
+    hgca.append_weights(shape, qd, pool, False, lp, a_cpu)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
+    assert bool(torch.isfinite(a_gpu).all()) and bool(torch.isfinite(a_cpu).all())
+    # every averaged weight row sums to 1 over what is visible (holds at any size)
+    assert float((a_gpu.sum(-1) - 1).abs().max()) <= 1e-4 and float((a_cpu.sum(-1) - 1).abs().max()) <= 1e-4
+
+    f = lambda x: wl.bf16_bits_to_f32(x).astype(np.float64)
+    rng = np.random.default_rng(42)
+    pairs = [(1, 5), (0, 0), (B - 1, Hq - 1)] + [(int(rng.integers(B)), int(rng.integers(Hq))) for _ in range(5)]
+    for b, h in pairs:
+        kvh = h // G
+        qs = f(q[b:b + 1, :, h:h + 1])
+        part = lambda K, V, lens, causal: ap.part_attention(qs, f(K[b:b + 1, kvh:kvh + 1]), f(V[b:b + 1, kvh:kvh + 1]),
+                                                            lens[b:b + 1], scale, causal)
+        o_g, l_g, A_g = part(Kw, Vw, wl_, True)
+        o_c, l_c, A_c = part(Kp, Vp, pl_, False)
+        o_r, l_r = ap.merge_state(o_c, l_c, o_g, l_g)
+        errs = {}
+        for name, got, want in (("O_gpu", ow[b, :, h], o_g[0, :, 0]), ("lse_g", lw[b, :, h], l_g[0, :, 0]),
+                                ("O_cpu", op[b, :, h], o_c[0, :, 0]), ("lse_c", lp[b, :, h], l_c[0, :, 0]),
+                                ("O", o[b, :, h], o_r[0, :, 0]), ("lse", lse[b, :, h], l_r[0, :, 0]),
+                                ("A_gpu", a_gpu[b, h], A_g[0, 0].mean(axis=0)), ("A_cpu", a_cpu[b, h], A_c[0, 0].mean(axis=0))):
+            errs[name] = float(np.max(np.abs(got.double().cpu().numpy() - want)))
+        say(f"    (b={b}, h={h}): " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+        assert max(errs["O_gpu"], errs["O_cpu"], errs["O"]) <= 2e-4
+        assert max(errs["lse_g"], errs["lse_c"], errs["lse"], errs["A_gpu"], errs["A_cpu"]) <= 2e-5
+        assert np.all(a_gpu[b, h, wl_[b]:].cpu().numpy() == 0) and np.all(a_cpu[b, h, pl_[b]:].cpu().numpy() == 0)
+
+
 def test_reevaluation_threshold_on_a_cpu(gpu, oracle):
     """Alg. 1, append: ids = A_cpu > beta / A_cpu.size; both sides threshold their own A_cpu, entries within
     rounding of the threshold may differ."""

@@ -104,6 +104,12 @@ def test_grouped_bf16(gpu, oracle, kw):
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], **kw))
 
 
+@pytest.mark.timeout(600)
+def test_grouped_full_size_c2(gpu, oracle):
+    """The shape bench.py times the grouped calls on."""
+    run_case(gpu, oracle, wl.CONFIGS["C2"])
+
+
 def test_grouped_fp32(gpu, oracle):
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C1"], B=2, Hq=8, Hkv=2, d=128, W=100, P=1200, k=77))
 

@@ -146,6 +146,17 @@ def test_decode_loop_mha_head_dim_64_blocks_of_32(gpu):
     assert status == 0
 
 
+@pytest.mark.timeout(600)
+def test_decode_loop_at_the_benchmark_window_size(gpu):
+    """B=8, 32 query heads on 8 KV heads, l_max = 4096 in 16-token blocks (the window of the benchmark shape), so
+    that every kernel of the managed step runs in the launch configuration bench.py times; two evictions."""
+    C, _, status = run_loop(gpu, B=8, Hq=32, Hkv=8, d=128, block_size=16, win_blocks=256, max_blocks=264, k_max=64,
+                            prefill=(4090, 4090, 4000, 4095, 4090, 3, 4090, 4089), steps=24, alpha=0.3, beta=1.0,
+                            seed=14)
+    assert status == 0
+    assert int(C.pool_lens.max()) == 32
+
+
 def test_beta_zero_keeps_everything_and_matches_full_attention(gpu):
     """With beta = 0 every evicted entry stays salient, so each step is full attention over the history
     (the oracle is pinned to exactly that with library softmax)."""
