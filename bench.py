@@ -163,6 +163,14 @@ def main() -> int:
     thr_cnt = torch.empty(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
     g_idx = torch.full((cfg.B, cfg.Hkv, max(k_max, 1)), -1, dtype=torch.int32, device=dev)
     g_cnt = torch.zeros(cfg.B, cfg.Hkv, dtype=torch.int32, device=dev)
+    # KV_ctx of Alg. 1: the kept entries copied to per-head contiguous storage, then read as a stream
+    kc = max(k_max, 1)
+    k_ctx = torch.zeros(cfg.B, cfg.Hq, kc, cfg.d, dtype=layers[0].q.dtype, device=dev)
+    v_ctx = torch.zeros_like(k_ctx)
+    ctx_cnt = torch.zeros(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
+    per_head = hgca.Shape(sh.dtype, cfg.B * cfg.Hq, 1, 1, cfg.d, sh.sm_scale)
+    ctx_tier = hgca.Tier(k_ctx.view(-1, 1, kc, cfg.d), v_ctx.view(-1, 1, kc, cfg.d), k_max, ctx_cnt.view(-1))
+    ws_ctx = hgca.alloc_workspace(per_head, k_max, 0, 0, dev)
     calls = {
         "dense_window_attn": lambda L: hgca.dense_window_attn(sh, L.q, L.window, step.o_w, step.lse_w, step.ws_dense),
         "pool_scores": lambda L: hgca.pool_scores(sh, L.q, L.pool, scores_buf),
@@ -185,6 +193,11 @@ def main() -> int:
                                                                         step.ws_sparse),
         "sparse_attn_grouped": lambda L: hgca.sparse_attn_grouped(sh, L.q, L.pool, g_idx, g_cnt, k_max, step.o_s,
                                                                   step.lse_s, step.ws_sparse),
+        "ctx_compact": lambda L: hgca.ctx_compact(sh, L.pool, step.idx, step.cnt, k_max, k_ctx, v_ctx, k_max,
+                                                  cnt_out=ctx_cnt),
+        "attn_over_kv_ctx": lambda L: hgca.dense_window_attn(per_head, L.q.view(-1, 1, cfg.d), ctx_tier,
+                                                             step.o_s.view(-1, 1, cfg.d), step.lse_s.view(-1, 1),
+                                                             ws_ctx),
     }
     call_ms = {name: time_call(fn) for name, fn in calls.items()}
     call_bytes = {"dense_window_attn": nbytes["dense"], "pool_scores": int(p_lens.sum()) * cfg.Hkv * cfg.d * cfg.elem_bytes,
@@ -197,7 +210,9 @@ def main() -> int:
                   # K of the pool once per KV head + one fp32 score per (KV head, token) written and read
                   "select_salient_grouped": int(p_lens.sum()) * cfg.Hkv * (cfg.d * cfg.elem_bytes + 8),
                   # K and V rows of the kept entries once per KV head
-                  "sparse_attn_grouped": 2 * cfg.Hkv * k_sum * cfg.d * cfg.elem_bytes}
+                  "sparse_attn_grouped": 2 * cfg.Hkv * k_sum * cfg.d * cfg.elem_bytes,
+                  # kept rows read and written once; then streamed once
+                  "ctx_compact": 2 * k_gather, "attn_over_kv_ctx": k_gather}
     call_gbps = {n: call_bytes[n] / (call_ms[n] * 1e-3) / 1e9 for n in call_bytes}
     log("[bench] per call (ms, moved GB/s): " + ", ".join(
         f"{n}={call_ms[n]:.4f}" + (f"/{call_gbps[n]:.0f}" if n in call_gbps else "") for n in call_ms))

@@ -374,6 +374,25 @@ int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache,
 int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
                   double beta, void *hip_stream);
 
+/* KV_ctx of Alg. 1 (KV_ctx.add(KV_evict[ids]); Sec. 3.2.2): per head, the
+ * salient entries held in contiguous storage, so that the sparse part reads a
+ * stream instead of following an index list.  For every (b, h) the K and V
+ * rows of pool positions idx[b,h,0..cnt[b,h]) (valid positions, as for
+ * hgca_sparse_attn) are copied, bit for bit and in list order, to rows
+ * first_row[b,h] + j of k_ctx / v_ctx [B, Hq, ctx_cap, d] (shape.dtype,
+ * 16-byte aligned, two different buffers).  first_row (device [B,Hq]) may be
+ * NULL = 0; rows that would land at ctx_cap or beyond are left out.  cnt_out
+ * (device [B,Hq], optional, not the same array as first_row or cnt) receives
+ * min(first_row + cnt, ctx_cap): pass it as first_row of the next call to add
+ * the entries of a later eviction behind the earlier ones.
+ * Attention over KV_ctx is hgca_dense_window_attn on the shape {batch = B*Hq,
+ * n_q_heads = 1, n_kv_heads = 1} with the view {k_ctx, v_ctx, seq_lens =
+ * cnt_out, cap = ctx_cap}: every head is a sequence of its own. */
+int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool,
+                     const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                     const int32_t *first_row, void *k_ctx, void *v_ctx,
+                     int32_t ctx_cap, int32_t *cnt_out, void *hip_stream);
+
 /* ---- Append stage (Sec. 2.1: N incoming tokens, Q in R^{h x N x d}; Alg. 2,
  * append branch).  bf16 only (both contractions run on the matrix cores). ----
  *

@@ -6,6 +6,7 @@
 // per window position: the evicted entries' averages are thresholded (Sec. 3.2.2) into the per-head
 // lists of salient pool positions and the rest of the row shifts down.
 #include "hgca_launch.hpp"
+#include "row_map.hpp"
 #include "threshold_compact.hpp"
 
 namespace hgca {
@@ -107,7 +108,59 @@ __global__ __launch_bounds__(kRowBlock) void evict_rows_kernel(CacheDev c, int32
     }
 }
 
+// KV_ctx of Alg. 1 (per head, the salient entries in contiguous storage): the K and V rows of the listed pool
+// positions are copied, in list order, behind the rows a head already holds.  One workgroup copies kCtxRows
+// listed entries of one (sequence, head): 16 bytes per lane, consecutive lanes on consecutive pieces of a row,
+// four loads in flight.  Rows that would land beyond ctx_cap are left out.
+constexpr int kCtxRows = 64;
+
+__global__ __launch_bounds__(kRowBlock) void ctx_compact_kernel(CtxCompactArgs a)
+{
+    __shared__ uint32_t s_row[kCtxRows];
+
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int64_t bh = (int64_t)b * a.sh.n_q_heads + h;
+    const int n = min(max(a.cnt[bh], 0), a.k_max);
+    const int first = a.first_row ? min(max(a.first_row[bh], 0), a.ctx_cap) : 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.cnt_out) a.cnt_out[bh] = (int32_t)min((int64_t)first + n, (int64_t)a.ctx_cap);
+    const int t0 = blockIdx.x * kCtxRows;
+    if (t0 >= n) return;                         // uniform over the workgroup
+    const int nt = min(min(kCtxRows, n - t0), max(a.ctx_cap - first - t0, 0));
+    if (nt <= 0) return;
+    const RowMap rows = make_row_map<true, kRowBlock>(s_row, a.kv, a.sh.n_kv_heads, b, h / a.sh.group, t0, nt,
+                                                      a.idx + bh * a.k_max + t0);
+    const int pieces = a.row_bytes / 16, total = nt * pieces;
+    const int64_t dst0 = (bh * a.ctx_cap + first + t0) * (int64_t)a.row_bytes;
+    constexpr int U = 4;
+    for (int base = threadIdx.x; base < total; base += kRowBlock * U) {
+        uint4 kr[U], vr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = min(base + u * kRowBlock, total - 1);
+            const int64_t src = (int64_t)rows(i / pieces) * a.row_bytes + 16 * (i % pieces);
+            kr[u] = load16_stream(a.kv.k + src);
+            vr[u] = load16_stream(a.kv.v + src);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + u * kRowBlock;
+            if (i < total) {
+                *reinterpret_cast<uint4 *>(a.k_ctx + dst0 + 16 * (int64_t)i) = kr[u];
+                *reinterpret_cast<uint4 *>(a.v_ctx + dst0 + 16 * (int64_t)i) = vr[u];
+            }
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_ctx_compact(const CtxCompactArgs &a, hipStream_t s)
+{
+    if (a.sh.batch == 0 || a.k_max == 0) return hipSuccess;
+    const dim3 grid((a.k_max + kCtxRows - 1) / kCtxRows, a.sh.n_q_heads, a.sh.batch);
+    hipLaunchKernelGGL(ctx_compact_kernel, grid, dim3(kRowBlock), 0, s, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
                             int32_t n_kv_heads, int32_t row_bytes, hipStream_t s)

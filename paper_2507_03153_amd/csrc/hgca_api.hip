@@ -621,6 +621,34 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache, double
     return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, static_cast<hipStream_t>(hip_stream)));
 }
 
+int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool, const int32_t *idx, const int32_t *cnt,
+                     int32_t k_max, const int32_t *first_row, void *k_ctx, void *v_ctx, int32_t ctx_cap,
+                     int32_t *cnt_out, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (k_max < 0 || ctx_cap < 0) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(shape, pool, true)) != HGCA_OK) return rc;
+    if (!cnt || (k_max > 0 && !idx)) return HGCA_ERR_INVALID_ARG;
+    if (ctx_cap > 0 && (!k_ctx || !v_ctx || !aligned16(k_ctx) || !aligned16(v_ctx) || k_ctx == v_ctx))
+        return HGCA_ERR_INVALID_ARG;
+    if (cnt_out && (cnt_out == first_row || cnt_out == cnt)) return HGCA_ERR_INVALID_ARG;   // read by other workgroups
+    CtxCompactArgs a{};
+    a.sh = to_dev(shape);
+    a.kv = to_dev(pool);
+    a.idx = idx;
+    a.cnt = cnt;
+    a.first_row = first_row;
+    a.cnt_out = cnt_out;
+    a.k_ctx = static_cast<char *>(k_ctx);
+    a.v_ctx = static_cast<char *>(v_ctx);
+    a.k_max = k_max;
+    a.ctx_cap = ctx_cap;
+    a.row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
+    return from_hip(launch_ctx_compact(a, static_cast<hipStream_t>(hip_stream)));
+}
+
 namespace {
 
 // Split size of the append-stage attention: enough workgroups to fill the GPU, few enough splits that the

@@ -135,4 +135,16 @@ hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_i
                             int32_t n_kv_heads, int32_t row_bytes, hipStream_t s);
 hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s);
 
+// Copy of listed pool entries into per-head contiguous storage (KV_ctx of Alg. 1).
+struct CtxCompactArgs {
+    ShapeDev sh;
+    KvDev kv;                  // the pool
+    const int32_t *idx, *cnt;  // [B*Hq, k_max], [B*Hq]
+    const int32_t *first_row;  // optional [B*Hq]: rows of KV_ctx already taken
+    int32_t *cnt_out;          // optional [B*Hq]: rows taken afterwards
+    char *k_ctx, *v_ctx;       // [B*Hq, ctx_cap, row_bytes]
+    int32_t k_max, ctx_cap, row_bytes;
+};
+hipError_t launch_ctx_compact(const CtxCompactArgs &a, hipStream_t s);
+
 }  // namespace hgca

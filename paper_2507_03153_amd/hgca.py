@@ -25,7 +25,7 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
-           "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step")
+           "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact")
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -102,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_union_lists.argtypes = [ps, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.hgca_sparse_attn_grouped.restype = ctypes.c_int
         L.hgca_sparse_attn_grouped.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.hgca_ctx_compact.restype = ctypes.c_int
+        L.hgca_ctx_compact.argtypes = [ps, pk, vp, vp, i32, vp, vp, vp, i32, vp, vp]
         L.hgca_hybrid_decode_step.restype = ctypes.c_int
         L.hgca_hybrid_decode_step.argtypes = [ps, vp, pk, pk, vp, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp]
         L.hgca_dense_window_attn_maw.restype = ctypes.c_int
@@ -398,3 +400,14 @@ def hybrid_decode_step(shape: Shape, q, window: Tier, pool: Tier, k, k_max: int,
                                          int(k_max), _ptr(idx_out), _ptr(cnt_out), _ptr(o_out), _dtype_code(o_out),
                                          _ptr(lse_out), _ptr(ws_dense), ws_dense.numel(), _ptr(ws_sparse),
                                          ws_sparse.numel(), _stream(stream)), "hgca_hybrid_decode_step")
+
+
+def ctx_compact(shape: Shape, pool: Tier, idx, cnt, k_max: int, k_ctx, v_ctx, ctx_cap: int, first_row=None,
+                cnt_out=None, stream=None) -> None:
+    """Copies the listed pool entries into per-head contiguous storage k_ctx / v_ctx [B,Hq,ctx_cap,d]."""
+    for t in (idx, cnt, k_ctx, v_ctx) + tuple(x for x in (first_row, cnt_out) if x is not None):
+        _require_gpu(t)
+    kv = pool.view()
+    _check(lib().hgca_ctx_compact(ctypes.byref(shape), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
+                                  _ptr(first_row), _ptr(k_ctx), _ptr(v_ctx), int(ctx_cap), _ptr(cnt_out),
+                                  _stream(stream)), "hgca_ctx_compact")

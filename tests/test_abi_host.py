@@ -318,3 +318,26 @@ def test_hybrid_decode_step_rejects_bad_arguments(hg):
     assert step(wd_bytes=hg.workspace_bytes(sh, 64, 0, 0) - 1) == hg.ERR_WORKSPACE
     assert step(wsp_bytes=hg.workspace_bytes(sh, 0, 256, 8) - 1) == hg.ERR_WORKSPACE
     assert step(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), q=None, o=None) == hg.OK   # empty batch: nothing to do
+
+
+def test_ctx_compact_rejects_bad_arguments(hg):
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    pool = _view(hg, cap=256)
+    K2, V2, C2 = ctypes.c_void_p(0x20000), ctypes.c_void_p(0x30000), ctypes.c_void_p(0x40000)
+
+    def compact(shape=sh, p=pool, idx=FAKE, cnt=FAKE, k_max=8, first=None, k=K2, v=V2, cap=16, cnt_out=C2):
+        return hg.lib().hgca_ctx_compact(ctypes.byref(shape), ctypes.byref(p), idx, cnt, k_max, first, k, v, cap,
+                                         cnt_out, None)
+
+    assert compact(shape=hg.Shape(hg.BF16, 2, 8, 3, 128, 0.088)) == hg.ERR_INVALID_ARG
+    assert compact(idx=None) == hg.ERR_INVALID_ARG
+    assert compact(cnt=None) == hg.ERR_INVALID_ARG
+    assert compact(k_max=-1) == hg.ERR_INVALID_ARG
+    assert compact(cap=-1) == hg.ERR_INVALID_ARG
+    assert compact(k=None) == hg.ERR_INVALID_ARG
+    assert compact(v=K2) == hg.ERR_INVALID_ARG                  # K and V storage must differ
+    assert compact(k=ODD) == hg.ERR_INVALID_ARG
+    assert compact(first=C2) == hg.ERR_INVALID_ARG              # cnt_out is written while other workgroups read first_row
+    assert compact(cnt=C2) == hg.ERR_INVALID_ARG
+    assert compact(p=_view(hg, cap=256, k=None)) == hg.ERR_INVALID_ARG
+    assert compact(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), idx=None, cnt=None) == hg.OK
