@@ -360,6 +360,9 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
         "lse_merge": lambda: hgca.lse_merge(merged, op, lp, ow, lw, o, lse),
         "append_weights_window": lambda: hgca.append_weights(L.shape, q, L.window, True, lw, a_gpu),
         "append_weights_pool": lambda: hgca.append_weights(L.shape, q, L.pool, False, lp, a_cpu),
+        # the same attention with the weights rounded once to bf16 for the second contraction (HGCA_APPEND_ONE_PART_P)
+        "append_attn_window_one_part_p": lambda: hgca.append_attn(L.shape, q, L.window, True, ow, lw, ws, one_part_p=True),
+        "append_attn_pool_one_part_p": lambda: hgca.append_attn(L.shape, q, L.pool, False, op, lp, ws, one_part_p=True),
     }
     ms = {}
     for name, fn in calls.items():
@@ -377,12 +380,17 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
     kv_bytes = 2 * B * Hkv * (W + P) * d * elem                 # K and V of both tiers, once per KV head
     flops = 4.0 * B * Hq * n_q * (W + P) * d                    # QK^T and PV, 2 flops per multiply-add (causal skip ignored)
     attn_ms = ms["append_attn_window"] + ms["append_attn_pool"] + ms["lse_merge"]
-    return {"n_q": n_q, "per_call_ms": ms, "attention_ms": attn_ms, "with_weights_ms": sum(ms.values()),
+    one_ms = ms["append_attn_window_one_part_p"] + ms["append_attn_pool_one_part_p"] + ms["lse_merge"]
+    weights_ms = ms["append_weights_window"] + ms["append_weights_pool"]
+    return {"n_q": n_q, "per_call_ms": ms, "attention_ms": attn_ms, "with_weights_ms": attn_ms + weights_ms,
             "tokens_per_s": B * n_q / (attn_ms * 1e-3),
             "kv_bytes": kv_bytes, "hbm_frac": kv_bytes / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "tflops": flops / (attn_ms * 1e-3) / 1e12, "mfma_frac_bf16": flops / (attn_ms * 1e-3) / 2.5e15,
             "note": "probabilities enter the second contraction as a high and a low bf16 part, so the matrix cores "
-                    "execute 1.5x the counted flops"}
+                    "execute 1.5x the counted flops",
+            "one_part_p": {"attention_ms": one_ms, "hbm_frac": kv_bytes / (one_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                           "tflops": flops / (one_ms * 1e-3) / 1e12,
+                           "mfma_frac_bf16": flops / (one_ms * 1e-3) / 2.5e15}}
 
 
 def copy_calibration(torch, dev) -> int:

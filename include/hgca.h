@@ -397,19 +397,29 @@ int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool,
  * append branch).  bf16 only (both contractions run on the matrix cores). ----
  *
  * q is [B, N, Hq, d].  Attention of all N queries over one tier; the two parts
- * of the hybrid step are two calls (the window with causal_tail = 1, the
- * complete older pool with causal_tail = 0) whose results hgca_lse_merge
- * combines with a shape whose batch is B*N.
- * causal_tail != 0: the tier's last N valid tokens are the incoming tokens
- * themselves and attention among them is causal: query i (0-based) sees tokens
- * [0, seq_lens[b] - N + i + 1).  causal_tail == 0: every query sees every valid
- * token.  o_out is fp32 [B, N, Hq, d], lse_out fp32 [B, N, Hq]; a query that
- * sees nothing gives O = 0, lse = -inf.  ws needs hgca_append_workspace_bytes
- * (shape, n_q, tier->cap) bytes.  n_q <= 4096. */
+ * of the hybrid step are two calls (the window with HGCA_APPEND_CAUSAL_TAIL,
+ * the complete older pool without) whose results hgca_lse_merge combines with
+ * a shape whose batch is B*N.  `flags` is a sum of:
+ * HGCA_APPEND_CAUSAL_TAIL: the tier's last N valid tokens are the incoming
+ * tokens themselves and attention among them is causal: query i (0-based) sees
+ * tokens [0, seq_lens[b] - N + i + 1).  Without it every query sees every valid
+ * token.
+ * HGCA_APPEND_ONE_PART_P: the softmax weights enter the second contraction
+ * rounded once to bf16 (relative error 2^-9 per weight: O within ~1e-3 of the
+ * exact result for unit-variance V, lse unaffected), a third fewer matrix
+ * instructions.  Without it they enter as a high and a low bf16 part and O
+ * keeps fp32-level accuracy (~1e-6).
+ * Other bits are rejected.  o_out is fp32 [B, N, Hq, d], lse_out fp32
+ * [B, N, Hq]; a query that sees nothing gives O = 0, lse = -inf.  ws needs
+ * hgca_append_workspace_bytes(shape, n_q, tier->cap) bytes.  n_q <= 4096. */
+enum {
+    HGCA_APPEND_CAUSAL_TAIL = 1,
+    HGCA_APPEND_ONE_PART_P = 2
+};
 size_t hgca_append_workspace_bytes(const hgca_shape *shape, int32_t n_q,
                                    int32_t max_tokens);
 int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q,
-                     const hgca_kv_view *tier, int32_t causal_tail,
+                     const hgca_kv_view *tier, int32_t flags,
                      float *o_out, float *lse_out,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
@@ -418,8 +428,8 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q,
  * and entry, the average over the N queries of the part's own softmax weights,
  * a_out[b,h,t] = (1/N) * sum_i e^{s_it - lse[b,i,h]} over the queries i that
  * see t, where lse is the lse_out of hgca_append_attn on the same tier (same q,
- * n_q, causal_tail).  a_out is fp32 [B, Hq, tier->cap], 0 at t >= seq_lens[b].
- * Only tier->k is read. */
+ * n_q, causal_tail != 0 iff HGCA_APPEND_CAUSAL_TAIL there).  a_out is fp32
+ * [B, Hq, tier->cap], 0 at t >= seq_lens[b].  Only tier->k is read. */
 int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q,
                         const hgca_kv_view *tier, int32_t causal_tail,
                         const float *lse, float *a_out, void *hip_stream);

@@ -2,25 +2,25 @@
 // O = A V with Q in R^{h x N x d}; Alg. 2, append branch).  bf16 inputs, both contractions on
 // v_mfma_f32_16x16x32_bf16.
 //
-// Work unit: one workgroup = one split of the tokens of one (sequence, KV head) and up to 128 query
-// rows (a row = one query x one head of the GQA group, query-major).  Each of the eight waves owns
-// one 16-row tile, so nothing is reduced across waves; all 512 threads stage the K and V rows of a
-// 64-token step into LDS with coalesced 16-byte loads.  The next step's loads are in flight during a
-// step's arithmetic (registers, parked into a double-buffered LDS stage, one barrier per step); two
-// workgroups share a CU, so 64 KB per CU are on their way from HBM while 16 waves do arithmetic.
-// A step is 64 tokens rather than 32 because the softmax of a step is one dependent chain (scores,
-// row maximum, exponentials, row sum, rounding, second contraction): four score tiles per chain give
-// the wave independent work to overlap it with.
+// Work unit of the attention kernel: one workgroup = one split of the tokens of one (sequence, KV head) and up
+// to 128 query rows (a row = one query x one head of the GQA group, query-major).  Every wave owns row tiles of 16
+// rows, so nothing is reduced across waves.  The K and V rows of a 64-token step are brought into a double-buffered
+// LDS stage by LDS-direct loads (no registers in between); the next step's loads are in flight during a step's
+// arithmetic, one barrier per step; two workgroups share a CU.  A step is 64 tokens rather than 32 because the
+// softmax of a step is one dependent chain (scores, row maximum, exponentials, row sum, rounding, second
+// contraction): four score tiles per chain give the wave independent work to overlap it with.
 //
 // Orientation (per 16-row tile, per step):
-//   S^T[token, row]  = K[token, :] . Q[row, :]        A = K tile (LDS, padded rows), B = Q (registers)
+//   S^T[token, row]  = K[token, :] . Q[row, :]        A = K tile (LDS, swizzled rows), B = Q (registers)
 //   O^T[dcol, row]  += V^T[dcol, token] . P^T[token, row]   A = V^T (LDS transpose reads of the rows), B = P
 // In both results a lane's column is the query row lane%16, so the running maximum, the running sum
 // and the rescaling factor of a row live in the lanes that hold its scores AND its output columns:
-// the online softmax needs two shuffles per row statistic and no LDS.  The probabilities go from
+// the online softmax needs two lane exchanges per row statistic and no LDS.  The probabilities go from
 // the score registers straight into the B operand of the second contraction (the contraction index
-// is matched by reading V^T in the same token order); they are rounded to bf16 there, optionally as
-// a high and a low part (two MFMAs) to keep fp32-level accuracy.
+// is matched by reading V^T in the same token order); they are rounded to bf16 there, as a high and a
+// low part (two MFMAs, fp32-level accuracy) or, on request, as one part.
+//
+// The weights kernel stages K through registers into padded LDS rows (StepLoader / AStage).
 #include "hgca_launch.hpp"
 #include "row_map.hpp"
 
@@ -49,6 +49,23 @@ template <int D> struct AStage {
 template <int ROT>
 __device__ __forceinline__ float row_rotate(float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + ROT, 0xf, 0xf, true));
+}
+
+// Reductions over the four 16-lane rows of a wave (lanes n, n + 16, n + 32, n + 48 hold partial results of one
+// query row).  v_permlane16_swap / v_permlane32_swap of a register with itself return (rows 0 0 2 2, rows 1 1 3 3)
+// and (lower half twice, upper half twice): two VALU instructions per level where a lane shuffle would go through
+// the LDS pipeline, which matters because the row maximum heads the dependent chain of every step.
+__device__ __forceinline__ float rows_max(float x) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 // Row bookkeeping of one 16-row tile for this lane (column n = lane % 16).
@@ -109,18 +126,19 @@ struct StepLoader {
 // Raw scores <q, k> (no softmax scale yet) of one 16-row tile for the step's tokens: sv[8*kb + 4*tt + r] belongs
 // to step token 32*kb + 16*tt + 4*g + r and query row lane % 16.  With MASK, tokens at or beyond `limit` (counted
 // from the step's first token) read -inf.
-template <int D, bool MASK>
-__device__ __forceinline__ void tile_scores(const uint4 *s_k, const bf16x8 (&qop)[D / 32], int limit,
+// `k_piece(t, kk)` reads this lane's A operand: 8 elements from column 32 kk + 8 (lane / 16) on of the K row of
+// token 16 t + lane % 16 of the step.
+template <int D, bool MASK, typename KPiece>
+__device__ __forceinline__ void tile_scores(KPiece k_piece, const bf16x8 (&qop)[D / 32], int limit,
                                             float (&sv)[8 * kStepBlocks])
 {
-    using S = AStage<D>;
-    const int lane = threadIdx.x % kWave, n = lane % 16, g = lane / 16;
+    const int lane = threadIdx.x % kWave, g = lane / 16;
 #pragma unroll
     for (int t = 0; t < 2 * kStepBlocks; ++t) {  // 16-token tiles of the step
         floatx4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
-            const uint4 ka = s_k[(t * 16 + n) * S::kKStride + 4 * kk + g];
+            const uint4 ka = k_piece(t, kk);
             c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qop[kk], c, 0, 0, 0);
         }
 #pragma unroll
@@ -146,14 +164,86 @@ __device__ __forceinline__ void for_each_step(const KvDev &kv, const RowMap &row
     }
 }
 
-template <int D, int G, bool SPLIT_P>
-__global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
+// LDS stage of the attention kernel: the rows of a step are brought in by LDS-direct loads (global_load_lds, 16
+// bytes per lane, no registers in between).  One such instruction fills 1024 consecutive bytes of LDS with whatever
+// 64 pieces its lanes address, so the layout inside each 1 KB group is chosen by the lane -> global address map:
+//   K: row-major rows with the 16-byte pieces of a row XOR-swizzled by the row, so that the 16 rows an A-operand
+//      read touches land on different banks without padding;
+//   V: the group's rows interleaved in 32-byte chunks ([column chunk][row][32 bytes]), so that the 4 rows x 32 bytes
+//      a 16-lane group takes with one transpose read are 128 consecutive bytes.
+#ifndef HGCA_APPEND_PV_GROUP
+#define HGCA_APPEND_PV_GROUP 4
+#endif
+#ifndef HGCA_APPEND_TILES
+#define HGCA_APPEND_TILES 2
+#endif
+
+// LDS stage of the attention kernel: the rows of a step are brought in by LDS-direct loads (global_load_lds, 16
+// bytes per lane, no registers in between).  One such instruction fills 1024 consecutive bytes of LDS with whatever
+// 64 pieces its lanes address, so the layout inside each 1 KB group is chosen by the lane -> global address map:
+//   K: row-major rows with the 16-byte pieces of a row XOR-swizzled by the row, so that the 16 rows an A-operand
+//      read touches land on different banks without padding;
+//   V: the group's rows interleaved in 32-byte chunks ([column chunk][row][32 bytes]), so that the 4 rows x 32 bytes
+//      a 16-lane group takes with one transpose read are 128 consecutive bytes.
+template <int D, int NW> struct DmaStage {
+    static constexpr int kPieces = D / 8;                        // 16-byte pieces per row
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kGroupRows = 1024 / kRowBytes;          // rows per load instruction of a wave
+    static constexpr int kGroups = kStepTokens / kGroupRows;     // per step and tensor
+    static constexpr int kLoads = kGroups / NW;                  // per wave, step and tensor
+    static constexpr int kBytes = kStepTokens * kRowBytes;       // per step and tensor
+    static_assert(kGroups % NW == 0 && kLoads >= 1, "the waves share the groups of a step evenly");
+
+    static __device__ __forceinline__ int k_swizzle(int row) { return (row / (16 / kPieces)) % kPieces; }
+    // byte offset, in a K stage, of logical piece `piece` of step row `row`
+    static __device__ __forceinline__ int k_offset(int row, int piece) {
+        return row * kRowBytes + 16 * (piece ^ k_swizzle(row));
+    }
+    // byte offset, in a V stage, of the 32-byte column chunk `dt` of step row `row`
+    static __device__ __forceinline__ int v_offset(int row, int dt) {
+        return (row / kGroupRows) * 1024 + dt * (kGroupRows * 32) + (row % kGroupRows) * 32;
+    }
+};
+
+template <int D, int NW, bool K_ROWS>
+__device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, int step, int nsub, char *stage)
 {
-    using S = AStage<D>;
+    using S = DmaStage<D, NW>;
+    const int lane = threadIdx.x % kWave, w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+#pragma unroll
+    for (int u = 0; u < S::kLoads; ++u) {
+        const int group = w + NW * u;                            // uniform over the wave
+        int row, piece;                                          // what lands at byte 16 * lane of the group
+        if (K_ROWS) {
+            row = group * S::kGroupRows + lane / S::kPieces;
+            piece = (lane % S::kPieces) ^ S::k_swizzle(row);
+        } else {
+            row = group * S::kGroupRows + (lane / 2) % S::kGroupRows;
+            piece = 2 * (lane / (2 * S::kGroupRows)) + lane % 2;
+        }
+        const int j = min(step * kStepTokens + row, nsub - 1);
+        const char *src = (K_ROWS ? kv.k : kv.v) + (size_t)rows(j) * S::kRowBytes + 16 * piece;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)(stage + group * 1024), 16, 0, 0);
+    }
+}
+
+// TILES row tiles of 16 query rows per wave (128 rows per workgroup, so 8 / TILES waves): with two tiles every K
+// and V operand read from LDS feeds two matrix instructions, and the two tiles' softmax chains are independent
+// work for the wave to overlap.
+template <int D, int G, bool SPLIT_P, int TILES>
+__global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel(AppendArgs a)
+{
+    constexpr int NW = kAWaves / TILES, BLOCK = NW * kWave;
+    using S = DmaStage<D, NW>;
     constexpr int DT = D / 16;
     constexpr float kLog2e = 1.4426950408889634f;
-    __shared__ uint4 s_k[2][kStepTokens * S::kKStride];
-    __shared__ __attribute__((aligned(16))) char s_v[2][kStepTokens * S::kVStride];
+    // two stages per tensor as separate arrays: the compiler then knows that a load into one stage does not
+    // touch the other and lets the reads of the current stage go ahead while the next one is being filled
+    __shared__ __attribute__((aligned(1024))) char s_k0[S::kBytes];
+    __shared__ __attribute__((aligned(1024))) char s_k1[S::kBytes];
+    __shared__ __attribute__((aligned(1024))) char s_v0[S::kBytes];
+    __shared__ __attribute__((aligned(1024))) char s_v1[S::kBytes];
     __shared__ uint32_t s_row[kSub];
 
     const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -163,24 +253,138 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
     const int t0 = split * a.chunk;
     const int nt_total = min(a.chunk, len - t0);                 // <= 0: nothing of this split is valid
 
-    const int tile_row0 = qb * kRowsPerBlock + w * 16;           // first row of the wave's tile
-    const bool tile_live = tile_row0 < a.n_q * G;                // uniform over the wave
-    const RowInfo ri = row_info<G>(a, b, kvh, tile_row0 + n);
-    // tokens [0, vis) of the tier are visible to the row
-    const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
-    int vis_min = vis;                           // over the rows of the tile: steps below it need no mask
+    const int tile_row0 = qb * kRowsPerBlock + w * 16 * TILES;   // first row of the wave's first tile
+    const bool wave_live = tile_row0 < a.n_q * G;                // uniform over the wave
+    RowInfo ri[TILES];
+    int vis[TILES];                              // tokens [0, vis) of the tier are visible to the row
+    int vis_min = INT32_MAX;                     // over the rows of the wave: steps below it need no mask
+    bf16x8 qop[TILES][D / 32];
+#pragma unroll
+    for (int x = 0; x < TILES; ++x) {
+        ri[x] = row_info<G>(a, b, kvh, tile_row0 + 16 * x + n);
+        vis[x] = !ri[x].valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri[x].query + 1, 0), len) : len;
+        vis_min = min(vis_min, vis[x]);
+        load_q_tile<D>(a, ri[x], g, qop[x]);
+    }
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) vis_min = min(vis_min, __shfl_xor(vis_min, off, kWave));
-    bf16x8 qop[D / 32];
-    load_q_tile<D>(a, ri, g, qop);
     // The running maximum m is kept on the RAW scores (the softmax scale is positive, so the order is the same) and
     // the scale, in units of ln 2, is applied inside the exponent: e^{scale (s - m)} = 2^{fma(s, scale2, -m scale2)},
     // one fused multiply-add and one bare v_exp_f32 per score.
     const float scale2 = a.sh.sm_scale * kLog2e;
-    float m = -INFINITY, l = 0.f;
-    floatx4 acc[DT];
+    float m[TILES], l[TILES];
+    floatx4 acc[TILES][DT];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int x = 0; x < TILES; ++x) {
+        m[x] = -INFINITY;
+        l[x] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) acc[x][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // this lane's byte offsets into a stage: the A operand of the first product (row n of a 16-token tile, one
+    // offset per 32-column slice because of the swizzle) and of the second.  The V^T operand (8 tokens of one column
+    // per lane) comes from two transpose reads: lane j of a group points at columns 4(j%4).. of the row of
+    // contraction index j/4 (first read) and 4 + j/4 (second read).
+    int k_lane[D / 32];
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) k_lane[kk] = S::k_offset(n, 4 * kk + g);
+    const int v_lane_lo = S::v_offset(block_token(g, n / 4), 0) + 8 * (n % 4);
+    const int v_lane_hi = S::v_offset(block_token(g, 4 + n / 4), 0) + 8 * (n % 4);
+
+    auto step_body = [&](const char *k_stage, const char *v_stage, int step0, int in_split) {
+        // raw scores: sv[x][8*kb + 4*tt + r] belongs to step token 32*kb + 16*tt + 4*g + r and row n of tile x
+        float sv[TILES][8 * kStepBlocks];
+        const bool masked = min(in_split, vis_min - step0) < kStepTokens;   // uniform over the wave
+#pragma unroll
+        for (int t = 0; t < 2 * kStepBlocks; ++t) {              // 16-token tiles of the step
+            floatx4 c[TILES];
+#pragma unroll
+            for (int x = 0; x < TILES; ++x) c[x] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk) {
+                const uint4 ka = *reinterpret_cast<const uint4 *>(k_stage + t * 16 * S::kRowBytes + k_lane[kk]);
+#pragma unroll
+                for (int x = 0; x < TILES; ++x)
+                    c[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qop[x][kk], c[x], 0, 0, 0);
+            }
+#pragma unroll
+            for (int x = 0; x < TILES; ++x)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) sv[x][4 * t + r] = c[x][r];
+        }
+        if (masked) {                                            // steps that touch a length or causal boundary
+#pragma unroll
+            for (int x = 0; x < TILES; ++x) {
+                const int limit = min(in_split, vis[x] - step0);
+#pragma unroll
+                for (int e = 0; e < 8 * kStepBlocks; ++e)
+                    if (16 * (e / 4) + 4 * g + e % 4 >= limit) sv[x][e] = -INFINITY;
+            }
+        }
+        bf16x8 ph[TILES][kStepBlocks], pl[TILES][kStepBlocks];
+#pragma unroll
+        for (int x = 0; x < TILES; ++x) {
+            float mx = sv[x][0];
+#pragma unroll
+            for (int e = 1; e < 8 * kStepBlocks; ++e) mx = fmaxf(mx, sv[x][e]);
+            const float m_new = fmaxf(m[x], rows_max(mx));
+            // a row that has seen nothing yet keeps m = -inf: shift by 0 then, every exponent is -inf and gives 0
+            const float shift = (m_new == -INFINITY) ? 0.f : -m_new * scale2;
+            float ps = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8 * kStepBlocks; ++e) {          // sv becomes the probabilities; masked scores give 0
+                sv[x][e] = __builtin_amdgcn_exp2f(fmaf(sv[x][e], scale2, shift));
+                ps += sv[x][e];
+            }
+            const float corr = (m[x] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(fmaf(m[x], scale2, shift));
+            l[x] = l[x] * corr + rows_sum(ps);
+            m[x] = m_new;
+            if (__any(corr != 1.f)) {                            // once the maxima have settled nothing is rescaled
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) acc[x][dt] *= corr;
+            }
+#pragma unroll
+            for (int kb = 0; kb < kStepBlocks; ++kb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {                    // round to nearest even; the low part carries the rounding error
+                    ph[x][kb][e] = (__bf16)sv[x][8 * kb + e];
+                    pl[x][kb][e] = SPLIT_P ? (__bf16)(sv[x][8 * kb + e] - (float)ph[x][kb][e]) : (__bf16)0.f;
+                }
+        }
+        // O^T += V^T P^T, one 16-column tile of the output at a time
+#pragma unroll
+        for (int kb = 0; kb < kStepBlocks; ++kb) {
+            const char *v_lo = v_stage + S::v_offset(32 * kb, 0) + v_lane_lo;
+            const char *v_hi = v_stage + S::v_offset(32 * kb, 0) + v_lane_hi;
+            // column tiles in groups of kPvGroup: the group's high-part products first, then its low-part ones, so
+            // that two MFMAs on the same accumulator are several instructions apart
+            constexpr int kPvGroup = HGCA_APPEND_PV_GROUP;
+#pragma unroll
+            for (int dt0 = 0; dt0 < DT; dt0 += kPvGroup) {
+                bf16x8 vop[kPvGroup];
+#pragma unroll
+                for (int u = 0; u < kPvGroup; ++u) {
+                    const int at = S::v_offset(0, dt0 + u);
+                    const short4v a0 = lds_read_tr16(v_lo + at), a1 = lds_read_tr16(v_hi + at);
+                    const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                    vop[u] = __builtin_bit_cast(bf16x8, both);
+                }
+#pragma unroll
+                for (int x = 0; x < TILES; ++x)
+#pragma unroll
+                    for (int u = 0; u < kPvGroup; ++u)
+                        acc[x][dt0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[u], ph[x][kb], acc[x][dt0 + u], 0, 0, 0);
+                if (SPLIT_P) {
+#pragma unroll
+                    for (int x = 0; x < TILES; ++x)
+#pragma unroll
+                        for (int u = 0; u < kPvGroup; ++u)
+                            acc[x][dt0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[u], pl[x][kb], acc[x][dt0 + u], 0, 0, 0);
+                }
+            }
+        }
+    };
 
     // a paged tier needs a row table in LDS, refilled every kSub tokens (which drains the load pipeline);
     // a contiguous tier is plain arithmetic and takes the whole split in one pass
@@ -188,87 +392,39 @@ __global__ __launch_bounds__(kABlock, 4) void append_attn_kernel(AppendArgs a)
     for (int sub0 = 0; sub0 < nt_total; sub0 += sub_len) {
         const int nsub = min(sub_len, nt_total - sub0);
         __syncthreads();                         // the previous table and stages are no longer in use
-        const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
-        for_each_step<D, true>(a.kv, rows, nsub, s_k, s_v, [&](int buf, int s) {
-            if (!tile_live) return;
-            const int step0 = t0 + sub0 + s * kStepTokens;       // tier position of the step's first token
-            const int in_split = nsub - s * kStepTokens;         // tokens of the step that belong to this split
-            float sv[8 * kStepBlocks];
-            if (min(in_split, vis_min - step0) >= kStepTokens)   // uniform over the wave: every token visible to every row
-                tile_scores<D, false>(s_k[buf], qop, 0, sv);
-            else
-                tile_scores<D, true>(s_k[buf], qop, min(in_split, vis - step0), sv);
-            float mx = sv[0];
-#pragma unroll
-            for (int e = 1; e < 8 * kStepBlocks; ++e) mx = fmaxf(mx, sv[e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float m_new = fmaxf(m, mx);
-            // a row that has seen nothing yet keeps m = -inf: shift by 0 then, every exponent is -inf and gives 0
-            const float shift = (m_new == -INFINITY) ? 0.f : -m_new * scale2;
-            float ps = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8 * kStepBlocks; ++e) {          // sv becomes the probabilities; masked scores give 0
-                sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], scale2, shift));
-                ps += sv[e];
+        const RowMap rows = make_row_map<false, BLOCK>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
+        // Step s reads the stages of its parity and requests the rows of step s + 1 into the stages of the other
+        // parity, which were last read in step s - 1: the barrier at the top of the step (before which every wave
+        // waits for its own loads) orders both.
+        const int steps = (nsub + kStepTokens - 1) / kStepTokens;
+        dma_step<D, NW, true>(a.kv, rows, 0, nsub, s_k0);
+        dma_step<D, NW, false>(a.kv, rows, 0, nsub, s_v0);
+        auto step = [&](int s, const char *k_cur, const char *v_cur, char *k_next, char *v_next) {
+            __syncthreads();
+            if (s + 1 < steps) {
+                dma_step<D, NW, true>(a.kv, rows, s + 1, nsub, k_next);
+                dma_step<D, NW, false>(a.kv, rows, s + 1, nsub, v_next);
             }
-            ps += __shfl_xor(ps, 16, kWave);
-            ps += __shfl_xor(ps, 32, kWave);
-            const float corr = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(fmaf(m, scale2, shift));
-            l = l * corr + ps;
-            m = m_new;
-            if (__any(corr != 1.f)) {
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) acc[dt] *= corr;
-            }
-#pragma unroll
-            for (int kb = 0; kb < kStepBlocks; ++kb) {
-                bf16x8 ph, pl;                   // round to nearest even; the low part carries the rounding error
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    ph[e] = (__bf16)sv[8 * kb + e];
-                    pl[e] = SPLIT_P ? (__bf16)(sv[8 * kb + e] - (float)ph[e]) : (__bf16)0.f;
-                }
-                // O^T += V^T P^T, one 16-column tile of the output at a time.  The V^T operand (8 tokens of one column
-                // per lane) comes from two transpose reads: lane j of a group points at columns 4(j%4).. of the row of
-                // contraction index j/4 (first read) and 4 + j/4 (second read).
-                const char *v_lo = s_v[buf] + (32 * kb + block_token(g, n / 4)) * S::kVStride + 8 * (n % 4);
-                const char *v_hi = s_v[buf] + (32 * kb + block_token(g, 4 + n / 4)) * S::kVStride + 8 * (n % 4);
-                // column tiles in groups of kPvGroup: the group's high-part products first, then its low-part ones, so
-                // that two MFMAs on the same accumulator are kPvGroup instructions apart
-                constexpr int kPvGroup = 4;
-#pragma unroll
-                for (int dt0 = 0; dt0 < DT; dt0 += kPvGroup) {
-                    bf16x8 vop[kPvGroup];
-#pragma unroll
-                    for (int u = 0; u < kPvGroup; ++u) {
-                        const short4v a0 = lds_read_tr16(v_lo + 32 * (dt0 + u)), a1 = lds_read_tr16(v_hi + 32 * (dt0 + u));
-                        const short8v both = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-                        vop[u] = __builtin_bit_cast(bf16x8, both);
-                    }
-#pragma unroll
-                    for (int u = 0; u < kPvGroup; ++u)
-                        acc[dt0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[u], ph, acc[dt0 + u], 0, 0, 0);
-                    if (SPLIT_P) {
-#pragma unroll
-                        for (int u = 0; u < kPvGroup; ++u)
-                            acc[dt0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[u], pl, acc[dt0 + u], 0, 0, 0);
-                    }
-                }
-            }
-        });
+            if (wave_live) step_body(k_cur, v_cur, t0 + sub0 + s * kStepTokens, nsub - s * kStepTokens);
+        };
+        for (int s2 = 0; s2 < steps; s2 += 2) {
+            step(s2, s_k0, s_v0, s_k1, s_v1);
+            if (s2 + 1 < steps) step(s2 + 1, s_k1, s_v1, s_k0, s_v0);
+        }
     }
 
-    // partial of every valid row: lane (n, g) holds output columns dt*16 + 4g .. +3 of row n
-    if (ri.valid) {
-        const int64_t at = ri.out_row * a.part.n_splits + split;
+    // partial of every valid row: lane (n, g) holds output columns dt*16 + 4g .. +3 of row n of each tile
+#pragma unroll
+    for (int x = 0; x < TILES; ++x) {
+        if (!ri[x].valid) continue;
+        const int64_t at = ri[x].out_row * a.part.n_splits + split;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
             *reinterpret_cast<float4 *>(a.part.o + at * D + dt * 16 + 4 * g) =
-                make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]);
+                make_float4(acc[x][dt][0], acc[x][dt][1], acc[x][dt][2], acc[x][dt][3]);
         if (g == 0) {
-            a.part.m[at] = m * a.sh.sm_scale;    // the maximum of the scaled scores (-inf stays -inf)
-            a.part.l[at] = l;
+            a.part.m[at] = m[x] * a.sh.sm_scale; // the maximum of the scaled scores (-inf stays -inf)
+            a.part.l[at] = l[x];
         }
     }
 }
@@ -328,7 +484,9 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
                 if (pending >= 0) fold(pending);                 // written before the barrier that preceded this call
                 float sv[8 * kStepBlocks];
                 const int step0 = sub0 + s * kStepTokens;
-                tile_scores<D, true>(s_k[buf], qop, min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
+                const uint4 *k_lane = s_k[buf] + n * S::kKStride + g;    // padded rows, see AStage
+                tile_scores<D, true>([&](int t, int kk) { return k_lane[t * 16 * S::kKStride + 4 * kk]; }, qop,
+                                     min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
 #pragma unroll
                 for (int e = 0; e < 8 * kStepBlocks; ++e) {
                     float x = __builtin_amdgcn_exp2f(fmaf(sv[e], scale2, neg_lse2));
@@ -356,11 +514,13 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
 template <int D, bool SPLIT_P>
 hipError_t launch_attn_group(const AppendArgs &a, dim3 grid, hipStream_t s)
 {
+    constexpr int T = HGCA_APPEND_TILES;
+    const dim3 block(kABlock / T);
     switch (a.sh.group) {
-    case 1: hipLaunchKernelGGL((append_attn_kernel<D, 1, SPLIT_P>), grid, dim3(kABlock), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((append_attn_kernel<D, 2, SPLIT_P>), grid, dim3(kABlock), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((append_attn_kernel<D, 4, SPLIT_P>), grid, dim3(kABlock), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((append_attn_kernel<D, 8, SPLIT_P>), grid, dim3(kABlock), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((append_attn_kernel<D, 1, SPLIT_P, T>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((append_attn_kernel<D, 2, SPLIT_P, T>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((append_attn_kernel<D, 4, SPLIT_P, T>), grid, block, 0, s, a); break;
+    case 8: hipLaunchKernelGGL((append_attn_kernel<D, 8, SPLIT_P, T>), grid, block, 0, s, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -381,18 +541,13 @@ hipError_t launch_weights_group(const AppendArgs &a, dim3 grid, hipStream_t s)
 
 }  // namespace
 
-#ifndef HGCA_APPEND_SPLIT_P
-#define HGCA_APPEND_SPLIT_P 1
-#endif
-
 hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s)
 {
     if (a.sh.batch == 0 || a.n_q == 0 || a.part.n_splits == 0) return hipSuccess;
     const int n_qb = (a.n_q * a.sh.group + kRowsPerBlock - 1) / kRowsPerBlock;
     dim3 grid(a.part.n_splits, a.sh.n_kv_heads * n_qb, a.sh.batch);
-    constexpr bool kSplit = HGCA_APPEND_SPLIT_P != 0;
-    if (head_dim == 64) return launch_attn_group<64, kSplit>(a, grid, s);
-    if (head_dim == 128) return launch_attn_group<128, kSplit>(a, grid, s);
+    if (head_dim == 64) return a.one_part_p ? launch_attn_group<64, false>(a, grid, s) : launch_attn_group<64, true>(a, grid, s);
+    if (head_dim == 128) return a.one_part_p ? launch_attn_group<128, false>(a, grid, s) : launch_attn_group<128, true>(a, grid, s);
     return hipErrorInvalidValue;
 }
 

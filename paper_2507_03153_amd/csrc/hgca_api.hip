@@ -706,10 +706,11 @@ size_t hgca_append_workspace_bytes(const hgca_shape *shape, int32_t n_q, int32_t
 }
 
 int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier,
-                     int32_t causal_tail, float *o_out, float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
+                     int32_t flags, float *o_out, float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     int rc = check_append(shape, q, n_q, tier, true);
     if (rc != HGCA_OK) return rc;
+    if (flags & ~(HGCA_APPEND_CAUSAL_TAIL | HGCA_APPEND_ONE_PART_P)) return HGCA_ERR_INVALID_ARG;
     if (shape->batch == 0 || n_q == 0) return HGCA_OK;
     if (!o_out || !lse_out || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
     const AppendWs w = append_layout(shape, n_q, tier->cap);
@@ -721,7 +722,8 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const 
     a.q = q;
     a.kv = to_dev(tier);
     a.n_q = n_q;
-    a.causal_tail = causal_tail ? 1 : 0;
+    a.causal_tail = (flags & HGCA_APPEND_CAUSAL_TAIL) ? 1 : 0;
+    a.one_part_p = (flags & HGCA_APPEND_ONE_PART_P) ? 1 : 0;
     a.chunk = append_chunk(shape, n_q, tier->cap);
     char *base = static_cast<char *>(ws);
     a.part.o = reinterpret_cast<float *>(base + w.o);

@@ -109,6 +109,7 @@ struct AppendArgs {
     KvDev kv;
     int32_t n_q;               // N
     int32_t causal_tail;       // 1: the tier's last N valid tokens are the queries' own; query i sees tokens < len-N+i+1
+    int32_t one_part_p;        // 1: the weights enter the second product as one bf16 value instead of a high and a low part
     int32_t chunk;             // tokens per split (attention) or per workgroup (weights), a multiple of 64
     Partials part;             // attention: rows are (b, query, head)
     const float *lse;          // weights: [B, N, Hq], the tier's log-sum-exp per query and head

@@ -33,7 +33,10 @@ constexpr int kBins = HGCA_SEL_BINS;
 constexpr int kBinsPerThread = kBins / kSelBlock;
 constexpr int kMaxCand = kSelBlock;              // one candidate per thread in the exact ranking
 constexpr int kStep = 4 * kWave;                 // scores a wave handles per step
-constexpr int kMaxCacheFloats = 33792;           // 132 KiB of LDS for the padded row
+#ifndef HGCA_SEL_CACHE_FLOATS
+#define HGCA_SEL_CACHE_FLOATS 33792
+#endif
+constexpr int kMaxCacheFloats = HGCA_SEL_CACHE_FLOATS;   // 132 KiB of LDS for the padded row
 
 // Larger float <=> larger key; -0.0 and +0.0 map to the same key.
 __device__ __forceinline__ uint32_t order_key(float s) {

@@ -321,12 +321,17 @@ def append_workspace(shape: Shape, n_q: int, max_tokens: int, device) -> torch.T
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def append_attn(shape: Shape, q, tier: Tier, causal_tail: bool, o_out, lse_out, ws, stream=None) -> None:
+APPEND_CAUSAL_TAIL, APPEND_ONE_PART_P = 1, 2
+
+
+def append_attn(shape: Shape, q, tier: Tier, causal_tail: bool, o_out, lse_out, ws, stream=None,
+                one_part_p: bool = False) -> None:
     """q [B,N,Hq,d] bf16; o_out [B,N,Hq,d], lse_out [B,N,Hq] fp32."""
     for t in (q, o_out, lse_out, ws):
         _require_gpu(t)
     kv = tier.view()
-    _check(lib().hgca_append_attn(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), int(causal_tail),
+    flags = (APPEND_CAUSAL_TAIL if causal_tail else 0) | (APPEND_ONE_PART_P if one_part_p else 0)
+    _check(lib().hgca_append_attn(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), flags,
                                   _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
            "hgca_append_attn")
 

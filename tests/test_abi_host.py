@@ -239,9 +239,11 @@ def test_append_entry_points_reject_bad_arguments(hg):
     assert hg.lib().hgca_append_workspace_bytes(byref(sh), -1, 4096) == 0
     assert hg.lib().hgca_append_workspace_bytes(byref(hg.Shape(hg.BF16, 2, 8, 3, 128, 1.0)), 4, 64) == 0
 
-    def attn(shape=sh, q=FAKE, n_q=4, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40):
-        return L.hgca_append_attn(byref(shape), q, n_q, byref(view), 1, o, lse, ws, ws_bytes, None)
+    def attn(shape=sh, q=FAKE, n_q=4, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40, flags=1):
+        return L.hgca_append_attn(byref(shape), q, n_q, byref(view), flags, o, lse, ws, ws_bytes, None)
     assert attn(q=None) == hg.ERR_INVALID_ARG
+    assert attn(flags=4) == hg.ERR_INVALID_ARG                  # an unknown flag bit
+    assert attn(flags=-1) == hg.ERR_INVALID_ARG
     assert attn(q=ODD) == hg.ERR_INVALID_ARG
     assert attn(n_q=-1) == hg.ERR_INVALID_ARG
     assert attn(n_q=5000) == hg.ERR_INVALID_ARG
