@@ -205,26 +205,33 @@ template <int D, int NW> struct DmaStage {
     }
 };
 
-template <int D, int NW, bool K_ROWS>
-__device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, int step, int nsub, char *stage)
+// Requests the K and the V rows of a step.  All row numbers are looked up before the first load is issued: the
+// lookup of a paged tier reads a table in LDS, and an LDS read placed after an LDS-direct load waits for that load.
+template <int D, int NW>
+__device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, int step, int nsub, char *k_stage,
+                                         char *v_stage)
 {
     using S = DmaStage<D, NW>;
     const int lane = threadIdx.x % kWave, w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const char *k_src[S::kLoads], *v_src[S::kLoads];
 #pragma unroll
     for (int u = 0; u < S::kLoads; ++u) {
         const int group = w + NW * u;                            // uniform over the wave
-        int row, piece;                                          // what lands at byte 16 * lane of the group
-        if (K_ROWS) {
-            row = group * S::kGroupRows + lane / S::kPieces;
-            piece = (lane % S::kPieces) ^ S::k_swizzle(row);
-        } else {
-            row = group * S::kGroupRows + (lane / 2) % S::kGroupRows;
-            piece = 2 * (lane / (2 * S::kGroupRows)) + lane % 2;
-        }
-        const int j = min(step * kStepTokens + row, nsub - 1);
-        const char *src = (K_ROWS ? kv.k : kv.v) + (size_t)rows(j) * S::kRowBytes + 16 * piece;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(stage + group * 1024), 16, 0, 0);
+        // what lands at byte 16 * lane of the group: K row-major with swizzled pieces, V chunk-interleaved
+        const int k_row = group * S::kGroupRows + lane / S::kPieces;
+        const int k_piece = (lane % S::kPieces) ^ S::k_swizzle(k_row);
+        const int v_row = group * S::kGroupRows + (lane / 2) % S::kGroupRows;
+        const int v_piece = 2 * (lane / (2 * S::kGroupRows)) + lane % 2;
+        k_src[u] = kv.k + (size_t)rows(min(step * kStepTokens + k_row, nsub - 1)) * S::kRowBytes + 16 * k_piece;
+        v_src[u] = kv.v + (size_t)rows(min(step * kStepTokens + v_row, nsub - 1)) * S::kRowBytes + 16 * v_piece;
+    }
+#pragma unroll
+    for (int u = 0; u < S::kLoads; ++u) {
+        const int group = w + NW * u;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)k_src[u],
+                                         (__attribute__((address_space(3))) void *)(k_stage + group * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)v_src[u],
+                                         (__attribute__((address_space(3))) void *)(v_stage + group * 1024), 16, 0, 0);
     }
 }
 
@@ -397,14 +404,10 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
         // parity, which were last read in step s - 1: the barrier at the top of the step (before which every wave
         // waits for its own loads) orders both.
         const int steps = (nsub + kStepTokens - 1) / kStepTokens;
-        dma_step<D, NW, true>(a.kv, rows, 0, nsub, s_k0);
-        dma_step<D, NW, false>(a.kv, rows, 0, nsub, s_v0);
+        dma_step<D, NW>(a.kv, rows, 0, nsub, s_k0, s_v0);
         auto step = [&](int s, const char *k_cur, const char *v_cur, char *k_next, char *v_next) {
             __syncthreads();
-            if (s + 1 < steps) {
-                dma_step<D, NW, true>(a.kv, rows, s + 1, nsub, k_next);
-                dma_step<D, NW, false>(a.kv, rows, s + 1, nsub, v_next);
-            }
+            if (s + 1 < steps) dma_step<D, NW>(a.kv, rows, s + 1, nsub, k_next, v_next);
             if (wave_live) step_body(k_cur, v_cur, t0 + sub0 + s * kStepTokens, nsub - s * kStepTokens);
         };
         for (int s2 = 0; s2 < steps; s2 += 2) {
