@@ -205,6 +205,11 @@ template <int D, int NW> struct DmaStage {
     }
 };
 
+// s_waitcnt vmcnt(0) (expcnt and lgkmcnt fields at their maxima = no wait): an LDS-direct load has landed in LDS
+// when the wave's memory-load counter has counted it down.  Every wave does this before the barrier after which
+// other waves read what it loaded.
+__device__ __forceinline__ void wait_for_own_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // Requests the K and the V rows of a step.  All row numbers are looked up before the first load is issued: the
 // lookup of a paged tier reads a table in LDS, and an LDS read placed after an LDS-direct load waits for that load.
 template <int D, int NW>
@@ -406,6 +411,7 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
         const int steps = (nsub + kStepTokens - 1) / kStepTokens;
         dma_step<D, NW>(a.kv, rows, 0, nsub, s_k0, s_v0);
         auto step = [&](int s, const char *k_cur, const char *v_cur, char *k_next, char *v_next) {
+            wait_for_own_loads();                // the barrier alone does not wait for LDS-direct loads
             __syncthreads();
             if (s + 1 < steps) dma_step<D, NW>(a.kv, rows, s + 1, nsub, k_next, v_next);
             if (wave_live) step_body(k_cur, v_cur, t0 + sub0 + s * kStepTokens, nsub - s * kStepTokens);
