@@ -205,6 +205,12 @@ def test_append_full_size_c2_sampled(gpu):
     torch.cuda.synchronize()
     assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
     assert bool(torch.isfinite(a_gpu).all()) and bool(torch.isfinite(a_cpu).all())
+    # a second run gives the same bits (a stage read before its loads had landed would show here or in the sums below)
+    ow2, lw2, op2, lp2 = (torch.full_like(x, float("nan")) for x in (ow, lw, op, lp))
+    hgca.append_attn(shape, qd, win, True, ow2, lw2, ws)
+    hgca.append_attn(shape, qd, pool, False, op2, lp2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ow2, ow) and torch.equal(lw2, lw) and torch.equal(op2, op) and torch.equal(lp2, lp)
     # every averaged weight row sums to 1 over what is visible (holds at any size)
     assert float((a_gpu.sum(-1) - 1).abs().max()) <= 1e-4 and float((a_cpu.sum(-1) - 1).abs().max()) <= 1e-4
 
