@@ -242,6 +242,7 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 
     if (MODE == kScores || (MODE == kDense && a.scores)) store_split_scores<NH>(a, s_p, bh0, t0, nt);
     if (MODE == kScores) return;
+    if (MODE == kDense && a.scores) __syncthreads();   // the softmax below overwrites the scores other waves are still storing
 
     split_softmax<NH>(s_p, s_m, s_l, nt);
     __syncthreads();
@@ -487,7 +488,10 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
     const RowMap rows = make_row_map<false, kBlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nt, nullptr);
     mfma_scores<D, G, kMaxChunk>(a, reinterpret_cast<uint4 *>(s_buf), s_p, bh0, nt, rows);
     __syncthreads();
-    if (a.scores) store_split_scores<G>(a, s_p, bh0, t0, nt);
+    if (a.scores) {                              // uniform over the workgroup
+        store_split_scores<G>(a, s_p, bh0, t0, nt);
+        __syncthreads();                         // the softmax below overwrites the scores other waves are still storing
+    }
     split_softmax<G>(s_p, s_m, s_l, nt);
     __syncthreads();
     if (kPvMfma)                                 // V stage first, reduction area behind it
