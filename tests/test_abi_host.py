@@ -343,3 +343,13 @@ def test_ctx_compact_rejects_bad_arguments(hg):
     assert compact(cnt=C2) == hg.ERR_INVALID_ARG
     assert compact(p=_view(hg, cap=256, k=None)) == hg.ERR_INVALID_ARG
     assert compact(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), idx=None, cnt=None) == hg.OK
+
+
+def test_header_is_valid_c99():
+    """include/hgca.h is a C header: a C99 compiler accepts it on its own."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = '#include "hgca.h"\nint main(void) { return sizeof(hgca_shape) + sizeof(hgca_kv_view) + sizeof(hgca_cache_state) > 0 ? 0 : 1; }\n'
+    run = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c",
+                          "-I" + os.path.join(root, "include"), "-"], input=src, capture_output=True, text=True)
+    assert run.returncode == 0, run.stderr
