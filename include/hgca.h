@@ -409,7 +409,8 @@ int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool,
  * exact result for unit-variance V, lse unaffected), a third fewer matrix
  * instructions.  Without it they enter as a high and a low bf16 part and O
  * keeps fp32-level accuracy (~1e-6).
- * Other bits are rejected.  o_out is fp32 [B, N, Hq, d], lse_out fp32
+ * Other bits are rejected.  shape.sm_scale must be positive and finite for the
+ * append entry points.  o_out is fp32 [B, N, Hq, d], lse_out fp32
  * [B, N, Hq]; a query that sees nothing gives O = 0, lse = -inf.  ws needs
  * hgca_append_workspace_bytes(shape, n_q, tier->cap) bytes.  n_q <= 4096. */
 enum {

@@ -692,6 +692,8 @@ int check_append(const hgca_shape *shape, const void *q, int32_t n_q, const hgca
     if (rc != HGCA_OK) return rc;
     if (n_q < 0 || n_q > 4096) return HGCA_ERR_INVALID_ARG;
     if (shape->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;      // the MFMA path is bf16 only
+    // the kernels keep the running maximum on the raw scores and apply the scale inside the exponent
+    if (!(shape->sm_scale > 0.f) || !(shape->sm_scale < 3.0e38f)) return HGCA_ERR_INVALID_ARG;
     if ((rc = check_view(shape, tier, need_v)) != HGCA_OK) return rc;
     if (shape->batch > 0 && n_q > 0 && (!q || !aligned16(q))) return HGCA_ERR_INVALID_ARG;
     return HGCA_OK;

@@ -242,6 +242,9 @@ def test_append_entry_points_reject_bad_arguments(hg):
     def attn(shape=sh, q=FAKE, n_q=4, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40, flags=1):
         return L.hgca_append_attn(byref(shape), q, n_q, byref(view), flags, o, lse, ws, ws_bytes, None)
     assert attn(q=None) == hg.ERR_INVALID_ARG
+    assert attn(shape=hg.Shape(hg.BF16, 2, 8, 2, 128, 0.0)) == hg.ERR_INVALID_ARG      # scale must be > 0 here
+    assert attn(shape=hg.Shape(hg.BF16, 2, 8, 2, 128, -0.1)) == hg.ERR_INVALID_ARG
+    assert attn(shape=hg.Shape(hg.BF16, 2, 8, 2, 128, float("inf"))) == hg.ERR_INVALID_ARG
     assert attn(flags=4) == hg.ERR_INVALID_ARG                  # an unknown flag bit
     assert attn(flags=-1) == hg.ERR_INVALID_ARG
     assert attn(q=ODD) == hg.ERR_INVALID_ARG
