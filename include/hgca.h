@@ -151,7 +151,8 @@ int hgca_select_topk(const hgca_shape *shape, const float *scores,
  * cpu_attention): softmax attention of query head (b,h) over pool rows
  * idx[b,h,0 .. cnt[b,h]).  Entries at or beyond cnt[b,h] are ignored; the
  * listed positions must be valid and distinct (a repeated position is counted
- * twice).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32); both NULL defers
+ * twice; a position outside [0, pool->cap) is read as the nearest one inside,
+ * so the result is meaningless but nothing outside the tier is touched).  Writes o_out [B,Hq,d] and lse_out [B,Hq] (fp32); both NULL defers
  * the result (see hgca_lse_merge_splits).
  * sel_scores (optional, NULL for none) is fp32 [B,Hq,k_max] holding the score
  * s_j = sm_scale * <q, k_j> of every listed entry for THIS q, as

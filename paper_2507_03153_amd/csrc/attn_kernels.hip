@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(KernelArgs a)
 
     const int64_t bh0 = (int64_t)b * Hq + h0;
     const int64_t list = PER_HEAD_LIST ? bh0 : (int64_t)b * Hkv + unit;      // row of idx / cnt
-    const int n = GATHER ? min(a.cnt[list], a.k_max) : tier_len(a.kv, b);
+    const int n = GATHER ? (a.kv.cap > 0 ? min(a.cnt[list], a.k_max) : 0) : tier_len(a.kv, b);
     const int t0 = split * a.chunk;
 
     if (t0 >= n) {                               // empty split (uniform over the workgroup)

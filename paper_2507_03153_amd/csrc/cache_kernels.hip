@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kRowBlock) void ctx_compact_kernel(CtxCompactArgs a
 
     const int h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * a.sh.n_q_heads + h;
-    const int n = min(max(a.cnt[bh], 0), a.k_max);
+    const int n = a.kv.cap > 0 ? min(max(a.cnt[bh], 0), a.k_max) : 0;
     const int first = a.first_row ? min(max(a.first_row[bh], 0), a.ctx_cap) : 0;
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.cnt_out) a.cnt_out[bh] = (int32_t)min((int64_t)first + n, (int64_t)a.ctx_cap);
     const int t0 = blockIdx.x * kCtxRows;

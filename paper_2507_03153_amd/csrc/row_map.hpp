@@ -49,7 +49,9 @@ __device__ __forceinline__ RowMap make_row_map(uint32_t *s_row, const KvDev &kv,
     const int32_t *blocks = nullptr;             // the sequence's table row, from the tier's first block on
     if (kv.block_table) blocks = kv.block_table + (int64_t)b * kv.max_blocks + (kv.first_block ? kv.first_block[b] : 0);
     for (int j = threadIdx.x; j < nt; j += BLOCK) {
-        const int32_t tok = GATHER ? listed[j] : t0 + j;
+        // a listed position outside the tier is clamped into it: the result is then meaningless, but no address
+        // outside the tier's buffers is formed (callers of a gather make sure that the tier is not empty)
+        const int32_t tok = GATHER ? min(max(listed[j], 0), kv.cap - 1) : t0 + j;
         uint32_t row;
         if (blocks) {
             const int32_t blk = blocks[tok / kv.block_size];

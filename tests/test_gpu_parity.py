@@ -448,3 +448,37 @@ def test_graph_replay_of_the_whole_step_equals_eager(gpu, oracle):
     o_ref, l_ref, _, _ = oracle.hybrid_step(wl.make_layer(cfg, 0).q, otier(oracle, wl.make_layer(cfg, 0).window),
                                             otier(oracle, wl.make_layer(cfg, 0).pool), L.k, L.k_max, cfg.scale)
     assert_partial("graph replay vs oracle (query of layer 0)", graphed.o, graphed.lse, o_ref, l_ref, TOL["bf16"])
+
+
+def test_positions_outside_the_tier_are_clamped_into_it(gpu, oracle):
+    """A listed position outside [0, cap) is read as the nearest one inside (no address outside the tier is
+    formed): the result equals attention over the clamped list."""
+    torch, hgca, runner = gpu
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=64, P=777, k=40)
+    say(f"\n[case] positions outside the tier, P={cfg.P}")
+    L = wl.make_layer(cfg)
+    tp = otier(oracle, L.pool)
+    D = runner.DeviceLayer.upload(L)
+    idx, cnt = oracle.select(L.q, tp, L.k, L.k_max, L.scale)
+    bad = idx.copy()
+    bad[0, 0, 0], bad[0, 1, 3], bad[1, 7, 39], bad[1, 2, 5] = -5, 2 ** 30, cfg.P, np.iinfo(np.int32).min
+    clamped = np.clip(bad, 0, cfg.P - 1)
+    clamped[idx < 0] = -1                                       # the padding beyond cnt stays as it was
+    step = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max)
+    dev = D.q.device
+    hgca.sparse_attn(D.shape, D.q, D.pool, torch.from_numpy(bad).to(dev), torch.from_numpy(cnt).to(dev), L.k_max,
+                     step.o_s, step.lse_s, step.ws_sparse)
+    torch.cuda.synchronize()
+    o_ref, l_ref = oracle.attend_indexed(L.q, tp, clamped, cnt, L.scale)
+    assert_partial("sparse on clamped positions", step.o_s, step.lse_s, o_ref, l_ref, min(TOL[cfg.dtype], TIGHT[cfg.dtype]))
+    # the copy into per-head storage takes the same rows
+    k_ctx = torch.zeros(cfg.B, cfg.Hq, L.k_max, cfg.d, dtype=D.q.dtype, device=dev)
+    v_ctx = torch.zeros_like(k_ctx)
+    hgca.ctx_compact(D.shape, D.pool, torch.from_numpy(bad).to(dev), torch.from_numpy(cnt).to(dev), L.k_max, k_ctx, v_ctx,
+                     L.k_max)
+    torch.cuda.synchronize()
+    G = cfg.Hq // cfg.Hkv
+    want = D.pool.k[0, 0 // G, int(clamped[0, 0, 0])]
+    assert torch.equal(k_ctx[0, 0, 0], want)
+    want = D.pool.k[1, 7 // G, int(clamped[1, 7, 39])]
+    assert torch.equal(k_ctx[1, 7, 39], want)
