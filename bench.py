@@ -284,9 +284,10 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
 
     B, Hq, Hkv, d, W, P = cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.W, cfg.P
     win_blocks, pool_blocks = W // block_size, P // block_size
-    spare = 2 * (n_steps // block_size) + 4                    # blocks for every step run below
+    runs = 3                                                   # timed runs below, each with a block of warm-up
+    spare = runs * (n_steps // block_size + 1) + 4             # blocks for every step run below
     C = cache.LayerCache(L.q.dtype, B, Hq, Hkv, d, block_size, win_blocks, pool_blocks + win_blocks + spare,
-                         k_max + n_steps + block_size, float(L.shape.sm_scale), dev)
+                         k_max + runs * (n_steps + block_size), float(L.shape.sm_scale), dev)
 
     def to_blocks(dst, src, first):                            # [B,Hkv,n,d] -> blocks first.. of every sequence
         n_blk = src.shape[2] // block_size
@@ -305,25 +306,29 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
     v_in = L.window.v[:, :, W - 1].contiguous()
     stream = torch.cuda.current_stream()
 
-    def run(n):
-        for _ in range(n):
-            C.decode_step(L.q, k_in, v_in, 0.3, 1.0)
-    run(block_size)                                            # warm-up: one block of steps, one eviction
-    torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_wall = time.perf_counter()
-    e0.record(stream)
-    run(n_steps)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t_wall) * 1e3 / n_steps
-    eager_ms = max(e0.elapsed_time(e1) / n_steps, wall)
+
+    def eager(one_call: bool) -> float:
+        def run(n):
+            for _ in range(n):
+                C.decode_step(L.q, k_in, v_in, 0.3, 1.0, one_call=one_call)
+        run(block_size)                                        # warm-up: one block of steps, one eviction
+        torch.cuda.synchronize()
+        t_wall = time.perf_counter()
+        e0.record(stream)
+        run(n_steps)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t_wall) * 1e3 / n_steps
+        return max(e0.elapsed_time(e1) / n_steps, wall)
+    eager_ms = eager(True)                                     # hgca_managed_decode_step: one call per step
+    separate_ms = eager(False)                                 # the five entry points it stands for
 
     # the same step captured once in a HIP graph (every decision of the step is taken on the device, so the
-    # captured launch sequence is valid for every step) and replayed: removes the host cost of ~10 launches
+    # captured launch sequence is valid for every step) and replayed: removes the host cost of the launches
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        C.decode_step(L.q, k_in, v_in, 0.3, 1.0)
+        C.decode_step(L.q, k_in, v_in, 0.3, 1.0, one_call=True)
     for _ in range(block_size - 1):                            # the capture ran no step; finish a block of warm-up
         graph.replay()
     torch.cuda.synchronize()
@@ -340,10 +345,14 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
     kept = C.ctx_cnt.float().mean().item()
     elem = 2 if L.q.dtype == torch.bfloat16 else 4
     moved = 2 * B * Hkv * (W - block_size // 2) * d * elem + 2 * B * Hq * kept * d * elem + 6 * 4 * B * Hq * W
-    return {"ms_per_step": ms, "layer_steps_per_s": 1e3 / ms, "graph_replay_ms_per_step": graph_ms, "steps": n_steps, "evictions": n_steps // block_size,
+    return {"ms_per_step": ms, "layer_steps_per_s": 1e3 / ms, "graph_replay_ms_per_step": graph_ms,
+            "separate_calls_ms_per_step": separate_ms, "steps": n_steps, "evictions": n_steps // block_size,
             "block_size": block_size, "salient_per_head": kept, "cache_status": status,
             "bytes_per_step": int(moved), "hbm_frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "calls_per_step": "kv_append, dense_window_attn_maw, sparse_attn (deferred), lse_merge_splits, kv_evict"}
+            "calls_per_step": "hgca_managed_decode_step (insert, window splits with scores, gather over the salient "
+                              "lists, one fold, weights + moving average, eviction: 6 kernels)",
+            "separate_calls": "kv_append, dense_window_attn_maw, sparse_attn (deferred), lse_merge_splits, kv_evict "
+                              "(7 kernels)"}
 
 
 def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20) -> dict:

@@ -338,7 +338,8 @@ typedef struct {
     int32_t       *ctx_cnt;             /* [B, Hq] (rw) their number                                */
     float         *a_evicted;           /* optional [B, Hq, pool_cap] (rw): moving average of every */
                                         /* evicted entry at its pool position; NULL to skip         */
-    int32_t       *plan;                /* [B, 4] scratch of hgca_kv_evict                          */
+    int32_t       *plan;                /* [B, 4] (rw) scratch of hgca_kv_evict: zero before the    */
+                                        /* first call, left with [.,3] = 0 by every call            */
     int32_t       *status;              /* [1] (rw) sticky HGCA_CACHE_* bits, 0 = consistent        */
     int32_t block_size;                 /* tokens per block, a multiple of 16                       */
     int32_t max_blocks;                 /* row length of block_table                                */
@@ -374,6 +375,29 @@ int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache,
  * hgca_maw_update of the step.  Sequences below l_max are left untouched. */
 int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
                   double beta, void *hip_stream);
+
+/* One decode step over the managed cache in one call, in the paper's order:
+ * Alg. 2, decode branch (KV_gpu' = concat(KV_gpu, KV_in); gpu_attention over
+ * the window, which returns A_gpu; cpu_attention over each head's salient
+ * entries KV_ctx; merge_state), then Alg. 1 (A_maw <- (1 - alpha) A_maw + alpha
+ * A_gpu, the inserted token taking its first observed weight; eviction and
+ * sparsification with beta where a window has reached l_max).  The same
+ * results as hgca_kv_append, hgca_dense_window_attn_maw, hgca_sparse_attn on
+ * (ctx_idx, ctx_cnt), hgca_lse_merge_splits and hgca_kv_evict in that order,
+ * with two launches fewer (the window's own lse comes out of the fold of all
+ * split partials).  q is [B,Hq,d], k_in / v_in [B,Hkv,d]; `active` (device [B]
+ * or NULL) as for hgca_kv_append; a_gpu (device fp32 [B,Hq,win_blocks *
+ * block_size], required) receives A_gpu; o_out [B,Hq,d] in o_dtype, lse_out
+ * [B,Hq] optional.  ws_dense needs hgca_workspace_bytes(shape, win_blocks *
+ * block_size, 0, 0), ws_sparse hgca_workspace_bytes(shape, 0, 0, k_max);
+ * different buffers.  Every decision is taken on the device: the launch
+ * sequence is the same every step. */
+int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *cache,
+                             const void *q, const void *k_in, const void *v_in,
+                             const int32_t *active, float alpha, double beta,
+                             float *a_gpu, void *o_out, int32_t o_dtype, float *lse_out,
+                             void *ws_dense, size_t ws_dense_bytes,
+                             void *ws_sparse, size_t ws_sparse_bytes, void *hip_stream);
 
 /* KV_ctx of Alg. 1 (KV_ctx.add(KV_evict[ids]); Sec. 3.2.2): per head, the
  * salient entries held in contiguous storage, so that the sparse part reads a

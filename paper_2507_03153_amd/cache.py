@@ -83,7 +83,12 @@ class LayerCache:
             hgca.maw_update(self.shape, self.a_maw, self.a_gpu, self.win_lens, self.win_cap, n_new, alpha)
         hgca.kv_evict(self.shape, self.state, beta)
 
-    def decode_step(self, q, k_in, v_in, alpha: float, beta: float, fused_maw: bool = True) -> None:
+    def decode_step(self, q, k_in, v_in, alpha: float, beta: float, fused_maw: bool = True,
+                    one_call: bool = False) -> None:
+        if one_call:
+            hgca.managed_decode_step(self.shape, self.state, q, k_in, v_in, alpha, beta, self.a_gpu, self.o, self.lse,
+                                     self.ws_dense, self.ws_sparse)
+            return
         self.append(k_in, v_in)
         self.attend(q, alpha if fused_maw else None)
         self.manage(alpha, beta, maw_done=fused_maw)

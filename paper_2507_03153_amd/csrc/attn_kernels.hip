@@ -509,7 +509,7 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
 // (the fusion is associative).  Thread (sg, c4) sums the splits sg, sg+SG, ... of four adjacent columns;
 // the SG groups are then added through LDS.
 template <int D, bool OUT_BF16>
-__global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse)
+__global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse, float *lse_p)
 {
     constexpr int C4 = D / 4;                    // threads across the columns (one float4 each)
     constexpr int SG = kBlock / C4;              // split groups
@@ -566,6 +566,14 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, Partials q,
             *reinterpret_cast<float4 *>(reinterpret_cast<float *>(o) + row * D + 4 * tid) = make_float4(r[0], r[1], r[2], r[3]);
         }
         if (tid == 0 && lse) lse[row] = (M != -INFINITY) ? M + logf(Lt) : -INFINITY;
+    }
+    // log-sum-exp of the first set alone (the window part of a step: its attention weights are normalised by it)
+    if (lse_p && tid == kBlock - 1) {
+        float Mp = -INFINITY, Lp = 0.f;
+        for (int s = 0; s < np; ++s) Mp = fmaxf(Mp, p.m[row * np + s]);
+        if (Mp != -INFINITY)
+            for (int s = 0; s < np; ++s) Lp = fmaf(p.l[row * np + s], expf(p.m[row * np + s] - Mp), Lp);
+        lse_p[row] = (Mp != -INFINITY) ? Mp + logf(Lp) : -INFINITY;
     }
 }
 
@@ -730,14 +738,14 @@ hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float
 }
 
 hipError_t launch_combine2(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
-                           float *lse, hipStream_t s)
+                           float *lse, hipStream_t s, float *lse_p)
 {
     if (n_rows == 0) return hipSuccess;
     const dim3 grid((unsigned)n_rows), block(kBlock);
-    if (head_dim == 64 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<64, false>), grid, block, s, p, q, o, lse);
-    else if (head_dim == 64 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<64, true>), grid, block, s, p, q, o, lse);
-    else if (head_dim == 128 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<128, false>), grid, block, s, p, q, o, lse);
-    else if (head_dim == 128 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<128, true>), grid, block, s, p, q, o, lse);
+    if (head_dim == 64 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<64, false>), grid, block, s, p, q, o, lse, lse_p);
+    else if (head_dim == 64 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<64, true>), grid, block, s, p, q, o, lse, lse_p);
+    else if (head_dim == 128 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<128, false>), grid, block, s, p, q, o, lse, lse_p);
+    else if (head_dim == 128 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<128, true>), grid, block, s, p, q, o, lse, lse_p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

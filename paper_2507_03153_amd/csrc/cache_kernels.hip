@@ -41,38 +41,24 @@ __global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const 
     if (threadIdx.x == 0) c.win_lens[b] = len + 1;
 }
 
-// One thread per sequence decides the eviction (Alg. 1: if l_cur >= l_max, the smallest whole number of
-// blocks that brings the window below l_max), records what the row kernel needs, and moves the boundary.
-__global__ void evict_plan_kernel(CacheDev c, int32_t batch)
-{
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= batch) return;
-    const int l_cur = c.win_lens[b], l_max = c.win_blocks * c.block_size;
-    int n_ev = 0;
-    if (l_cur >= l_max) n_ev = min((l_cur - l_max + c.block_size) / c.block_size, l_cur / c.block_size);
-    const int l_ev = n_ev * c.block_size;
-    const int p_len = c.pool_lens[b];
-    c.plan[4 * b + 0] = l_ev;
-    c.plan[4 * b + 1] = l_cur;
-    c.plan[4 * b + 2] = p_len;
-    c.plan[4 * b + 3] = 0;
-    if (n_ev == 0) return;
-    c.first_win_block[b] += n_ev;
-    c.win_lens[b] = l_cur - l_ev;
-    c.pool_lens[b] = p_len + l_ev;
-}
-
-// One workgroup per (sequence, query head) row of a sequence that evicts: the evicted entries whose moving
-// average exceeds beta / l_cur join the head's list of salient pool positions (appended in position order),
-// optionally the evicted averages are saved at their pool positions, and the row shifts down by l_evict.
-__global__ __launch_bounds__(kRowBlock) void evict_rows_kernel(CacheDev c, int32_t n_q_heads, double beta)
+// Eviction and sparsification of Alg. 1.  One workgroup per (sequence, query head) row.  Every workgroup of a
+// sequence takes the same decision from the same state (if l_cur >= l_max: evict the smallest whole number of
+// blocks that brings the window below l_max); for a sequence that evicts, the evicted entries whose moving average
+// exceeds beta / l_cur join the head's list of salient pool positions (appended in position order), optionally the
+// evicted averages are saved at their pool positions, and the row shifts down by l_evict.  The last workgroup of
+// the sequence to finish (an arrival counter in plan[4b + 3], left at zero) moves the boundary: by then every
+// workgroup of the sequence has read the state it is about to change.
+__global__ __launch_bounds__(kRowBlock) void evict_kernel(CacheDev c, int32_t n_q_heads, double beta)
 {
     __shared__ CompactShared s_compact;
     const int64_t row = blockIdx.x;
     const int b = (int)(row / n_q_heads), tid = threadIdx.x;
-    const int l_ev = c.plan[4 * b + 0];
-    if (l_ev == 0) return;
-    const int l_cur = c.plan[4 * b + 1], p_old = c.plan[4 * b + 2];
+    const int l_cur = c.win_lens[b], l_max = c.win_blocks * c.block_size;
+    int n_ev = 0;
+    if (l_cur >= l_max) n_ev = min((l_cur - l_max + c.block_size) / c.block_size, l_cur / c.block_size);
+    const int l_ev = n_ev * c.block_size;
+    if (l_ev == 0) return;                                     // the same for every workgroup of the sequence
+    const int p_old = c.pool_lens[b];
     const int win_cap = c.win_blocks * c.block_size;
     float *maw = c.a_maw + row * win_cap;
 
@@ -104,6 +90,20 @@ __global__ __launch_bounds__(kRowBlock) void evict_rows_kernel(CacheDev c, int32
         for (int e = 0; e < kPerThread; ++e) {
             const int j = t0 + e * kRowBlock + tid;
             if (j < l_cur) maw[j] = x[e];                      // entries [n_stay, l_cur) become 0
+        }
+    }
+
+    // every thread of this workgroup read the sequence's state before the barriers above
+    if (tid == 0) {
+        int32_t *arrived = c.plan + 4 * b + 3;
+        if (atomicAdd(arrived, 1) == n_q_heads - 1) {
+            *arrived = 0;
+            c.plan[4 * b + 0] = l_ev;                          // what was done, for whoever wants to look
+            c.plan[4 * b + 1] = l_cur;
+            c.plan[4 * b + 2] = p_old;
+            c.first_win_block[b] += n_ev;
+            c.win_lens[b] = l_cur - l_ev;
+            c.pool_lens[b] = p_old + l_ev;
         }
     }
 }
@@ -174,11 +174,7 @@ hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_i
 hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s)
 {
     if (batch == 0) return hipSuccess;
-    hipLaunchKernelGGL(evict_plan_kernel, dim3((batch + 63) / 64), dim3(64), 0, s, c, batch);
-    hipError_t rc = hipGetLastError();
-    if (rc != hipSuccess) return rc;
-    hipLaunchKernelGGL(evict_rows_kernel, dim3((unsigned)((int64_t)batch * n_q_heads)), dim3(kRowBlock), 0, s, c,
-                       n_q_heads, beta);
+    hipLaunchKernelGGL(evict_kernel, dim3((unsigned)((int64_t)batch * n_q_heads)), dim3(kRowBlock), 0, s, c, n_q_heads, beta);
     return hipGetLastError();
 }
 

@@ -103,9 +103,9 @@ int pick_chunk(int64_t n, int64_t units, int target, int max_chunk = kMaxChunk)
 
 int n_splits_for(int64_t n, int chunk) { return (int)((n + chunk - 1) / chunk); }
 
-// Workspace layout: [partials o | partials m | partials l | scores | scores of the kept entries].
+// Workspace layout: [partials o | partials m | partials l | one float per row | scores | scores of the kept entries].
 struct WsLayout {
-    size_t part_o, part_m, part_l, scores, sel, total;
+    size_t part_o, part_m, part_l, row_aux, scores, sel, total;
 };
 
 WsLayout layout(const hgca_shape *s, int64_t max_attn_tokens, int64_t max_pool)
@@ -117,6 +117,7 @@ WsLayout layout(const hgca_shape *s, int64_t max_attn_tokens, int64_t max_pool)
     w.part_o = at; at += align_up(rows * max_splits * s->head_dim * sizeof(float));
     w.part_m = at; at += align_up(rows * max_splits * sizeof(float));
     w.part_l = at; at += align_up(rows * max_splits * sizeof(float));
+    w.row_aux = at; at += align_up(rows * sizeof(float));
     w.scores = at; at += align_up(rows * (size_t)std::max<int64_t>(max_pool, 0) * sizeof(float));
     w.sel = at; at += max_pool > 0 ? align_up(rows * (size_t)std::max<int64_t>(max_attn_tokens, 0) * sizeof(float)) : 0;
     w.total = std::max<size_t>(at, kAlign);
@@ -619,6 +620,77 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache, double
     if (!(beta >= 0.0)) return HGCA_ERR_INVALID_ARG;
     if (shape->batch == 0) return HGCA_OK;
     return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, static_cast<hipStream_t>(hip_stream)));
+}
+
+int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *cache, const void *q, const void *k_in,
+                             const void *v_in, const int32_t *active, float alpha, double beta, float *a_gpu,
+                             void *o_out, int32_t o_dtype, float *lse_out, void *ws_dense, size_t ws_dense_bytes,
+                             void *ws_sparse, size_t ws_sparse_bytes, void *hip_stream)
+{
+    CacheDev c{};
+    int rc = check_cache(shape, cache, &c);
+    if (rc != HGCA_OK) return rc;
+    if (o_dtype != HGCA_F32 && o_dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
+    if (!(alpha >= 0.f && alpha <= 1.f) || !(beta >= 0.0)) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return HGCA_OK;
+    if (!q || !aligned16(q) || !k_in || !v_in || !aligned16(k_in) || !aligned16(v_in) || !a_gpu || !o_out ||
+        !aligned16(o_out))
+        return HGCA_ERR_INVALID_ARG;
+    // the two tiers as ranges of the sequence's block list
+    hgca_kv_view window{}, pool{};
+    window.k = pool.k = cache->k_blocks;
+    window.v = pool.v = cache->v_blocks;
+    window.block_table = pool.block_table = cache->block_table;
+    window.block_size = pool.block_size = cache->block_size;
+    window.max_blocks = pool.max_blocks = cache->max_blocks;
+    window.seq_lens = cache->win_lens;
+    window.first_block = cache->first_win_block;
+    window.cap = cache->win_blocks * cache->block_size;
+    pool.seq_lens = cache->pool_lens;
+    pool.cap = cache->pool_cap;
+    if ((rc = check_view(shape, &window, true)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, &pool, true)) != HGCA_OK) return rc;
+    const WsLayout wd = layout(shape, window.cap, 0);
+    const WsLayout wsp = layout(shape, cache->k_max, 0);
+    if (!ws_dense || ws_dense_bytes < wd.total || !aligned16(ws_dense)) return HGCA_ERR_WORKSPACE;
+    if (!ws_sparse || ws_sparse_bytes < wsp.total || !aligned16(ws_sparse) || ws_sparse == ws_dense) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
+
+    // Alg. 2: KV_gpu' = concat(KV_gpu, KV_in)
+    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, active, shape->batch, shape->n_kv_heads, row_bytes, s))) != HGCA_OK)
+        return rc;
+    // gpu_attention: split kernels of the window, leaving the scaled scores in a_gpu
+    AttnArgs da{};
+    da.sh = to_dev(shape);
+    da.q = q;
+    da.kv = to_dev(&window);
+    da.chunk = pick_chunk(window.cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
+    da.part = partials_at(ws_dense, wd, n_splits_for(window.cap, da.chunk));
+    da.raw_scores = a_gpu;
+    if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
+    // cpu_attention over KV_ctx: split kernels over each head's list of salient pool positions
+    AttnArgs ga{};
+    ga.sh = da.sh;
+    ga.q = q;
+    ga.kv = to_dev(&pool);
+    ga.idx = cache->ctx_idx;
+    ga.cnt = cache->ctx_cnt;
+    ga.k_max = cache->k_max;
+    ga.chunk = pick_chunk(cache->k_max, rows, HGCA_TARGET_WGS_SPARSE);
+    ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(cache->k_max, ga.chunk)));
+    if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
+    // merge_state over all split partials; the window's own lse comes out of the same fold
+    float *lse_w = reinterpret_cast<float *>(static_cast<char *>(ws_dense) + wd.row_aux);
+    if ((rc = from_hip(launch_combine2(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, s, lse_w))) != HGCA_OK)
+        return rc;
+    // A_gpu = e^{s - lse_g}; Alg. 1: A_maw <- (1 - alpha) A_maw + alpha A_gpu (the inserted token has no history)
+    if ((rc = from_hip(launch_window_weights(a_gpu, lse_w, window.seq_lens, rows, shape->n_q_heads, window.cap, c.a_maw, 1,
+                                             alpha, s))) != HGCA_OK)
+        return rc;
+    // Alg. 1: eviction and sparsification where a window is full
+    return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, s));
 }
 
 int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool, const int32_t *idx, const int32_t *cnt,

@@ -43,7 +43,7 @@ hipError_t launch_attn_partial_gather(int dtype, int head_dim, const AttnArgs &a
 hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float *o, float *lse, hipStream_t s);
 // Folds the splits of two partial sets (either may have n_splits == 0) into one result; o_dtype 0 fp32, 1 bf16.
 hipError_t launch_combine2(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
-                           float *lse, hipStream_t s);
+                           float *lse, hipStream_t s, float *lse_p = nullptr);   // lse_p: optional lse of set p alone
 
 hipError_t launch_merge(int head_dim, int64_t n_rows, const float *o_a, const float *lse_a, const float *o_b,
                         const float *lse_b, void *o_out, int o_dtype, float *lse_out, hipStream_t s);

@@ -25,7 +25,8 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
-           "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact")
+           "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact",
+           "hgca_managed_decode_step")
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -102,6 +103,9 @@ def lib() -> ctypes.CDLL:
         L.hgca_union_lists.argtypes = [ps, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.hgca_sparse_attn_grouped.restype = ctypes.c_int
         L.hgca_sparse_attn_grouped.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.hgca_managed_decode_step.restype = ctypes.c_int
+        L.hgca_managed_decode_step.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp, ctypes.c_float,
+                                               ctypes.c_double, vp, vp, i32, vp, vp, sz, vp, sz, vp]
         L.hgca_ctx_compact.restype = ctypes.c_int
         L.hgca_ctx_compact.argtypes = [ps, pk, vp, vp, i32, vp, vp, vp, i32, vp, vp]
         L.hgca_hybrid_decode_step.restype = ctypes.c_int
@@ -416,3 +420,15 @@ def ctx_compact(shape: Shape, pool: Tier, idx, cnt, k_max: int, k_ctx, v_ctx, ct
     _check(lib().hgca_ctx_compact(ctypes.byref(shape), ctypes.byref(kv), _ptr(idx), _ptr(cnt), int(k_max),
                                   _ptr(first_row), _ptr(k_ctx), _ptr(v_ctx), int(ctx_cap), _ptr(cnt_out),
                                   _stream(stream)), "hgca_ctx_compact")
+
+
+def managed_decode_step(shape: Shape, state: "CacheState", q, k_in, v_in, alpha: float, beta: float, a_gpu, o_out,
+                        lse_out, ws_dense, ws_sparse, active=None, stream=None) -> None:
+    """One decode step over the managed cache (insert, attend, merge, moving average, eviction) in one call."""
+    for t in (q, k_in, v_in, a_gpu, o_out, ws_dense, ws_sparse) + tuple(x for x in (lse_out, active) if x is not None):
+        _require_gpu(t)
+    _check(lib().hgca_managed_decode_step(ctypes.byref(shape), ctypes.byref(state), _ptr(q), _ptr(k_in), _ptr(v_in),
+                                          _ptr(active), float(alpha), float(beta), _ptr(a_gpu), _ptr(o_out),
+                                          _dtype_code(o_out), _ptr(lse_out), _ptr(ws_dense), ws_dense.numel(),
+                                          _ptr(ws_sparse), ws_sparse.numel(), _stream(stream)),
+           "hgca_managed_decode_step")

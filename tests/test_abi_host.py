@@ -356,3 +356,37 @@ def test_header_is_valid_c99():
     run = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c",
                           "-I" + os.path.join(root, "include"), "-"], input=src, capture_output=True, text=True)
     assert run.returncode == 0, run.stderr
+
+
+def test_managed_decode_step_rejects_bad_arguments(hg):
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    WS2, A = ctypes.c_void_p(0x40000), ctypes.c_void_p(0x50000)
+
+    def state(**kw):
+        f = dict(k_blocks=0x10000, v_blocks=0x20000, block_table=0x30000, first_win_block=0x30100, win_lens=0x30200,
+                 pool_lens=0x30300, a_maw=0x30400, ctx_idx=0x30500, ctx_cnt=0x30600, a_evicted=None, plan=0x30700,
+                 status=0x30800, block_size=16, max_blocks=8, win_blocks=2, k_max=32, pool_cap=128)
+        f.update(kw)
+        return hg.CacheState(**f)
+
+    def step(st=None, shape=sh, q=FAKE, k=FAKE, v=FAKE, alpha=0.3, beta=1.0, a=A, o=FAKE, o_dtype=0, wd=FAKE,
+             wd_bytes=1 << 40, wsp=WS2, wsp_bytes=1 << 40):
+        st = st or state()
+        return hg.lib().hgca_managed_decode_step(ctypes.byref(shape), ctypes.byref(st), q, k, v, None, alpha, beta, a, o,
+                                                 o_dtype, None, wd, wd_bytes, wsp, wsp_bytes, None)
+
+    assert step(st=state(block_size=24)) == hg.ERR_UNSUPPORTED
+    assert step(st=state(win_lens=None)) == hg.ERR_INVALID_ARG
+    assert step(q=None) == hg.ERR_INVALID_ARG
+    assert step(k=None) == hg.ERR_INVALID_ARG
+    assert step(v=ODD) == hg.ERR_INVALID_ARG
+    assert step(a=None) == hg.ERR_INVALID_ARG
+    assert step(o=None) == hg.ERR_INVALID_ARG
+    assert step(o_dtype=9) == hg.ERR_UNSUPPORTED
+    assert step(alpha=1.5) == hg.ERR_INVALID_ARG
+    assert step(beta=-1.0) == hg.ERR_INVALID_ARG
+    assert step(wd=None) == hg.ERR_WORKSPACE
+    assert step(wsp=FAKE) == hg.ERR_WORKSPACE                  # one buffer for both parts
+    assert step(wd_bytes=hg.workspace_bytes(sh, 32, 0, 0) - 1) == hg.ERR_WORKSPACE
+    assert step(wsp_bytes=hg.workspace_bytes(sh, 0, 0, 32) - 1) == hg.ERR_WORKSPACE
+    assert step(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), q=None, o=None, a=None) == hg.OK

@@ -45,12 +45,12 @@ def make_tokens(seed, T, B, Hq, Hkv, d, boost=3.0):
 
 
 def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, prefill, steps, alpha, beta, seed,
-             expect_list_full=False, fused_tail=True, fused_maw=True):
+             expect_list_full=False, fused_tail=True, fused_maw=True, one_call=False):
     torch, hgca, runner, cache = gpu
     dev = "cuda:0"
     T = max(prefill) + steps
     say(f"\n[case] decode loop B={B} Hq={Hq} Hkv={Hkv} d={d} block={block_size} l_max={win_blocks * block_size} "
-        f"prefill={prefill} steps={steps} alpha={alpha} beta={beta} k_max={k_max}")
+        f"prefill={prefill} steps={steps} alpha={alpha} beta={beta} k_max={k_max} one_call={one_call}")
     qb, kb, vb = make_tokens(seed, T, B, Hq, Hkv, d)
     qf, kf, vf = (wl.bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
     scale = 1.0 / np.sqrt(d)
@@ -76,7 +76,7 @@ def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, pref
     for s in range(steps):
         t = max(prefill) + s
         C.decode_step(runner._to_gpu(qb[t], dev), runner._to_gpu(kb[t], dev), runner._to_gpu(vb[t], dev), alpha, beta,
-                      fused_maw=fused_maw)
+                      fused_maw=fused_maw, one_call=one_call)
         torch.cuda.synchronize()
         o_g, l_g = C.o.double().cpu().numpy(), C.lse.double().cpu().numpy()
         cnt_g, idx_g = C.ctx_cnt.cpu().numpy(), C.ctx_idx.cpu().numpy()
@@ -139,6 +139,16 @@ def test_decode_loop_ragged_windows_gqa4(gpu):
     assert kept.min() > 0 and np.all(kept.max(axis=1) < pool)    # beta = 1 keeps some entries, not all
 
 
+def test_decode_loop_in_one_call_per_step(gpu):
+    """The same loop through hgca_managed_decode_step: one library call per decode step."""
+    C, mgr, status = run_loop(gpu, B=3, Hq=8, Hkv=2, d=128, block_size=16, win_blocks=4, max_blocks=24, k_max=384,
+                              prefill=(0, 37, 63), steps=260, alpha=0.3, beta=1.0, seed=11, one_call=True)
+    assert status == 0
+    _, _, status = run_loop(gpu, B=2, Hq=4, Hkv=4, d=64, block_size=32, win_blocks=3, max_blocks=8, k_max=256,
+                            prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12, one_call=True)
+    assert status == 0
+
+
 def test_decode_loop_mha_head_dim_64_blocks_of_32(gpu):
     _, _, status = run_loop(gpu, B=2, Hq=4, Hkv=4, d=64, block_size=32, win_blocks=3, max_blocks=8, k_max=256,
                             prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12, fused_tail=False,
@@ -155,6 +165,10 @@ def test_decode_loop_at_the_benchmark_window_size(gpu):
                             seed=14)
     assert status == 0
     assert int(C.pool_lens.max()) == 32
+    C, _, status = run_loop(gpu, B=8, Hq=32, Hkv=8, d=128, block_size=16, win_blocks=256, max_blocks=264, k_max=64,
+                            prefill=(4090, 4090, 4000, 4095, 4090, 3, 4090, 4089), steps=24, alpha=0.3, beta=1.0,
+                            seed=14, one_call=True)
+    assert status == 0
 
 
 def test_beta_zero_keeps_everything_and_matches_full_attention(gpu):
@@ -192,7 +206,8 @@ def test_status_bits_for_full_list_full_window_and_full_context(gpu):
     assert int(C.pool_lens.cpu()[0]) + int(C.win_lens.cpu()[0]) == 64     # nothing written beyond the row
 
 
-def test_graph_replay_of_the_decode_step_equals_eager(gpu):
+@pytest.mark.parametrize("one_call", [False, True], ids=["separate_calls", "one_call"])
+def test_graph_replay_of_the_decode_step_equals_eager(gpu, one_call):
     """The decode step takes every decision on the device, so one captured launch sequence serves every step.
     Each replay is checked against an eager twin fed the same tokens, with eager work and synchronisation
     between the replays, across two evictions."""
@@ -209,14 +224,14 @@ def test_graph_replay_of_the_decode_step_equals_eager(gpu):
     with torch.cuda.stream(side):                                # capture on a non-default stream
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            G.decode_step(q, k, v, 0.3, 1.0)
+            G.decode_step(q, k, v, 0.3, 1.0, one_call=one_call)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     assert int(G.win_lens.cpu()[0]) == 0                         # capturing executes nothing
     for t in range(60):
         q.copy_(runner._to_gpu(qb[t], dev)); k.copy_(runner._to_gpu(kb[t], dev)); v.copy_(runner._to_gpu(vb[t], dev))
         graph.replay()
-        E.decode_step(q, k, v, 0.3, 1.0)
+        E.decode_step(q, k, v, 0.3, 1.0, one_call=one_call)
         torch.cuda.synchronize()
         for name in ("o", "lse", "a_maw", "ctx_idx", "ctx_cnt", "win_lens", "pool_lens", "first_win_block"):
             assert torch.equal(getattr(E, name), getattr(G, name)), f"step {t}: {name} differs"
