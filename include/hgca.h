@@ -385,16 +385,17 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
  * results as hgca_kv_append, hgca_dense_window_attn_maw, hgca_sparse_attn on
  * (ctx_idx, ctx_cnt), hgca_lse_merge_splits and hgca_kv_evict in that order,
  * with two launches fewer (the window's own lse comes out of the fold of all
- * split partials).  q is [B,Hq,d], k_in / v_in [B,Hkv,d]; `active` (device [B]
- * or NULL) as for hgca_kv_append; a_gpu (device fp32 [B,Hq,win_blocks *
- * block_size], required) receives A_gpu; o_out [B,Hq,d] in o_dtype, lse_out
+ * split partials).  q is [B,Hq,d], k_in / v_in [B,Hkv,d]: every sequence of the
+ * batch receives a token (batches in which some do not use the separate
+ * calls); a_gpu (device fp32 [B,Hq,win_blocks * block_size], required)
+ * receives A_gpu; o_out [B,Hq,d] in o_dtype, lse_out
  * [B,Hq] optional.  ws_dense needs hgca_workspace_bytes(shape, win_blocks *
  * block_size, 0, 0), ws_sparse hgca_workspace_bytes(shape, 0, 0, k_max);
  * different buffers.  Every decision is taken on the device: the launch
  * sequence is the same every step. */
 int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *cache,
                              const void *q, const void *k_in, const void *v_in,
-                             const int32_t *active, float alpha, double beta,
+                             float alpha, double beta,
                              float *a_gpu, void *o_out, int32_t o_dtype, float *lse_out,
                              void *ws_dense, size_t ws_dense_bytes,
                              void *ws_sparse, size_t ws_sparse_bytes, void *hip_stream);

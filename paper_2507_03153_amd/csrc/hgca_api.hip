@@ -623,7 +623,7 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache, double
 }
 
 int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *cache, const void *q, const void *k_in,
-                             const void *v_in, const int32_t *active, float alpha, double beta, float *a_gpu,
+                             const void *v_in, float alpha, double beta, float *a_gpu,
                              void *o_out, int32_t o_dtype, float *lse_out, void *ws_dense, size_t ws_dense_bytes,
                              void *ws_sparse, size_t ws_sparse_bytes, void *hip_stream)
 {
@@ -659,7 +659,7 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
 
     // Alg. 2: KV_gpu' = concat(KV_gpu, KV_in)
-    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, active, shape->batch, shape->n_kv_heads, row_bytes, s))) != HGCA_OK)
+    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, s))) != HGCA_OK)
         return rc;
     // gpu_attention: split kernels of the window, leaving the scaled scores in a_gpu
     AttnArgs da{};

@@ -104,7 +104,7 @@ def lib() -> ctypes.CDLL:
         L.hgca_sparse_attn_grouped.restype = ctypes.c_int
         L.hgca_sparse_attn_grouped.argtypes = [ps, vp, pk, vp, vp, i32, vp, vp, vp, sz, vp]
         L.hgca_managed_decode_step.restype = ctypes.c_int
-        L.hgca_managed_decode_step.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp, ctypes.c_float,
+        L.hgca_managed_decode_step.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, ctypes.c_float,
                                                ctypes.c_double, vp, vp, i32, vp, vp, sz, vp, sz, vp]
         L.hgca_ctx_compact.restype = ctypes.c_int
         L.hgca_ctx_compact.argtypes = [ps, pk, vp, vp, i32, vp, vp, vp, i32, vp, vp]
@@ -423,12 +423,12 @@ def ctx_compact(shape: Shape, pool: Tier, idx, cnt, k_max: int, k_ctx, v_ctx, ct
 
 
 def managed_decode_step(shape: Shape, state: "CacheState", q, k_in, v_in, alpha: float, beta: float, a_gpu, o_out,
-                        lse_out, ws_dense, ws_sparse, active=None, stream=None) -> None:
+                        lse_out, ws_dense, ws_sparse, stream=None) -> None:
     """One decode step over the managed cache (insert, attend, merge, moving average, eviction) in one call."""
-    for t in (q, k_in, v_in, a_gpu, o_out, ws_dense, ws_sparse) + tuple(x for x in (lse_out, active) if x is not None):
+    for t in (q, k_in, v_in, a_gpu, o_out, ws_dense, ws_sparse) + (() if lse_out is None else (lse_out,)):
         _require_gpu(t)
     _check(lib().hgca_managed_decode_step(ctypes.byref(shape), ctypes.byref(state), _ptr(q), _ptr(k_in), _ptr(v_in),
-                                          _ptr(active), float(alpha), float(beta), _ptr(a_gpu), _ptr(o_out),
+                                          float(alpha), float(beta), _ptr(a_gpu), _ptr(o_out),
                                           _dtype_code(o_out), _ptr(lse_out), _ptr(ws_dense), ws_dense.numel(),
                                           _ptr(ws_sparse), ws_sparse.numel(), _stream(stream)),
            "hgca_managed_decode_step")

@@ -372,7 +372,7 @@ def test_managed_decode_step_rejects_bad_arguments(hg):
     def step(st=None, shape=sh, q=FAKE, k=FAKE, v=FAKE, alpha=0.3, beta=1.0, a=A, o=FAKE, o_dtype=0, wd=FAKE,
              wd_bytes=1 << 40, wsp=WS2, wsp_bytes=1 << 40):
         st = st or state()
-        return hg.lib().hgca_managed_decode_step(ctypes.byref(shape), ctypes.byref(st), q, k, v, None, alpha, beta, a, o,
+        return hg.lib().hgca_managed_decode_step(ctypes.byref(shape), ctypes.byref(st), q, k, v, alpha, beta, a, o,
                                                  o_dtype, None, wd, wd_bytes, wsp, wsp_bytes, None)
 
     assert step(st=state(block_size=24)) == hg.ERR_UNSUPPORTED
