@@ -31,7 +31,7 @@ def gpu():
     return torch, hgca, runner
 
 
-def make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens):
+def make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens, lean=0.6):
     rng = np.random.default_rng(seed)
     bits = lambda *s: wl.f32_to_bf16_bits(rng.standard_normal(s).astype(np.float32))
     q, Kw, Vw, Kp, Vp = bits(B, N, Hq, d), bits(B, Hkv, W, d), bits(B, Hkv, W, d), bits(B, Hkv, max(P, 1), d), \
@@ -41,7 +41,7 @@ def make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens):
     for b in range(B):
         for kvh in range(Hkv):
             for j in range(0, P, 37):
-                kf = wl.bf16_bits_to_f32(Kp[b, kvh, j]) + 0.6 * qf[b, 0, kvh * (Hq // Hkv)]
+                kf = wl.bf16_bits_to_f32(Kp[b, kvh, j]) + lean * qf[b, 0, kvh * (Hq // Hkv)]
                 Kp[b, kvh, j] = wl.f32_to_bf16_bits(kf.astype(np.float32))
     w_lens = np.full(B, W, np.int32) if w_lens is None else np.asarray(w_lens, np.int32)
     p_lens = np.full(B, P, np.int32) if p_lens is None else np.asarray(p_lens, np.int32)
@@ -70,11 +70,11 @@ def to_paged(runner, hgca, torch, K, V, lens, cap, block, seed, dev):
     return hgca.Tier(g(kb), g(vb), cap, g(lens), g(table), block, g(first))
 
 
-def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=False):
+def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=False, lean=0.6):
     torch, hgca, runner = gpu
     dev = "cuda:0"
     say(f"\n[case] append N={N} B={B} Hq={Hq} Hkv={Hkv} d={d} W={W} P={P} w_lens={w_lens} p_lens={p_lens} paged={paged}")
-    q, Kw, Vw, wl_, Kp, Vp, pl_ = make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens)
+    q, Kw, Vw, wl_, Kp, Vp, pl_ = make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens, lean)
     scale = 1.0 / np.sqrt(d)
     f = lambda x: wl.bf16_bits_to_f32(x).astype(np.float64)
     o_g, l_g, A_g = ap.part_attention(f(q), f(Kw), f(Vw), wl_, scale, True)
@@ -156,6 +156,14 @@ def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=
 ], ids=["n5", "n32", "n40_two_blocks", "mha", "gqa8", "d64", "n1"])
 def test_append_shapes(gpu, kw):
     run_case(gpu, 31, **kw)
+
+
+@pytest.mark.parametrize("lean", [8.0, -8.0], ids=["scores_plus_90", "scores_minus_90"])
+def test_append_extreme_scores(gpu, lean):
+    """Every 37th pool key leans towards (away from) a query by 8 |q|: scaled scores of about +-90 for that query's
+    head.  The running maximum is kept on raw scores and the scale folded into the exponent; nothing may overflow,
+    and the merge of a pool part that outweighs the window by e^80 must stay finite and equal to the oracle's."""
+    run_case(gpu, 37, B=2, N=8, Hq=8, Hkv=2, d=128, W=200, P=1500, lean=lean)
 
 
 def test_append_ragged_and_degenerate_lengths(gpu):

@@ -482,3 +482,13 @@ def test_positions_outside_the_tier_are_clamped_into_it(gpu, oracle):
     assert torch.equal(k_ctx[0, 0, 0], want)
     want = D.pool.k[1, 7 // G, int(clamped[1, 7, 39])]
     assert torch.equal(k_ctx[1, 7, 39], want)
+
+
+@pytest.mark.parametrize("c", [40.0, 120.0, -120.0], ids=["scores_40", "scores_120", "scores_minus_120"])
+def test_extreme_scores_do_not_overflow_or_lose_a_part(gpu, oracle, c):
+    """Planted keys with scaled scores of about c: e^c overflows fp32 without the maximum subtraction, and with
+    c = 120 the window part's weight in the merge (about e^-110) underflows to nothing: the merged result must
+    then be the sparse part, finite.  With c = -120 the planted keys are the last ones anybody selects."""
+    run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=300, P=3001, k=300, plant_scale=c))
+    if abs(c) <= 40:      # fp32 inputs are held to 1e-5 absolute: one ulp of a score of 120 is already 8e-6
+        run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C1"], B=2, Hq=4, Hkv=2, d=64, W=100, P=700, k=40, plant_scale=c))
