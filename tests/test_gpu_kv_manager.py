@@ -45,13 +45,13 @@ def make_tokens(seed, T, B, Hq, Hkv, d, boost=3.0):
 
 
 def run_loop(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, prefill, steps, alpha, beta, seed,
-             expect_list_full=False, fused_tail=True, fused_maw=True, one_call=False):
+             expect_list_full=False, fused_tail=True, fused_maw=True, one_call=False, boost=3.0):
     torch, hgca, runner, cache = gpu
     dev = "cuda:0"
     T = max(prefill) + steps
     say(f"\n[case] decode loop B={B} Hq={Hq} Hkv={Hkv} d={d} block={block_size} l_max={win_blocks * block_size} "
         f"prefill={prefill} steps={steps} alpha={alpha} beta={beta} k_max={k_max} one_call={one_call}")
-    qb, kb, vb = make_tokens(seed, T, B, Hq, Hkv, d)
+    qb, kb, vb = make_tokens(seed, T, B, Hq, Hkv, d, boost)
     qf, kf, vf = (wl.bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
     scale = 1.0 / np.sqrt(d)
     C = cache.LayerCache(torch.bfloat16, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, scale, dev,
@@ -147,6 +147,16 @@ def test_decode_loop_in_one_call_per_step(gpu):
     _, _, status = run_loop(gpu, B=2, Hq=4, Hkv=4, d=64, block_size=32, win_blocks=3, max_blocks=8, k_max=256,
                             prefill=(5, 90), steps=150, alpha=0.5, beta=0.7, seed=12, one_call=True)
     assert status == 0
+
+
+def test_decode_loop_with_sharply_peaked_attention(gpu):
+    """Every 7th key leans ten times as far towards the queries' direction: scaled scores of about 70 against
+    N(0,1) for the rest, so the window weights are ~1/n_boosted on a few entries and underflow to zero on the others;
+    the moving averages, the thresholds and the merge must cope (one call per step and separate calls)."""
+    for one_call in (False, True):
+        _, _, status = run_loop(gpu, B=2, Hq=8, Hkv=2, d=128, block_size=16, win_blocks=3, max_blocks=16, k_max=256,
+                                prefill=(0, 40), steps=150, alpha=0.3, beta=1.0, seed=15, one_call=one_call, boost=30.0)
+        assert status == 0
 
 
 def test_decode_loop_mha_head_dim_64_blocks_of_32(gpu):
