@@ -10,7 +10,7 @@
  *      older, offloaded context, returning O and lse likewise;
  *   3. merge_state: O = (e^{lse_c} O_c + e^{lse_g} O_g) / (e^{lse_c} + e^{lse_g}).
  * Selection of the salient entries (Sec. 3.2.2) is per head.  In the paper the
- * older context lives in host memory and parts 2 runs on CPU cores; here both
+ * older context lives in host memory and part 2 runs on CPU cores; here both
  * tiers are HBM buffers on the same GPU and all parts are GPU kernels.
  *
  * Conventions that hold for every entry point
@@ -28,10 +28,11 @@
  *    (first_block = NULL counts as 0), slot t % block_size; the caller guarantees
  *    that the entries a sequence's valid tokens reach lie inside its table row.
  *    Two tiers may share one table: the window and the older pool of a sequence
- *    are then two ranges of the same list of blocks (see hgca_cache_state).  Valid tokens of sequence b are [0, seq_lens[b]) (all `cap`
- *    when seq_lens is NULL).  The order of tokens inside a tier does not matter
- *    to the result (softmax attention is a function of the key set).  A tier
- *    holds fewer than 2^32 rows (B*Hkv*cap, or n_blocks*Hkv*block_size).
+ *    are then two ranges of the same list of blocks (see hgca_cache_state).
+ *    Valid tokens of sequence b are [0, seq_lens[b]) (all `cap` when seq_lens is
+ *    NULL).  The order of tokens inside a tier does not matter to the result
+ *    (softmax attention is a function of the key set).  A tier holds fewer than
+ *    2^32 rows (B*Hkv*cap, or n_blocks*Hkv*block_size).
  *  - Scores are s_j = sm_scale * <q, k_j>; lse is the natural log of sum e^{s_j}.
  *  - Partial outputs are fp32: O [B, Hq, d], lse [B, Hq].  An empty set gives
  *    O = 0 and lse = -inf.
