@@ -58,8 +58,10 @@ struct SelShared {
     uint32_t scan_scratch[kSelWaves];
     float wave_min[kSelWaves], wave_max[kSelWaves];
     uint32_t wave_gt[kSelWaves], wave_eq[kSelWaves];
+    uint32_t wave_keq[kSelWaves];                // entries equal to the threshold that are kept, per wave (kCachedBins)
     uint32_t found[2];                           // selected bin / threshold bits, remaining rank
-    uint32_t n_cand;
+    uint32_t n_cand, n_uncertain;
+    __device__ __forceinline__ uint32_t *uncertain() { return hist + 2 * kMaxCand; }
 };
 
 // Exclusive prefix sum over the workgroup; *total receives the sum of all values.
@@ -144,6 +146,20 @@ __host__ __device__ inline int padded_length(int n) {
     return seg ? (n + seg - 1) / seg * seg : 0;
 }
 
+// How a row is held during the passes: re-read from memory every time, cached in LDS as it is (rows of up to
+// kMaxCacheFloats scores), or -- for rows up to four times as long -- cached as one byte per score: the upper 7 of
+// the 12 bits of its histogram bin, and one flag bit.  A score whose 7 bits differ from those of the threshold bin
+// lies above or below the threshold whatever its lower bits are.  The positions that share the threshold's 7 bits
+// (about 1 in 128) are listed and read again, all at once, to be counted, collected as candidates of the exact
+// ranking, or flagged as kept; the ranking flags the candidates it keeps; so the compaction reads bytes only, and
+// the kept scores (they are part of the output) are read again without anything waiting for them.
+enum RowMode { kFromMemory = 0, kCachedScores = 1, kCachedBins = 2 };
+constexpr int kCoarseShift = 5;                  // histogram bin -> 7 bits of the cached byte
+constexpr uint32_t kCoarseMask = 127u, kKeptFlag = 128u;
+constexpr int kMaxUncertain = 2 * kMaxCand;      // listed positions that share the threshold's 7 bits
+static_assert((kBins >> kCoarseShift) <= 128, "a coarse bin and the flag fit a byte");
+static_assert(kBins >= 2 * kMaxCand + kMaxUncertain, "that list lives behind the candidate lists");
+
 template <bool CACHED>
 struct Row {
     const float *sc, *cache;
@@ -162,10 +178,12 @@ struct Row {
     }
 };
 
-template <bool CACHED>
+template <int MODE>
 __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, float *cache, const float *sc,
                                            int32_t *out, int n, int k)
 {
+    constexpr bool CACHED = MODE == kCachedScores, BINS = MODE == kCachedBins;
+    uint8_t *cbin = reinterpret_cast<uint8_t *>(cache);         // kCachedBins: one byte per position of the padded row
     const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
     Row<CACHED> row;
     row.sc = sc;
@@ -181,7 +199,11 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     {
         constexpr int U = 8;                     // 16-byte loads in flight per lane
         const int n4 = padded / 4;
-        for (int base = 0; base < n4; base += kSelBlock * U) {
+        // kCachedBins: the range is taken from the first kSelBlock * U * 4 scores only.  Any range gives a correct
+        // selection (scores beyond it land in the end bins, and a threshold bin that turns out crowded is resolved
+        // exactly below); a range that misses part of the row only makes the end bins fuller.
+        const int n4_range = BINS ? min(n4, kSelBlock * U) : n4;
+        for (int base = 0; base < n4_range; base += kSelBlock * U) {
             float4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -209,8 +231,8 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     if (lane == 0) { sh.wave_min[w] = mn; sh.wave_max[w] = mx; }
     // the padding will be counted into bin 0: start that bin at minus the number of pads
     for (int i = tid; i < kBins; i += kSelBlock) sh.hist[i] = (i == 0) ? (uint32_t)(n - padded) : 0u;
-    if (tid == 0) sh.n_cand = 0;
-    if (tid < kSelWaves) { sh.wave_gt[tid] = 0; sh.wave_eq[tid] = 0; }
+    if (tid == 0) { sh.n_cand = 0; sh.n_uncertain = 0; }
+    if (tid < kSelWaves) { sh.wave_gt[tid] = 0; sh.wave_eq[tid] = 0; sh.wave_keq[tid] = 0; }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kSelWaves; ++i) { mn = fminf(mn, sh.wave_min[i]); mx = fmaxf(mx, sh.wave_max[i]); }
@@ -221,11 +243,16 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     // ---- pass 1: histogram, threshold bin --------------------------------------------------------------
 #pragma unroll 4
     for (int i = 0; i < steps; ++i) {
-        const float4 v = row.at(row.pos(i));
-        atomicAdd(&sh.hist[bin(v.x)], 1u);
-        atomicAdd(&sh.hist[bin(v.y)], 1u);
-        atomicAdd(&sh.hist[bin(v.z)], 1u);
-        atomicAdd(&sh.hist[bin(v.w)], 1u);
+        const int t = row.pos(i);
+        const float4 v = row.at(t);
+        const int b0 = bin(v.x), b1 = bin(v.y), b2 = bin(v.z), b3 = bin(v.w);
+        atomicAdd(&sh.hist[b0], 1u);
+        atomicAdd(&sh.hist[b1], 1u);
+        atomicAdd(&sh.hist[b2], 1u);
+        atomicAdd(&sh.hist[b3], 1u);
+        if (BINS)
+            *reinterpret_cast<uint32_t *>(cbin + t) = (uint32_t)(b0 >> kCoarseShift) | (uint32_t)(b1 >> kCoarseShift) << 8 |
+                                                      (uint32_t)(b2 >> kCoarseShift) << 16 | (uint32_t)(b3 >> kCoarseShift) << 24;
     }
     __syncthreads();
     locate_rank(sh, kBins, (uint32_t)k);
@@ -239,19 +266,64 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
     // topmost bin has no upper edge, padding and NaN fail both compares)
     const float edge_lo = (float)tb, edge_hi = (tb == kBins - 1) ? INFINITY : (float)(tb + 1);
     uint32_t above = 0;
-    for (int i = 0; i < steps; ++i) {
-        const int t = row.pos(i);
-        const float4 v = row.at(t);
-        const float s[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t tb7 = (uint32_t)tb >> kCoarseShift;          // kCachedBins: the 7 cached bits of the threshold bin
+    auto classify = [&](float sc_e, int pos) {                   // one score against the threshold bin
+        bool over, inside;
+        if (BINS) {
+            // the range of this mode may not cover the row, so scores beyond it sit in the end bins by clamping:
+            // the bin itself is compared, not the bin's edges
+            const int b = bin(sc_e);
+            over = b > tb;
+            inside = b == tb && pos < n;
+        } else {
+            const float x = bin.scaled(sc_e);
+            over = x >= edge_hi;
+            inside = x >= edge_lo && !over;
+        }
+        if (inside) {
+            const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
+            if (slot < (uint32_t)kMaxCand) { sh.cand_score()[slot] = sc_e; sh.cand_idx()[slot] = pos; }
+        }
+        return over;
+    };
+    bool use_bytes = BINS;                       // uniform over the workgroup
+    if (BINS) {
+        for (int i = 0; i < steps; ++i) {
+            const int t = row.pos(i);
+            const uint32_t bytes = *reinterpret_cast<const uint32_t *>(cbin + t);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float x = bin.scaled(s[e]);
-            const bool over = x >= edge_hi;
-            above += over;
-            if (x >= edge_lo && !over) {
-                const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
-                if (slot < (uint32_t)kMaxCand) { sh.cand_score()[slot] = s[e]; sh.cand_idx()[slot] = t + e; }
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t c = (bytes >> (8 * e)) & kCoarseMask;
+                above += c > tb7;
+                if (c == tb7) {
+                    const uint32_t slot = atomicAdd(&sh.n_uncertain, 1u);
+                    if (slot < (uint32_t)kMaxUncertain) sh.uncertain()[slot] = (uint32_t)(t + e);
+                }
             }
+        }
+        __syncthreads();
+        const uint32_t n_unc = sh.n_uncertain;
+        if (n_unc <= (uint32_t)kMaxUncertain) {
+            for (uint32_t j = tid; j < n_unc; j += kSelBlock) {  // one round trip to memory for all of them
+                const int pos = (int)sh.uncertain()[j];
+                if (pos >= n) continue;                          // padding
+                if (classify(sc[pos], pos)) {
+                    cbin[pos] |= (uint8_t)kKeptFlag;             // above the threshold bin after all: kept
+                    atomicAdd(&sh.wave_gt[pos / row.seg], 1u);
+                }
+            }
+        } else {                                 // too many to list: this row goes on as if it had no cache
+            use_bytes = false;
+            above = 0;
+        }
+    }
+    if (!use_bytes) {
+        for (int i = 0; i < steps; ++i) {
+            const int t = row.pos(i);
+            const float4 v = row.at(t);
+            const float s[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) above += classify(s[e], t + e);
         }
     }
     above = (uint32_t)wave_sum((float)above);    // exact: far below 2^24 per wave
@@ -263,10 +335,11 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         // exact rank of every candidate in (score descending, position ascending) order
         float my_s = 0.f;
         int32_t my_idx = 0;
+        uint32_t eq_lower = 0;                   // candidates with my score at lower positions
         if ((uint32_t)tid < n_cand) {
             my_s = sh.cand_score()[tid];
             my_idx = sh.cand_idx()[tid];
-            uint32_t gt = 0, eq_lower = 0;
+            uint32_t gt = 0;
             for (uint32_t j = 0; j < n_cand; ++j) {
                 const float sj = sh.cand_score()[j];
                 gt += sj > my_s;
@@ -281,11 +354,17 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         if ((uint32_t)tid < n_cand) {
             if (my_s > thr) atomicAdd(&sh.wave_gt[my_idx / row.seg], 1u);
             if (my_s == thr) atomicAdd(&sh.wave_eq[my_idx / row.seg], 1u);
+            if (use_bytes) {                     // the kept candidates are flagged: ties are settled here, by position
+                const bool kept_eq = my_s == thr && eq_lower < need_eq;
+                if (my_s > thr || kept_eq) cbin[my_idx] |= (uint8_t)kKeptFlag;
+                if (kept_eq) atomicAdd(&sh.wave_keq[my_idx / row.seg], 1u);
+            }
         }
         if (lane == 0) atomicAdd(&sh.wave_gt[w], above);
         __syncthreads();
     } else {
         // crowded bin: exact radix select (12 + 12 + 8 bits) over the keys of the bin's entries
+        use_bytes = false;                       // the bytes cannot tell the entries of one bin apart
         uint32_t prefix = 0, mask = 0;
         const int shifts[3] = {20, 8, 0}, widths[3] = {12, 12, 8};
 #pragma unroll
@@ -343,7 +422,34 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         all_eq += sh.wave_eq[i];
     }
     const bool pad_ties = thr == -INFINITY;      // only then could padding tie with the threshold
-    if (need_eq == all_eq && !pad_ties) {
+    bool sel_deferred = false;                   // the kept scores are fetched after the positions are all known
+    if (BINS && use_bytes && !pad_ties) {
+        // Every decision is in the bytes by now: kept iff flagged, or in a bin above the threshold's 7 bits.
+        // The kept scores are not at hand: fetching each inside this loop would put a round trip to memory into
+        // every step, so they are gathered afterwards from the list of kept positions, all at once.
+        sel_deferred = sel != nullptr;
+        uint32_t run = run_gt;
+        for (int i = 0; i < w; ++i) run += sh.wave_keq[i];
+        for (int i = 0; i < steps; ++i) {
+            const int t = row.pos(i);
+            const uint32_t bytes = *reinterpret_cast<const uint32_t *>(cbin + t);
+            bool keep[4];
+            uint32_t before = run;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t c = (bytes >> (8 * e)) & 255u;
+                keep[e] = (c & kKeptFlag) != 0 || (c & kCoarseMask) > tb7;
+                const unsigned long long m = __ballot(keep[e]);
+                before += lanes_below(m);
+                run += __popcll(m);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (keep[e]) dst[before] = t + e;
+                before += keep[e];
+            }
+        }
+    } else if (need_eq == all_eq && !pad_ties) {
         // Usual case: no tie is cut by the budget, so an entry is kept iff its score is >= T, and one
         // lane mask per score gives its place.
         uint32_t run = run_gt + run_eq;
@@ -406,10 +512,15 @@ __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, f
         } else {
             for (int j = tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
         }
+        if (sel_deferred)
+            for (int j = tid; j < k; j += kSelBlock) sel[j] = sc[sh.hist[j]];
+    } else if (sel_deferred) {
+        __syncthreads();                         // the positions written above by other threads of the workgroup
+        for (int j = tid; j < k; j += kSelBlock) sel[j] = sc[out[j]];
     }
 }
 
-__global__ __launch_bounds__(kSelBlock) void select_topk_kernel(SelectArgs a, int cache_floats)
+__global__ __launch_bounds__(kSelBlock) void select_topk_kernel(SelectArgs a, int cache_floats, int cache_bytes)
 {
     extern __shared__ __attribute__((aligned(16))) float s_cache[];
     __shared__ SelShared sh;
@@ -434,8 +545,9 @@ __global__ __launch_bounds__(kSelBlock) void select_topk_kernel(SelectArgs a, in
         }
         return;
     }
-    if (padded_length(n) <= cache_floats) select_row<true>(a, sh, s_cache, sc, out, n, k);
-    else select_row<false>(a, sh, s_cache, sc, out, n, k);
+    if (padded_length(n) <= cache_floats) select_row<kCachedScores>(a, sh, s_cache, sc, out, n, k);
+    else if (padded_length(n) <= cache_bytes) select_row<kCachedBins>(a, sh, s_cache, sc, out, n, k);
+    else select_row<kFromMemory>(a, sh, s_cache, sc, out, n, k);
 }
 
 }  // namespace
@@ -447,13 +559,16 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s)
     // rows whose padded length fits are cached in LDS (dynamic, beyond the 64 KiB default limit)
     // (the padded length grows with n in steps, so the capacity's padded length covers every row)
     const int cache_floats = padded_length(a.kv.cap) <= kMaxCacheFloats ? padded_length(a.kv.cap) : 0;
+    // longer rows, up to four times that: one byte per score in the same space
+    const int cache_bytes = cache_floats == 0 && padded_length(a.kv.cap) <= 4 * kMaxCacheFloats ? padded_length(a.kv.cap) : 0;
     // once per process (thread-safe static initialisation): lift the dynamic LDS limit of the kernel
     static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel),
                                                           hipFuncAttributeMaxDynamicSharedMemorySize,
                                                           kMaxCacheFloats * (int)sizeof(float));
     if (attr_rc != hipSuccess) return attr_rc;
     hipLaunchKernelGGL(select_topk_kernel, dim3((unsigned)rows), dim3(kSelBlock),
-                       (size_t)cache_floats * sizeof(float), s, a, cache_floats);
+                       cache_floats ? (size_t)cache_floats * sizeof(float) : (size_t)cache_bytes, s, a, cache_floats,
+                       cache_bytes);
     return hipGetLastError();
 }
 

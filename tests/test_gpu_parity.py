@@ -492,3 +492,72 @@ def test_extreme_scores_do_not_overflow_or_lose_a_part(gpu, oracle, c):
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], B=2, Hq=8, Hkv=2, W=300, P=3001, k=300, plant_scale=c))
     if abs(c) <= 40:      # fp32 inputs are held to 1e-5 absolute: one ulp of a score of 120 is already 8e-6
         run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C1"], B=2, Hq=4, Hkv=2, d=64, W=100, P=700, k=40, plant_scale=c))
+
+
+# ---------------------------------------------------------------- rows too long for the LDS score cache
+
+def _select_vs_oracle(gpu, oracle, L, cfg, label):
+    torch, hgca, runner = gpu
+    say(f"\n[case] {label}: P={cfg.P} k={cfg.k}")
+    D = runner.DeviceLayer.upload(L)
+    step = runner.HybridStep(D.shape, cfg.W, cfg.P, L.k_max)
+    step.sel_scores.fill_(float("nan"))
+    hgca.select_salient(D.shape, D.q, D.pool, D.k, L.k_max, step.idx, step.cnt, step.ws_sparse,
+                        sel_scores_out=step.sel_scores)
+    torch.cuda.synchronize()
+    idx = step.idx.cpu().numpy()[:, :, :L.k_max]
+    idx_ref, cnt_ref = oracle.select(L.q, otier(oracle, L.pool), L.k, L.k_max, L.scale)
+    assert np.array_equal(step.cnt.cpu().numpy(), cnt_ref)
+    return idx, idx_ref, step
+
+
+@pytest.mark.parametrize("P,k", [(40000, 5000), (140000, 3000)], ids=["bins_cached", "from_memory"])
+def test_long_rows_all_scores_equal(gpu, oracle, P, k):
+    """q = 0 on a row that is held as one byte per score (P = 40000) or re-read from memory (P = 140000): the kept
+    set must be the first k positions."""
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=1, Hq=4, Hkv=1, W=64, P=P, k=k)
+    L = wl.make_layer(cfg)
+    L.q[:] = 0
+    idx, idx_ref, _ = _select_vs_oracle(gpu, oracle, L, cfg, "long row, all scores equal")
+    assert np.all(idx == np.arange(k, dtype=np.int32)) and np.array_equal(idx, idx_ref)
+
+
+@pytest.mark.parametrize("P", [40000, 140000], ids=["bins_cached", "from_memory"])
+def test_long_rows_duplicates_at_the_threshold(gpu, oracle, P):
+    """Half of the keys are one and the same key whose score sits where the budget cuts: exactly the lowest
+    positions among them are kept, and the scores handed on are those of the kept entries."""
+    k = P // 3
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=1, Hq=4, Hkv=1, W=64, P=P, k=k, plant_frac=0.0)
+    L = wl.make_layer(cfg)
+    rng = np.random.default_rng(8)
+    dup = np.sort(rng.choice(P, P // 2, replace=False))
+    qf = wl.to_f32(L.q)[0]
+    row = 0.5 * (qf / np.linalg.norm(qf, axis=-1, keepdims=True)).sum(0)
+    L.pool.k[0, 0, dup] = wl.f32_to_bf16_bits(row.astype(np.float32))
+    idx, idx_ref, step = _select_vs_oracle(gpu, oracle, L, cfg, "long row, duplicates at the threshold")
+    scores = oracle.scores(L.q, otier(oracle, L.pool), L.scale)
+    sel = step.sel_scores.double().cpu().numpy()[:, :, :k]
+    for h in range(4):
+        s_dup = scores[0, h, dup[0]]
+        others = np.delete(scores[0, h], dup)
+        if np.min(np.abs(others - s_dup)) > BAND["bf16"] and (others > s_dup).sum() < k < (others > s_dup).sum() + len(dup):
+            assert np.array_equal(idx[0, h], idx_ref[0, h])      # the cut falls inside the group: unique result
+        assert np.max(np.abs(sel[0, h] - scores[0, h, idx[0, h]])) <= BAND["bf16"] / 2
+
+
+def test_long_row_whose_first_part_is_constant(gpu, oracle):
+    """The byte-cached mode takes the histogram's range from the first 32768 scores; here those are all one value,
+    so the range is empty, every score lands in one bin and the exact fallback has to sort it out."""
+    P, k = 40000, 900
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=1, Hq=4, Hkv=1, W=64, P=P, k=k)
+    L = wl.make_layer(cfg)
+    L.pool.k[0, 0, :33000] = L.pool.k[0, 0, 0]
+    idx, idx_ref, _ = _select_vs_oracle(gpu, oracle, L, cfg, "long row, constant first part")
+    scores = oracle.scores(L.q, otier(oracle, L.pool), L.scale)
+    n_band = assert_selection("select", idx, np.full((1, 4), k), scores, np.array([P]), np.array([k]), BAND["bf16"])
+    if n_band == 0:
+        assert np.array_equal(idx, idx_ref)
+
+
+def test_row_beyond_the_byte_cache_whole_step(gpu, oracle):
+    run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C4"], B=1, Hq=8, Hkv=1, W=256, P=140000, k=2500))
