@@ -432,8 +432,8 @@ int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool,
  * tokens [0, seq_lens[b] - N + i + 1).  Without it every query sees every valid
  * token.
  * HGCA_APPEND_ONE_PART_P: the softmax weights enter the second contraction
- * rounded once to bf16 (relative error 2^-9 per weight: O within ~1e-3 of the
- * exact result for unit-variance V, lse unaffected), a third fewer matrix
+ * rounded once to bf16 (relative error 2^-9 per weight: |dO| <= 2^-9 max|v|,
+ * typically ~1e-3 for unit-variance V; lse unaffected), a third fewer matrix
  * instructions.  Without it they enter as a high and a low bf16 part and O
  * keeps fp32-level accuracy (~1e-6).
  * Other bits are rejected.  shape.sm_scale must be positive and finite for the

@@ -5,7 +5,7 @@ pool, their merge, the query-averaged weights of each part, and the re-evaluatio
 Bars (bf16 inputs; scores accumulate exact products in fp32; the probabilities enter the second
 contraction as a high and a low bf16 part): lse within 2e-5, O within 2e-4 (the stated bar is 2e-2),
 averaged weights within 2e-5 and summing to 1 within 1e-4.  With HGCA_APPEND_ONE_PART_P (weights rounded
-once to bf16) lse is the same bit for bit and O is held to 4e-3."""
+once to bf16) lse is the same bit for bit and O is held to 1e-2 (2^-9 max|v|)."""
 import sys
 
 import numpy as np
@@ -119,8 +119,9 @@ def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=
     check("pool", op, lp, o_c, l_c)
     check("merged", o, lse, o_ref, l_ref)
 
-    # the same with the weights rounded once to bf16 for the second product: lse is untouched (bit for bit),
-    # O within a few 2^-9 relative steps of the weights
+    # the same with the weights rounded once to bf16 for the second product: lse is untouched (bit for bit); every
+    # weight is off by at most 2^-9 of itself and the weights sum to 1, so |dO| <= 2^-9 max|v| (about 9e-3 for
+    # N(0,1) values; reached when a query sees only a few tokens)
     ow1, lw1 = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
     op1, lp1 = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
     hgca.append_attn(shape, qd, win, True, ow1, lw1, ws, one_part_p=True)
@@ -130,7 +131,7 @@ def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=
     for name, got, want in (("window", ow1, o_g), ("pool", op1, o_c)):
         err = float(np.max(np.abs(got.double().cpu().numpy() - want), initial=0.0))
         say(f"    {name}, one-part P: max|dO|={err:.2e}")
-        assert np.all(np.isfinite(got.cpu().numpy())) and err <= 4e-3
+        assert np.all(np.isfinite(got.cpu().numpy())) and err <= 1e-2
 
     for name, a_t, A, lens, cap in (("A_gpu", a_gpu, A_g, wl_, W), ("A_cpu", a_cpu, A_c, pl_, P)):
         a_t = a_t.double().cpu().numpy()[:, :, :cap]
