@@ -561,3 +561,33 @@ def test_long_row_whose_first_part_is_constant(gpu, oracle):
 
 def test_row_beyond_the_byte_cache_whole_step(gpu, oracle):
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C4"], B=1, Hq=8, Hkv=1, W=256, P=140000, k=2500))
+
+
+def _mid_size_shapes(n, seed):
+    """Pools around and beyond the two LDS cache limits of the selection (33 792 scores as fp32, 135 168 as bytes),
+    windows of several splits, budgets from 1 to P - 1 (beyond 4 096 the kept positions are not staged in LDS)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        G = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2]))
+        d = int(rng.choice([64, 128]))
+        W = int(rng.choice([257, 1000, 4100]))
+        P = int(rng.choice([9000, 20000, 33800, 34000, 50000, 135200, 140000]))
+        k = int(rng.choice([1, 17, 500, 2048, 4096, P // 3, P - 1]))
+        kw = dict(B=int(rng.integers(1, 3)), Hq=G * Hkv, Hkv=Hkv, d=d, W=W, P=P, k=k)
+        mode, base = rng.random(), "C2"
+        if mode < 0.3 and P < 60000:                           # ragged paged, blocks of 16
+            kw.update(ragged=(W // 2, W + P), k_frac=float(rng.choice([0.05, 0.3])), block_size=16, W=W // 16 * 16,
+                      P=P // 16 * 16)
+            base = "C5"
+        elif mode < 0.5:                                       # ragged contiguous
+            kw.update(ragged=(W // 3, W + P), k_frac=float(rng.choice([0.05, 0.3])), block_size=0)
+            base = "C5"
+        out.append((f"m{i}_g{G}_d{d}_W{kw['W']}_P{kw['P']}_k{k}", base, kw))
+    return out
+
+
+@pytest.mark.parametrize("name,base,kw", _mid_size_shapes(12, 7), ids=lambda x: x if isinstance(x, str) and x[0] == "m" else None)
+def test_seeded_sweep_of_mid_size_shapes(gpu, oracle, name, base, kw):
+    run_case(gpu, oracle, wl.scaled(wl.CONFIGS[base], **kw))
