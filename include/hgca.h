@@ -138,8 +138,9 @@ int hgca_select_salient(const hgca_shape *shape, const void *q,
  * 3.2.2: the sparsifier ranks entries by a per-head relevance value, which may
  * as well be the moving average of attention weights that hgca_maw_update
  * keeps): per (b, h) row of scores (device fp32 [B,Hq,cap], 16-byte aligned,
- * finite values; with infinities or NaN the selection is unspecified) keep the k_b = min(k, len_b) largest of the first len_b =
- * seq_lens[b] entries (all `cap` if seq_lens is NULL).  Tie rule, budgets,
+ * finite values; with infinities or NaN the selection is unspecified) keep
+ * the k_b = min(k, len_b) largest of the first len_b = seq_lens[b] entries (all
+ * `cap` if seq_lens is NULL).  Tie rule, budgets,
  * k_max, idx_out, cnt_out and sel_scores_out as in hgca_select_salient.  Only
  * batch and n_q_heads of `shape` are used. */
 int hgca_select_topk(const hgca_shape *shape, const float *scores,
