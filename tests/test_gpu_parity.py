@@ -591,3 +591,70 @@ def _mid_size_shapes(n, seed):
 @pytest.mark.parametrize("name,base,kw", _mid_size_shapes(12, 7), ids=lambda x: x if isinstance(x, str) and x[0] == "m" else None)
 def test_seeded_sweep_of_mid_size_shapes(gpu, oracle, name, base, kw):
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS[base], **kw))
+
+
+# ---------------------------------------------------------------- more rows than compute units: the small workgroups
+
+@pytest.mark.parametrize("base,kw", [
+    ("C2", dict(B=20, Hq=16, Hkv=4, d=64, W=40, P=700, k=100)),                   # rows held as fp32
+    ("C2", dict(B=9, Hq=32, Hkv=4, d=64, W=64, P=6000, k=700)),                   # rows held as bytes
+    ("C2", dict(B=5, Hq=64, Hkv=8, d=64, W=33, P=9001, k=5000)),                  # budget beyond the LDS staging
+    ("C5", dict(B=40, Hq=8, Hkv=2, d=64, W=64, P=8192, ragged=(30, 8256), k_frac=0.1, block_size=16)),
+    ("C1", dict(B=33, Hq=8, Hkv=8, d=64, W=20, P=4500, k=64)),                    # fp32 inputs
+], ids=["fp32_cache", "byte_cache", "large_budget", "ragged_paged", "f32_inputs"])
+def test_more_rows_than_compute_units(gpu, oracle, base, kw):
+    cfg = wl.scaled(wl.CONFIGS[base], **kw)
+    assert cfg.B * cfg.Hq > 256
+    run_case(gpu, oracle, cfg)
+
+
+@pytest.mark.parametrize("P,k", [(3000, 1000), (20000, 6000)], ids=["fp32_cache", "byte_cache"])
+def test_many_rows_all_scores_equal(gpu, oracle, P, k):
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=5, Hq=64, Hkv=8, d=64, W=64, P=P, k=k)
+    L = wl.make_layer(cfg)
+    L.q[:] = 0
+    idx, idx_ref, _ = _select_vs_oracle(gpu, oracle, L, cfg, "320 rows, all scores equal")
+    assert np.all(idx == np.arange(k, dtype=np.int32)) and np.array_equal(idx, idx_ref)
+
+
+@pytest.mark.parametrize("P", [3000, 20000], ids=["fp32_cache", "byte_cache"])
+def test_many_rows_duplicates_at_the_threshold(gpu, oracle, P):
+    """As test_long_rows_duplicates_at_the_threshold, in 65 sequences of 4 heads (260 rows)."""
+    B, k = 65, P // 3
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=B, Hq=4, Hkv=1, d=64, W=64, P=P, k=k, plant_frac=0.0)
+    L = wl.make_layer(cfg)
+    rng = np.random.default_rng(9)
+    dup = np.sort(rng.choice(P, P // 2, replace=False))
+    for b in range(B):
+        qf = wl.to_f32(L.q)[b]
+        row = 0.5 * (qf / np.linalg.norm(qf, axis=-1, keepdims=True)).sum(0)
+        L.pool.k[b, 0, dup] = wl.f32_to_bf16_bits(row.astype(np.float32))
+    idx, idx_ref, step = _select_vs_oracle(gpu, oracle, L, cfg, "260 rows, duplicates at the threshold")
+    scores = oracle.scores(L.q, otier(oracle, L.pool), L.scale)
+    sel = step.sel_scores.double().cpu().numpy()[:, :, :k]
+    unique = 0
+    for b in range(B):
+        for h in range(4):
+            s_dup = scores[b, h, dup[0]]
+            others = np.delete(scores[b, h], dup)
+            above = (others > s_dup).sum()
+            if np.min(np.abs(others - s_dup)) > BAND["bf16"] and above < k < above + len(dup):
+                assert np.array_equal(idx[b, h], idx_ref[b, h])
+                unique += 1
+            assert np.max(np.abs(sel[b, h] - scores[b, h, idx[b, h]])) <= BAND["bf16"] / 2
+    say(f"    rows with a unique result: {unique} of {4 * B}")
+    assert unique > B
+
+
+def test_many_rows_whose_first_part_is_constant(gpu, oracle):
+    """As test_long_row_whose_first_part_is_constant for the small workgroups, whose range comes from the first
+    16384 scores."""
+    B, P, k = 65, 20000, 900
+    cfg = wl.scaled(wl.CONFIGS["C2"], B=B, Hq=4, Hkv=1, d=64, W=64, P=P, k=k)
+    L = wl.make_layer(cfg)
+    L.pool.k[:, 0, :17000] = L.pool.k[:, 0, :1]
+    idx, idx_ref, _ = _select_vs_oracle(gpu, oracle, L, cfg, "260 rows, constant first part")
+    scores = oracle.scores(L.q, otier(oracle, L.pool), L.scale)
+    n_band = assert_selection("select", idx, np.full((B, 4), k), scores, np.full(B, P), np.full(B, k), BAND["bf16"])
+    if n_band == 0:
+        assert np.array_equal(idx, idx_ref)
