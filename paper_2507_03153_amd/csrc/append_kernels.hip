@@ -20,7 +20,7 @@
 // is matched by reading V^T in the same token order); they are rounded to bf16 there, as a high and a
 // low part (two MFMAs, fp32-level accuracy) or, on request, as one part.
 //
-// The weights kernel stages K through registers into padded LDS rows (StepLoader / AStage).
+// The weights kernel brings its K rows in the same way (it has no second contraction).
 #include "hgca_launch.hpp"
 #include "row_map.hpp"
 
@@ -35,15 +35,6 @@ constexpr int kStepTokens = 32 * kStepBlocks;
 constexpr int kRowsPerBlock = 128;               // query rows per workgroup = 8 tiles of 16, one per wave
 static_assert(kRowsPerBlock == 16 * kAWaves, "one row tile per wave");
 constexpr int kSub = kMaxChunk;                  // tokens per refill of the row table
-
-template <int D> struct AStage {
-    static constexpr int kPieces = D / 8;                        // 16-byte pieces per row
-    static constexpr int kKStride = kPieces + 1;                 // K row stride in uint4 (conflict-free b128 reads)
-    static constexpr int kVStride = D * 2 + 32;                  // V row stride in bytes: 4 consecutive rows x 32 bytes
-                                                                 // cover all banks (transpose reads of a lane group)
-    static constexpr int kTotal = kStepTokens * kPieces;         // 16-byte pieces of a step, per tensor
-    static constexpr int kLoads = (kTotal + kABlock - 1) / kABlock;  // loads per thread, step and tensor
-};
 
 // The value of the lane ROT places further on in the same row of 16 lanes (DPP row_ror).
 template <int ROT>
@@ -94,35 +85,6 @@ __device__ __forceinline__ void load_q_tile(const AppendArgs &a, const RowInfo &
     }
 }
 
-// Stages the K (and V) rows of a step: global -> registers -> LDS, one step ahead.
-template <int D, bool WITH_V>
-struct StepLoader {
-    using S = AStage<D>;
-    static constexpr size_t ROW_BYTES = D * 2;
-    uint4 kr[S::kLoads], vr[S::kLoads];
-
-    __device__ __forceinline__ void fetch(const KvDev &kv, const RowMap &rows, int step, int nsub) {
-#pragma unroll
-        for (int u = 0; u < S::kLoads; ++u) {
-            const int p = threadIdx.x + kABlock * u, trow = p / S::kPieces, piece = p % S::kPieces;
-            if (p >= S::kTotal) break;
-            const int j = min(step * kStepTokens + trow, nsub - 1);
-            const size_t off = rows(j) * ROW_BYTES + 16 * piece;
-            kr[u] = load16_stream(kv.k + off);
-            if (WITH_V) vr[u] = load16_stream(kv.v + off);
-        }
-    }
-    __device__ __forceinline__ void park(uint4 *s_k, char *s_v) const {
-#pragma unroll
-        for (int u = 0; u < S::kLoads; ++u) {
-            const int p = threadIdx.x + kABlock * u, trow = p / S::kPieces, piece = p % S::kPieces;
-            if (p >= S::kTotal) break;
-            s_k[trow * S::kKStride + piece] = kr[u];
-            if (WITH_V) *reinterpret_cast<uint4 *>(s_v + trow * S::kVStride + 16 * piece) = vr[u];
-        }
-    }
-};
-
 // Raw scores <q, k> (no softmax scale yet) of one 16-row tile for the step's tokens: sv[8*kb + 4*tt + r] belongs
 // to step token 32*kb + 16*tt + 4*g + r and query row lane % 16.  With MASK, tokens at or beyond `limit` (counted
 // from the step's first token) read -inf.
@@ -146,31 +108,6 @@ __device__ __forceinline__ void tile_scores(KPiece k_piece, const bf16x8 (&qop)[
     }
 }
 
-// Runs `body(stage, step)` for every step of a sub-chunk with the next step's loads in flight.  A stage
-// written in step s is read in step s and rewritten in step s + 2; the barrier of step s + 1 lies between,
-// so one barrier per step orders everything.
-template <int D, bool WITH_V, typename Body>
-__device__ __forceinline__ void for_each_step(const KvDev &kv, const RowMap &rows, int nsub, uint4 (*s_k)[kStepTokens * AStage<D>::kKStride],
-                                              char (*s_v)[kStepTokens * AStage<D>::kVStride], Body body)
-{
-    const int steps = (nsub + kStepTokens - 1) / kStepTokens;
-    StepLoader<D, WITH_V> ld;
-    ld.fetch(kv, rows, 0, nsub);
-    for (int s = 0; s < steps; ++s) {
-        ld.park(s_k[s & 1], WITH_V ? s_v[s & 1] : nullptr);
-        if (s + 1 < steps) ld.fetch(kv, rows, s + 1, nsub);
-        __syncthreads();
-        body(s & 1, s);
-    }
-}
-
-// LDS stage of the attention kernel: the rows of a step are brought in by LDS-direct loads (global_load_lds, 16
-// bytes per lane, no registers in between).  One such instruction fills 1024 consecutive bytes of LDS with whatever
-// 64 pieces its lanes address, so the layout inside each 1 KB group is chosen by the lane -> global address map:
-//   K: row-major rows with the 16-byte pieces of a row XOR-swizzled by the row, so that the 16 rows an A-operand
-//      read touches land on different banks without padding;
-//   V: the group's rows interleaved in 32-byte chunks ([column chunk][row][32 bytes]), so that the 4 rows x 32 bytes
-//      a 16-lane group takes with one transpose read are 128 consecutive bytes.
 #ifndef HGCA_APPEND_PV_GROUP
 #define HGCA_APPEND_PV_GROUP 4
 #endif
@@ -212,7 +149,7 @@ __device__ __forceinline__ void wait_for_own_loads() { __builtin_amdgcn_s_waitcn
 
 // Requests the K and the V rows of a step.  All row numbers are looked up before the first load is issued: the
 // lookup of a paged tier reads a table in LDS, and an LDS read placed after an LDS-direct load waits for that load.
-template <int D, int NW>
+template <int D, int NW, bool WITH_V = true>
 __device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, int step, int nsub, char *k_stage,
                                          char *v_stage)
 {
@@ -228,15 +165,16 @@ __device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, in
         const int v_row = group * S::kGroupRows + (lane / 2) % S::kGroupRows;
         const int v_piece = 2 * (lane / (2 * S::kGroupRows)) + lane % 2;
         k_src[u] = kv.k + (size_t)rows(min(step * kStepTokens + k_row, nsub - 1)) * S::kRowBytes + 16 * k_piece;
-        v_src[u] = kv.v + (size_t)rows(min(step * kStepTokens + v_row, nsub - 1)) * S::kRowBytes + 16 * v_piece;
+        if (WITH_V) v_src[u] = kv.v + (size_t)rows(min(step * kStepTokens + v_row, nsub - 1)) * S::kRowBytes + 16 * v_piece;
     }
 #pragma unroll
     for (int u = 0; u < S::kLoads; ++u) {
         const int group = w + NW * u;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)k_src[u],
                                          (__attribute__((address_space(3))) void *)(k_stage + group * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)v_src[u],
-                                         (__attribute__((address_space(3))) void *)(v_stage + group * 1024), 16, 0, 0);
+        if (WITH_V)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)v_src[u],
+                                             (__attribute__((address_space(3))) void *)(v_stage + group * 1024), 16, 0, 0);
     }
 }
 
@@ -445,10 +383,12 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
 template <int D, int G>
 __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
 {
-    using S = AStage<D>;
-    __shared__ uint4 s_k[2][kStepTokens * S::kKStride];
+    using S = DmaStage<D, kAWaves>;
+    // the K rows of a step arrive by LDS-direct loads, as in the attention kernel: two stages as separate arrays
+    __shared__ __attribute__((aligned(1024))) char s_k0[S::kBytes];
+    __shared__ __attribute__((aligned(1024))) char s_k1[S::kBytes];
     __shared__ uint32_t s_row[kSub];
-    __shared__ float s_part[2][kAWaves][G][kStepTokens];         // per stage: read after the next step's barrier
+    __shared__ __attribute__((aligned(16))) float s_part[2][kAWaves][G][kStepTokens];   // read after the next step's barrier
 
     const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave, n = lane % 16, g = lane / 16;
@@ -460,6 +400,10 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     constexpr float kLog2e = 1.4426950408889634f;
     const float scale2 = a.sh.sm_scale * kLog2e;
     float *out = a.a_out + ((int64_t)b * a.sh.n_q_heads + kvh * G) * a.kv.cap + t0;
+
+    int k_lane[D / 32];                          // this lane's A-operand offsets in a stage (swizzled pieces)
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) k_lane[kk] = S::k_offset(n, 4 * kk + g);
 
     const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
     const int sub_len = a.kv.block_table ? kSub : max(nt_total, 1);
@@ -488,14 +432,22 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
                     *dst = qb == 0 ? v * inv_n : fmaf(v, inv_n, *dst);
                 }
             };
-            for_each_step<D, false>(a.kv, rows, nsub, s_k, static_cast<char (*)[kStepTokens * S::kVStride]>(nullptr),
-                                    [&](int buf, int s) {
-                if (pending >= 0) fold(pending);                 // written before the barrier that preceded this call
+            // Step s reads the stage of its parity and requests the rows of step s + 1 into the other one, which was
+            // last read in step s - 1; the sums of step s - 1 wait in s_part and are folded after the same barrier.
+            const int steps = (nsub + kStepTokens - 1) / kStepTokens;
+            dma_step<D, kAWaves, false>(a.kv, rows, 0, nsub, s_k0, nullptr);
+            auto step = [&](int s, const char *k_cur, char *k_next) {
+                wait_for_own_loads();            // the barrier alone does not wait for LDS-direct loads
+                __syncthreads();
+                if (pending >= 0) fold(pending);                 // written before the barrier above
+                if (s + 1 < steps) dma_step<D, kAWaves, false>(a.kv, rows, s + 1, nsub, k_next, nullptr);
                 float sv[8 * kStepBlocks];
                 const int step0 = sub0 + s * kStepTokens;
-                const uint4 *k_lane = s_k[buf] + n * S::kKStride + g;    // padded rows, see AStage
-                tile_scores<D, true>([&](int t, int kk) { return k_lane[t * 16 * S::kKStride + 4 * kk]; }, qop,
-                                     min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
+                tile_scores<D, true>(
+                    [&](int t, int kk) {
+                        return *reinterpret_cast<const uint4 *>(k_cur + t * 16 * S::kRowBytes + k_lane[kk]);
+                    },
+                    qop, min(nsub - s * kStepTokens, vis - (t0 + step0)), sv);
 #pragma unroll
                 for (int e = 0; e < 8 * kStepBlocks; ++e) {
                     float x = __builtin_amdgcn_exp2f(fmaf(sv[e], scale2, neg_lse2));
@@ -505,10 +457,20 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
                     if (G <= 4) x += row_rotate<4>(x);
                     if (G <= 2) x += row_rotate<2>(x);
                     if (G <= 1) x += row_rotate<1>(x);
-                    if (n < G) s_part[s & 1][w][n][16 * (e / 4) + 4 * g + (e % 4)] = x;
+                    sv[e] = x;
+                }
+                if (n < G) {                     // tokens 16 t + 4 g .. + 3 of the step, head n of the group
+#pragma unroll
+                    for (int t = 0; t < 2 * kStepBlocks; ++t)
+                        *reinterpret_cast<float4 *>(&s_part[s & 1][w][n][16 * t + 4 * g]) =
+                            make_float4(sv[4 * t], sv[4 * t + 1], sv[4 * t + 2], sv[4 * t + 3]);
                 }
                 pending = s;
-            });
+            };
+            for (int s2 = 0; s2 < steps; s2 += 2) {
+                step(s2, s_k0, s_k1);
+                if (s2 + 1 < steps) step(s2 + 1, s_k1, s_k0);
+            }
             __syncthreads();
             if (pending >= 0) fold(pending);
         }
