@@ -117,7 +117,7 @@ struct Sel {
     static __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *scratch, uint32_t *total) {
         const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave;
         uint32_t incl = v;
-    #pragma unroll
+#pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
             const uint32_t up = __shfl_up(incl, off, kWave);
             if (lane >= off) incl += up;
@@ -125,7 +125,7 @@ struct Sel {
         if (lane == kWave - 1) scratch[w] = incl;
         __syncthreads();
         uint32_t before = 0, all = 0;
-    #pragma unroll
+#pragma unroll
         for (int i = 0; i < kSelWaves; ++i) {
             const uint32_t t = scratch[i];
             if (i < w) before += t;
@@ -142,14 +142,14 @@ struct Sel {
         constexpr int BPT = kBinsPerThread;          // thread tid owns bins nb-1-BPT*tid .. (descending value)
         const int tid = threadIdx.x;
         uint32_t c[BPT], local = 0;
-    #pragma unroll
+#pragma unroll
         for (int i = 0; i < BPT; ++i) {
             c[i] = (BPT * tid + i < nb) ? sh.hist[nb - 1 - (BPT * tid + i)] : 0u;
             local += c[i];
         }
         uint32_t total;
         uint32_t running = block_exclusive_scan(local, sh.scan_scratch, &total);
-    #pragma unroll
+#pragma unroll
         for (int i = 0; i < BPT; ++i) {
             if (BPT * tid + i < nb && running < k_rem && running + c[i] >= k_rem) {
                 sh.found[0] = (uint32_t)(nb - 1 - (BPT * tid + i));
@@ -162,8 +162,10 @@ struct Sel {
     // The padded row: wave w owns the positions [w*seg, (w+1)*seg), seg a multiple of kStep; in step i a
     // lane holds the 4 scores at w*seg + kStep*i + 4*lane.  Positions >= n hold -inf.  The row is padded to a
     // whole number of segments (not of workgroups of segments): waves whose segment lies beyond it have no steps.
-    // Positions per wave, and the padded length of a row of n scores.
-    static __host__ __device__ inline int segment_length(int n) { return ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep; }
+    // Positions per wave, and the padded length of a row of n scores:
+    static __host__ __device__ inline int segment_length(int n) {
+        return ((n + kSelWaves - 1) / kSelWaves + kStep - 1) / kStep * kStep;
+    }
     static __host__ __device__ inline int padded_length(int n) {
         const int seg = segment_length(n);
         return seg ? (n + seg - 1) / seg * seg : 0;
@@ -172,7 +174,7 @@ struct Sel {
     static_assert((kBins >> kCoarseShift) <= 128, "a coarse bin and the flag fit a byte");
     static_assert(kBins >= 2 * kMaxCand + kMaxUncertain, "that list lives behind the candidate lists");
 
-
+    // A thread's view of the padded row: from the LDS copy (CACHED) or from memory.
     template <bool CACHED>
     struct Row {
         const float *sc, *cache;
@@ -192,8 +194,8 @@ struct Sel {
     };
 
     template <int MODE>
-    static __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, float *cache, const float *sc,
-                                               int32_t *out, int n, int k)
+    static __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, float *cache,
+                                                      const float *sc, int32_t *out, int n, int k)
     {
         constexpr bool CACHED = MODE == kCachedScores, BINS = MODE == kCachedBins;
         uint8_t *cbin = reinterpret_cast<uint8_t *>(cache);         // kCachedBins: one byte per position of the padded row
@@ -218,16 +220,16 @@ struct Sel {
             const int n4_range = BINS ? min(n4, kSelBlock * U) : n4;
             for (int base = 0; base < n4_range; base += kSelBlock * U) {
                 float4 v[U];
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u)
                     v[u] = load4_padded(sc, row.sc_vec, 4 * min(base + u * kSelBlock + tid, n4 - 1), n);
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int i = base + u * kSelBlock + tid;
                     if (i < n4) {
                         if (CACHED) reinterpret_cast<float4 *>(cache)[i] = v[u];
                         const float s[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-    #pragma unroll
+#pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             mx = fmaxf(mx, s[e]);                            // padding is -inf: no effect
                             mn = fminf(mn, 4 * i + e < n ? s[e] : INFINITY);
@@ -236,7 +238,7 @@ struct Sel {
                 }
             }
         }
-    #pragma unroll
+#pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
             mn = fminf(mn, __shfl_xor(mn, off, kWave));
             mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
@@ -247,14 +249,14 @@ struct Sel {
         if (tid == 0) { sh.n_cand = 0; sh.n_uncertain = 0; }
         if (tid < kSelWaves) { sh.wave_gt[tid] = 0; sh.wave_eq[tid] = 0; sh.wave_keq[tid] = 0; }
         __syncthreads();
-    #pragma unroll
+#pragma unroll
         for (int i = 0; i < kSelWaves; ++i) { mn = fminf(mn, sh.wave_min[i]); mx = fmaxf(mx, sh.wave_max[i]); }
         Binning bin;
         bin.lo = mn;
         bin.inv_w = (mx > mn) ? (float)kBins / (mx - mn) : 0.f;
 
         // ---- pass 1: histogram, threshold bin --------------------------------------------------------------
-    #pragma unroll 4
+#pragma unroll 4
         for (int i = 0; i < steps; ++i) {
             const int t = row.pos(i);
             const float4 v = row.at(t);
@@ -263,9 +265,11 @@ struct Sel {
             atomicAdd(&sh.hist[b1], 1u);
             atomicAdd(&sh.hist[b2], 1u);
             atomicAdd(&sh.hist[b3], 1u);
-            if (BINS)
-                *reinterpret_cast<uint32_t *>(cbin + t) = (uint32_t)(b0 >> kCoarseShift) | (uint32_t)(b1 >> kCoarseShift) << 8 |
-                                                          (uint32_t)(b2 >> kCoarseShift) << 16 | (uint32_t)(b3 >> kCoarseShift) << 24;
+            if (BINS) {
+                const uint32_t c0 = b0 >> kCoarseShift, c1 = b1 >> kCoarseShift, c2 = b2 >> kCoarseShift,
+                               c3 = b3 >> kCoarseShift;
+                *reinterpret_cast<uint32_t *>(cbin + t) = c0 | c1 << 8 | c2 << 16 | c3 << 24;
+            }
         }
         __syncthreads();
         locate_rank(sh, kBins, (uint32_t)k);
@@ -304,7 +308,7 @@ struct Sel {
             for (int i = 0; i < steps; ++i) {
                 const int t = row.pos(i);
                 const uint32_t bytes = *reinterpret_cast<const uint32_t *>(cbin + t);
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const uint32_t c = (bytes >> (8 * e)) & kCoarseMask;
                     above += c > tb7;
@@ -335,7 +339,7 @@ struct Sel {
                 const int t = row.pos(i);
                 const float4 v = row.at(t);
                 const float s[4] = {v.x, v.y, v.z, v.w};
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) above += classify(s[e], t + e);
             }
         }
@@ -380,7 +384,7 @@ struct Sel {
             use_bytes = false;                       // the bytes cannot tell the entries of one bin apart
             uint32_t prefix = 0, mask = 0;
             const int shifts[3] = {20, 8, 0}, widths[3] = {12, 12, 8};
-    #pragma unroll
+#pragma unroll
             for (int pass = 0; pass < 3; ++pass) {
                 const int shift = shifts[pass], nb = 1 << widths[pass];
                 __syncthreads();
@@ -390,7 +394,7 @@ struct Sel {
                     const int t = row.pos(i);
                     const float4 v = row.at(t);
                     const float s[4] = {v.x, v.y, v.z, v.w};
-    #pragma unroll
+#pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const uint32_t key = order_key(s[e]);
                         if (t + e < n && bin(s[e]) == tb && (key & mask) == prefix)
@@ -411,7 +415,7 @@ struct Sel {
                 const int t = row.pos(i);
                 const float4 v = row.at(t);
                 const float s[4] = {v.x, v.y, v.z, v.w};
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     my_gt += t + e < n && s[e] > thr;
                     my_eq += t + e < n && s[e] == thr;
@@ -448,7 +452,7 @@ struct Sel {
                 const uint32_t bytes = *reinterpret_cast<const uint32_t *>(cbin + t);
                 bool keep[4];
                 uint32_t before = run;
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const uint32_t c = (bytes >> (8 * e)) & 255u;
                     keep[e] = (c & kKeptFlag) != 0 || (c & kCoarseMask) > tb7;
@@ -456,7 +460,7 @@ struct Sel {
                     before += lanes_below(m);
                     run += __popcll(m);
                 }
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (keep[e]) dst[before] = t + e;
                     before += keep[e];
@@ -472,14 +476,14 @@ struct Sel {
                 const float s[4] = {v.x, v.y, v.z, v.w};
                 bool keep[4];
                 uint32_t before = run;
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     keep[e] = s[e] >= thr;
                     const unsigned long long m = __ballot(keep[e]);
                     before += lanes_below(m);
                     run += __popcll(m);
                 }
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (keep[e]) {
                         dst[before] = t + e;
@@ -495,7 +499,7 @@ struct Sel {
             const float s[4] = {v.x, v.y, v.z, v.w};
             bool gt[4], eq[4];
             uint32_t gt_before = run_gt, eq_before = run_eq;    // entries before this lane's first position
-    #pragma unroll
+#pragma unroll
             for (int e = 0; e < 4; ++e) {
                 gt[e] = s[e] > thr;
                 eq[e] = s[e] == thr && !(pad_ties && t + e >= n);
@@ -505,7 +509,7 @@ struct Sel {
                 run_gt += __popcll(m_gt);
                 run_eq += __popcll(m_eq);
             }
-    #pragma unroll
+#pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (gt[e] || (eq[e] && eq_before < need_eq)) {
                     const uint32_t at = gt_before + min(eq_before, need_eq);
