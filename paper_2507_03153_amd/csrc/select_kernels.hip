@@ -22,6 +22,8 @@
 // stand at the launch).
 #include "hgca_launch.hpp"
 
+#include <atomic>
+
 namespace hgca {
 
 namespace {
@@ -593,11 +595,19 @@ hipError_t launch_select_block(const SelectArgs &a, int64_t rows, int max_cache_
     const int cache_floats = padded <= max_cache_floats ? padded : 0;
     // longer rows, up to four times the large cache: one byte per score
     const int cache_bytes = cache_floats == 0 && padded <= 4 * kMaxCacheFloats ? padded : 0;
-    // once per process (thread-safe static initialisation): lift the dynamic LDS limit of the kernel
-    static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel<BLOCK>),
-                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                          kMaxCacheFloats * (int)sizeof(float));
-    if (attr_rc != hipSuccess) return attr_rc;
+    // once per device: lift the dynamic LDS limit of the kernel (the attribute belongs to a device's copy of it)
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> limit_lifted[kMaxDevices];          // zero-initialised
+    int dev = 0;
+    hipError_t rc = hipGetDevice(&dev);
+    if (rc != hipSuccess) return rc;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (!tracked || !limit_lifted[dev].load(std::memory_order_acquire)) {
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(select_topk_kernel<BLOCK>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxCacheFloats * (int)sizeof(float));
+        if (rc != hipSuccess) return rc;
+        if (tracked) limit_lifted[dev].store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL(select_topk_kernel<BLOCK>, dim3((unsigned)rows), dim3(BLOCK),
                        cache_floats ? (size_t)cache_floats * sizeof(float) : (size_t)cache_bytes, s, a, cache_floats,
                        cache_bytes);
