@@ -258,6 +258,8 @@ def test_decode_steps_maw_then_threshold_then_sparse_attention(gpu, oracle):
 @pytest.mark.parametrize("B,Hq,cap,k,kind", [
     (2, 8, 700, 100, "normal"), (2, 4, 4097, 512, "maw"), (1, 4, 33000, 1200, "maw"), (3, 2, 64, 64, "coarse"),
     (8, 32, 4096, 409, "maw"),
+    # more rows than compute units (512-thread workgroups): rows held as fp32, rows held as bytes with plenty of ties
+    (10, 32, 4096, 409, "maw"), (10, 32, 9000, 900, "coarse"), (9, 32, 20001, 6667, "normal"),
 ])
 def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kind):
     torch, hgca, _ = gpu
