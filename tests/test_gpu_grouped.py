@@ -99,7 +99,9 @@ def run_case(gpu, oracle, cfg):
     dict(B=3, Hq=4, Hkv=4, W=64, P=1500, k=257),                 # groups of one head: the per-head case
     dict(B=2, Hq=8, Hkv=2, W=64, P=512, k=0),
     dict(B=2, Hq=8, Hkv=2, W=64, P=0, k=16),
-], ids=["gqa4", "gqa8", "gqa2_d64", "mha", "k0", "P0"])
+    dict(B=36, Hq=16, Hkv=8, d=64, W=40, P=1500, k=150),         # 288 lists: the selection's small workgroups
+    dict(B=33, Hq=16, Hkv=8, d=64, W=40, P=6000, k=700),         # the same with rows held as bytes
+], ids=["gqa4", "gqa8", "gqa2_d64", "mha", "k0", "P0", "many_lists", "many_lists_byte_cache"])
 def test_grouped_bf16(gpu, oracle, kw):
     run_case(gpu, oracle, wl.scaled(wl.CONFIGS["C2"], **kw))
 
