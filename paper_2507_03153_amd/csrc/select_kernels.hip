@@ -172,7 +172,8 @@ struct Sel {
         const int seg = segment_length(n);
         return seg ? (n + seg - 1) / seg * seg : 0;
     }
-    static constexpr int kMaxUncertain = 2 * kMaxCand;      // listed positions that share the threshold's 7 bits
+    // listed positions that share the threshold's 7 bits: whatever the histogram's space holds behind the candidates
+    static constexpr int kMaxUncertain = kBins - 2 * kMaxCand;
     static_assert((kBins >> kCoarseShift) <= 128, "a coarse bin and the flag fit a byte");
     static_assert(kBins >= 2 * kMaxCand + kMaxUncertain, "that list lives behind the candidate lists");
 
