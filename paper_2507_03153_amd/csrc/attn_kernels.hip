@@ -525,8 +525,16 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, Partials q,
         const float *base = s < np ? p.o + (row * np + s) * D : q.o + (row * q.n_splits + (s - np)) * D;
         return *reinterpret_cast<const float4 *>(base + 4 * c4);
     };
+    // the maximum over all splits: one split per thread, then over the workgroup (a loop over the splits in every
+    // thread would be a chain of dependent round trips to memory)
+    __shared__ float s_M[kWaves];
     float M = -INFINITY;
-    for (int s = 0; s < n; ++s) M = fmaxf(M, m_of(s));
+    for (int s = tid; s < n; s += kBlock) M = fmaxf(M, m_of(s));
+    M = wave_max(M);
+    if (tid % kWave == 0) s_M[tid / kWave] = M;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, s_M[w]);
     float L = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (M != -INFINITY) {                        // else every split is empty (uniform over the workgroup)
