@@ -105,6 +105,26 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q,
                            float *o_out, float *lse_out,
                            void *ws, size_t ws_bytes, void *hip_stream);
 
+/* hgca_dense_window_attn for callers that cannot allocate device memory or
+ * bring a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels and same result as
+ * hgca_dense_window_attn with o_out and lse_out given (both are required
+ * here), but the split partials live in a device array that is part of the
+ * library's code object (HGCA_STATIC_SCRATCH_BYTES on every GPU the library
+ * runs on, held until the process ends) instead of in `ws`.  The call
+ * allocates nothing and frees nothing; the first call on a device looks up
+ * the address of that device's copy of the array.  Shapes whose partials do
+ * not fit -- hgca_workspace_bytes(shape, window->cap, 0, 0) greater than
+ * HGCA_STATIC_SCRATCH_BYTES -- are refused with HGCA_ERR_WORKSPACE and
+ * nothing is enqueued.  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams) race; calls in stream order
+ * do not, and nothing in the array needs clearing between calls. */
+#define HGCA_STATIC_SCRATCH_BYTES (16u << 20)
+int hgca_dense_window_attn_static(const hgca_shape *shape, const void *q,
+                                  const hgca_kv_view *window,
+                                  float *o_out, float *lse_out,
+                                  void *hip_stream);
+
 /* Raw attention scores of the older context (Sec. 3.3, s_j = q . k_j; what
  * Alg. 2's cpu_attention hands to the re-evaluation as A_cpu, before the
  * softmax): scores_out[b,h,t] = sm_scale * <q[b,h], K[b,h/G,t]> for every valid

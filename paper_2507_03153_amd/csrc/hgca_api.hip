@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdint>
 
 #include "hgca_launch.hpp"
@@ -197,6 +198,54 @@ int hgca_dense_window_attn(const hgca_shape *shape, const void *q, const hgca_kv
                            float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     return dense_window(shape, q, window, o_out, lse_out, nullptr, nullptr, 0, 0.f, ws, ws_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+// ---- dense window attention for callers that cannot allocate ---------------------------------------------
+// The split partials of the call live in a file-scope device array instead of a caller's workspace.  Its name is
+// a host-side stand-in here, not a device address: the address of each device's copy comes from
+// hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[HGCA_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of the current device's copy of `scratch`; NULL (and *err set) if the runtime refuses.
+void *static_scratch(hipError_t *err)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> known[kMaxDevices];               // zero-initialised
+    int dev = 0;
+    if ((*err = hipGetDevice(&dev)) != hipSuccess) return nullptr;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    void *ptr = tracked ? known[dev].load(std::memory_order_acquire) : nullptr;
+    if (!ptr) {
+        if ((*err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) != hipSuccess) return nullptr;
+        if (tracked) known[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hgca_dense_window_attn_static(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,
+                                  float *lse_out, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(shape, window, true)) != HGCA_OK) return rc;
+    if (!o_out || !lse_out) return HGCA_ERR_INVALID_ARG;         // no deferred result: the partials are not the caller's
+    if (layout(shape, window->cap, 0).total > (size_t)HGCA_STATIC_SCRATCH_BYTES) return HGCA_ERR_WORKSPACE;
+    hipError_t err = hipSuccess;
+    void *ws = static_scratch(&err);
+    if (!ws) return HGCA_ERR_DEVICE;
+    // every split writes its whole partial (empty ones included) and the fold reads only those, so nothing in the
+    // array has to be cleared between calls
+    return dense_window(shape, q, window, o_out, lse_out, nullptr, nullptr, 0, 0.f, ws, HGCA_STATIC_SCRATCH_BYTES,
+                        hip_stream);
 }
 
 int hgca_dense_window_attn_weights(const hgca_shape *shape, const void *q, const hgca_kv_view *window, float *o_out,

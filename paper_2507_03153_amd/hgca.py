@@ -26,7 +26,8 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
            "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact",
-           "hgca_managed_decode_step")
+           "hgca_managed_decode_step", "hgca_dense_window_attn_static")
+STATIC_SCRATCH_BYTES = 16 << 20                  # HGCA_STATIC_SCRATCH_BYTES of include/hgca.h
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
 
@@ -73,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_workspace_bytes.argtypes = [ps, i32, i32, i32]
         L.hgca_dense_window_attn.restype = ctypes.c_int
         L.hgca_dense_window_attn.argtypes = [ps, vp, pk, vp, vp, vp, sz, vp]
+        L.hgca_dense_window_attn_static.restype = ctypes.c_int
+        L.hgca_dense_window_attn_static.argtypes = [ps, vp, pk, vp, vp, vp]
         L.hgca_pool_scores.restype = ctypes.c_int
         L.hgca_pool_scores.argtypes = [ps, vp, pk, vp, vp]
         L.hgca_select_salient.restype = ctypes.c_int
@@ -199,6 +202,15 @@ def dense_window_attn(shape: Shape, q, window: Tier, o_out, lse_out, ws, stream=
     kv = window.view()
     _check(lib().hgca_dense_window_attn(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out), _ptr(lse_out),
                                         _ptr(ws), ws.numel(), _stream(stream)), "hgca_dense_window_attn")
+
+
+def dense_window_attn_static(shape: Shape, q, window: Tier, o_out, lse_out, stream=None) -> None:
+    """dense_window_attn without a workspace: the split partials live in the library's own device array."""
+    for t in (q, o_out, lse_out):
+        _require_gpu(t)
+    kv = window.view()
+    _check(lib().hgca_dense_window_attn_static(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_out),
+                                               _ptr(lse_out), _stream(stream)), "hgca_dense_window_attn_static")
 
 
 def pool_scores(shape: Shape, q, pool: Tier, scores_out, stream=None) -> None:

@@ -93,6 +93,28 @@ def test_dense_rejects_bad_arguments(hg):
         == hg.ERR_INVALID_ARG
 
 
+def test_static_dense_rejects_bad_arguments_and_sizes_beyond_its_array(hg):
+    """The allocation-free variant validates like hgca_dense_window_attn, wants both outputs, and refuses a shape
+    whose split partials exceed the library's device array before anything touches the device."""
+    def call(sh, view, q=FAKE, o=FAKE, lse=FAKE):
+        return hg.lib().hgca_dense_window_attn_static(ctypes.byref(sh), q, ctypes.byref(view), o, lse, None)
+    good = hg.Shape(hg.F32, 1, 4, 4, 64, 0.125)
+    v = _view(hg)
+    assert call(hg.Shape(hg.F32, 1, 4, 3, 64, 0.125), v) == hg.ERR_INVALID_ARG
+    assert call(hg.Shape(hg.F32, 1, 4, 4, 80, 0.125), v) == hg.ERR_UNSUPPORTED
+    assert call(good, v, o=None) == hg.ERR_INVALID_ARG           # no deferred result here
+    assert call(good, v, lse=None) == hg.ERR_INVALID_ARG
+    assert call(good, v, o=None, lse=None) == hg.ERR_INVALID_ARG
+    assert call(good, _view(hg, k=None)) == hg.ERR_INVALID_ARG
+    assert call(good, _view(hg, table=FAKE, bs=24, mb=8)) == hg.ERR_UNSUPPORTED
+    big = hg.Shape(hg.BF16, 64, 64, 8, 128, 0.1)
+    assert hg.workspace_bytes(big, 4096, 0, 0) > hg.STATIC_SCRATCH_BYTES
+    assert call(big, _view(hg, cap=4096)) == hg.ERR_WORKSPACE
+    c2 = hg.Shape(hg.BF16, 8, 32, 8, 128, 0.088)                 # the benchmarked shape's window fits
+    assert hg.workspace_bytes(c2, 4096, 0, 0) <= hg.STATIC_SCRATCH_BYTES
+    assert call(hg.Shape(hg.BF16, 0, 32, 8, 128, 0.088), v) == hg.OK   # batch 0: a no-op
+
+
 def test_select_and_sparse_reject_bad_arguments(hg):
     sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
     v = _view(hg, cap=256)
