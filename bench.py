@@ -3,6 +3,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--streams 1|2] [--no-cpu]
 
+Protocol: --reps repetitions (default 5) of (--warmup untimed steps, then exactly --steps timed steps); the
+line reports the median repetition, with the minimum and maximum beside it.
+
 A step is one pass of the whole hot path over one batch: dense window attention,
 salient selection, sparse attention and log-sum-exp merge on the 8B-shape 32K-context
 workload (C2: bf16, B=8, Hq=32, Hkv=8, d=128, window 4096, pool 28672, k=2048) with
@@ -19,7 +22,7 @@ hgca_lse_merge joining them.  In all of them the selection hands the scores of
 the kept entries to the sparse part, which therefore re-reads only V of those entries;
 `algorithmic_bytes_per_step` keeps counting their K rows (the definition of the metric),
 `moved_bytes_per_step` does not.  The `steady` step reuses a selection, as the paper's decode
-branch does, and gathers K and V.
+branch does, and gathers K and V (ONE call of hgca_hybrid_decode_step_selected).
 """
 from __future__ import annotations
 
@@ -35,9 +38,24 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 METRIC = "hybrid decode-attn layer-steps/s + achieved HBM GB/s vs peak (8B shape, 32K)"
 
-# HBM bytes per launch of the pool-score kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
-# scaled by the same counters on a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = 495_292_337
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "c2_step_hbm_traffic.md")
+
+
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the tracked rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE scaled by
+    the same counters on a copy of known size): its `total MB` column, and the commit the summary was measured at.
+    (None, None) if the summary does not list the kernel."""
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None, None
+    import re
+    at = re.search(r"measured at commit `?([0-9a-f]{7,40})`?", text)
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) > 6 and cells[1].strip("`").startswith(kernel):
+            return int(round(float(cells[6]) * 1e6)), (at.group(1) if at else None)
+    return None, None
 
 
 WORKLOADS = {
@@ -61,6 +79,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--reps", type=int, default=5,
+                    help="repetitions of (warm-up, timed steps); the line reports their median, min and max")
+    ap.add_argument("--spin-up", type=float, default=0.5,
+                    help="seconds of untimed steps before the first repetition: the figures are those of a device that "
+                         "is already serving (clocks and power state settled), as in a decode loop; 0 disables it")
     ap.add_argument("--layers", type=int, default=4, help="independent KV draws cycled through")
     ap.add_argument("--config", default="C2", choices=("C2", "C3", "C4", "C5"),
                     help="workload; C2 is the one the metric is quoted on (the others are for comparison)")
@@ -112,44 +135,68 @@ def main() -> int:
     prepared_by_tail = {fused: [st.prepare(L) for L in layers] for fused, st in steps_by_tail.items()}
     step = steps_by_tail[False]                                 # buffers used by the per-call timings below
 
-    def timed(fused: bool, select: bool):
+    def timed(fused, select: bool) -> dict:
+        """args.reps repetitions of (args.warmup untimed steps, then exactly args.steps timed steps between two events
+        on the launch stream, bracketed by device synchronisations); a step's time is the larger of the device and the
+        wall-clock figure (host-side launch cost counts too).  Median, min and max over the repetitions."""
         prepared = prepared_by_tail[fused]                      # arguments marshalled once per layer
 
         def run_steps(n: int, first: int = 0) -> None:
             for i in range(n):
                 prepared[(first + i) % len(prepared)](select)
 
-        run_steps(args.warmup)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t_wall = time.perf_counter()
-        e0.record(main_stream)
-        run_steps(args.steps, args.warmup)
-        e1.record(main_stream)
-        torch.cuda.synchronize()
-        wall = (time.perf_counter() - t_wall) * 1e3 / args.steps
-        dev_ms = e0.elapsed_time(e1) / args.steps
-        return max(dev_ms, wall), dev_ms, wall                  # host-side launch cost counts too
+        per_rep, dev_rep, wall_rep = [], [], []
+        for _ in range(max(1, args.reps)):
+            run_steps(args.warmup)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t_wall = time.perf_counter()
+            e0.record(main_stream)
+            run_steps(args.steps, args.warmup)
+            e1.record(main_stream)
+            torch.cuda.synchronize()
+            wall = (time.perf_counter() - t_wall) * 1e3 / args.steps
+            dev_ms = e0.elapsed_time(e1) / args.steps
+            per_rep.append(max(dev_ms, wall))
+            dev_rep.append(dev_ms)
+            wall_rep.append(wall)
+        return {"ms": float(np.median(per_rep)), "min": min(per_rep), "max": max(per_rep), "reps": per_rep,
+                "dev_ms": float(np.median(dev_rep)), "wall_ms": float(np.median(wall_rep))}
+
+    def spin_up(prepared) -> int:
+        """Untimed steps for args.spin_up seconds (nothing of it is measured)."""
+        n, t_end = 0, time.perf_counter() + args.spin_up
+        while args.spin_up > 0 and time.perf_counter() < t_end:
+            for i in range(16):
+                prepared[(n + i) % len(prepared)](True)
+            n += 16
+            torch.cuda.synchronize()
+        return n
 
     head = not args.four_calls                                  # tail of the headline step
     one_call = head and pass_scores and args.streams == 1       # the whole step through hgca_hybrid_decode_step
-    separate_ms = None
+    separate = None
     if one_call:
         steps_by_tail["one"] = runner.HybridStep(layers[0].shape, cfg.W, cfg.P, k_max, dev, fused_tail=True,
                                                  one_call=True)
         prepared_by_tail["one"] = [steps_by_tail["one"].prepare(L) for L in layers]
-        ms_per_step, full_ms, wall_ms = timed("one", True)
-        separate_ms, _, _ = timed(head, True)                   # the same kernels through the separate entry points
+        spin_steps = spin_up(prepared_by_tail["one"])
+        full = timed("one", True)
+        steady = timed("one", False)                            # selection reused: hgca_hybrid_decode_step_selected
+        separate = timed(head, True)                            # the same work through the separate entry points
+        separate_steady = timed(head, False)
     else:
-        ms_per_step, full_ms, wall_ms = timed(head, True)
-    steady_ms, _, _ = timed(head, False)                        # selection reused
-    other_ms, _, _ = timed(not head, True)
-    other_steady_ms, _, _ = timed(not head, False)
+        spin_steps = spin_up(prepared_by_tail[head])
+        full = timed(head, True)
+        steady = timed(head, False)                             # selection reused
+    other = timed(not head, True)
+    other_steady = timed(not head, False)
+    ms_per_step, steady_ms = full["ms"], steady["ms"]
 
     # ---- per-call device time: HIP events on the stream the kernels are launched on ---------------------
     def time_call(fn, n=args.steps) -> float:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-        for i in range(min(args.warmup, 5)):
+        for i in range(args.warmup):
             fn(layers[i % len(layers)])
         torch.cuda.synchronize()
         for i, (a, b) in enumerate(evs):
@@ -225,14 +272,30 @@ def main() -> int:
     # dominant kernel: the pool-score pass (K of the whole older context, once per KV head)
     score_bytes = call_bytes["pool_scores"]
     achieved = score_bytes / (call_ms["pool_scores"] * 1e-3) / 1e9
+    traffic, traffic_commit = measured_traffic("pool_scores_mfma_kernel") if args.config == "C2" else (None, None)
     roof = {"bound": "hbm", "kernel": "pool_scores_mfma_kernel<128,4> (hgca_pool_scores; first kernel of "
-                                      "hgca_select_salient)",
+                                      "hgca_select_salient): a figure of this ONE kernel, not of the step",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": score_bytes,
-            "avg_launch_ms": call_ms["pool_scores"]}
+            "traffic": traffic, "traffic_source": "profiles/c2_step_hbm_traffic.md" if traffic else None,
+            "traffic_measured_at_commit": traffic_commit, "bytes_per_launch": score_bytes,
+            "avg_launch_ms": call_ms["pool_scores"],
+            # the step as a whole against the same peak, on algorithmic bytes (the metric) and on the bytes it moves
+            "step_frac_algorithmic": nbytes["full"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "step_frac_moved": moved_full / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "steady_step_frac_algorithmic": nbytes["steady"] / (steady_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
     def rate(nb, ms):
         return nb / (ms * 1e-3) / 1e9
+
+    props = torch.cuda.get_device_properties(0)
+    device = {"name": torch.cuda.get_device_name(0), "arch": getattr(props, "gcnArchName", None),
+              "compute_units": props.multi_processor_count, "hbm_gib": round(props.total_memory / 2**30, 1),
+              "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
+              "memory_clock_mhz": getattr(props, "memory_clock_rate", 0) / 1e3 or None,
+              "rocm": torch.version.hip, "torch": torch.__version__}
+
+    def spread(t: dict) -> dict:
+        return {"ms_per_step": t["ms"], "min_ms": t["min"], "max_ms": t["max"], "repetitions": len(t["reps"])}
 
     out = {
         "metric": METRIC, "value": 1e3 / ms_per_step, "unit": "layer-steps/s", "n_gpus": 1,
@@ -245,24 +308,34 @@ def main() -> int:
                             "hgca_dense_window_attn, hgca_select_salient, hgca_sparse_attn (results deferred), "
                             "hgca_lse_merge_splits" if head else
                             "hgca_select_salient, hgca_sparse_attn, hgca_dense_window_attn, hgca_lse_merge"},
+        "protocol": f"{len(full['reps'])} repetitions of ({args.warmup} warm-up steps, {args.steps} timed steps between "
+                    "two HIP events, device synchronised on both sides); ms_per_step and value are the median "
+                    "repetition, a step's time the larger of device and wall-clock time; before the first "
+                    f"repetition the device runs {spin_steps} untimed steps ({args.spin_up:g} s) so that clocks and "
+                    "power state are those of a device that is already serving",
+        "repetitions": len(full["reps"]), "ms_per_step_min": full["min"], "ms_per_step_max": full["max"],
+        "ms_per_step_reps": full["reps"], "device": device,
         "achieved_hbm_gbps": rate(nbytes["full"], ms_per_step),
         "hbm_frac": rate(nbytes["full"], ms_per_step) / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": nbytes["full"],
         "moved_bytes_per_step": moved_full,
         "moved_hbm_frac": rate(moved_full, ms_per_step) / HBM_PEAK_GBPS,
-        "steady": {"ms_per_step": steady_ms, "layer_steps_per_s": 1e3 / steady_ms,
+        "steady": {**spread(steady), "layer_steps_per_s": 1e3 / steady_ms,
                    "achieved_hbm_gbps": rate(nbytes["steady"], steady_ms),
                    "hbm_frac": rate(nbytes["steady"], steady_ms) / HBM_PEAK_GBPS,
-                   "algorithmic_bytes_per_step": nbytes["steady"]},
+                   "algorithmic_bytes_per_step": nbytes["steady"],
+                   "calls": "hgca_hybrid_decode_step_selected" if one_call else "separate entry points"},
         ("four_calls" if head else "deferred_tail"): {
-            "ms_per_step": other_ms, "layer_steps_per_s": 1e3 / other_ms,
-            "hbm_frac": rate(nbytes["full"], other_ms) / HBM_PEAK_GBPS,
-            "steady_ms_per_step": other_steady_ms,
-            "steady_hbm_frac": rate(nbytes["steady"], other_steady_ms) / HBM_PEAK_GBPS},
-        "separate_calls_deferred": None if separate_ms is None else {
-            "ms_per_step": separate_ms, "hbm_frac": rate(nbytes["full"], separate_ms) / HBM_PEAK_GBPS},
+            **spread(other), "layer_steps_per_s": 1e3 / other["ms"],
+            "hbm_frac": rate(nbytes["full"], other["ms"]) / HBM_PEAK_GBPS,
+            "steady_ms_per_step": other_steady["ms"],
+            "steady_hbm_frac": rate(nbytes["steady"], other_steady["ms"]) / HBM_PEAK_GBPS},
+        "separate_calls_deferred": None if separate is None else {
+            **spread(separate), "hbm_frac": rate(nbytes["full"], separate["ms"]) / HBM_PEAK_GBPS,
+            "steady_ms_per_step": separate_steady["ms"],
+            "steady_hbm_frac": rate(nbytes["steady"], separate_steady["ms"]) / HBM_PEAK_GBPS},
         "per_call_ms": call_ms, "per_call_gbps": call_gbps,
-        "device_ms_per_step": full_ms, "wall_ms_per_step": wall_ms,
+        "device_ms_per_step": full["dev_ms"], "wall_ms_per_step": full["wall_ms"],
         "roofline": roof,
     }
     if args.config == "C2" and not args.no_decode_loop:
@@ -424,8 +497,8 @@ def copy_calibration(torch, dev) -> int:
 
 def cpu_baseline(L, target_s: float) -> dict:
     """The fp64 oracle as it stands, timed on this machine's host cores: whole layer-steps of the workload
-    (dense, select, sparse, merge for all sequences and heads) repeated until about `target_s` seconds
-    have gone."""
+    (dense, select, sparse, merge for all sequences and heads), first on ONE core (a few steps), then on all
+    cores until about `target_s` seconds have gone.  `value` is the all-core rate."""
     import oracle
 
     def tier(t):
@@ -436,13 +509,29 @@ def cpu_baseline(L, target_s: float) -> dict:
         oracle.hybrid_step(L.q, tier(L.window), tier(L.pool), L.k, L.k_max, L.scale)
         return time.perf_counter() - t0
 
-    times = [one_step()]
-    while sum(times) < target_s and len(times) < 200:
-        times.append(one_step())
-    mean = sum(times) / len(times)
-    return {"value": 1.0 / mean, "unit": "layer-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+    def sample(budget_s: float, at_most: int):
+        times = [one_step()]
+        while sum(times) < budget_s and len(times) < at_most:
+            times.append(one_step())
+        return times
+
+    all_cores = oracle.num_threads()
+    oracle.set_num_threads(1)
+    single = sample(min(6.0, target_s / 2), 5)
+    oracle.set_num_threads(all_cores)
+    times = sample(target_s, 200)
+    med, med1 = float(np_median(times)), float(np_median(single))
+    return {"value": 1.0 / med, "unit": "layer-steps/s", "cores": all_cores, "kind": "oracle",
+            "one_core": {"value": 1.0 / med1, "unit": "layer-steps/s", "cores": 1,
+                         "sample": f"{len(single)} whole {L.cfg.name} layer-steps ({sum(single):.1f}s), median"},
             "sample": f"{len(times)} whole {L.cfg.name} layer-steps on layer 0 ({sum(times):.1f}s of fp64 oracle time, "
-                      f"OpenMP over (batch, head))"}
+                      f"OpenMP over (batch, head)), median"}
+
+
+def np_median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
 if __name__ == "__main__":

@@ -225,6 +225,27 @@ int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q,
                             void *ws_sparse, size_t ws_sparse_bytes,
                             void *hip_stream);
 
+/* The decode branch of Alg. 2 as the paper runs it for every token: the salient
+ * entries are already selected (kv_manager.load returns KV_ctx), so the step is
+ * gpu_attention over the window beside cpu_attention over each head's listed
+ * entries, then merge_state.  Same results as hgca_dense_window_attn and
+ * hgca_sparse_attn with deferred results + hgca_lse_merge_splits, bit for bit,
+ * in one crossing of the boundary; the split kernels of the two parts, which
+ * need nothing from each other, share one launch where the shapes allow.
+ * idx / cnt / k_max / sel_scores as in hgca_sparse_attn (sel_scores NULL unless
+ * it holds the scores of the listed entries for THIS q).  o_out is [B,Hq,d] in
+ * o_dtype, lse_out [B,Hq] optional.  ws_dense needs
+ * hgca_workspace_bytes(shape, window->cap, 0, 0), ws_sparse
+ * hgca_workspace_bytes(shape, 0, 0, k_max); they must be different buffers. */
+int hgca_hybrid_decode_step_selected(const hgca_shape *shape, const void *q,
+                                     const hgca_kv_view *window, const hgca_kv_view *pool,
+                                     const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                                     const float *sel_scores,
+                                     void *o_out, int32_t o_dtype, float *lse_out,
+                                     void *ws_dense, size_t ws_dense_bytes,
+                                     void *ws_sparse, size_t ws_sparse_bytes,
+                                     void *hip_stream);
+
 /* merge_state (Sec. 3.3 "Merging states"): combines two partial results over
  * disjoint key sets into the result of one softmax over their union.  Evaluated
  * with both exponents shifted by max(lse_a, lse_b).  o_out is [B,Hq,d] in

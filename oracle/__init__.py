@@ -56,7 +56,7 @@ def lib():
         _lib = ctypes.CDLL(build())
         for name in ("oracle_scores", "oracle_attend_all", "oracle_attend_indexed",
                      "oracle_attend_union", "oracle_select", "oracle_merge",
-                     "oracle_hybrid_step", "oracle_num_threads", "oracle_window_weights",
+                     "oracle_hybrid_step", "oracle_num_threads", "oracle_set_num_threads", "oracle_window_weights",
                      "oracle_maw_update", "oracle_threshold_select", "oracle_select_given"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
@@ -64,6 +64,11 @@ def lib():
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the (batch, head) loops use from now on."""
+    lib().oracle_set_num_threads(int(n))
 
 
 @dataclass

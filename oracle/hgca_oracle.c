@@ -110,6 +110,15 @@ int oracle_num_threads(void)
 #endif
 }
 
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int oracle_scores(const oracle_shape *sh, const void *q, const oracle_kv *kv,
                   double *scores)
 {

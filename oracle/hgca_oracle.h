@@ -154,6 +154,8 @@ int oracle_threshold_select(int64_t rows, int32_t cap, const int32_t *lens,
 
 /* Number of OpenMP threads the (batch, head) loop will use. */
 int oracle_num_threads(void);
+/* Threads the (batch, head) loops may use from now on (timing of the baseline on 1 core and on all cores). */
+void oracle_set_num_threads(int n);
 
 #ifdef __cplusplus
 }

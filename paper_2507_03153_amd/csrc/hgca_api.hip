@@ -26,6 +26,11 @@ constexpr size_t kAlign = 256;
 #define HGCA_TARGET_WGS_SPARSE 2048
 #endif
 
+// 1: the window's split kernels and the sparse part's split kernels of a step share a launch where the shapes allow
+#ifndef HGCA_FUSE_DENSE_GATHER
+#define HGCA_FUSE_DENSE_GATHER 1
+#endif
+
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -562,8 +567,13 @@ int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q, const hgca_k
     da.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
     da.part = partials_at(ws_dense, wd, n_splits_for(window->cap, da.chunk));
 
-    // 1. split kernels of the window part, score pass over the pool (independent of each other)
-    if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
+    // The window's splits and the sparse part's splits are two streaming passes that need nothing from each other:
+    // where the shapes allow they share one launch (after the selection), so the second needs no ramp-up of its own.
+    const bool fuse_gather = HGCA_FUSE_DENSE_GATHER && pool->cap > 0 && window->cap > 0 && k_max > 0 &&
+                             dense_gather_fusable(shape->dtype, shape->head_dim, group_of(shape));
+    // 1. split kernels of the window part (unless they go with the sparse part's), score pass over the pool
+    if (!fuse_gather && (rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK)
+        return rc;
     if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
     // 2. per-head top-k; the kept entries' scores stay in the workspace for the sparse part
     float *sel = k_max > 0 && pool->cap > 0 ? reinterpret_cast<float *>(static_cast<char *>(ws_sparse) + wsp.sel) : nullptr;
@@ -589,8 +599,60 @@ int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q, const hgca_k
     ga.k_max = k_max;
     ga.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
     ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(k_max, ga.chunk)));
-    if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
+    if (fuse_gather) rc = from_hip(launch_dense_gather(shape->dtype, shape->head_dim, da, ga, s));
+    else rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s));
+    if (rc != HGCA_OK) return rc;
     // 4. one fold of all split partials = merge_state over all of them
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    return from_hip(launch_combine2(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, s));
+}
+
+int hgca_hybrid_decode_step_selected(const hgca_shape *shape, const void *q, const hgca_kv_view *window,
+                                     const hgca_kv_view *pool, const int32_t *idx, const int32_t *cnt, int32_t k_max,
+                                     const float *sel_scores, void *o_out, int32_t o_dtype, float *lse_out,
+                                     void *ws_dense, size_t ws_dense_bytes, void *ws_sparse, size_t ws_sparse_bytes,
+                                     void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != HGCA_OK) return rc;
+    if (o_dtype != HGCA_F32 && o_dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return HGCA_OK;
+    if ((rc = check_view(shape, window, true)) != HGCA_OK) return rc;
+    if ((rc = check_view(shape, pool, true)) != HGCA_OK) return rc;
+    if (!q || !aligned16(q) || !o_out || !aligned16(o_out) || !cnt || k_max < 0 || (k_max > 0 && !idx))
+        return HGCA_ERR_INVALID_ARG;
+    const WsLayout wd = layout(shape, window->cap, 0);
+    const WsLayout wsp = layout(shape, k_max, 0);
+    if (!ws_dense || ws_dense_bytes < wd.total || !aligned16(ws_dense)) return HGCA_ERR_WORKSPACE;
+    if (!ws_sparse || ws_sparse_bytes < wsp.total || !aligned16(ws_sparse)) return HGCA_ERR_WORKSPACE;
+    if (ws_dense == ws_sparse) return HGCA_ERR_WORKSPACE;       // the two parts are live at the same time
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    AttnArgs da{};
+    da.sh = to_dev(shape);
+    da.q = q;
+    da.kv = to_dev(window);
+    da.chunk = pick_chunk(window->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
+    da.part = partials_at(ws_dense, wd, n_splits_for(window->cap, da.chunk));
+    AttnArgs ga{};
+    ga.sh = da.sh;
+    ga.q = q;
+    ga.kv = to_dev(pool);
+    ga.idx = idx;
+    ga.cnt = cnt;
+    ga.sel_scores = sel_scores;
+    ga.k_max = k_max;
+    ga.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
+    ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(k_max, ga.chunk)));
+    // gpu_attention over the window and cpu_attention over the listed entries: one launch where the shapes allow
+    if (HGCA_FUSE_DENSE_GATHER && window->cap > 0 && k_max > 0 && pool->cap > 0 &&
+        dense_gather_fusable(shape->dtype, shape->head_dim, group_of(shape))) {
+        if ((rc = from_hip(launch_dense_gather(shape->dtype, shape->head_dim, da, ga, s))) != HGCA_OK) return rc;
+    } else {
+        if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
+        if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
+    }
+    // merge_state over all split partials of both parts
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     return from_hip(launch_combine2(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, s));
 }

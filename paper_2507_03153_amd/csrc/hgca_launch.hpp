@@ -71,6 +71,11 @@ struct SelectArgs {
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t s);
 
+// The window's split kernels and the per-head gather's split kernels (launch_attn_partial_dense and
+// launch_attn_partial_gather with the same arguments) as one launch; bf16, groups of 1, 2 or 4, per-head lists.
+bool dense_gather_fusable(int dtype, int head_dim, int group);
+hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, const AttnArgs &gather, hipStream_t s);
+
 // Union of the index lists of the heads of each group: idx [B, Hq, k_max] / cnt [B, Hq] -> out [B, Hkv, k_max_out]
 // ascending, -1 padded, out_cnt [B, Hkv].  Positions must lie in [0, n_positions).
 hipError_t launch_union_lists(const int32_t *idx, const int32_t *cnt, int32_t k_max, int32_t batch, int32_t n_q_heads,

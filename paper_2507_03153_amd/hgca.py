@@ -26,7 +26,7 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
            "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact",
-           "hgca_managed_decode_step", "hgca_dense_window_attn_static")
+           "hgca_managed_decode_step", "hgca_dense_window_attn_static", "hgca_hybrid_decode_step_selected")
 STATIC_SCRATCH_BYTES = 16 << 20                  # HGCA_STATIC_SCRATCH_BYTES of include/hgca.h
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
@@ -113,6 +113,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_ctx_compact.argtypes = [ps, pk, vp, vp, i32, vp, vp, vp, i32, vp, vp]
         L.hgca_hybrid_decode_step.restype = ctypes.c_int
         L.hgca_hybrid_decode_step.argtypes = [ps, vp, pk, pk, vp, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp]
+        L.hgca_hybrid_decode_step_selected.restype = ctypes.c_int
+        L.hgca_hybrid_decode_step_selected.argtypes = [ps, vp, pk, pk, vp, vp, i32, vp, vp, i32, vp, vp, sz, vp, sz, vp]
         L.hgca_dense_window_attn_maw.restype = ctypes.c_int
         L.hgca_dense_window_attn_maw.argtypes = [ps, vp, pk, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         L.hgca_maw_update.restype = ctypes.c_int
@@ -421,6 +423,19 @@ def hybrid_decode_step(shape: Shape, q, window: Tier, pool: Tier, k, k_max: int,
                                          int(k_max), _ptr(idx_out), _ptr(cnt_out), _ptr(o_out), _dtype_code(o_out),
                                          _ptr(lse_out), _ptr(ws_dense), ws_dense.numel(), _ptr(ws_sparse),
                                          ws_sparse.numel(), _stream(stream)), "hgca_hybrid_decode_step")
+
+
+def hybrid_decode_step_selected(shape: Shape, q, window: Tier, pool: Tier, idx, cnt, k_max: int, o_out, lse_out,
+                                ws_dense, ws_sparse, stream=None, sel_scores=None) -> None:
+    """The decode step over an existing selection (dense window part beside sparse part, merge) in one call."""
+    for t in (q, idx, cnt, o_out, ws_dense, ws_sparse) + tuple(x for x in (lse_out, sel_scores) if x is not None):
+        _require_gpu(t)
+    kw, kp = window.view(), pool.view()
+    _check(lib().hgca_hybrid_decode_step_selected(ctypes.byref(shape), _ptr(q), ctypes.byref(kw), ctypes.byref(kp),
+                                                  _ptr(idx), _ptr(cnt), int(k_max), _ptr(sel_scores), _ptr(o_out),
+                                                  _dtype_code(o_out), _ptr(lse_out), _ptr(ws_dense), ws_dense.numel(),
+                                                  _ptr(ws_sparse), ws_sparse.numel(), _stream(stream)),
+           "hgca_hybrid_decode_step_selected")
 
 
 def ctx_compact(shape: Shape, pool: Tier, idx, cnt, k_max: int, k_ctx, v_ctx, ctx_cap: int, first_row=None,

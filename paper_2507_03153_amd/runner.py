@@ -65,7 +65,7 @@ class HybridStep:
         self.shape, self.k_max, self.device = shape, k_max, device
         self.pass_scores = pass_scores                              # select hands its scores to the sparse part
         self.fused_tail = fused_tail                                # one fold of all splits instead of three kernels
-        self.one_call = one_call                                    # a step with a fresh selection = hgca_hybrid_decode_step
+        self.one_call = one_call                                    # a step = hgca_hybrid_decode_step / _selected
         if one_call and (two_streams or not fused_tail or not pass_scores):
             raise ValueError("one_call implies fused_tail and pass_scores on one stream")
         self.o_w, self.lse_w = torch.empty(B, Hq, d, **f32), torch.empty(B, Hq, **f32)
@@ -109,11 +109,17 @@ class HybridStep:
         a_step = (ref(sh), ptr(L.q), ref(win), ref(pool), k_ptr, k_uni, self.k_max, ptr(self.idx), ptr(self.cnt),
                   ptr(self.o), hgca._dtype_code(self.o), ptr(self.lse), ptr(self.ws_dense), self.ws_dense.numel(),
                   ptr(self.ws_sparse), self.ws_sparse.numel(), s_main)
+        a_selected = (ref(sh), ptr(L.q), ref(win), ref(pool), ptr(self.idx), ptr(self.cnt), self.k_max, None,
+                      ptr(self.o), hgca._dtype_code(self.o), ptr(self.lse), ptr(self.ws_dense), self.ws_dense.numel(),
+                      ptr(self.ws_sparse), self.ws_sparse.numel(), s_main)
         keep = (sh, win, pool, L)                               # the structs must outlive the closure
 
         def run(select: bool = True) -> None:
-            if select and self.one_call:
-                hgca._check(lib.hgca_hybrid_decode_step(*a_step), "hgca_hybrid_decode_step")
+            if self.one_call:
+                if select:
+                    hgca._check(lib.hgca_hybrid_decode_step(*a_step), "hgca_hybrid_decode_step")
+                else:
+                    hgca._check(lib.hgca_hybrid_decode_step_selected(*a_selected), "hgca_hybrid_decode_step_selected")
                 return
             if self.side is not None:
                 self._fork.record(main)
@@ -135,9 +141,13 @@ class HybridStep:
 
     def run(self, L: DeviceLayer, select: bool = True, stream=None) -> None:
         main = torch.cuda.current_stream() if stream is None else stream
-        if select and self.one_call:
-            hgca.hybrid_decode_step(self.shape, L.q, L.window, L.pool, L.k, self.k_max, self.idx, self.cnt, self.o,
-                                    self.lse, self.ws_dense, self.ws_sparse, main)
+        if self.one_call:
+            if select:
+                hgca.hybrid_decode_step(self.shape, L.q, L.window, L.pool, L.k, self.k_max, self.idx, self.cnt, self.o,
+                                        self.lse, self.ws_dense, self.ws_sparse, main)
+            else:
+                hgca.hybrid_decode_step_selected(self.shape, L.q, L.window, L.pool, self.idx, self.cnt, self.k_max,
+                                                 self.o, self.lse, self.ws_dense, self.ws_sparse, main)
             return
         side = main
         if self.side is not None:

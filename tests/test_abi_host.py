@@ -347,6 +347,35 @@ def test_hybrid_decode_step_rejects_bad_arguments(hg):
     assert step(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), q=None, o=None) == hg.OK   # empty batch: nothing to do
 
 
+def test_hybrid_decode_step_selected_rejects_bad_arguments(hg):
+    sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
+    win, pool = _view(hg, cap=256), _view(hg, cap=1024)
+    big = 1 << 40
+
+    def call(shape=sh, q=FAKE, w=win, p=pool, idx=FAKE, cnt=FAKE, k_max=64, sel=None, o=FAKE, o_dtype=hg.F32, lse=FAKE,
+             wd=FAKE, wd_bytes=big, ws=ctypes.c_void_p(0x20000), ws_bytes=big):
+        return hg.lib().hgca_hybrid_decode_step_selected(ctypes.byref(shape), q, ctypes.byref(w), ctypes.byref(p), idx,
+                                                         cnt, k_max, sel, o, o_dtype, lse, wd, wd_bytes, ws, ws_bytes,
+                                                         None)
+    assert call(shape=hg.Shape(hg.BF16, 2, 8, 3, 128, 0.088)) == hg.ERR_INVALID_ARG
+    assert call(shape=hg.Shape(hg.BF16, 2, 8, 2, 96, 0.088)) == hg.ERR_UNSUPPORTED
+    assert call(o_dtype=5) == hg.ERR_UNSUPPORTED
+    assert call(q=None) == hg.ERR_INVALID_ARG
+    assert call(q=ODD) == hg.ERR_INVALID_ARG
+    assert call(o=None) == hg.ERR_INVALID_ARG
+    assert call(cnt=None) == hg.ERR_INVALID_ARG
+    assert call(idx=None) == hg.ERR_INVALID_ARG
+    assert call(k_max=-1) == hg.ERR_INVALID_ARG
+    assert call(w=_view(hg, cap=256, v=None)) == hg.ERR_INVALID_ARG
+    assert call(p=_view(hg, cap=1024, v=None)) == hg.ERR_INVALID_ARG        # the sparse part reads V
+    assert call(wd=None) == hg.ERR_WORKSPACE
+    assert call(ws=None) == hg.ERR_WORKSPACE
+    assert call(wd_bytes=hg.workspace_bytes(sh, 256, 0, 0) - 1) == hg.ERR_WORKSPACE
+    assert call(ws_bytes=hg.workspace_bytes(sh, 0, 0, 64) - 1) == hg.ERR_WORKSPACE
+    assert call(ws=FAKE) == hg.ERR_WORKSPACE                               # the two workspaces must differ
+    assert call(shape=hg.Shape(hg.BF16, 0, 8, 2, 128, 0.088), q=None, o=None) == hg.OK     # batch 0: a no-op
+
+
 def test_ctx_compact_rejects_bad_arguments(hg):
     sh = hg.Shape(hg.BF16, 2, 8, 2, 128, 0.088)
     pool = _view(hg, cap=256)

@@ -177,6 +177,20 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
         fused.run(D, select=False)                             # reused selection: K and V gathered
         torch.cuda.synchronize()
         assert_partial("steady, fused tail", fused.o, fused.lse, o_h, l_h, tol if n_band else min(tol, tight))
+        say("  step over an existing selection as one library call (on the oracle's lists)")
+        one.idx[..., :L.k_max].copy_(idx_d[..., :L.k_max]) if L.k_max else None
+        one.cnt.copy_(cnt_d)
+        one.o.fill_(float("nan"))
+        one.lse.fill_(float("nan"))
+        one.run(D, select=False)
+        torch.cuda.synchronize()
+        assert_partial("selected step, one call", one.o, one.lse, ou, lu, min(tol, tight))
+        # the same split kernels as the separate deferred calls on the same lists: identical bits
+        fused.idx.copy_(one.idx)
+        fused.cnt.copy_(one.cnt)
+        fused.run(D, select=False)
+        torch.cuda.synchronize()
+        assert torch.equal(one.o, fused.o) and torch.equal(one.lse, fused.lse)
     return step, D, L
 
 
