@@ -25,6 +25,9 @@ constexpr size_t kAlign = 256;
 #ifndef HGCA_TARGET_WGS_SPARSE
 #define HGCA_TARGET_WGS_SPARSE 2048
 #endif
+#ifndef HGCA_TARGET_WGS_SPARSE_SCORED            // the sparse part inside hgca_hybrid_decode_step (scores given, V only)
+#define HGCA_TARGET_WGS_SPARSE_SCORED 2048
+#endif
 
 // 1: the window's split kernels and the sparse part's split kernels of a step share a launch where the shapes allow
 #ifndef HGCA_FUSE_DENSE_GATHER
@@ -597,7 +600,7 @@ int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q, const hgca_k
     ga.cnt = cnt_out;
     ga.sel_scores = sel;
     ga.k_max = k_max;
-    ga.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE);
+    ga.chunk = pick_chunk(k_max, (int64_t)shape->batch * shape->n_q_heads, HGCA_TARGET_WGS_SPARSE_SCORED);
     ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(k_max, ga.chunk)));
     if (fuse_gather) rc = from_hip(launch_dense_gather(shape->dtype, shape->head_dim, da, ga, s));
     else rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s));

@@ -8,13 +8,6 @@ namespace hgca {
 
 namespace {
 
-#ifdef HGCA_SEL_TRACE
-__device__ unsigned long long *g_sel_trace;      // development only: phase time stamps of row 0
-#define HGCA_SEL_STAMP(i) do { if (g_sel_trace && blockIdx.x == 0 && threadIdx.x == 0) g_sel_trace[i] = wall_clock64(); } while (0)
-#else
-#define HGCA_SEL_STAMP(i) do { } while (0)
-#endif
-
 #ifndef HGCA_SEL_BINS
 #define HGCA_SEL_BINS 4096
 #endif
@@ -201,7 +194,6 @@ struct Sel {
         const int steps = w * seg < padded ? seg / kStep : 0;        // uniform over a wave
         const int pos0 = w * seg + 4 * lane;                          // position of the lane's first score
 
-        HGCA_SEL_STAMP(0);
         float4 v[STEPS];
 #pragma unroll
         for (int i = 0; i < STEPS; ++i) {
@@ -209,7 +201,6 @@ struct Sel {
             if (i < steps) v[i] = load4_padded(sc, sc_vec, min(pos0 + kStep * i, (n + 3) / 4 * 4), n);
         }
         float mn = INFINITY, mx = -INFINITY;
-        HGCA_SEL_STAMP(1);
 #pragma unroll
         for (int i = 0; i < STEPS; ++i) {
             const float s[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
@@ -236,7 +227,6 @@ struct Sel {
         bin.lo = mn;
         bin.inv_w = (mx > mn) ? (float)kBins / (mx - mn) : 0.f;
 
-        HGCA_SEL_STAMP(2);
         // histogram, threshold bin
 #pragma unroll
         for (int i = 0; i < STEPS; ++i) {
@@ -248,13 +238,11 @@ struct Sel {
             }
         }
         __syncthreads();
-        HGCA_SEL_STAMP(3);
         locate_rank(sh, kBins, (uint32_t)k);
         const int tb = (int)sh.found[0];
         const uint32_t k_rem = sh.found[1];          // rank of the k-th entry inside bin tb
         __syncthreads();
 
-        HGCA_SEL_STAMP(4);
         // entries above the threshold bin are counted, those inside it listed (the same two compares against the
         // bin's edges as in select_row: padding and NaN fail both)
         const float edge_lo = (float)tb, edge_hi = (tb == kBins - 1) ? INFINITY : (float)(tb + 1);
@@ -277,15 +265,31 @@ struct Sel {
         }
         above = (uint32_t)wave_sum((float)above);    // exact: far below 2^24 per wave
         __syncthreads();
-        HGCA_SEL_STAMP(5);
         const uint32_t n_cand = sh.n_cand;
         if (n_cand > (uint32_t)kMaxCand) return false;               // crowded bin (uniform over the workgroup)
-        // exact rank of every candidate in (score descending, position ascending) order
+        // exact rank of every candidate in (score descending, position ascending) order; up to 64 candidates (the
+        // usual case) are ranked by the first wave alone out of its registers, more than that one per thread
         float my_s = 0.f;
         int32_t my_idx = 0;
         if ((uint32_t)tid < n_cand) {
             my_s = sh.cand_score()[tid];
             my_idx = sh.cand_idx()[tid];
+        }
+        if (n_cand <= (uint32_t)kWave) {
+            if (w == 0) {
+                uint32_t gt = 0, eq_lower = 0;
+                for (uint32_t j = 0; j < n_cand; ++j) {
+                    const float sj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_s), j));
+                    const int32_t ij = __builtin_amdgcn_readlane(my_idx, j);
+                    gt += sj > my_s;
+                    eq_lower += (sj == my_s) && (ij < my_idx);
+                }
+                if ((uint32_t)lane < n_cand && gt + eq_lower == k_rem - 1) {
+                    sh.found[0] = __float_as_uint(my_s);
+                    sh.found[1] = k_rem - gt;
+                }
+            }
+        } else if ((uint32_t)tid < n_cand) {
             uint32_t gt = 0, eq_lower = 0;
             for (uint32_t j = 0; j < n_cand; ++j) {
                 const float sj = sh.cand_score()[j];
@@ -310,13 +314,9 @@ struct Sel {
         }
         if (need_eq != all_eq || thr == -INFINITY) return false;     // a tie that the budget cuts: the general path
 
-        HGCA_SEL_STAMP(6);
-        // ordered compaction: an entry is kept iff its score is >= T, one lane mask per score gives its place;
-        // positions (and, where they fit beside them, the kept scores) are staged in LDS and leave coalesced
-        const bool staged = k <= kBins, sel_staged = 2 * k <= kBins;
-        int32_t *dst = staged ? reinterpret_cast<int32_t *>(sh.hist) : out;
+        // ordered compaction: an entry is kept iff its score is >= T, one lane mask per score gives its place; the
+        // lanes of a wave write ascending, mostly adjacent places, so positions and scores go straight to memory
         float *sel = a.sel_scores ? a.sel_scores + bh * a.k_max : nullptr;
-        float *sel_dst = sel_staged ? reinterpret_cast<float *>(sh.hist) + k : sel;
 #pragma unroll
         for (int i = 0; i < STEPS; ++i) {
             if (i < steps) {
@@ -333,27 +333,13 @@ struct Sel {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (keep[e]) {
-                        dst[before] = pos0 + kStep * i + e;
-                        if (sel) sel_dst[before] = s[e];
+                        out[before] = pos0 + kStep * i + e;
+                        if (sel) sel[before] = s[e];
                     }
                     before += keep[e];
                 }
             }
         }
-        HGCA_SEL_STAMP(7);
-        if (staged) {
-            __syncthreads();
-            if ((a.k_max & 3) == 0) {                // output rows start 16-byte aligned
-                for (int j = tid; j < k / 4; j += kSelBlock)
-                    reinterpret_cast<int4 *>(out)[j] = reinterpret_cast<const int4 *>(sh.hist)[j];
-                for (int j = k / 4 * 4 + tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
-            } else {
-                for (int j = tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
-            }
-            if (sel && sel_staged)
-                for (int j = tid; j < k; j += kSelBlock) sel[j] = __uint_as_float(sh.hist[k + j]);
-        }
-        HGCA_SEL_STAMP(8);
         return true;
     }
 

@@ -90,10 +90,6 @@ hipError_t launch_select_block(const SelectArgs &a, int64_t rows, int max_cache_
 
 }  // namespace
 
-#ifdef HGCA_SEL_TRACE
-extern "C" int hgca_debug_set_sel_trace(void *p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_sel_trace), &p, sizeof(p)); }
-#endif
-
 hipError_t launch_select(const SelectArgs &a, hipStream_t s)
 {
     const int64_t rows = (int64_t)a.sh.batch * a.sh.n_q_heads;
