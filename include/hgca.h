@@ -336,9 +336,11 @@ int hgca_select_salient_grouped(const hgca_shape *shape, const void *q,
 
 /* Union: per (b, KV head) the ascending union of the lists idx [B,Hq,k_max] /
  * cnt [B,Hq] of the group's heads (nothing a head selected is lost).  Positions
- * lie in [0, n_positions), n_positions <= 2^19.  idx_out is [B,Hkv,k_max_out],
+ * lie in [0, n_positions), n_positions <= HGCA_UNION_MAX_POSITIONS (more is
+ * HGCA_ERR_UNSUPPORTED).  idx_out is [B,Hkv,k_max_out],
  * -1 padded, cnt_out [B,Hkv]; a union longer than k_max_out is cut (lowest
  * positions kept) and bit 0 of *status (device int32, optional) is set. */
+#define HGCA_UNION_MAX_POSITIONS 523776
 int hgca_union_lists(const hgca_shape *shape, const int32_t *idx, const int32_t *cnt,
                      int32_t k_max, int32_t n_positions,
                      int32_t *idx_out, int32_t *cnt_out, int32_t k_max_out,
@@ -363,8 +365,9 @@ int hgca_sparse_attn_grouped(const hgca_shape *shape, const void *q,
  * its first first_win_block[b] blocks, the window the blocks after them.
  * Evicting the oldest window block therefore moves a boundary and copies no KV
  * row.  Views for the attention calls:
- *   window = { k_blocks, v_blocks, win_lens,  block_table, cap = win_blocks *
- *              block_size, block_size, max_blocks, first_block = first_win_block }
+ *   window = { k_blocks, v_blocks, win_lens,  block_table, cap = window capacity
+ *              (see win_cap_blocks), block_size, max_blocks, first_block =
+ *              first_win_block }
  *   pool   = { k_blocks, v_blocks, pool_lens, block_table, cap = pool_cap,
  *              block_size, max_blocks, first_block = NULL }
  * All pointers are device memory owned by the caller; the struct itself is host
@@ -375,7 +378,7 @@ typedef struct {
     int32_t       *first_win_block;     /* [B] (rw) first window block = number of pool blocks      */
     int32_t       *win_lens;            /* [B] (rw) tokens in the window                            */
     int32_t       *pool_lens;           /* [B] (rw) tokens in the pool = first_win_block*block_size */
-    float         *a_maw;               /* [B, Hq, win_blocks*block_size] (rw) moving average of    */
+    float         *a_maw;               /* [B, Hq, window capacity] (rw) moving average of          */
                                         /* attention weights, by window position                    */
     int32_t       *ctx_idx;             /* [B, Hq, k_max] (rw) salient pool positions, ascending    */
     int32_t       *ctx_cnt;             /* [B, Hq] (rw) their number                                */
@@ -389,10 +392,15 @@ typedef struct {
     int32_t win_blocks;                 /* blk_num of Alg. 1: l_max = win_blocks * block_size       */
     int32_t k_max;                      /* row length of ctx_idx                                    */
     int32_t pool_cap;                   /* capacity of the pool view and row length of a_evicted    */
+    int32_t win_cap_blocks;             /* blocks the window may hold for a moment, >= win_blocks   */
+                                        /* (0 counts as win_blocks): window capacity = row length   */
+                                        /* of a_maw = win_cap_blocks * block_size tokens.  A decode */
+                                        /* step needs no more than l_max; a prompt of N tokens      */
+                                        /* needs l_max - 1 + N, until its eviction has run          */
 } hgca_cache_state;
 
 enum {
-    HGCA_CACHE_WINDOW_FULL = 1,   /* append on a window that already holds l_max tokens: token dropped  */
+    HGCA_CACHE_WINDOW_FULL = 1,   /* insertion beyond the window's capacity: the tokens were dropped      */
     HGCA_CACHE_CONTEXT_FULL = 2,  /* append beyond the last block of the table row: token dropped        */
     HGCA_CACHE_LIST_FULL = 4      /* more salient entries than k_max: the later ones were not listed     */
 };
@@ -407,6 +415,15 @@ enum {
 int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache,
                    const void *k_in, const void *v_in, const int32_t *active,
                    void *hip_stream);
+
+/* hgca_kv_append for a prompt: n_tokens entries per sequence at once (Alg. 1
+ * with KV_in.size = N).  k_in, v_in are [B, n_tokens, Hkv, d], oldest first; they
+ * go to window positions win_lens[b] .. win_lens[b] + n_tokens - 1.  A sequence
+ * whose window capacity or table row cannot take all of them receives none
+ * (status bit). */
+int hgca_kv_append_tokens(const hgca_shape *shape, const hgca_cache_state *cache,
+                          const void *k_in, const void *v_in, int32_t n_tokens,
+                          const int32_t *active, void *hip_stream);
 
 /* Eviction and sparsification of Alg. 1, per sequence, decided on the device:
  * if l_cur = win_lens[b] >= l_max, the oldest l_evict = ceil((l_cur - l_max + 1)
@@ -430,10 +447,10 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
  * with two launches fewer (the window's own lse comes out of the fold of all
  * split partials).  q is [B,Hq,d], k_in / v_in [B,Hkv,d]: every sequence of the
  * batch receives a token (batches in which some do not use the separate
- * calls); a_gpu (device fp32 [B,Hq,win_blocks * block_size], required)
+ * calls); a_gpu (device fp32 [B,Hq,window capacity], required)
  * receives A_gpu; o_out [B,Hq,d] in o_dtype, lse_out
- * [B,Hq] optional.  ws_dense needs hgca_workspace_bytes(shape, win_blocks *
- * block_size, 0, 0), ws_sparse hgca_workspace_bytes(shape, 0, 0, k_max);
+ * [B,Hq] optional.  ws_dense needs hgca_workspace_bytes(shape, window capacity,
+ * 0, 0), ws_sparse hgca_workspace_bytes(shape, 0, 0, k_max);
  * different buffers.  Every decision is taken on the device: the launch
  * sequence is the same every step. */
 int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *cache,
@@ -442,6 +459,34 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
                              float *a_gpu, void *o_out, int32_t o_dtype, float *lse_out,
                              void *ws_dense, size_t ws_dense_bytes,
                              void *ws_sparse, size_t ws_sparse_bytes, void *hip_stream);
+
+/* One append turn over the managed cache in one call (a prompt of n_q tokens per
+ * sequence), in the paper's order: Alg. 2, append branch -- KV_gpu' =
+ * concat(KV_gpu, KV_in); gpu_attention over the window, causal among the
+ * incoming tokens; cpu_attention over the COMPLETE offloaded cache (not the
+ * salient lists); merge_state per query -- then Alg. 1 with KV_in.size = n_q:
+ * the moving averages are updated with the query-averaged A_gpu (the n_q new
+ * entries take their first observed weight); the salient lists are REPLACED by
+ * the re-evaluation of Sec. 3.2.2, ids = A_cpu > beta / A_cpu.size with A_cpu the
+ * query-averaged weights over the offloaded cache and A_cpu.size = pool_lens[b];
+ * then windows that have reached l_max evict as many whole blocks as it takes,
+ * their salient entries joining the new lists.  The same results as
+ * hgca_kv_append_tokens, hgca_append_attn on the window (causal tail) and on the
+ * pool, hgca_lse_merge, hgca_append_weights on both, hgca_maw_update (n_new =
+ * n_q), hgca_threshold_select on a_cpu and hgca_kv_evict in that order.
+ * q is [B, n_q, Hq, d], k_in / v_in [B, n_q, Hkv, d] (bf16, as hgca_append_attn);
+ * flags: HGCA_APPEND_ONE_PART_P or 0; a_gpu (fp32 [B,Hq,window capacity]) and
+ * a_cpu (fp32 [B,Hq,pool_cap]) receive the two weight rows (0 beyond the
+ * lengths); o_out is fp32 [B,n_q,Hq,d], lse_out fp32
+ * [B,n_q,Hq].  The window capacity must take l_cur = win_lens[b] + n_q (see
+ * win_cap_blocks).  `ws` needs hgca_managed_append_workspace_bytes. */
+size_t hgca_managed_append_workspace_bytes(const hgca_shape *shape, const hgca_cache_state *cache,
+                                           int32_t n_q);
+int hgca_managed_append_step(const hgca_shape *shape, const hgca_cache_state *cache,
+                             const void *q, const void *k_in, const void *v_in, int32_t n_q,
+                             float alpha, double beta, int32_t flags,
+                             float *a_gpu, float *a_cpu, float *o_out, float *lse_out,
+                             void *ws, size_t ws_bytes, void *hip_stream);
 
 /* KV_ctx of Alg. 1 (KV_ctx.add(KV_evict[ids]); Sec. 3.2.2): per head, the
  * salient entries held in contiguous storage, so that the sparse part reads a

@@ -13,32 +13,35 @@ namespace hgca {
 
 namespace {
 
-// One workgroup per sequence: the token's K and V rows of every KV head go to slot len % block_size of
-// window block len / block_size; then the length grows by one.
+// One workgroup per sequence: the K and V rows of the n_tokens incoming tokens of every KV head go to the window
+// positions len .. len + n_tokens - 1 (slot p % block_size of window block p / block_size); then the length grows.
+// A sequence whose window capacity or table row cannot take all of them receives none (status bit).
 __global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const char *k_in, const char *v_in,
                                                               const int32_t *active, int32_t n_kv_heads,
-                                                              int32_t row_bytes)
+                                                              int32_t row_bytes, int32_t n_tokens)
 {
     const int b = blockIdx.x;
     if (active && !active[b]) return;
     const int len = c.win_lens[b];
-    const int blk_i = c.first_win_block[b] + len / c.block_size;
-    if (len < 0 || len >= c.win_blocks * c.block_size || blk_i >= c.max_blocks) {   // uniform over the workgroup
-        if (threadIdx.x == 0) atomicOr(c.status, len >= c.win_blocks * c.block_size ? kCacheWindowFull : kCacheContextFull);
+    const int first = c.first_win_block[b];
+    const bool no_room = len + n_tokens > c.win_cap;
+    if (len < 0 || no_room || first + (len + n_tokens - 1) / c.block_size >= c.max_blocks) {   // uniform over the workgroup
+        if (threadIdx.x == 0) atomicOr(c.status, no_room ? kCacheWindowFull : kCacheContextFull);
         return;
     }
-    const int64_t blk = c.block_table[(int64_t)b * c.max_blocks + blk_i];
-    const int slot = len % c.block_size;
     const int pieces = row_bytes / 16;                         // 16-byte pieces of one row
-    for (int i = threadIdx.x; i < n_kv_heads * pieces; i += kRowBlock) {
-        const int kvh = i / pieces, p = i % pieces;
-        const int64_t dst = ((blk * n_kv_heads + kvh) * c.block_size + slot) * row_bytes + 16 * p;
-        const int64_t src = ((int64_t)b * n_kv_heads + kvh) * row_bytes + 16 * p;
+    const int per_token = n_kv_heads * pieces;
+    for (int i = threadIdx.x; i < n_tokens * per_token; i += kRowBlock) {
+        const int t = i / per_token, kvh = (i % per_token) / pieces, p = i % pieces;
+        const int pos = len + t;
+        const int64_t blk = c.block_table[(int64_t)b * c.max_blocks + first + pos / c.block_size];
+        const int64_t dst = ((blk * n_kv_heads + kvh) * c.block_size + pos % c.block_size) * row_bytes + 16 * p;
+        const int64_t src = (((int64_t)b * n_tokens + t) * n_kv_heads + kvh) * row_bytes + 16 * p;
         *reinterpret_cast<uint4 *>(c.k_blocks + dst) = *reinterpret_cast<const uint4 *>(k_in + src);
         *reinterpret_cast<uint4 *>(c.v_blocks + dst) = *reinterpret_cast<const uint4 *>(v_in + src);
     }
     __syncthreads();                                           // every thread has read `len` by now
-    if (threadIdx.x == 0) c.win_lens[b] = len + 1;
+    if (threadIdx.x == 0) c.win_lens[b] = len + n_tokens;
 }
 
 // Eviction and sparsification of Alg. 1.  One workgroup per (sequence, query head) row.  Every workgroup of a
@@ -59,8 +62,7 @@ __global__ __launch_bounds__(kRowBlock) void evict_kernel(CacheDev c, int32_t n_
     const int l_ev = n_ev * c.block_size;
     if (l_ev == 0) return;                                     // the same for every workgroup of the sequence
     const int p_old = c.pool_lens[b];
-    const int win_cap = c.win_blocks * c.block_size;
-    float *maw = c.a_maw + row * win_cap;
+    float *maw = c.a_maw + row * c.win_cap;
 
     const int start = min(max(c.ctx_cnt[row], 0), c.k_max);
     float unused = 0.f;
@@ -163,11 +165,11 @@ hipError_t launch_ctx_compact(const CtxCompactArgs &a, hipStream_t s)
 }
 
 hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
-                            int32_t n_kv_heads, int32_t row_bytes, hipStream_t s)
+                            int32_t n_kv_heads, int32_t row_bytes, int32_t n_tokens, hipStream_t s)
 {
-    if (batch == 0) return hipSuccess;
+    if (batch == 0 || n_tokens == 0) return hipSuccess;
     hipLaunchKernelGGL(kv_append_kernel, dim3(batch), dim3(kRowBlock), 0, s, c, static_cast<const char *>(k_in),
-                       static_cast<const char *>(v_in), active, n_kv_heads, row_bytes);
+                       static_cast<const char *>(v_in), active, n_kv_heads, row_bytes, n_tokens);
     return hipGetLastError();
 }
 

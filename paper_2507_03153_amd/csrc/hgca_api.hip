@@ -465,7 +465,9 @@ int hgca_union_lists(const hgca_shape *shape, const int32_t *idx, const int32_t 
 {
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
-    if (k_max < 0 || k_max_out < 0 || n_positions < 0 || n_positions > (1 << 19)) return HGCA_ERR_INVALID_ARG;
+    if (k_max < 0 || k_max_out < 0 || n_positions < 0) return HGCA_ERR_INVALID_ARG;
+    // one bit per position in the 64 KiB of LDS a kernel may use without asking for more (64 bytes of it are static)
+    if (n_positions > HGCA_UNION_MAX_POSITIONS) return HGCA_ERR_UNSUPPORTED;
     if (shape->batch == 0) return HGCA_OK;
     if (!cnt || !cnt_out || (k_max > 0 && !idx) || (k_max_out > 0 && !idx_out)) return HGCA_ERR_INVALID_ARG;
     return from_hip(launch_union_lists(idx, cnt, k_max, shape->batch, shape->n_q_heads, shape->n_kv_heads, n_positions,
@@ -686,6 +688,8 @@ int check_cache(const hgca_shape *shape, const hgca_cache_state *c, CacheDev *ou
         c->pool_cap < 0)
         return HGCA_ERR_INVALID_ARG;
     if (c->block_size % 16 != 0) return HGCA_ERR_UNSUPPORTED;
+    if (c->win_cap_blocks != 0 && (c->win_cap_blocks < c->win_blocks || c->win_cap_blocks > c->max_blocks))
+        return HGCA_ERR_INVALID_ARG;
     if (shape->batch > 0 &&
         (!c->k_blocks || !c->v_blocks || !aligned16(c->k_blocks) || !aligned16(c->v_blocks) || !c->block_table ||
          !c->first_win_block || !c->win_lens || !c->pool_lens || !c->a_maw || !c->ctx_cnt || !c->plan || !c->status ||
@@ -708,22 +712,30 @@ int check_cache(const hgca_shape *shape, const hgca_cache_state *c, CacheDev *ou
     out->win_blocks = c->win_blocks;
     out->k_max = c->k_max;
     out->pool_cap = c->pool_cap;
+    out->win_cap = (c->win_cap_blocks ? c->win_cap_blocks : c->win_blocks) * c->block_size;
     return HGCA_OK;
 }
 
 }  // namespace
 
-int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache, const void *k_in, const void *v_in,
-                   const int32_t *active, void *hip_stream)
+int hgca_kv_append_tokens(const hgca_shape *shape, const hgca_cache_state *cache, const void *k_in, const void *v_in,
+                          int32_t n_tokens, const int32_t *active, void *hip_stream)
 {
     CacheDev c{};
     int rc = check_cache(shape, cache, &c);
     if (rc != HGCA_OK) return rc;
-    if (shape->batch == 0) return HGCA_OK;
+    if (n_tokens < 0) return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0 || n_tokens == 0) return HGCA_OK;
     if (!k_in || !v_in || !aligned16(k_in) || !aligned16(v_in)) return HGCA_ERR_INVALID_ARG;
     const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
-    return from_hip(launch_kv_append(c, k_in, v_in, active, shape->batch, shape->n_kv_heads, row_bytes,
+    return from_hip(launch_kv_append(c, k_in, v_in, active, shape->batch, shape->n_kv_heads, row_bytes, n_tokens,
                                      static_cast<hipStream_t>(hip_stream)));
+}
+
+int hgca_kv_append(const hgca_shape *shape, const hgca_cache_state *cache, const void *k_in, const void *v_in,
+                   const int32_t *active, void *hip_stream)
+{
+    return hgca_kv_append_tokens(shape, cache, k_in, v_in, 1, active, hip_stream);
 }
 
 int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache, double beta, void *hip_stream)
@@ -759,7 +771,7 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     window.max_blocks = pool.max_blocks = cache->max_blocks;
     window.seq_lens = cache->win_lens;
     window.first_block = cache->first_win_block;
-    window.cap = cache->win_blocks * cache->block_size;
+    window.cap = c.win_cap;
     pool.seq_lens = cache->pool_lens;
     pool.cap = cache->pool_cap;
     if ((rc = check_view(shape, &window, true)) != HGCA_OK) return rc;
@@ -773,7 +785,7 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
 
     // Alg. 2: KV_gpu' = concat(KV_gpu, KV_in)
-    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, s))) != HGCA_OK)
+    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, 1, s))) != HGCA_OK)
         return rc;
     // gpu_attention: split kernels of the window, leaving the scaled scores in a_gpu
     AttnArgs da{};
@@ -901,6 +913,8 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const 
     if (flags & ~(HGCA_APPEND_CAUSAL_TAIL | HGCA_APPEND_ONE_PART_P)) return HGCA_ERR_INVALID_ARG;
     if (shape->batch == 0 || n_q == 0) return HGCA_OK;
     if (!o_out || !lse_out || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    // (KV head, block of 128 query rows) pairs are one grid dimension of the launch
+    if ((int64_t)shape->n_kv_heads * (((int64_t)n_q * group_of(shape) + 127) / 128) > 65535) return HGCA_ERR_UNSUPPORTED;
     const AppendWs w = append_layout(shape, n_q, tier->cap);
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -945,6 +959,117 @@ int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, con
     while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < 1024) a.chunk /= 2;
     return from_hip(launch_append_weights(shape->head_dim, a, n_splits_for(tier->cap, a.chunk),
                                           static_cast<hipStream_t>(hip_stream)));
+}
+
+namespace {
+
+// Workspace of hgca_managed_append_step: [scratch of hgca_append_attn | O, lse of the window part | O, lse of the pool part]
+struct ManagedAppendWs {
+    size_t attn, o_w, lse_w, o_p, lse_p, total;
+    size_t attn_bytes;
+};
+
+ManagedAppendWs managed_append_layout(const hgca_shape *s, int32_t n_q, int32_t win_cap, int32_t pool_cap)
+{
+    ManagedAppendWs w{};
+    const size_t rows = (size_t)s->batch * n_q * s->n_q_heads;
+    w.attn_bytes = append_layout(s, n_q, std::max(win_cap, pool_cap)).total;
+    size_t at = 0;
+    w.attn = at; at += align_up(w.attn_bytes);
+    w.o_w = at; at += align_up(rows * s->head_dim * sizeof(float));
+    w.lse_w = at; at += align_up(rows * sizeof(float));
+    w.o_p = at; at += align_up(rows * s->head_dim * sizeof(float));
+    w.lse_p = at; at += align_up(rows * sizeof(float));
+    w.total = std::max<size_t>(at, kAlign);
+    return w;
+}
+
+}  // namespace
+
+size_t hgca_managed_append_workspace_bytes(const hgca_shape *shape, const hgca_cache_state *cache, int32_t n_q)
+{
+    CacheDev c{};
+    hgca_shape host_only = shape ? *shape : hgca_shape{};
+    host_only.batch = shape ? std::min(shape->batch, 0) : 0;     // sizing needs no device pointers
+    if (!shape || !cache || n_q < 0 || n_q > 4096 || check_shape(shape) != HGCA_OK || check_cache(&host_only, cache, &c) != HGCA_OK)
+        return 0;
+    return managed_append_layout(shape, n_q, c.win_cap, c.pool_cap).total;
+}
+
+int hgca_managed_append_step(const hgca_shape *shape, const hgca_cache_state *cache, const void *q, const void *k_in,
+                             const void *v_in, int32_t n_q, float alpha, double beta, int32_t flags, float *a_gpu,
+                             float *a_cpu, float *o_out, float *lse_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    CacheDev c{};
+    int rc = check_cache(shape, cache, &c);
+    if (rc != HGCA_OK) return rc;
+    if (n_q < 0 || n_q > 4096 || !(alpha >= 0.f && alpha <= 1.f) || !(beta >= 0.0) || (flags & ~HGCA_APPEND_ONE_PART_P))
+        return HGCA_ERR_INVALID_ARG;
+    if (shape->batch == 0 || n_q == 0) return HGCA_OK;
+    // the two tiers as ranges of the sequence's block list
+    hgca_kv_view window{}, pool{};
+    window.k = pool.k = cache->k_blocks;
+    window.v = pool.v = cache->v_blocks;
+    window.block_table = pool.block_table = cache->block_table;
+    window.block_size = pool.block_size = cache->block_size;
+    window.max_blocks = pool.max_blocks = cache->max_blocks;
+    window.seq_lens = cache->win_lens;
+    window.first_block = cache->first_win_block;
+    window.cap = c.win_cap;
+    pool.seq_lens = cache->pool_lens;
+    pool.cap = cache->pool_cap;
+    if ((rc = check_append(shape, q, n_q, &window, true)) != HGCA_OK) return rc;
+    if ((rc = check_append(shape, q, n_q, &pool, true)) != HGCA_OK) return rc;
+    if ((int64_t)shape->batch * n_q > 65535) return HGCA_ERR_UNSUPPORTED;        // the merge runs on batch * n_q rows
+    if (!k_in || !v_in || !aligned16(k_in) || !aligned16(v_in) || !a_gpu || (cache->pool_cap > 0 && !a_cpu) || !o_out ||
+        !lse_out || !aligned16(o_out))
+        return HGCA_ERR_INVALID_ARG;
+    const ManagedAppendWs w = managed_append_layout(shape, n_q, c.win_cap, c.pool_cap);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    char *base = static_cast<char *>(ws);
+    float *o_w = reinterpret_cast<float *>(base + w.o_w), *lse_w = reinterpret_cast<float *>(base + w.lse_w);
+    float *o_p = reinterpret_cast<float *>(base + w.o_p), *lse_p = reinterpret_cast<float *>(base + w.lse_p);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
+
+    // Alg. 2, append branch: KV_gpu' = concat(KV_gpu, KV_in)
+    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, n_q, s))) != HGCA_OK)
+        return rc;
+    // gpu_attention over the window (causal among the incoming tokens), cpu_attention over the complete offloaded cache
+    if ((rc = hgca_append_attn(shape, q, n_q, &window, flags | HGCA_APPEND_CAUSAL_TAIL, o_w, lse_w, base + w.attn,
+                               w.attn_bytes, hip_stream)) != HGCA_OK)
+        return rc;
+    if ((rc = hgca_append_attn(shape, q, n_q, &pool, flags, o_p, lse_p, base + w.attn, w.attn_bytes, hip_stream)) != HGCA_OK)
+        return rc;
+    // merge_state per (sequence, query, head)
+    hgca_shape merged = *shape;
+    merged.batch = shape->batch * n_q;
+    if ((rc = hgca_lse_merge(&merged, o_p, lse_p, o_w, lse_w, o_out, HGCA_F32, lse_out, hip_stream)) != HGCA_OK) return rc;
+    // A_gpu, A_cpu: the query-averaged weights of the two parts
+    if ((rc = hgca_append_weights(shape, q, n_q, &window, 1, lse_w, a_gpu, hip_stream)) != HGCA_OK) return rc;
+    if ((rc = hgca_append_weights(shape, q, n_q, &pool, 0, lse_p, a_cpu, hip_stream)) != HGCA_OK) return rc;
+    // Alg. 1: moving averages (the n_q new entries take their first observed weight)
+    const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
+    if ((rc = from_hip(launch_maw_update(c.a_maw, a_gpu, c.win_lens, rows, shape->n_q_heads, c.win_cap, n_q, alpha, s))) != HGCA_OK)
+        return rc;
+    // re-evaluation (Sec. 3.2.2): the salient lists are replaced by ids = A_cpu > beta / A_cpu.size
+    if (cache->pool_cap > 0) {
+        ThresholdArgs t{};
+        t.w = a_cpu;
+        t.seq_lens = c.pool_lens;
+        t.sizes = c.pool_lens;
+        t.beta = beta;
+        t.n_q_heads = shape->n_q_heads;
+        t.cap = cache->pool_cap;
+        t.k_max = c.k_max;
+        t.idx = c.ctx_idx;
+        t.cnt = c.ctx_cnt;
+        t.status = c.status;
+        t.status_bit = kCacheListFull;
+        if ((rc = from_hip(launch_threshold_select(t, rows, s))) != HGCA_OK) return rc;
+    }
+    // eviction of as many whole blocks as it takes, sparsification of what leaves
+    return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, s));
 }
 
 }  // extern "C"

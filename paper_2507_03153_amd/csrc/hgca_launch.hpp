@@ -101,6 +101,8 @@ struct ThresholdArgs {
     int32_t *idx;              // [B*Hq, k_max]
     int32_t *cnt;              // [B*Hq]
     float *w_norm;             // optional [B*Hq, k_max]
+    int32_t *status;           // optional: receives status_bit (atomic or) when a row has more than k_max passing entries
+    int32_t status_bit;
 };
 hipError_t launch_threshold_select(const ThresholdArgs &a, int64_t n_rows, hipStream_t s);
 
@@ -135,10 +137,12 @@ struct CacheDev {
     int32_t *ctx_idx, *ctx_cnt, *plan, *status;
     float *a_evicted;          // optional [B*Hq, pool_cap]
     int32_t block_size, max_blocks, win_blocks, k_max, pool_cap;
+    int32_t win_cap;           // tokens the window may hold (>= win_blocks * block_size = l_max); row length of a_maw
 };
 
+// k_in / v_in: [B, n_tokens, Hkv, row]
 hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
-                            int32_t n_kv_heads, int32_t row_bytes, hipStream_t s);
+                            int32_t n_kv_heads, int32_t row_bytes, int32_t n_tokens, hipStream_t s);
 hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s);
 
 // Copy of listed pool entries into per-head contiguous storage (KV_ctx of Alg. 1).

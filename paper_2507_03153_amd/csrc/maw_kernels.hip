@@ -75,8 +75,12 @@ __global__ __launch_bounds__(kRowBlock) void threshold_select_kernel(ThresholdAr
     float *wn = a.w_norm ? a.w_norm + row * a.k_max : nullptr;
 
     float my_sum = 0.f;
-    const int passing = threshold_compact<true>(s_compact, a.w + row * a.cap, n, thr, idx, 0, a.k_max, 0, wn, my_sum);
+    // with a status word the whole row is examined, so that a list that left entries out is reported
+    const int passing = a.status
+        ? threshold_compact<false>(s_compact, a.w + row * a.cap, n, thr, idx, 0, a.k_max, 0, wn, my_sum)
+        : threshold_compact<true>(s_compact, a.w + row * a.cap, n, thr, idx, 0, a.k_max, 0, wn, my_sum);
     const int kept = min(passing, a.k_max);
+    if (a.status && tid == 0 && passing > a.k_max) atomicOr(a.status, a.status_bit);
     for (int j = kept + tid; j < a.k_max; j += kRowBlock) {
         idx[j] = -1;
         if (wn) wn[j] = 0.f;

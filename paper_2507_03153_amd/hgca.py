@@ -26,7 +26,8 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
            "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact",
-           "hgca_managed_decode_step", "hgca_dense_window_attn_static", "hgca_hybrid_decode_step_selected")
+           "hgca_managed_decode_step", "hgca_dense_window_attn_static", "hgca_hybrid_decode_step_selected", "hgca_kv_append_tokens",
+           "hgca_managed_append_workspace_bytes", "hgca_managed_append_step")
 STATIC_SCRATCH_BYTES = 16 << 20                  # HGCA_STATIC_SCRATCH_BYTES of include/hgca.h
 CACHE_WINDOW_FULL, CACHE_CONTEXT_FULL, CACHE_LIST_FULL = 1, 2, 4
 
@@ -46,7 +47,8 @@ class CacheState(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("k_blocks", "v_blocks", "block_table", "first_win_block", "win_lens",
                                                "pool_lens", "a_maw", "ctx_idx", "ctx_cnt", "a_evicted", "plan",
                                                "status")] + \
-               [(n, ctypes.c_int32) for n in ("block_size", "max_blocks", "win_blocks", "k_max", "pool_cap")]
+               [(n, ctypes.c_int32) for n in ("block_size", "max_blocks", "win_blocks", "k_max", "pool_cap",
+                                               "win_cap_blocks")]
 
 
 class HgcaError(RuntimeError):
@@ -98,6 +100,13 @@ def lib() -> ctypes.CDLL:
         L.hgca_append_weights.argtypes = [ps, vp, i32, pk, i32, vp, vp, vp]
         L.hgca_kv_append.restype = ctypes.c_int
         L.hgca_kv_append.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, vp]
+        L.hgca_kv_append_tokens.restype = ctypes.c_int
+        L.hgca_kv_append_tokens.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, i32, vp, vp]
+        L.hgca_managed_append_workspace_bytes.restype = sz
+        L.hgca_managed_append_workspace_bytes.argtypes = [ps, ctypes.POINTER(CacheState), i32]
+        L.hgca_managed_append_step.restype = ctypes.c_int
+        L.hgca_managed_append_step.argtypes = [ps, ctypes.POINTER(CacheState), vp, vp, vp, i32, ctypes.c_float,
+                                               ctypes.c_double, i32, vp, vp, vp, vp, vp, sz, vp]
         L.hgca_kv_evict.restype = ctypes.c_int
         L.hgca_kv_evict.argtypes = [ps, ctypes.POINTER(CacheState), ctypes.c_double, vp]
         L.hgca_select_salient_grouped.restype = ctypes.c_int
@@ -324,6 +333,34 @@ def kv_append(shape: Shape, cache: CacheState, k_in, v_in, active=None, stream=N
         _require_gpu(t)
     _check(lib().hgca_kv_append(ctypes.byref(shape), ctypes.byref(cache), _ptr(k_in), _ptr(v_in), _ptr(active),
                                 _stream(stream)), "hgca_kv_append")
+
+
+def kv_append_tokens(shape: Shape, cache: CacheState, k_in, v_in, active=None, stream=None) -> None:
+    """Writes a prompt's K/V rows [B,N,Hkv,d] behind every (active) sequence's window."""
+    for t in (k_in, v_in) + (() if active is None else (active,)):
+        _require_gpu(t)
+    _check(lib().hgca_kv_append_tokens(ctypes.byref(shape), ctypes.byref(cache), _ptr(k_in), _ptr(v_in),
+                                       int(k_in.shape[1]), _ptr(active), _stream(stream)), "hgca_kv_append_tokens")
+
+
+def managed_append_workspace(shape: Shape, cache: CacheState, n_q: int, device) -> torch.Tensor:
+    n = int(lib().hgca_managed_append_workspace_bytes(ctypes.byref(shape), ctypes.byref(cache), int(n_q)))
+    if n == 0:
+        raise HgcaError(ERR_INVALID_ARG, "hgca_managed_append_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def managed_append_step(shape: Shape, cache: CacheState, q, k_in, v_in, alpha: float, beta: float, a_gpu, a_cpu,
+                        o_out, lse_out, ws, stream=None, one_part_p: bool = False) -> None:
+    """One append turn over the managed cache (insert N tokens, attend to window and complete pool, merge, moving
+    averages, re-evaluation of the salient lists, eviction) in one call.  q [B,N,Hq,d], k_in / v_in [B,N,Hkv,d]."""
+    for t in (q, k_in, v_in, a_gpu, o_out, lse_out, ws) + (() if a_cpu is None else (a_cpu,)):
+        _require_gpu(t)
+    _check(lib().hgca_managed_append_step(ctypes.byref(shape), ctypes.byref(cache), _ptr(q), _ptr(k_in), _ptr(v_in),
+                                          int(q.shape[1]), float(alpha), float(beta),
+                                          APPEND_ONE_PART_P if one_part_p else 0, _ptr(a_gpu), _ptr(a_cpu), _ptr(o_out),
+                                          _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "hgca_managed_append_step")
 
 
 def kv_evict(shape: Shape, cache: CacheState, beta: float, stream=None) -> None:

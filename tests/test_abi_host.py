@@ -228,12 +228,47 @@ def test_kv_manager_entry_points_reject_bad_arguments(hg):
     def state(**kw):
         f = dict(k_blocks=p, v_blocks=p, block_table=p, first_win_block=p, win_lens=p, pool_lens=p, a_maw=p,
                  ctx_idx=p, ctx_cnt=p, a_evicted=None, plan=p, status=p,
-                 block_size=16, max_blocks=8, win_blocks=4, k_max=64, pool_cap=128)
+                 block_size=16, max_blocks=8, win_blocks=4, k_max=64, pool_cap=128, win_cap_blocks=0)
         f.update(kw)
         return hg.CacheState(**f)
 
     def append(st, k=FAKE, v=FAKE):
         return L.hgca_kv_append(ctypes.byref(sh), ctypes.byref(st), k, v, None, None)
+
+    def append_n(st, n, k=FAKE, v=FAKE):
+        return L.hgca_kv_append_tokens(ctypes.byref(sh), ctypes.byref(st), k, v, n, None, None)
+
+    def turn(st, q=FAKE, k=FAKE, v=FAKE, n_q=8, alpha=0.3, beta=1.0, flags=0, a_gpu=FAKE, a_cpu=FAKE, o=FAKE, lse=FAKE,
+             ws=FAKE, ws_bytes=1 << 40):
+        return L.hgca_managed_append_step(ctypes.byref(sh), ctypes.byref(st), q, k, v, n_q, alpha, beta, flags, a_gpu,
+                                          a_cpu, o, lse, ws, ws_bytes, None)
+    assert append_n(state(), -1) == hg.ERR_INVALID_ARG
+    assert append_n(state(), 0, k=None) == hg.OK                 # nothing to insert
+    assert append_n(state(), 5, k=None) == hg.ERR_INVALID_ARG
+    assert append_n(state(win_cap_blocks=3), 5) == hg.ERR_INVALID_ARG        # capacity below l_max
+    assert append_n(state(win_cap_blocks=9), 5) == hg.ERR_INVALID_ARG        # capacity beyond the table row
+    need = L.hgca_managed_append_workspace_bytes(ctypes.byref(sh), ctypes.byref(state(win_cap_blocks=6)), 8)
+    assert need > 0
+    assert L.hgca_managed_append_workspace_bytes(ctypes.byref(sh), ctypes.byref(state()), -1) == 0
+    assert L.hgca_managed_append_workspace_bytes(ctypes.byref(sh), ctypes.byref(state(block_size=0)), 8) == 0
+    st6 = state(win_cap_blocks=6)
+    assert turn(st6, q=None) == hg.ERR_INVALID_ARG
+    assert turn(st6, k=ODD) == hg.ERR_INVALID_ARG
+    assert turn(st6, a_gpu=None) == hg.ERR_INVALID_ARG
+    assert turn(st6, a_cpu=None) == hg.ERR_INVALID_ARG
+    assert turn(st6, o=None) == hg.ERR_INVALID_ARG
+    assert turn(st6, lse=None) == hg.ERR_INVALID_ARG
+    assert turn(st6, alpha=1.5) == hg.ERR_INVALID_ARG
+    assert turn(st6, beta=-1.0) == hg.ERR_INVALID_ARG
+    assert turn(st6, flags=64) == hg.ERR_INVALID_ARG
+    assert turn(st6, n_q=-1) == hg.ERR_INVALID_ARG
+    assert turn(st6, ws=None) == hg.ERR_WORKSPACE
+    assert turn(st6, ws_bytes=need - 1) == hg.ERR_WORKSPACE
+    assert turn(state(block_size=24)) == hg.ERR_UNSUPPORTED
+    f32 = hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)
+    assert L.hgca_managed_append_step(ctypes.byref(f32), ctypes.byref(st6), FAKE, FAKE, FAKE, 8, 0.3, 1.0, 0, FAKE, FAKE,
+                                      FAKE, FAKE, FAKE, 1 << 40, None) == hg.ERR_UNSUPPORTED   # append stage: bf16
+    assert turn(st6, n_q=0, q=None) == hg.OK                     # an empty prompt: nothing to do
 
     def evict(st, beta=1.0):
         return L.hgca_kv_evict(ctypes.byref(sh), ctypes.byref(st), beta, None)
@@ -278,6 +313,9 @@ def test_append_entry_points_reject_bad_arguments(hg):
     assert attn(ws_bytes=64) == hg.ERR_WORKSPACE
     assert attn(shape=hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)) == hg.ERR_UNSUPPORTED      # bf16 only
     assert attn(n_q=0) == hg.OK                                                          # nothing to do
+    # (KV head, block of 128 query rows) pairs are one grid dimension: 2048 heads x 32 blocks do not fit 65 535
+    assert attn(shape=hg.Shape(hg.BF16, 1, 2048, 2048, 128, 0.088), n_q=4096) == hg.ERR_UNSUPPORTED
+    assert attn(shape=hg.Shape(hg.BF16, 1, 2047, 2047, 128, 0.088), n_q=4096, ws_bytes=64) == hg.ERR_WORKSPACE
 
     def weights(q=FAKE, n_q=4, lse=FAKE, a=FAKE):
         return L.hgca_append_weights(byref(sh), q, n_q, byref(view), 0, lse, a, None)
@@ -307,7 +345,9 @@ def test_grouped_entry_points_reject_bad_arguments(hg):
     assert uni(cnt=None) == hg.ERR_INVALID_ARG
     assert uni(out=None) == hg.ERR_INVALID_ARG
     assert uni(n_pos=-1) == hg.ERR_INVALID_ARG
-    assert uni(n_pos=(1 << 19) + 1) == hg.ERR_INVALID_ARG
+    # one bit per position must fit the 64 KiB of LDS a launch gets without asking for more: refused on the host
+    assert uni(n_pos=523776 + 1) == hg.ERR_UNSUPPORTED
+    assert uni(n_pos=1 << 19) == hg.ERR_UNSUPPORTED
     assert uni(k_max=-1) == hg.ERR_INVALID_ARG
 
     def att(q=FAKE, idx=FAKE, cnt=FAKE, k_max=8, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40):

@@ -1,0 +1,233 @@
+"""Multi-turn parity of the managed cache with the numpy fp64 oracle (paper Alg. 1 and both branches of Alg. 2):
+append turns (a prompt of N tokens: attention over the window and over the COMPLETE offloaded cache, moving
+averages updated with the query-averaged weights, salient lists replaced by the re-evaluation of Sec. 3.2.2,
+several blocks evicted at once) interleaved with decode steps.  Both sides run the whole sequence of turns on their
+own from the same seeded tokens.
+
+Bars: O and lse of every query within 2e-4 (bf16 inputs, fp32 accumulation; the stated bar is 2e-2); the
+query-averaged weights A_gpu and A_cpu within 2e-5; moving averages within 2e-5; per-head salient lists
+identical except for entries whose deciding value (A_cpu at a re-evaluation, the moving average at an eviction)
+lies within 1e-5 (relative) of its threshold, where the two sides' rounding may decide differently (after such a
+difference the outputs are held to the stated 2e-2 only); window / pool contents, lengths and block boundaries exact."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle.kv_manager import KvManager
+from paper_2507_03153_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2507_03153_amd import cache, hgca, runner
+    hgca.lib()
+    return torch, hgca, runner, cache
+
+
+def make_tokens(seed, T, B, Hq, Hkv, d, boost=3.0):
+    """Seeded q, k, v per token as bf16 bit patterns [T, B, heads, d].  Every 7th token's key leans towards a fixed
+    direction u of its KV head and every query leans the same way, so those tokens collect weight."""
+    rng = np.random.default_rng(seed)
+    u = rng.standard_normal((B, Hkv, d))
+    u /= np.linalg.norm(u, axis=-1, keepdims=True)
+    q = rng.standard_normal((T, B, Hq, d)) + 2.5 * np.repeat(u, Hq // Hkv, axis=1)[None] * np.sqrt(d) / 4
+    k = rng.standard_normal((T, B, Hkv, d))
+    k[3::7] += boost * u[None] * np.sqrt(d) / 4
+    v = rng.standard_normal((T, B, Hkv, d))
+    return tuple(wl.f32_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v))
+
+
+def run_turns(gpu, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, turns, alpha, beta, seed, one_call=True,
+              prefill=None):
+    torch, hgca, runner, cache = gpu
+    dev = "cuda:0"
+    prefill = prefill or (0,) * B
+    T = max(prefill) + sum(n for _, n in turns)
+    n_max = max(n for kind, n in turns if kind == "a")
+    l_max = win_blocks * block_size
+    win_cap_blocks = -(-(l_max - 1 + n_max) // block_size)
+    say(f"\n[case] turns B={B} Hq={Hq} Hkv={Hkv} d={d} block={block_size} l_max={l_max} window capacity "
+        f"{win_cap_blocks * block_size} prefill={prefill} turns={turns} alpha={alpha} beta={beta} one_call={one_call}")
+    qb, kb, vb = make_tokens(seed, T, B, Hq, Hkv, d)
+    qf, kf, vf = (wl.bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
+    scale = 1.0 / np.sqrt(d)
+    C = cache.LayerCache(torch.bfloat16, B, Hq, Hkv, d, block_size, win_blocks, max_blocks, k_max, scale, dev,
+                         keep_evicted_maw=True, win_cap_blocks=win_cap_blocks)
+    mgr = [KvManager(Hq, Hkv, d, win_blocks, block_size, alpha, beta, scale) for _ in range(B)]
+
+    # sequences start with different window fill, so that their evictions fall on different calls
+    for t in range(max(prefill)):
+        active = np.array([t < p for p in prefill], np.int32)
+        C.append(runner._to_gpu(kb[t], dev), runner._to_gpu(vb[t], dev), torch.from_numpy(active).to(dev))
+    maw0 = np.zeros((B, Hq, C.win_cap), np.float32)
+    for b, p in enumerate(prefill):
+        assert p < l_max
+        maw0[b, :, :p] = 1.0 / max(p, 1)
+        mgr[b].K_gpu, mgr[b].V_gpu = kf[:p, b].copy(), vf[:p, b].copy()
+        mgr[b].A_maw = maw0[b, :, :p].astype(np.float64)
+    C.a_maw.copy_(torch.from_numpy(maw0))
+    torch.cuda.synchronize()
+
+    state = dict(differing=0, worst_o=0.0, worst_l=0.0, worst_a=0.0, evicted_blocks=0, reinstated=0, dropped=0)
+
+    def check_lists(b, near):
+        """near(h, j) says whether pool position j's deciding value lies within rounding of its threshold."""
+        cnt_g, idx_g = C.ctx_cnt.cpu().numpy(), C.ctx_idx.cpu().numpy()
+        for h in range(Hq):
+            got = set(idx_g[b, h, :cnt_g[b, h]].tolist())
+            want = set(mgr[b].ctx[h].tolist())
+            for j in got ^ want:
+                assert near(h, j), f"seq {b} head {h}: lists differ at pool position {j}"
+                state["differing"] += 1
+            row = idx_g[b, h, :cnt_g[b, h]]
+            assert np.all(np.diff(row) > 0) and np.all(idx_g[b, h, cnt_g[b, h]:k_max] == -1)
+
+    t = max(prefill)
+    for kind, n in turns:
+        if kind == "a":
+            as_bn = lambda x: runner._to_gpu(np.ascontiguousarray(x[t:t + n].transpose(1, 0, 2, 3)), dev)
+            C.append_step(as_bn(qb), as_bn(kb), as_bn(vb), alpha, beta, one_call=one_call)
+            torch.cuda.synchronize()
+            o_g, l_g = C.o_app.double().cpu().numpy(), C.lse_app.double().cpu().numpy()
+            ag, ac = C.a_gpu.double().cpu().numpy(), C.a_cpu.double().cpu().numpy()
+            for b in range(B):
+                o_ref, l_ref, A_gpu, A_cpu = mgr[b].append_attention(qf[t:t + n, b], kf[t:t + n, b], vf[t:t + n, b])
+                tol = 2e-4 if state["differing"] == 0 else 2e-2
+                err_o, err_l = np.max(np.abs(o_g[b] - o_ref)), np.max(np.abs(l_g[b] - l_ref))
+                assert err_o <= tol and err_l <= tol, f"append at token {t} seq {b}: dO={err_o} dlse={err_l}"
+                state["worst_o"], state["worst_l"] = max(state["worst_o"], err_o), max(state["worst_l"], err_l)
+                n_old, m_old = mgr[b].K_gpu.shape[0], mgr[b].K_cpu.shape[0]
+                l_cur = n_old + n
+                err_a = max(np.max(np.abs(ag[b, :, :l_cur] - A_gpu), initial=0.0),
+                            np.max(np.abs(ac[b, :, :m_old] - A_cpu), initial=0.0))
+                assert err_a <= 2e-5, f"append at token {t} seq {b}: weights differ by {err_a}"
+                assert np.all(ag[b, :, l_cur:] == 0.0)
+                state["worst_a"] = max(state["worst_a"], err_a)
+                maw_then = np.concatenate([(1 - alpha) * mgr[b].A_maw + alpha * A_gpu[:, :n_old], A_gpu[:, n_old:]], 1)
+                before = [set(c.tolist()) for c in mgr[b].ctx]
+                ev = mgr[b].manage_append(kf[t:t + n, b], vf[t:t + n, b], A_gpu, A_cpu)
+                state["evicted_blocks"] = max(state["evicted_blocks"], ev // block_size)
+                for h in range(Hq):
+                    after = set(j for j in mgr[b].ctx[h].tolist() if j < m_old)
+                    state["reinstated"] += len(after - before[h])
+                    state["dropped"] += len(before[h] - after)
+
+                def near(h, j, m_old=m_old, l_cur=l_cur, A_cpu=A_cpu, maw_then=maw_then):
+                    if j < m_old:                               # decided by the re-evaluation
+                        thr = beta / m_old
+                        return abs(A_cpu[h, j] - thr) <= 1e-5 * thr
+                    thr = beta / l_cur                          # decided at this call's eviction
+                    return abs(maw_then[h, j - m_old] - thr) <= 1e-5 * thr
+                check_lists(b, near)
+            t += n
+            continue
+        for _ in range(n):
+            C.decode_step(runner._to_gpu(qb[t], dev), runner._to_gpu(kb[t], dev), runner._to_gpu(vb[t], dev), alpha, beta,
+                          one_call=one_call)
+            torch.cuda.synchronize()
+            o_g, l_g = C.o.double().cpu().numpy(), C.lse.double().cpu().numpy()
+            for b in range(B):
+                o_ref, l_ref, A_gpu = mgr[b].hybrid_attention(qf[t, b], kf[t, b], vf[t, b])
+                tol = 2e-4 if state["differing"] == 0 else 2e-2
+                err_o, err_l = np.max(np.abs(o_g[b] - o_ref)), np.max(np.abs(l_g[b] - l_ref))
+                assert err_o <= tol and err_l <= tol, f"decode at token {t} seq {b}: dO={err_o} dlse={err_l}"
+                state["worst_o"], state["worst_l"] = max(state["worst_o"], err_o), max(state["worst_l"], err_l)
+                l_cur, m_old = mgr[b].K_gpu.shape[0] + 1, mgr[b].K_cpu.shape[0]
+                maw_then = np.concatenate([(1 - alpha) * mgr[b].A_maw + alpha * A_gpu[:, :-1], A_gpu[:, -1:]], 1)
+                mgr[b].manage(kf[t, b], vf[t, b], A_gpu)
+
+                def near(h, j, m_old=m_old, l_cur=l_cur, maw_then=maw_then):
+                    thr = beta / l_cur
+                    return j >= m_old and abs(maw_then[h, j - m_old] - thr) <= 1e-5 * thr
+                check_lists(b, near)
+            t += 1
+
+    # final state
+    win_lens, pool_lens, first = (x.cpu().numpy() for x in (C.win_lens, C.pool_lens, C.first_win_block))
+    maw_g, aev_g = C.a_maw.double().cpu().numpy(), C.a_evicted.double().cpu().numpy()
+    kblk, vblk, table = C.k_blocks.cpu().view(torch.int16).numpy().view(np.uint16), \
+        C.v_blocks.cpu().view(torch.int16).numpy().view(np.uint16), C.block_table.cpu().numpy()
+    for b in range(B):
+        n, m = mgr[b].K_gpu.shape[0], mgr[b].K_cpu.shape[0]
+        assert win_lens[b] == n and pool_lens[b] == m and first[b] * block_size == m and n < l_max
+        assert np.max(np.abs(maw_g[b, :, :n] - mgr[b].A_maw), initial=0.0) <= 2e-5
+        assert np.all(maw_g[b, :, n:] == 0.0)
+        assert np.max(np.abs(aev_g[b, :, :m] - mgr[b].A_cpu_maw), initial=0.0) <= 2e-5
+        toks = [tt for tt in range(T) if tt < prefill[b] or tt >= max(prefill)]
+        assert len(toks) == n + m
+        for pos, tt in enumerate(toks):                          # every token of the sequence, in arrival order
+            blk, slot = table[b, pos // block_size], pos % block_size
+            assert np.array_equal(kblk[blk, :, slot], kb[tt, b]) and np.array_equal(vblk[blk, :, slot], vb[tt, b])
+    status = int(C.status.cpu()[0])
+    cnt_g = C.ctx_cnt.cpu().numpy()
+    say(f"    max|dO|={state['worst_o']:.2e} max|dlse|={state['worst_l']:.2e} max|dA|={state['worst_a']:.2e}; most blocks "
+        f"evicted by one call: {state['evicted_blocks']}; re-evaluations reinstated {state['reinstated']} and dropped "
+        f"{state['dropped']} list entries; decided differently inside the rounding band: {state['differing']}; kept per "
+        f"head: {cnt_g.min()}..{cnt_g.max()} of {pool_lens.max()}; status={status}")
+    return C, mgr, status, state
+
+
+TURNS = [("a", 40), ("d", 30), ("a", 33), ("d", 20), ("a", 1), ("d", 17), ("a", 70), ("d", 25)]
+
+
+@pytest.mark.parametrize("one_call", [True, False], ids=["one_call", "separate_calls"])
+def test_append_and_decode_turns_gqa4(gpu, one_call):
+    C, mgr, status, st = run_turns(gpu, B=3, Hq=8, Hkv=2, d=128, block_size=16, win_blocks=4, max_blocks=32, k_max=320,
+                                   turns=TURNS, alpha=0.3, beta=1.0, seed=31, one_call=one_call, prefill=(0, 37, 63))
+    assert status == 0
+    assert st["evicted_blocks"] >= 4                            # the 70-token prompt pushes out several blocks at once
+    assert st["reinstated"] > 0 and st["dropped"] > 0          # the re-evaluation replaces the lists, both ways
+
+
+def test_turns_mha_head_dim_64_blocks_of_32(gpu):
+    _, _, status, _ = run_turns(gpu, B=2, Hq=4, Hkv=4, d=64, block_size=32, win_blocks=2, max_blocks=12, k_max=320,
+                                turns=[("a", 50), ("d", 40), ("a", 64), ("d", 10), ("a", 17), ("d", 33)], alpha=0.5,
+                                beta=0.7, seed=32, prefill=(5, 40))
+    assert status == 0
+
+
+def test_turns_beta_zero_keep_everything(gpu):
+    """beta = 0: nothing is dropped at evictions or re-evaluations, so every decode step attends to the whole
+    history (the oracle is pinned to exactly that with library softmax)."""
+    C, mgr, status, _ = run_turns(gpu, B=2, Hq=8, Hkv=1, d=128, block_size=16, win_blocks=2, max_blocks=16, k_max=256,
+                                  turns=[("a", 45), ("d", 20), ("a", 30), ("d", 40)], alpha=0.2, beta=0.0, seed=33)
+    assert status == 0
+    assert np.array_equal(C.ctx_cnt.cpu().numpy(), np.repeat(C.pool_lens.cpu().numpy()[:, None], 8, axis=1))
+
+
+def test_prompt_beyond_the_window_capacity_is_refused_whole(gpu):
+    torch, hgca, runner, cache = gpu
+    say("\n[case] prompt longer than the window's capacity")
+    C = cache.LayerCache(torch.bfloat16, 1, 4, 2, 128, 16, 2, 8, 64, 0.1, win_cap_blocks=3)     # capacity 48 tokens
+    tok = torch.ones(1, 40, 2, 128, dtype=torch.bfloat16, device="cuda:0")
+    hgca.kv_append_tokens(C.shape, C.state, tok, tok)
+    hgca.kv_append_tokens(C.shape, C.state, tok, tok)            # 40 + 40 > 48: none of them is inserted
+    torch.cuda.synchronize()
+    assert int(C.win_lens.cpu()[0]) == 40 and int(C.status.cpu()[0]) == hgca.CACHE_WINDOW_FULL
+
+
+def test_re_evaluation_reports_a_list_that_is_too_short(gpu):
+    """With beta = 0 the re-evaluation keeps every offloaded entry; a list of 8 cannot hold them: the first 8 stay and
+    the status says so."""
+    torch, hgca, runner, cache = gpu
+    say("\n[case] re-evaluation into a list that is too short")
+    B, Hq, Hkv, d = 1, 4, 2, 128
+    qb, kb, vb = make_tokens(34, 80, B, Hq, Hkv, d)
+    dev = "cuda:0"
+    C = cache.LayerCache(torch.bfloat16, B, Hq, Hkv, d, 16, 2, 12, 8, 1.0 / np.sqrt(d), dev, win_cap_blocks=5)
+    as_bn = lambda x, a, b: runner._to_gpu(np.ascontiguousarray(x[a:b].transpose(1, 0, 2, 3)), dev)
+    C.append_step(as_bn(qb, 0, 40), as_bn(kb, 0, 40), as_bn(vb, 0, 40), 0.3, 0.0)
+    C.append_step(as_bn(qb, 40, 60), as_bn(kb, 40, 60), as_bn(vb, 40, 60), 0.3, 0.0)
+    torch.cuda.synchronize()
+    assert int(C.status.cpu()[0]) == hgca.CACHE_LIST_FULL
+    assert np.array_equal(C.ctx_idx.cpu().numpy()[0, :, :8], np.broadcast_to(np.arange(8, dtype=np.int32), (4, 8)))
