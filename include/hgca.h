@@ -474,7 +474,7 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
  * hgca_kv_append_tokens, hgca_append_attn on the window (causal tail) and on the
  * pool, hgca_lse_merge, hgca_append_weights on both, hgca_maw_update (n_new =
  * n_q), hgca_threshold_select on a_cpu and hgca_kv_evict in that order.
- * q is [B, n_q, Hq, d], k_in / v_in [B, n_q, Hkv, d] (bf16, as hgca_append_attn);
+ * q is [B, n_q, Hq, d], k_in / v_in [B, n_q, Hkv, d] (dtypes as hgca_append_attn);
  * flags: HGCA_APPEND_ONE_PART_P or 0; a_gpu (fp32 [B,Hq,window capacity]) and
  * a_cpu (fp32 [B,Hq,pool_cap]) receive the two weight rows (0 beyond the
  * lengths); o_out is fp32 [B,n_q,Hq,d], lse_out fp32
@@ -508,7 +508,10 @@ int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool,
                      int32_t ctx_cap, int32_t *cnt_out, void *hip_stream);
 
 /* ---- Append stage (Sec. 2.1: N incoming tokens, Q in R^{h x N x d}; Alg. 2,
- * append branch).  bf16 only (both contractions run on the matrix cores). ----
+ * append branch).  bf16 inputs run both contractions on the matrix cores;
+ * fp32 inputs (the exact shapes) run on the vector units: every (sequence,
+ * query) pair is then a one-query attention over the tokens that query sees,
+ * served by the split kernels of the decode path (B * n_q <= 65 535). ----
  *
  * q is [B, N, Hq, d].  Attention of all N queries over one tier; the two parts
  * of the hybrid step are two calls (the window with HGCA_APPEND_CAUSAL_TAIL,
@@ -522,7 +525,8 @@ int hgca_ctx_compact(const hgca_shape *shape, const hgca_kv_view *pool,
  * rounded once to bf16 (relative error 2^-9 per weight: |dO| <= 2^-9 max|v|,
  * typically ~1e-3 for unit-variance V; lse unaffected), a third fewer matrix
  * instructions.  Without it they enter as a high and a low bf16 part and O
- * keeps fp32-level accuracy (~1e-6).
+ * keeps fp32-level accuracy (~1e-6).  (Ignored for fp32 inputs, whose weights
+ * stay fp32 throughout.)
  * Other bits are rejected.  shape.sm_scale must be positive and finite for the
  * append entry points.  o_out is fp32 [B, N, Hq, d], lse_out fp32
  * [B, N, Hq]; a query that sees nothing gives O = 0, lse = -inf.  ws needs

@@ -482,6 +482,82 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     }
 }
 
+// The same weights for fp32 inputs, on the VALU (the fp32 shapes are the small, exact ones: this pass is written for
+// clarity, not for bandwidth).  One workgroup = 64 tokens of one (sequence, KV head): their K rows are parked in LDS
+// (one pad per row, a thread walks its own row); thread (t, part) adds e^{s_it - lse_i} over the queries
+// i = part, part + 4, ... for every head of the group, the four parts are added through LDS.
+constexpr int kF32Tokens = 64, kF32Block = 256, kF32Parts = kF32Block / kF32Tokens;
+
+template <int D, int G>
+__global__ __launch_bounds__(kF32Block) void append_weights_f32_kernel(AppendArgs a)
+{
+    __shared__ float s_k[kF32Tokens][D + 1];
+    __shared__ float s_q[kF32Parts][D];
+    __shared__ float s_sum[kF32Parts][G][kF32Tokens];
+    __shared__ uint32_t s_row[kF32Tokens];
+
+    const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, t = tid % kF32Tokens, part = tid / kF32Tokens;
+    const int len = tier_len(a.kv, b);
+    const int t0 = chunk_id * kF32Tokens;
+    const int n_here = min(kF32Tokens, a.kv.cap - t0);           // entries of a_out this workgroup writes
+    const int nt = min(kF32Tokens, len - t0);                    // valid tokens among them (may be <= 0)
+    float *out = a.a_out + ((int64_t)b * a.sh.n_q_heads + kvh * G) * a.kv.cap + t0;
+    if (nt <= 0) {                                               // uniform over the workgroup
+        for (int i = tid; i < G * n_here; i += kF32Block) out[(int64_t)(i / n_here) * a.kv.cap + i % n_here] = 0.f;
+        return;
+    }
+    const RowMap rows = make_row_map<false, kF32Block>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nt, nullptr);
+    const float *k = reinterpret_cast<const float *>(a.kv.k);
+    for (int i = tid; i < nt * D; i += kF32Block) s_k[i / D][i % D] = k[(int64_t)rows(i / D) * D + i % D];
+    const float *q = static_cast<const float *>(a.q);
+    float acc[G];
+#pragma unroll
+    for (int gh = 0; gh < G; ++gh) acc[gh] = 0.f;
+    const int rounds = (a.n_q + kF32Parts - 1) / kF32Parts;
+    for (int gh = 0; gh < G; ++gh) {
+        const int h = kvh * G + gh;
+        for (int r = 0; r < rounds; ++r) {
+            const int i = r * kF32Parts + part;                  // this part's query of the round
+            __syncthreads();                                     // the K rows are in place; the previous query is done with
+            if (i < a.n_q)
+                for (int e = t; e < D; e += kF32Tokens) s_q[part][e] = q[(((int64_t)b * a.n_q + i) * a.sh.n_q_heads + h) * D + e];
+            __syncthreads();
+            if (i >= a.n_q || t >= nt) continue;                 // no barrier below this line inside the round
+            const int vis = a.causal_tail ? min(max(len - a.n_q + i + 1, 0), len) : len;
+            if (t0 + t >= vis) continue;
+            float dot = 0.f;
+#pragma unroll 8
+            for (int e = 0; e < D; ++e) dot = fmaf(s_q[part][e], s_k[t][e], dot);
+            acc[gh] += expf(dot * a.sh.sm_scale - a.lse[((int64_t)b * a.n_q + i) * a.sh.n_q_heads + h]);
+        }
+    }
+#pragma unroll
+    for (int gh = 0; gh < G; ++gh) s_sum[part][gh][t] = acc[gh];
+    __syncthreads();
+    const float inv_n = 1.f / (float)a.n_q;
+    for (int i = tid; i < G * n_here; i += kF32Block) {
+        const int gh = i / n_here, j = i % n_here;
+        float v = 0.f;
+#pragma unroll
+        for (int p = 0; p < kF32Parts; ++p) v += s_sum[p][gh][j];
+        out[(int64_t)gh * a.kv.cap + j] = j < nt ? v * inv_n : 0.f;
+    }
+}
+
+template <int D>
+hipError_t launch_weights_f32_group(const AppendArgs &a, dim3 grid, hipStream_t s)
+{
+    switch (a.sh.group) {
+    case 1: hipLaunchKernelGGL((append_weights_f32_kernel<D, 1>), grid, dim3(kF32Block), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((append_weights_f32_kernel<D, 2>), grid, dim3(kF32Block), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((append_weights_f32_kernel<D, 4>), grid, dim3(kF32Block), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((append_weights_f32_kernel<D, 8>), grid, dim3(kF32Block), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <int D, bool SPLIT_P>
 hipError_t launch_attn_group(const AppendArgs &a, dim3 grid, hipStream_t s)
 {
@@ -528,6 +604,15 @@ hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks
     dim3 grid(n_chunks, a.sh.n_kv_heads, a.sh.batch);
     if (head_dim == 64) return launch_weights_group<64>(a, grid, s);
     if (head_dim == 128) return launch_weights_group<128>(a, grid, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_append_weights_f32(int head_dim, const AppendArgs &a, hipStream_t s)
+{
+    if (a.sh.batch == 0 || a.kv.cap == 0) return hipSuccess;
+    dim3 grid((a.kv.cap + kF32Tokens - 1) / kF32Tokens, a.sh.n_kv_heads, a.sh.batch);
+    if (head_dim == 64) return launch_weights_f32_group<64>(a, grid, s);
+    if (head_dim == 128) return launch_weights_f32_group<128>(a, grid, s);
     return hipErrorInvalidValue;
 }
 

@@ -874,7 +874,9 @@ struct AppendWs {
 AppendWs append_layout(const hgca_shape *s, int32_t n_q, int64_t max_tokens)
 {
     AppendWs w{};
-    w.max_splits = std::max(append_want_splits(s, n_q), n_splits_for(std::max<int64_t>(max_tokens, 1), kMaxAppendChunk));
+    // bf16: splits of up to kMaxAppendChunk tokens; fp32 runs on the one-query kernels, whose splits hold kMaxChunk
+    w.max_splits = std::max(append_want_splits(s, n_q), n_splits_for(std::max<int64_t>(max_tokens, 1),
+                                                                     s->dtype == HGCA_F32 ? kMaxChunk : kMaxAppendChunk));
     const size_t rows = (size_t)s->batch * n_q * s->n_q_heads;
     size_t at = 0;
     w.o = at; at += align_up(rows * w.max_splits * s->head_dim * sizeof(float));
@@ -889,7 +891,6 @@ int check_append(const hgca_shape *shape, const void *q, int32_t n_q, const hgca
     int rc = check_shape(shape);
     if (rc != HGCA_OK) return rc;
     if (n_q < 0 || n_q > 4096) return HGCA_ERR_INVALID_ARG;
-    if (shape->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;      // the MFMA path is bf16 only
     // the kernels keep the running maximum on the raw scores and apply the scale inside the exponent
     if (!(shape->sm_scale > 0.f) || !(shape->sm_scale < 3.0e38f)) return HGCA_ERR_INVALID_ARG;
     if ((rc = check_view(shape, tier, need_v)) != HGCA_OK) return rc;
@@ -919,6 +920,32 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const 
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
+    if (shape->dtype == HGCA_F32) {
+        // fp32 inputs: every (sequence, query) pair is a one-query attention over the tokens that query sees, so the
+        // split kernels of the decode path serve, on a batch of B * n_q queries that share their sequence's rows
+        if ((int64_t)shape->batch * n_q > 65535) return HGCA_ERR_UNSUPPORTED;
+        AttnArgs d{};
+        d.sh = to_dev(shape);
+        d.sh.batch = shape->batch * n_q;
+        d.q = q;
+        d.kv = to_dev(tier);
+        d.kv.n_q = n_q;
+        d.kv.causal_tail = (flags & HGCA_APPEND_CAUSAL_TAIL) ? 1 : 0;
+        d.chunk = pick_chunk(tier->cap, (int64_t)d.sh.batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
+        char *base = static_cast<char *>(ws);
+        d.part.o = reinterpret_cast<float *>(base + w.o);
+        d.part.m = reinterpret_cast<float *>(base + w.m);
+        d.part.l = reinterpret_cast<float *>(base + w.l);
+        d.part.n_splits = std::max(1, n_splits_for(tier->cap, d.chunk));
+        if (d.part.n_splits > w.max_splits) return HGCA_ERR_WORKSPACE;
+        const int64_t rows = (int64_t)d.sh.batch * shape->n_q_heads;
+        if (tier->cap == 0) {                    // nothing to attend to: the fold of one empty split writes O = 0, lse = -inf
+            Partials none{};
+            return from_hip(launch_combine2(shape->head_dim, rows, none, none, o_out, 0, lse_out, s));
+        }
+        if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, d, s))) != HGCA_OK) return rc;
+        return from_hip(launch_combine(shape->head_dim, rows, d.part, o_out, lse_out, s));
+    }
     AppendArgs a{};
     a.sh = to_dev(shape);
     a.q = q;
@@ -954,6 +981,8 @@ int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, con
     a.causal_tail = causal_tail ? 1 : 0;
     a.lse = lse;
     a.a_out = a_out;
+    if (shape->dtype == HGCA_F32)
+        return from_hip(launch_append_weights_f32(shape->head_dim, a, static_cast<hipStream_t>(hip_stream)));
     const int64_t units = (int64_t)shape->batch * shape->n_kv_heads;
     a.chunk = 2048;                                  // tokens per workgroup, halved until the GPU is filled
     while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < 1024) a.chunk /= 2;

@@ -17,6 +17,10 @@ struct KvDev {
     const int32_t *block_table;
     const int32_t *first_block;     // paged only: per-sequence offset into the table row, or null
     int32_t cap, block_size, max_blocks;
+    // N queries per sequence on a path written for one: batch index bv of the launch stands for query bv % n_q of
+    // sequence bv / n_q (n_q <= 1: off).  With causal_tail the tier's last n_q valid tokens are the queries' own and
+    // query i sees the tokens before position len - n_q + i + 1.
+    int32_t n_q, causal_tail;
 };
 
 // Shape scalars passed by value to kernels.
@@ -45,8 +49,14 @@ template <> struct Elem<bf16_t> {
     }
 };
 
+// The sequence whose K/V rows batch index b of a launch reads.
+__device__ __forceinline__ int kv_seq(const KvDev &kv, int b) { return kv.n_q > 1 ? b / kv.n_q : b; }
+
 __device__ __forceinline__ int32_t tier_len(const KvDev &kv, int b) {
-    return kv.seq_lens ? min(max(kv.seq_lens[b], 0), kv.cap) : kv.cap;   // never beyond the buffer
+    const int seq = kv_seq(kv, b);
+    const int32_t len = kv.seq_lens ? min(max(kv.seq_lens[seq], 0), kv.cap) : kv.cap;   // never beyond the buffer
+    if (kv.n_q > 1 && kv.causal_tail) return min(max(len - kv.n_q + (b - seq * kv.n_q) + 1, 0), len);
+    return len;
 }
 
 __device__ __forceinline__ uint4 load16(const char *p) {

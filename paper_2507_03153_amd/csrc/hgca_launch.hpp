@@ -124,6 +124,8 @@ struct AppendArgs {
 };
 hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s);
 hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks, hipStream_t s);
+// the same for fp32 inputs (q [B, N, Hq, d] fp32, fp32 tier): VALU pass, 64 tokens per workgroup
+hipError_t launch_append_weights_f32(int head_dim, const AppendArgs &a, hipStream_t s);
 
 // ---- KV manager over a block pool (mirrors hgca_cache_state; all pointers device memory) ----
 

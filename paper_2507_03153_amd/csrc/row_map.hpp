@@ -40,6 +40,7 @@ template <bool GATHER, int BLOCK>
 __device__ __forceinline__ RowMap make_row_map(uint32_t *s_row, const KvDev &kv, int n_kv_heads, int b, int kvh,
                                                int t0, int nt, const int32_t *listed)
 {
+    b = kv_seq(kv, b);                           // the sequence whose rows are read
     RowMap m;
     if (!GATHER && kv.block_table == nullptr) {
         m.table = nullptr;

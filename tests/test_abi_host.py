@@ -267,7 +267,7 @@ def test_kv_manager_entry_points_reject_bad_arguments(hg):
     assert turn(state(block_size=24)) == hg.ERR_UNSUPPORTED
     f32 = hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)
     assert L.hgca_managed_append_step(ctypes.byref(f32), ctypes.byref(st6), FAKE, FAKE, FAKE, 8, 0.3, 1.0, 0, FAKE, FAKE,
-                                      FAKE, FAKE, FAKE, 1 << 40, None) == hg.ERR_UNSUPPORTED   # append stage: bf16
+                                      FAKE, FAKE, FAKE, 64, None) == hg.ERR_WORKSPACE          # fp32 is served too
     assert turn(st6, n_q=0, q=None) == hg.OK                     # an empty prompt: nothing to do
 
     def evict(st, beta=1.0):
@@ -311,7 +311,8 @@ def test_append_entry_points_reject_bad_arguments(hg):
     assert attn(lse=None) == hg.ERR_INVALID_ARG
     assert attn(ws=None) == hg.ERR_WORKSPACE
     assert attn(ws_bytes=64) == hg.ERR_WORKSPACE
-    assert attn(shape=hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)) == hg.ERR_UNSUPPORTED      # bf16 only
+    assert attn(shape=hg.Shape(hg.F32, 2, 8, 2, 128, 0.088), ws_bytes=64) == hg.ERR_WORKSPACE   # fp32 is served too
+    assert attn(shape=hg.Shape(hg.F32, 4096, 8, 2, 128, 0.088), n_q=32) == hg.ERR_UNSUPPORTED     # B * n_q > 65 535
     assert attn(n_q=0) == hg.OK                                                          # nothing to do
     # (KV head, block of 128 query rows) pairs are one grid dimension: 2048 heads x 32 blocks do not fit 65 535
     assert attn(shape=hg.Shape(hg.BF16, 1, 2048, 2048, 128, 0.088), n_q=4096) == hg.ERR_UNSUPPORTED

@@ -183,10 +183,11 @@ def test_append_long_pool_many_splits_and_row_table_refills(gpu):
 
 
 @pytest.mark.timeout(600)
-def test_append_full_size_c2_sampled(gpu):
+@pytest.mark.timeout(600)
+def test_append_full_size_c2_every_unit(gpu):
     """The shape and launch configuration bench.py times for the append stage (B=8, N=32, 32 query heads on 8 KV
-    heads, window 4096, pool 28672); the oracle computes sampled (sequence, head) pairs: all N queries of the pair
-    and its two query-averaged weight rows."""
+    heads, window 4096, pool 28672); the oracle computes every one of the 256 (sequence, head) units: all N queries
+    of the unit, both parts, the merge and the two query-averaged weight rows."""
     torch, hgca, runner = gpu
     dev = "cuda:0"
     c2 = wl.CONFIGS["C2"]
@@ -223,27 +224,112 @@ def test_append_full_size_c2_sampled(gpu):
     # every averaged weight row sums to 1 over what is visible (holds at any size)
     assert float((a_gpu.sum(-1) - 1).abs().max()) <= 1e-4 and float((a_cpu.sum(-1) - 1).abs().max()) <= 1e-4
 
+    # every (sequence, head) unit against the oracle: all N queries of the unit, both parts, the merge, and the two
+    # query-averaged weight rows (a few of them printed)
     f = lambda x: wl.bf16_bits_to_f32(x).astype(np.float64)
-    rng = np.random.default_rng(42)
-    pairs = [(1, 5), (0, 0), (B - 1, Hq - 1)] + [(int(rng.integers(B)), int(rng.integers(Hq))) for _ in range(5)]
-    for b, h in pairs:
-        kvh = h // G
-        qs = f(q[b:b + 1, :, h:h + 1])
-        part = lambda K, V, lens, causal: ap.part_attention(qs, f(K[b:b + 1, kvh:kvh + 1]), f(V[b:b + 1, kvh:kvh + 1]),
-                                                            lens[b:b + 1], scale, causal)
-        o_g, l_g, A_g = part(Kw, Vw, wl_, True)
-        o_c, l_c, A_c = part(Kp, Vp, pl_, False)
-        o_r, l_r = ap.merge_state(o_c, l_c, o_g, l_g)
-        errs = {}
-        for name, got, want in (("O_gpu", ow[b, :, h], o_g[0, :, 0]), ("lse_g", lw[b, :, h], l_g[0, :, 0]),
-                                ("O_cpu", op[b, :, h], o_c[0, :, 0]), ("lse_c", lp[b, :, h], l_c[0, :, 0]),
-                                ("O", o[b, :, h], o_r[0, :, 0]), ("lse", lse[b, :, h], l_r[0, :, 0]),
-                                ("A_gpu", a_gpu[b, h], A_g[0, 0].mean(axis=0)), ("A_cpu", a_cpu[b, h], A_c[0, 0].mean(axis=0))):
-            errs[name] = float(np.max(np.abs(got.double().cpu().numpy() - want)))
-        say(f"    (b={b}, h={h}): " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
-        assert max(errs["O_gpu"], errs["O_cpu"], errs["O"]) <= 2e-4
-        assert max(errs["lse_g"], errs["lse_c"], errs["lse"], errs["A_gpu"], errs["A_cpu"]) <= 2e-5
-        assert np.all(a_gpu[b, h, wl_[b]:].cpu().numpy() == 0) and np.all(a_cpu[b, h, pl_[b]:].cpu().numpy() == 0)
+    got = {name: t.double().cpu().numpy() for name, t in (("O_gpu", ow), ("lse_g", lw), ("O_cpu", op), ("lse_c", lp),
+                                                          ("O", o), ("lse", lse), ("A_gpu", a_gpu), ("A_cpu", a_cpu))}
+
+    def unit_group(b, kvh):
+        """The G heads that share KV head kvh of sequence b: worst error per quantity."""
+        kw, vw, kp, vp = (f(x[b:b + 1, kvh:kvh + 1]) for x in (Kw, Vw, Kp, Vp))
+        worst = {}
+        for h in range(kvh * G, (kvh + 1) * G):
+            qs = f(q[b:b + 1, :, h:h + 1])
+            o_g, l_g, A_g = ap.part_attention(qs, kw, vw, wl_[b:b + 1], scale, True)
+            o_c, l_c, A_c = ap.part_attention(qs, kp, vp, pl_[b:b + 1], scale, False)
+            o_r, l_r = ap.merge_state(o_c, l_c, o_g, l_g)
+            want = {"O_gpu": o_g[0, :, 0], "lse_g": l_g[0, :, 0], "O_cpu": o_c[0, :, 0], "lse_c": l_c[0, :, 0],
+                    "O": o_r[0, :, 0], "lse": l_r[0, :, 0], "A_gpu": A_g[0, 0].mean(axis=0), "A_cpu": A_c[0, 0].mean(axis=0)}
+            for name, ref in want.items():
+                mine = got[name][b, h] if name.startswith("A_") else got[name][b, :, h]
+                worst[name] = max(worst.get(name, 0.0), float(np.max(np.abs(mine - ref))))
+            assert np.all(got["A_gpu"][b, h, wl_[b]:] == 0) and np.all(got["A_cpu"][b, h, pl_[b]:] == 0)
+        return b, kvh, worst
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(8) as pool_:
+        results = list(pool_.map(lambda bk: unit_group(*bk), [(b, kvh) for b in range(B) for kvh in range(Hkv)]))
+    assert len(results) * G == B * Hq                           # all 256 units
+    for b, kvh, errs in results:
+        if kvh in (0, Hkv - 1):
+            say(f"    (b={b}, heads {kvh * G}..{kvh * G + G - 1}): " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+        assert max(errs["O_gpu"], errs["O_cpu"], errs["O"]) <= 2e-4, (b, kvh, errs)
+        assert max(errs["lse_g"], errs["lse_c"], errs["lse"], errs["A_gpu"], errs["A_cpu"]) <= 2e-5, (b, kvh, errs)
+
+
+def run_case_f32(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=False):
+    """fp32 inputs: the bar is 1e-5 on O and lse of both parts and of the merge, and on the averaged weights."""
+    torch, hgca, runner = gpu
+    dev = "cuda:0"
+    say(f"\n[case] append fp32 N={N} B={B} Hq={Hq} Hkv={Hkv} d={d} W={W} P={P} w_lens={w_lens} p_lens={p_lens} paged={paged}")
+    qb, Kwb, Vwb, wl_, Kpb, Vpb, pl_ = make_inputs(seed, B, N, Hq, Hkv, d, W, P, w_lens, p_lens)
+    rng = np.random.default_rng(seed + 100)
+    # fp32 values with a full mantissa: the bf16 draw plus a small fp32 perturbation
+    full = lambda bits: (wl.bf16_bits_to_f32(bits) + 1e-3 * rng.standard_normal(bits.shape)).astype(np.float32)
+    q, Kw, Vw, Kp, Vp = (full(x) for x in (qb, Kwb, Vwb, Kpb, Vpb))
+    scale = 1.0 / np.sqrt(d)
+    f = lambda x: x.astype(np.float64)
+    o_g, l_g, A_g = ap.part_attention(f(q), f(Kw), f(Vw), wl_, scale, True)
+    o_c, l_c, A_c = ap.part_attention(f(q), f(Kp), f(Vp), pl_, scale, False)
+    o_ref, l_ref = ap.merge_state(o_c, l_c, o_g, l_g)
+    g = lambda a: runner._to_gpu(a, dev)
+    qd = g(q)
+    if paged:
+        win = to_paged(runner, hgca, torch, Kw, Vw, wl_, W, 16, seed + 1, dev)
+        pool = to_paged(runner, hgca, torch, Kp, Vp, pl_, max(P, 1), 16, seed + 2, dev)
+        pool.cap = P
+    else:
+        win = hgca.Tier(g(Kw), g(Vw), W, g(wl_))
+        pool = hgca.Tier(g(Kp), g(Vp), P, g(pl_))
+    shape = hgca.Shape(hgca.F32, B, Hq, Hkv, d, scale)
+    f32 = dict(dtype=torch.float32, device=dev)
+    ws = hgca.append_workspace(shape, N, max(W, P), dev)
+    ow, lw = torch.full((B, N, Hq, d), float("nan"), **f32), torch.full((B, N, Hq), float("nan"), **f32)
+    op, lp = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
+    hgca.append_attn(shape, qd, win, True, ow, lw, ws)
+    hgca.append_attn(shape, qd, pool, False, op, lp, ws)
+    o, lse = torch.empty_like(ow), torch.empty_like(lw)
+    hgca.lse_merge(hgca.Shape(hgca.F32, B * N, Hq, Hkv, d, scale), op, lp, ow, lw, o, lse)
+    a_gpu = torch.full((B, Hq, W), float("nan"), **f32)
+    a_cpu = torch.full((B, Hq, max(P, 1)), float("nan"), **f32)
+    hgca.append_weights(shape, qd, win, True, lw, a_gpu)
+    hgca.append_weights(shape, qd, pool, False, lp, a_cpu)
+    torch.cuda.synchronize()
+    for name, o_t, l_t, o_r, l_r in (("window (causal)", ow, lw, o_g, l_g), ("pool", op, lp, o_c, l_c),
+                                     ("merged", o, lse, o_ref, l_ref)):
+        o_t, l_t = o_t.double().cpu().numpy(), l_t.double().cpu().numpy()
+        empty = np.isneginf(l_r)
+        assert np.array_equal(np.isneginf(l_t), empty), f"{name}: empty sets differ"
+        assert np.all(np.isfinite(o_t)) and np.all(o_t[empty] == 0)
+        err_l = np.max(np.abs(l_t[~empty] - l_r[~empty]), initial=0.0)
+        err_o = np.max(np.abs(o_t - o_r), initial=0.0)
+        say(f"    {name}: max|dO|={err_o:.2e} max|dlse|={err_l:.2e} (bar 1e-5)")
+        assert err_l <= 1e-5 and err_o <= 1e-5, f"{name}: dO={err_o} dlse={err_l}"
+    for name, a_t, A, lens, cap in (("A_gpu", a_gpu, A_g, wl_, W), ("A_cpu", a_cpu, A_c, pl_, P)):
+        a_t = a_t.double().cpu().numpy()[:, :, :cap]
+        err = np.max(np.abs(a_t - A.mean(axis=2)), initial=0.0)
+        say(f"    {name}: max|dA|={err:.2e}")
+        assert err <= 1e-5
+        for b in range(B):
+            assert np.all(a_t[b, :, lens[b]:] == 0.0)
+            if lens[b] and (name == "A_cpu" or lens[b] >= N):
+                assert np.max(np.abs(a_t[b, :, :lens[b]].sum(-1) - 1.0)) <= 1e-5
+
+
+def test_append_fp32_tiny_config_shape(gpu):
+    """The fp32 configuration's shape (B=1, 4 MHA heads of 64, window 256, pool 2048) with a prompt of 32 tokens."""
+    run_case_f32(gpu, 51, B=1, N=32, Hq=4, Hkv=4, d=64, W=256, P=2048)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(B=2, N=5, Hq=8, Hkv=2, d=128, W=100, P=333),
+    dict(B=3, N=17, Hq=8, Hkv=1, d=64, W=300, P=700, w_lens=(300, 17, 5), p_lens=(700, 0, 64)),     # a prompt longer than the window
+    dict(B=2, N=9, Hq=4, Hkv=2, d=128, W=160, P=600, w_lens=(160, 33), p_lens=(555, 600), paged=True),
+    dict(B=1, N=3, Hq=2, Hkv=2, d=64, W=64, P=0),
+], ids=["gqa4", "gqa8_ragged", "paged", "no_pool"])
+def test_append_fp32_shapes(gpu, kw):
+    run_case_f32(gpu, 52, **kw)
 
 
 def test_reevaluation_threshold_on_a_cpu(gpu, oracle):
