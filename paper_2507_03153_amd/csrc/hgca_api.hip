@@ -112,6 +112,14 @@ int pick_chunk(int64_t n, int64_t units, int target, int max_chunk = kMaxChunk)
 
 int n_splits_for(int64_t n, int chunk) { return (int)((n + chunk - 1) / chunk); }
 
+// Tokens per workgroup of the score pass over a pool of `cap` tokens.  Groups of 8 heads take half the tokens per
+// workgroup (64 instead of 128 on the 70B shape: 317 against 321 us per step).
+int score_chunk(const hgca_shape *s, int64_t cap)
+{
+    const int target = HGCA_TARGET_WGS_SCORES * (s->n_q_heads / s->n_kv_heads >= 8 ? 2 : 1);
+    return pick_chunk(cap, (int64_t)s->batch * s->n_kv_heads, target, s->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+}
+
 // Workspace layout: [partials o | partials m | partials l | one float per row | scores | scores of the kept entries].
 struct WsLayout {
     size_t part_o, part_m, part_l, row_aux, scores, sel, total;
@@ -323,8 +331,7 @@ int hgca_pool_scores(const hgca_shape *shape, const void *q, const hgca_kv_view 
     sa.q = q;
     sa.kv = to_dev(pool);
     sa.scores = scores_out;
-    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
-                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+    sa.chunk = score_chunk(shape, pool->cap);
     sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
     return from_hip(launch_scores(shape->dtype, shape->head_dim, sa, static_cast<hipStream_t>(hip_stream)));
 }
@@ -348,8 +355,7 @@ int hgca_select_salient(const hgca_shape *shape, const void *q, const hgca_kv_vi
     sa.q = q;
     sa.kv = to_dev(pool);
     sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws) + w.scores);
-    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
-                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+    sa.chunk = score_chunk(shape, pool->cap);
     sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
     if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
 
@@ -441,8 +447,7 @@ int hgca_select_salient_grouped(const hgca_shape *shape, const void *q, const hg
     sa.kv = to_dev(pool);
     sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws) + w.scores);    // [B, Hkv, cap] of the region
     sa.group_max = 1;
-    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
-                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+    sa.chunk = score_chunk(shape, pool->cap);
     sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
     if ((rc = from_hip(launch_scores(shape->dtype, shape->head_dim, sa, s))) != HGCA_OK) return rc;
 
@@ -561,8 +566,7 @@ int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q, const hgca_k
     sa.q = q;
     sa.kv = to_dev(pool);
     sa.scores = reinterpret_cast<float *>(static_cast<char *>(ws_sparse) + wsp.scores);
-    sa.chunk = pick_chunk(pool->cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_SCORES,
-                          shape->dtype == HGCA_BF16 ? kMaxScoreChunk : kMaxChunk);
+    sa.chunk = score_chunk(shape, pool->cap);
     sa.n_chunks = n_splits_for(pool->cap, sa.chunk);
 
     AttnArgs da{};

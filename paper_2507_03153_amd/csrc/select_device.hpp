@@ -499,13 +499,30 @@ struct Sel {
         float thr;
         uint32_t need_eq;
         if (n_cand <= (uint32_t)kMaxCand) {
-            // exact rank of every candidate in (score descending, position ascending) order
+            // exact rank of every candidate in (score descending, position ascending) order; up to 64 candidates
+            // (the usual case) are ranked by the first wave alone out of its registers, more than that one per thread
             float my_s = 0.f;
             int32_t my_idx = 0;
             uint32_t eq_lower = 0;                   // candidates with my score at lower positions
             if ((uint32_t)tid < n_cand) {
                 my_s = sh.cand_score()[tid];
                 my_idx = sh.cand_idx()[tid];
+            }
+            if (n_cand <= (uint32_t)kWave) {
+                if (w == 0) {
+                    uint32_t gt = 0;
+                    for (uint32_t j = 0; j < n_cand; ++j) {
+                        const float sj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_s), j));
+                        const int32_t ij = __builtin_amdgcn_readlane(my_idx, j);
+                        gt += sj > my_s;
+                        eq_lower += (sj == my_s) && (ij < my_idx);
+                    }
+                    if ((uint32_t)lane < n_cand && gt + eq_lower == k_rem - 1) {
+                        sh.found[0] = __float_as_uint(my_s);
+                        sh.found[1] = k_rem - gt;
+                    }
+                }
+            } else if ((uint32_t)tid < n_cand) {
                 uint32_t gt = 0;
                 for (uint32_t j = 0; j < n_cand; ++j) {
                     const float sj = sh.cand_score()[j];
@@ -578,10 +595,9 @@ struct Sel {
         }
 
         // ---- pass 3: ordered compaction ----------------------------------------------------------------------
-        // The kept positions are placed in LDS (the histogram is dead by now) and copied out with
-        // coalesced stores; budgets beyond its size go to global memory directly.
-        const bool staged = k <= kBins;
-        int32_t *dst = staged ? reinterpret_cast<int32_t *>(sh.hist) : out;
+        // The lanes of a wave write ascending, mostly adjacent places, so the kept positions (and scores) go straight
+        // to memory.
+        int32_t *dst = out;
         float *sel = a.sel_scores ? a.sel_scores + bh * a.k_max : nullptr;
         uint32_t run_gt = 0, run_eq = 0, all_eq = 0; // kept / tied entries before the wave's current step
         for (int i = 0; i < kSelWaves; ++i) {
@@ -670,18 +686,7 @@ struct Sel {
                 eq_before += eq[e];
             }
         }
-        if (staged) {
-            __syncthreads();
-            if ((a.k_max & 3) == 0) {                // output rows start 16-byte aligned
-                for (int j = tid; j < k / 4; j += kSelBlock)
-                    reinterpret_cast<int4 *>(out)[j] = reinterpret_cast<const int4 *>(sh.hist)[j];
-                for (int j = k / 4 * 4 + tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
-            } else {
-                for (int j = tid; j < k; j += kSelBlock) out[j] = (int32_t)sh.hist[j];
-            }
-            if (sel_deferred)
-                for (int j = tid; j < k; j += kSelBlock) sel[j] = sc[sh.hist[j]];
-        } else if (sel_deferred) {
+        if (sel_deferred) {
             __syncthreads();                         // the positions written above by other threads of the workgroup
             for (int j = tid; j < k; j += kSelBlock) sel[j] = sc[out[j]];
         }
