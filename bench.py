@@ -340,6 +340,9 @@ def main() -> int:
     }
     if args.config == "C2" and not args.no_decode_loop:
         out["paper_literal_decode"] = decode_loop_timing(torch, hgca, cfg, layers[0], k_max, dev)
+        # Alg. 1's blk_size is a free constant: the same loop with the cache in 64-token blocks
+        out["paper_literal_decode_blocks_of_64"] = decode_loop_timing(torch, hgca, cfg, layers[0], k_max, dev,
+                                                                      block_size=64)
         out["append_stage"] = append_stage_timing(torch, hgca, cfg, layers[0], dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host_layers[0], args.cpu_seconds)

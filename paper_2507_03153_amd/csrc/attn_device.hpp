@@ -52,8 +52,8 @@ __device__ __forceinline__ void write_empty_partial(const Partials &part, int64_
 }
 
 // s_p[g][0..nt) holds scores on entry and weights e^{s-m} on exit; one wave per head.
-template <int NH, int BLOCK = kBlock>
-__device__ __forceinline__ void split_softmax(float (*s_p)[kMaxChunk], float *s_m, float *s_l, int nt)
+template <int NH, int BLOCK = kBlock, int LD = kMaxChunk>
+__device__ __forceinline__ void split_softmax(float (*s_p)[LD], float *s_m, float *s_l, int nt)
 {
     const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     for (int g = w; g < NH; g += BLOCK / kWave) {
@@ -72,8 +72,8 @@ __device__ __forceinline__ void split_softmax(float (*s_p)[kMaxChunk], float *s_
 }
 
 // o[g][:] = sum_j p[g][j] v_j over the split, reduced over the workgroup and written as a partial.
-template <typename T, int D, int NH, bool GATHER, int BLOCK = kBlock, int UNROLL = kUnroll>
-__device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[kMaxChunk],
+template <typename T, int D, int NH, bool GATHER, int BLOCK = kBlock, int UNROLL = kUnroll, int LD = kMaxChunk>
+__device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[LD],
                                            float (*s_red)[NH][D], const float *s_m, const float *s_l,
                                            int64_t bh0, int split, int nt, const RowMap &rows)
 {
@@ -140,8 +140,8 @@ __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[kMa
 }
 
 // Scaled scores of the split to a.scores[b, h, t0 .. t0+nt) for the NH heads of the workgroup.
-template <int NH, int BLOCK = kBlock>
-__device__ __forceinline__ void store_split_scores(const KernelArgs &a, const float (*s_p)[kMaxChunk], int64_t bh0,
+template <int NH, int BLOCK = kBlock, int LD = kMaxChunk>
+__device__ __forceinline__ void store_split_scores(const KernelArgs &a, const float (*s_p)[LD], int64_t bh0,
                                                    int t0, int nt)
 {
     if (a.group_max) {                           // one row per KV head: row index bh0 / NH (bh0 is the group's first head)
@@ -336,8 +336,8 @@ constexpr int kPvPad = 32;                       // bytes of padding per V row i
 // per block.  The block's V rows are parked in a wave-private LDS stage as loaded (row-major) and come back
 // through transpose reads as the A operand; the weights of the block (fp32 in s_p) are rounded to a high and a
 // low bf16 part for the B operand (column = head, zero beyond the group).
-template <int D, int G, int BLOCK = kBlock>
-__device__ __forceinline__ void value_pass_mfma(const KernelArgs &a, float (*s_p)[kMaxChunk], char *stage,
+template <int D, int G, int BLOCK = kBlock, int LD = kMaxChunk>
+__device__ __forceinline__ void value_pass_mfma(const KernelArgs &a, float (*s_p)[LD], char *stage,
                                                 float (*s_red)[G][D], const float *s_m, const float *s_l, int64_t bh0,
                                                 int split, int nt, const RowMap &rows)
 {
@@ -413,7 +413,8 @@ __device__ __forceinline__ void value_pass_mfma(const KernelArgs &a, float (*s_p
 // the split on the matrix cores, softmax statistics of the split in LDS, V pass, one partial (m, l, o) per head.
 // A split without tokens (nt == 0) goes through the same barriers and writes the empty partial (m = -inf, l = 0,
 // o = 0), so workgroups that run several roles or splits side by side stay in step.
-template <int D, int G, int BLOCK = kBlock, int UNROLL = kUnroll>
+// LD is the largest split the workgroup's LDS is sized for (the caller's chunk must not exceed it).
+template <int D, int G, int BLOCK = kBlock, int UNROLL = kUnroll, int LD = kMaxChunk>
 struct DenseSplit {
     static constexpr int kNW = BLOCK / kWave;
     // the K stage is dead once the scores are in s_p; the V stage and the output reduction reuse its space
@@ -422,32 +423,32 @@ struct DenseSplit {
     static constexpr int kVStageBytes = kPvMfma ? kNW * 32 * (D * 2 + kPvPad) : 0;
     static constexpr int kRedBytes = kNW * G * D * 4 + kVStageBytes;
     static constexpr int kBufBytes = kStageBytes > kRedBytes ? kStageBytes : kRedBytes;
-    static constexpr int kPBytes = G * kMaxChunk * 4;
+    static constexpr int kPBytes = G * LD * 4;
     static constexpr int kStatBytes = 64;                        // s_m[G], s_l[G]
-    static constexpr int kLdsBytes = kBufBytes + kPBytes + kStatBytes + kMaxChunk * 4;
+    static constexpr int kLdsBytes = kBufBytes + kPBytes + kStatBytes + LD * 4;
 
     // lds: kLdsBytes, 16-byte aligned.  t0 .. t0+nt are the split's tokens (nt may be 0).
     static __device__ __forceinline__ void run(const KernelArgs &a, char *lds, int split, int kvh, int b, int t0, int nt)
     {
         char *s_buf = lds;
-        float(*s_p)[kMaxChunk] = reinterpret_cast<float(*)[kMaxChunk]>(lds + kBufBytes);
+        float(*s_p)[LD] = reinterpret_cast<float(*)[LD]>(lds + kBufBytes);
         float *s_m = reinterpret_cast<float *>(lds + kBufBytes + kPBytes), *s_l = s_m + G;
         uint32_t *s_row = reinterpret_cast<uint32_t *>(lds + kBufBytes + kPBytes + kStatBytes);
         const int64_t bh0 = (int64_t)b * a.sh.n_q_heads + (int64_t)kvh * G;
         const RowMap rows = make_row_map<false, BLOCK>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0, nt, nullptr);
-        mfma_scores<D, G, kMaxChunk, kNW>(a, reinterpret_cast<uint4 *>(s_buf), s_p, bh0, nt, rows);
+        mfma_scores<D, G, LD, kNW>(a, reinterpret_cast<uint4 *>(s_buf), s_p, bh0, nt, rows);
         __syncthreads();
         if (a.scores) {                          // uniform over the workgroup
-            store_split_scores<G, BLOCK>(a, s_p, bh0, t0, nt);
+            store_split_scores<G, BLOCK, LD>(a, s_p, bh0, t0, nt);
             __syncthreads();                     // the softmax below overwrites the scores other waves are still storing
         }
-        split_softmax<G, BLOCK>(s_p, s_m, s_l, nt);
+        split_softmax<G, BLOCK, LD>(s_p, s_m, s_l, nt);
         __syncthreads();
         if (kPvMfma)                             // V stage first, reduction area behind it
-            value_pass_mfma<D, G, BLOCK>(a, s_p, s_buf, reinterpret_cast<float(*)[G][D]>(s_buf + kVStageBytes), s_m, s_l,
+            value_pass_mfma<D, G, BLOCK, LD>(a, s_p, s_buf, reinterpret_cast<float(*)[G][D]>(s_buf + kVStageBytes), s_m, s_l,
                                          bh0, split, nt, rows);
         else
-            value_pass<bf16_t, D, G, false, BLOCK, UNROLL>(a, s_p, reinterpret_cast<float(*)[G][D]>(s_buf), s_m, s_l, bh0,
+            value_pass<bf16_t, D, G, false, BLOCK, UNROLL, LD>(a, s_p, reinterpret_cast<float(*)[G][D]>(s_buf), s_m, s_l, bh0,
                                                            split, nt, rows);
     }
 };

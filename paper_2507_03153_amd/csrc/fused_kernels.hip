@@ -20,12 +20,12 @@ namespace {
 #define HGCA_DG_UNROLL 4                         // V loads a lane of a window split keeps in flight
 #endif
 
-template <int D, int G, int GMODE>
+template <int D, int G, int GMODE, int LD>
 __global__ __launch_bounds__(kBlock, HGCA_DG_OCC) void dense_gather_kernel(KernelArgs da, KernelArgs ga, int n_dense,
                                                                           int dense_splits, int gather_splits,
                                                                           int gather_first)
 {
-    using DS = DenseSplit<D, G, kBlock, HGCA_DG_UNROLL>;
+    using DS = DenseSplit<D, G, kBlock, HGCA_DG_UNROLL, LD>;   // LDS sized for window splits of up to LD tokens
     using GS = SplitValu<bf16_t, D, 1, GMODE>;
     constexpr int kLds = DS::kLdsBytes > GS::kLdsBytes ? DS::kLdsBytes : GS::kLdsBytes;
     __shared__ __attribute__((aligned(16))) char s_lds[kLds];
@@ -79,19 +79,25 @@ hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, c
     const KernelArgs da = to_ka(dense), ga = to_ka(gather);
     const dim3 grid((unsigned)(n_dense + n_gather)), block(kBlock);
     const int g = dense.sh.group;
+    // the window's splits size the launch's LDS: the common 256-token splits leave room for seven workgroups per unit
+#define HGCA_DG_LAUNCH(D, G, GMODE, LD, FIRST)                                                                      \
+    hipLaunchKernelGGL((dense_gather_kernel<D, G, GMODE, LD>), grid, block, 0, s, da, ga, (int)n_dense,             \
+                       dense.part.n_splits, gather.part.n_splits, FIRST)
 #define HGCA_DG_CASE(D, G)                                                                                          \
     if (head_dim == D && g == G) {                                                                                  \
-        if (gather.sel_scores)                                                                                      \
-            hipLaunchKernelGGL((dense_gather_kernel<D, G, kGatherScored>), grid, block, 0, s, da, ga, (int)n_dense, \
-                               dense.part.n_splits, gather.part.n_splits, 0);                                       \
-        else                                                                                                        \
-            hipLaunchKernelGGL((dense_gather_kernel<D, G, kGather>), grid, block, 0, s, da, ga, (int)n_dense,       \
-                               dense.part.n_splits, gather.part.n_splits, 1);                                       \
+        if (gather.sel_scores) {                                                                                    \
+            if (dense.chunk <= 256) HGCA_DG_LAUNCH(D, G, kGatherScored, 256, 0);                                    \
+            else HGCA_DG_LAUNCH(D, G, kGatherScored, kMaxChunk, 0);                                                 \
+        } else {                                                                                                    \
+            if (dense.chunk <= 256) HGCA_DG_LAUNCH(D, G, kGather, 256, 1);                                          \
+            else HGCA_DG_LAUNCH(D, G, kGather, kMaxChunk, 1);                                                       \
+        }                                                                                                           \
         return hipGetLastError();                                                                                   \
     }
     HGCA_DG_CASE(64, 1) HGCA_DG_CASE(64, 2) HGCA_DG_CASE(64, 4)
     HGCA_DG_CASE(128, 1) HGCA_DG_CASE(128, 2) HGCA_DG_CASE(128, 4)
 #undef HGCA_DG_CASE
+#undef HGCA_DG_LAUNCH
     return hipErrorInvalidValue;
 }
 

@@ -799,7 +799,6 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     da.chunk = pick_chunk(window.cap, (int64_t)shape->batch * shape->n_kv_heads, HGCA_TARGET_WGS_DENSE);
     da.part = partials_at(ws_dense, wd, n_splits_for(window.cap, da.chunk));
     da.raw_scores = a_gpu;
-    if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
     // cpu_attention over KV_ctx: split kernels over each head's list of salient pool positions
     AttnArgs ga{};
     ga.sh = da.sh;
@@ -810,7 +809,14 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     ga.k_max = cache->k_max;
     ga.chunk = pick_chunk(cache->k_max, rows, HGCA_TARGET_WGS_SPARSE);
     ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(cache->k_max, ga.chunk)));
-    if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
+    // the two parts need nothing from each other: one launch where the shapes allow
+    if (HGCA_FUSE_DENSE_GATHER && window.cap > 0 && cache->k_max > 0 && cache->pool_cap > 0 &&
+        dense_gather_fusable(shape->dtype, shape->head_dim, group_of(shape))) {
+        if ((rc = from_hip(launch_dense_gather(shape->dtype, shape->head_dim, da, ga, s))) != HGCA_OK) return rc;
+    } else {
+        if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
+        if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
+    }
     // merge_state over all split partials; the window's own lse comes out of the same fold
     float *lse_w = reinterpret_cast<float *>(static_cast<char *>(ws_dense) + wd.row_aux);
     if ((rc = from_hip(launch_combine2(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, s, lse_w))) != HGCA_OK)
