@@ -50,7 +50,7 @@ def measured_traffic(kernel: str):
     except OSError:
         return None, None
     import re
-    at = re.search(r"measured at commit `?([0-9a-f]{7,40})`?", text)
+    at = re.search(r"measured at commit `?([0-9a-f]{7,40})`?", text, re.I)
     for line in text.splitlines():
         cells = [c.strip() for c in line.split("|")]
         if len(cells) > 6 and cells[1].strip("`").startswith(kernel):
@@ -295,7 +295,8 @@ def main() -> int:
               "rocm": torch.version.hip, "torch": torch.__version__}
 
     def spread(t: dict) -> dict:
-        return {"ms_per_step": t["ms"], "min_ms": t["min"], "max_ms": t["max"], "repetitions": len(t["reps"])}
+        return {"ms_per_step": t["ms"], "min_ms": t["min"], "max_ms": t["max"], "repetitions": len(t["reps"]),
+                "device_ms_per_step": t["dev_ms"], "wall_ms_per_step": t["wall_ms"]}
 
     out = {
         "metric": METRIC, "value": 1e3 / ms_per_step, "unit": "layer-steps/s", "n_gpus": 1,
