@@ -426,8 +426,9 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
             "separate_calls_ms_per_step": separate_ms, "steps": n_steps, "evictions": n_steps // block_size,
             "block_size": block_size, "salient_per_head": kept, "cache_status": status,
             "bytes_per_step": int(moved), "hbm_frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "calls_per_step": "hgca_managed_decode_step (insert, window splits with scores, gather over the salient "
-                              "lists, one fold, weights + moving average, eviction: 6 kernels)",
+            "calls_per_step": "hgca_managed_decode_step (2 launches: window splits with scores, the token's insert "
+                              "and the gather over the salient lists; then fold, weights + moving average and "
+                              "eviction per row)",
             "separate_calls": "kv_append, dense_window_attn_maw, sparse_attn (deferred), lse_merge_splits, kv_evict "
                               "(7 kernels)"}
 

@@ -444,8 +444,13 @@ int hgca_kv_evict(const hgca_shape *shape, const hgca_cache_state *cache,
  * sparsification with beta where a window has reached l_max).  The same
  * results as hgca_kv_append, hgca_dense_window_attn_maw, hgca_sparse_attn on
  * (ctx_idx, ctx_cnt), hgca_lse_merge_splits and hgca_kv_evict in that order,
- * with two launches fewer (the window's own lse comes out of the fold of all
- * split partials).  q is [B,Hq,d], k_in / v_in [B,Hkv,d]: every sequence of the
+ * in two launches where the shapes allow (bf16, groups of 1, 2 or 4): the
+ * window split that owns the token's position writes its rows, the splits of
+ * window and salient lists share the launch, and one launch per (sequence,
+ * head) row folds the partials, forms A_gpu with the window's own lse from
+ * the same fold, updates A_maw, evicts and stores the window's new length.
+ * If the token does not fit (status bits as for hgca_kv_append) the step runs
+ * on the window as it stands.  q is [B,Hq,d], k_in / v_in [B,Hkv,d]: every sequence of the
  * batch receives a token (batches in which some do not use the separate
  * calls); a_gpu (device fp32 [B,Hq,window capacity], required)
  * receives A_gpu; o_out [B,Hq,d] in o_dtype, lse_out

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libhgca.so")
 SOURCES = ["hgca_api.hip", "attn_kernels.hip", "select_kernels.hip", "maw_kernels.hip", "cache_kernels.hip", "append_kernels.hip", "group_kernels.hip", "fused_kernels.hip"]
-HEADERS = ["hgca_device.hpp", "hgca_launch.hpp", "threshold_compact.hpp", "row_map.hpp", "attn_device.hpp", "select_device.hpp", os.path.join("..", "..", "include", "hgca.h")]
+HEADERS = ["hgca_device.hpp", "hgca_launch.hpp", "threshold_compact.hpp", "row_map.hpp", "attn_device.hpp", "fold_device.hpp", "select_device.hpp", os.path.join("..", "..", "include", "hgca.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

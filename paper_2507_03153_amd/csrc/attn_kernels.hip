@@ -14,6 +14,7 @@
 // LDS, a V pass with coalesced 16-byte loads and fp32 FMAs, a reduction through
 // shuffles and LDS, and one partial (m, l, o) per head and split.
 #include "attn_device.hpp"
+#include "fold_device.hpp"
 
 namespace hgca {
 
@@ -105,106 +106,13 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
 
 // ---- combine and merge ------------------------------------------------------------------------------
 
-// Folds split partials of one (b, h) row: M = max m_s, L = sum l_s e^{m_s-M}, O = sum o_s e^{m_s-M} / L,
-// lse = M + ln L.  The splits may come from two partial sets (p and q): folding the splits of the dense
-// window part and of the sparse part in one go is merge_state applied to all of them at once
-// (the fusion is associative).  Thread (sg, c4) sums the splits sg, sg+SG, ... of four adjacent columns;
-// the SG groups are then added through LDS.
+// One workgroup folds one (b, h) row (fold_device.hpp); lse_p, if given, receives the log-sum-exp of set p alone.
 template <int D, bool OUT_BF16>
-__global__ __launch_bounds__(kBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse, float *lse_p)
+__global__ __launch_bounds__(kFoldBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse, float *lse_p)
 {
-    constexpr int C4 = D / 4;                    // threads across the columns (one float4 each)
-    constexpr int SG = kBlock / C4;              // split groups
-    constexpr int PRE = 4;                       // splits per thread whose loads are issued before anything is used
-    __shared__ float4 s_acc[SG][C4];
-    __shared__ float s_L[SG];
-    __shared__ float s_M[kWaves];
-
-    const int64_t row = blockIdx.x;
-    const int tid = threadIdx.x, sg = tid / C4, c4 = tid % C4;
-    const int np = p.n_splits, n = np + q.n_splits;
-    auto m_of = [&](int s) { return s < np ? p.m[row * np + s] : q.m[row * q.n_splits + (s - np)]; };
-    auto l_of = [&](int s) { return s < np ? p.l[row * np + s] : q.l[row * q.n_splits + (s - np)]; };
-    auto o_of = [&](int s) {
-        const float *base = s < np ? p.o + (row * np + s) * D : q.o + (row * q.n_splits + (s - np)) * D;
-        return *reinterpret_cast<const float4 *>(base + 4 * c4);
-    };
-    // One round trip to memory for the usual split counts: a thread's first PRE splits (m, l and its four columns
-    // of o) are requested together with the maxima it contributes to the row's maximum; the weights e^{m-M} need
-    // M, but the loads do not.
-    float pm[PRE], pl[PRE];
-    float4 po[PRE];
-#pragma unroll
-    for (int i = 0; i < PRE; ++i) {
-        const int s = sg + i * SG;
-        pm[i] = -INFINITY;
-        pl[i] = 0.f;
-        po[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (s < n) { pm[i] = m_of(s); pl[i] = l_of(s); po[i] = o_of(s); }
-    }
-    // the maximum over all splits: one split per thread, then over the workgroup
-    float M = -INFINITY;
-    for (int s = tid; s < n; s += kBlock) M = fmaxf(M, m_of(s));
-    M = wave_max(M);
-    if (tid % kWave == 0) s_M[tid / kWave] = M;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, s_M[w]);
-    float L = 0.f;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (M != -INFINITY) {                        // else every split is empty (uniform over the workgroup)
-#pragma unroll
-        for (int i = 0; i < PRE; ++i) {
-            const float wgt = expf(pm[i] - M);   // 0 for empty splits and for splits beyond n (m = -inf)
-            L = fmaf(pl[i], wgt, L);
-            acc.x = fmaf(po[i].x, wgt, acc.x); acc.y = fmaf(po[i].y, wgt, acc.y);
-            acc.z = fmaf(po[i].z, wgt, acc.z); acc.w = fmaf(po[i].w, wgt, acc.w);
-        }
-        for (int s = sg + PRE * SG; s < n; s += SG) {
-            const float wgt = expf(m_of(s) - M);
-            const float4 v = o_of(s);
-            L = fmaf(l_of(s), wgt, L);
-            acc.x = fmaf(v.x, wgt, acc.x); acc.y = fmaf(v.y, wgt, acc.y);
-            acc.z = fmaf(v.z, wgt, acc.z); acc.w = fmaf(v.w, wgt, acc.w);
-        }
-    }
-    s_acc[sg][c4] = acc;
-    if (c4 == 0) s_L[sg] = L;
-    __syncthreads();
-    if (tid < C4) {
-        float Lt = 0.f;
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int g = 0; g < SG; ++g) {
-            const float4 v = s_acc[g][tid];
-            t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
-            Lt += s_L[g];
-        }
-        const float inv = (M != -INFINITY) ? 1.f / Lt : 0.f;
-        const float r[4] = {t.x * inv, t.y * inv, t.z * inv, t.w * inv};
-        if (OUT_BF16) {
-            uint16_t h[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                uint32_t u = __float_as_uint(r[e]);
-                u += 0x7fffu + ((u >> 16) & 1u); // round to nearest even (finite values)
-                h[e] = (uint16_t)(u >> 16);
-            }
-            uint2 packed = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
-            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(o) + row * D + 4 * tid) = packed;
-        } else {
-            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(o) + row * D + 4 * tid) = make_float4(r[0], r[1], r[2], r[3]);
-        }
-        if (tid == 0 && lse) lse[row] = (M != -INFINITY) ? M + logf(Lt) : -INFINITY;
-    }
-    // log-sum-exp of the first set alone (the window part of a step: its attention weights are normalised by it)
-    if (lse_p && tid == kBlock - 1) {
-        float Mp = -INFINITY, Lp = 0.f;
-        for (int s = 0; s < np; ++s) Mp = fmaxf(Mp, p.m[row * np + s]);
-        if (Mp != -INFINITY)
-            for (int s = 0; s < np; ++s) Lp = fmaf(p.l[row * np + s], expf(p.m[row * np + s] - Mp), Lp);
-        lse_p[row] = (Mp != -INFINITY) ? Mp + logf(Lp) : -INFINITY;
-    }
+    __shared__ FoldShared<D> sh;
+    if (lse_p) fold_row<D, OUT_BF16, true>(sh, p, q, o, lse, lse_p, blockIdx.x);     // uniform over the launch
+    else fold_row<D, OUT_BF16, false>(sh, p, q, o, lse, nullptr, blockIdx.x);
 }
 
 // merge_state on one (b, h) row per workgroup, one thread per column.
@@ -371,7 +279,7 @@ hipError_t launch_combine2(int head_dim, int64_t n_rows, const Partials &p, cons
                            float *lse, hipStream_t s, float *lse_p)
 {
     if (n_rows == 0) return hipSuccess;
-    const dim3 grid((unsigned)n_rows), block(kBlock);
+    const dim3 grid((unsigned)n_rows), block(kFoldBlock);
     if (head_dim == 64 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<64, false>), grid, block, s, p, q, o, lse, lse_p);
     else if (head_dim == 64 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<64, true>), grid, block, s, p, q, o, lse, lse_p);
     else if (head_dim == 128 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<128, false>), grid, block, s, p, q, o, lse, lse_p);

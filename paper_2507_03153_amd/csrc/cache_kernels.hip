@@ -6,6 +6,7 @@
 // per window position: the evicted entries' averages are thresholded (Sec. 3.2.2) into the per-head
 // lists of salient pool positions and the rest of the row shifts down.
 #include "hgca_launch.hpp"
+#include "fold_device.hpp"
 #include "row_map.hpp"
 #include "threshold_compact.hpp"
 
@@ -24,9 +25,9 @@ __global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const 
     if (active && !active[b]) return;
     const int len = c.win_lens[b];
     const int first = c.first_win_block[b];
-    const bool no_room = len + n_tokens > c.win_cap;
-    if (len < 0 || no_room || first + (len + n_tokens - 1) / c.block_size >= c.max_blocks) {   // uniform over the workgroup
-        if (threadIdx.x == 0) atomicOr(c.status, no_room ? kCacheWindowFull : kCacheContextFull);
+    int32_t fail_bits = 0;
+    if (pending_window_len(len, first, n_tokens, c.win_cap, c.block_size, c.max_blocks, &fail_bits) == len) {   // uniform
+        if (threadIdx.x == 0) atomicOr(c.status, fail_bits);
         return;
     }
     const int pieces = row_bytes / 16;                         // 16-byte pieces of one row
@@ -44,69 +45,148 @@ __global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const 
     if (threadIdx.x == 0) c.win_lens[b] = len + n_tokens;
 }
 
-// Eviction and sparsification of Alg. 1.  One workgroup per (sequence, query head) row.  Every workgroup of a
-// sequence takes the same decision from the same state (if l_cur >= l_max: evict the smallest whole number of
-// blocks that brings the window below l_max); for a sequence that evicts, the evicted entries whose moving average
-// exceeds beta / l_cur join the head's list of salient pool positions (appended in position order), optionally the
-// evicted averages are saved at their pool positions, and the row shifts down by l_evict.  The last workgroup of
-// the sequence to finish (an arrival counter in plan[4b + 3], left at zero) moves the boundary: by then every
-// workgroup of the sequence has read the state it is about to change.
-__global__ __launch_bounds__(kRowBlock) void evict_kernel(CacheDev c, int32_t n_q_heads, double beta)
+// Eviction and sparsification of Alg. 1 for one (sequence, query head) row, called by all kRowBlock threads of the
+// row's workgroup.  Every workgroup of a sequence takes the same decision from the same state (if l_cur >= l_max:
+// evict the smallest whole number of blocks that brings the window below l_max); for a sequence that evicts, the
+// evicted entries whose moving average exceeds beta / l_cur join the head's list of salient pool positions
+// (appended in position order), optionally the evicted averages are saved at their pool positions, and the row
+// shifts down by l_evict.  The last workgroup of the sequence to finish (an arrival counter in plan[4b + 3], left
+// at zero) moves the boundary: by then every workgroup of the sequence has read the state it is about to change.
+// l_cur is the window's length as the caller read it (every thread of the workgroup, before a barrier).  With
+// store_len the stored length is not l_cur yet (a token joined the window in this step without its length having
+// been stored): the last workgroup stores it also when nothing is evicted, and raises fail_bits (if any) in the
+// cache's status word.
+// Alg. 1's eviction rule: whole blocks a window of l_cur tokens gives up (0 below l_max).
+__device__ __forceinline__ int blocks_to_evict(const CacheDev &c, int l_cur)
 {
-    __shared__ CompactShared s_compact;
-    const int64_t row = blockIdx.x;
+    const int l_max = c.win_blocks * c.block_size;
+    return l_cur >= l_max ? min((l_cur - l_max + c.block_size) / c.block_size, l_cur / c.block_size) : 0;
+}
+
+__device__ __forceinline__ void evict_row(CompactShared &s_compact, const CacheDev &c, int64_t row, int32_t n_q_heads,
+                                          double beta, int l_cur, bool store_len, int32_t fail_bits)
+{
     const int b = (int)(row / n_q_heads), tid = threadIdx.x;
-    const int l_cur = c.win_lens[b], l_max = c.win_blocks * c.block_size;
-    int n_ev = 0;
-    if (l_cur >= l_max) n_ev = min((l_cur - l_max + c.block_size) / c.block_size, l_cur / c.block_size);
+    const int n_ev = blocks_to_evict(c, l_cur);
     const int l_ev = n_ev * c.block_size;
-    if (l_ev == 0) return;                                     // the same for every workgroup of the sequence
-    const int p_old = c.pool_lens[b];
-    float *maw = c.a_maw + row * c.win_cap;
+    if (l_ev == 0 && !store_len) return;                       // the same for every workgroup of the sequence
+    int p_old = 0;
+    if (l_ev > 0) {
+        p_old = c.pool_lens[b];
+        float *maw = c.a_maw + row * c.win_cap;
 
-    const int start = min(max(c.ctx_cnt[row], 0), c.k_max);
-    float unused = 0.f;
-    const int total = threshold_compact<false>(s_compact, maw, l_ev, beta / (double)l_cur, c.ctx_idx + row * c.k_max, start,
-                                        c.k_max, p_old, nullptr, unused);
-    if (tid == 0) {
-        c.ctx_cnt[row] = min(total, c.k_max);
-        if (total > c.k_max) atomicOr(c.status, kCacheListFull);
-    }
-    if (c.a_evicted) {
-        float *dst = c.a_evicted + row * (int64_t)c.pool_cap + p_old;
-        for (int j = tid; j < l_ev && p_old + j < c.pool_cap; j += kRowBlock) dst[j] = maw[j];
-    }
-    __syncthreads();                                           // the evicted averages have been read
-
-    // shift down: a step reads [t0 + l_ev, ...) which no earlier step has written (they wrote below t0)
-    const int n_stay = l_cur - l_ev;
-    for (int t0 = 0; t0 < l_cur; t0 += kRowStep) {
-        float x[kPerThread];
-#pragma unroll
-        for (int e = 0; e < kPerThread; ++e) {
-            const int j = t0 + e * kRowBlock + tid;
-            x[e] = j < n_stay ? maw[j + l_ev] : 0.f;
+        const int start = min(max(c.ctx_cnt[row], 0), c.k_max);
+        float unused = 0.f;
+        const int total = threshold_compact<false>(s_compact, maw, l_ev, beta / (double)l_cur, c.ctx_idx + row * c.k_max,
+                                                   start, c.k_max, p_old, nullptr, unused);
+        if (tid == 0) {
+            c.ctx_cnt[row] = min(total, c.k_max);
+            if (total > c.k_max) atomicOr(c.status, kCacheListFull);
         }
-        __syncthreads();
+        if (c.a_evicted) {
+            float *dst = c.a_evicted + row * (int64_t)c.pool_cap + p_old;
+            for (int j = tid; j < l_ev && p_old + j < c.pool_cap; j += kRowBlock) dst[j] = maw[j];
+        }
+        __syncthreads();                                       // the evicted averages have been read
+
+        // shift down: a step reads [t0 + l_ev, ...) which no earlier step has written (they wrote below t0)
+        const int n_stay = l_cur - l_ev;
+        for (int t0 = 0; t0 < l_cur; t0 += kRowStep) {
+            float x[kPerThread];
 #pragma unroll
-        for (int e = 0; e < kPerThread; ++e) {
-            const int j = t0 + e * kRowBlock + tid;
-            if (j < l_cur) maw[j] = x[e];                      // entries [n_stay, l_cur) become 0
+            for (int e = 0; e < kPerThread; ++e) {
+                const int j = t0 + e * kRowBlock + tid;
+                x[e] = j < n_stay ? maw[j + l_ev] : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < kPerThread; ++e) {
+                const int j = t0 + e * kRowBlock + tid;
+                if (j < l_cur) maw[j] = x[e];                  // entries [n_stay, l_cur) become 0
+            }
         }
     }
 
-    // every thread of this workgroup read the sequence's state before the barriers above
+    // every thread of this workgroup read the sequence's state before a barrier that lies behind it by now
     if (tid == 0) {
         int32_t *arrived = c.plan + 4 * b + 3;
         if (atomicAdd(arrived, 1) == n_q_heads - 1) {
             *arrived = 0;
-            c.plan[4 * b + 0] = l_ev;                          // what was done, for whoever wants to look
-            c.plan[4 * b + 1] = l_cur;
-            c.plan[4 * b + 2] = p_old;
-            c.first_win_block[b] += n_ev;
-            c.win_lens[b] = l_cur - l_ev;
-            c.pool_lens[b] = p_old + l_ev;
+            if (l_ev > 0) {
+                c.plan[4 * b + 0] = l_ev;                      // what was done, for whoever wants to look
+                c.plan[4 * b + 1] = l_cur;
+                c.plan[4 * b + 2] = p_old;
+                c.first_win_block[b] += n_ev;
+                c.pool_lens[b] = p_old + l_ev;
+            }
+            if (l_ev > 0 || store_len) c.win_lens[b] = l_cur - l_ev;
+            if (fail_bits) atomicOr(c.status, fail_bits);
         }
+    }
+}
+
+__global__ __launch_bounds__(kRowBlock) void evict_kernel(CacheDev c, int32_t n_q_heads, double beta)
+{
+    __shared__ CompactShared s_compact;
+    const int l_cur = c.win_lens[blockIdx.x / n_q_heads];
+    __syncthreads();
+    evict_row(s_compact, c, blockIdx.x, n_q_heads, beta, l_cur, false, 0);
+}
+
+// The tail of a decode step over the managed cache as one launch, one workgroup per (sequence, query head) row:
+// merge_state over the row's split partials (set p: the window's, set q: the salient list's), the window's attention
+// weights A_gpu = e^{s - lse_window} from the scaled scores the split kernels left in a_gpu, Alg. 1's moving average
+// (the newest token has no history and takes its first weight), then eviction and sparsification of the row.
+// Nothing here needs another row's results, so the three steps need no launch boundary between them; the row's
+// scores and averages are requested together with the partials, so the launch costs one round trip to memory.
+// With token_pending the step's token was written into the window by the split kernels and its length is still the
+// old one: the length this step works with is taken from the same rule (pending_window_len) and stored here.
+template <int D, bool OUT_BF16>
+__global__ __launch_bounds__(kRowBlock) void decode_tail_kernel(Partials p, Partials q, void *o, float *lse, float *a_gpu,
+                                                                CacheDev c, int32_t n_q_heads, float alpha, double beta,
+                                                                int32_t token_pending)
+{
+    static_assert(kFoldBlock == kRowBlock, "one workgroup shape for the fold and the row passes");
+    constexpr int PF = 16;                                     // entries per thread requested before the fold
+    __shared__ FoldShared<D> s_fold;
+    __shared__ CompactShared s_compact;
+    const int64_t row = blockIdx.x;
+    const int b = (int)(row / n_q_heads), tid = threadIdx.x, cap = c.win_cap;
+    float *ar = a_gpu + row * cap;
+    float *m = c.a_maw + row * cap;
+    float s[PF], h[PF];
+#pragma unroll
+    for (int e = 0; e < PF; ++e) {
+        const int j = tid + e * kRowBlock;
+        s[e] = j < cap ? ar[j] : 0.f;                          // beyond the length: not used
+        h[e] = j < cap ? m[j] : 0.f;
+    }
+    int32_t fail_bits = 0;
+    const int n = token_pending ? pending_window_len(c.win_lens[b], c.first_win_block[b], 1, cap, c.block_size,
+                                                     c.max_blocks, &fail_bits)
+                                : c.win_lens[b];
+    const int nc = min(max(n, 0), cap);
+    const float lse_w = fold_row<D, OUT_BF16, true>(s_fold, p, q, o, lse, nullptr, row);
+    // A row that evicts nothing only reports its arrival (the sequence's last row stores the length): that round
+    // trip runs beside the weights pass, which reads nothing the arrival changes.
+    const bool evicts = blocks_to_evict(c, n) > 0;             // uniform over the sequence's workgroups
+    if (!evicts) evict_row(s_compact, c, row, n_q_heads, beta, n, token_pending != 0, fail_bits);
+
+    const float keep = 1.f - alpha;
+    auto update = [&](int j, float sj, float hj) {
+        const float x = j < nc ? expf(sj - lse_w) : 0.f;
+        ar[j] = x;
+        if (j < nc) m[j] = j >= nc - 1 ? x : fmaf(alpha, x, keep * hj);
+    };
+#pragma unroll
+    for (int e = 0; e < PF; ++e) {
+        const int j = tid + e * kRowBlock;
+        if (j < cap) update(j, s[e], h[e]);
+    }
+    for (int j = PF * kRowBlock + tid; j < cap; j += kRowBlock) update(j, ar[j], m[j]);
+    if (evicts) {
+        __syncthreads();                                       // the row's averages are written before they are thresholded
+        evict_row(s_compact, c, row, n_q_heads, beta, n, token_pending != 0, fail_bits);
     }
 }
 
@@ -170,6 +250,25 @@ hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_i
     if (batch == 0 || n_tokens == 0) return hipSuccess;
     hipLaunchKernelGGL(kv_append_kernel, dim3(batch), dim3(kRowBlock), 0, s, c, static_cast<const char *>(k_in),
                        static_cast<const char *>(v_in), active, n_kv_heads, row_bytes, n_tokens);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_tail(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
+                              float *lse, float *a_gpu, const CacheDev &c, int32_t n_q_heads, float alpha, double beta,
+                              int32_t token_pending, hipStream_t s)
+{
+    if (n_rows == 0) return hipSuccess;
+    const dim3 grid((unsigned)n_rows), block(kRowBlock);
+#define HGCA_TAIL_CASE(D, BF)                                                                                       \
+    if (head_dim == D && o_dtype == (BF ? 1 : 0))                                                                   \
+        hipLaunchKernelGGL((decode_tail_kernel<D, BF>), grid, block, 0, s, p, q, o, lse, a_gpu, c, n_q_heads, alpha, beta, \
+                           token_pending)
+    HGCA_TAIL_CASE(64, false);
+    else HGCA_TAIL_CASE(64, true);
+    else HGCA_TAIL_CASE(128, false);
+    else HGCA_TAIL_CASE(128, true);
+    else return hipErrorInvalidValue;
+#undef HGCA_TAIL_CASE
     return hipGetLastError();
 }
 

@@ -23,7 +23,8 @@ namespace {
 template <int D, int G, int GMODE, int LD>
 __global__ __launch_bounds__(kBlock, HGCA_DG_OCC) void dense_gather_kernel(KernelArgs da, KernelArgs ga, int n_dense,
                                                                           int dense_splits, int gather_splits,
-                                                                          int gather_first)
+                                                                          int gather_first, const char *k_new,
+                                                                          const char *v_new)
 {
     using DS = DenseSplit<D, G, kBlock, HGCA_DG_UNROLL, LD>;   // LDS sized for window splits of up to LD tokens
     using GS = SplitValu<bf16_t, D, 1, GMODE>;
@@ -36,8 +37,28 @@ __global__ __launch_bounds__(kBlock, HGCA_DG_OCC) void dense_gather_kernel(Kerne
     if (dense_role) {                            // uniform over the workgroup
         const int split = u % dense_splits, kvh = (u / dense_splits) % da.sh.n_kv_heads,
                   b = u / (dense_splits * da.sh.n_kv_heads);
-        const int n = tier_len(da.kv, b);
+        int n = tier_len(da.kv, b);
         const int t0 = split * da.chunk;
+        if (k_new) {                             // uniform over the launch: the window takes one more token first
+            const int len = da.kv.seq_lens[b], first = da.kv.first_block[b];
+            const int grown = pending_window_len(len, first, 1, da.kv.cap, da.kv.block_size, da.kv.max_blocks, nullptr);
+            n = min(max(grown, 0), da.kv.cap);
+            if (grown > len && len >= t0 && len < t0 + da.chunk) {
+                // this split owns the token's position: its K and V rows go into the window's block, then the split
+                // reads them back like any other row (no other workgroup of the launch touches that position)
+                constexpr int kPieces = D * 2 / 16, kRow = D * 2;
+                if (threadIdx.x < 2 * kPieces) {
+                    const bool is_v = threadIdx.x >= kPieces;
+                    const int piece = threadIdx.x % kPieces;
+                    const int64_t blk = da.kv.block_table[(int64_t)b * da.kv.max_blocks + first + len / da.kv.block_size];
+                    const int64_t dst = ((blk * da.sh.n_kv_heads + kvh) * da.kv.block_size + len % da.kv.block_size) * kRow;
+                    const int64_t src = ((int64_t)b * da.sh.n_kv_heads + kvh) * kRow;
+                    *reinterpret_cast<uint4 *>(const_cast<char *>(is_v ? da.kv.v : da.kv.k) + dst + 16 * piece) =
+                        *reinterpret_cast<const uint4 *>((is_v ? v_new : k_new) + src + 16 * piece);
+                }
+                __syncthreads();
+            }
+        }
         if (t0 >= n) {
             write_empty_partial<D, G>(da.part, (int64_t)b * da.sh.n_q_heads + (int64_t)kvh * G, split);
             return;
@@ -55,9 +76,12 @@ bool dense_gather_fusable(int dtype, int head_dim, int group)
     return dtype == 1 && (head_dim == 64 || head_dim == 128) && (group == 1 || group == 2 || group == 4);
 }
 
-hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, const AttnArgs &gather, hipStream_t s)
+hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, const AttnArgs &gather, hipStream_t s,
+                               const void *k_new, const void *v_new)
 {
     if (!dense_gather_fusable(dtype, head_dim, dense.sh.group) || gather.grouped) return hipErrorInvalidValue;
+    if ((k_new != nullptr) != (v_new != nullptr)) return hipErrorInvalidValue;
+    if (k_new && (!dense.kv.block_table || !dense.kv.first_block || !dense.kv.seq_lens)) return hipErrorInvalidValue;
     const int64_t n_dense = (int64_t)dense.sh.batch * dense.sh.n_kv_heads * dense.part.n_splits;
     const int64_t n_gather = (int64_t)gather.sh.batch * gather.sh.n_q_heads * gather.part.n_splits;
     if (n_dense + n_gather == 0) return hipSuccess;
@@ -82,7 +106,8 @@ hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, c
     // the window's splits size the launch's LDS: the common 256-token splits leave room for seven workgroups per unit
 #define HGCA_DG_LAUNCH(D, G, GMODE, LD, FIRST)                                                                      \
     hipLaunchKernelGGL((dense_gather_kernel<D, G, GMODE, LD>), grid, block, 0, s, da, ga, (int)n_dense,             \
-                       dense.part.n_splits, gather.part.n_splits, FIRST)
+                       dense.part.n_splits, gather.part.n_splits, FIRST, static_cast<const char *>(k_new),        \
+                       static_cast<const char *>(v_new))
 #define HGCA_DG_CASE(D, G)                                                                                          \
     if (head_dim == D && g == G) {                                                                                  \
         if (gather.sel_scores) {                                                                                    \

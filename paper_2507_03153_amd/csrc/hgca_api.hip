@@ -29,6 +29,14 @@ constexpr size_t kAlign = 256;
 #define HGCA_TARGET_WGS_SPARSE_SCORED 2048
 #endif
 
+// 1: the token of a managed decode step is written into the window by the window split that reads it (needs the two below)
+#ifndef HGCA_FUSE_KV_APPEND
+#define HGCA_FUSE_KV_APPEND 1
+#endif
+// 1: the tail of the managed decode step (fold, window weights + moving average, eviction) is one launch
+#ifndef HGCA_FUSE_DECODE_TAIL
+#define HGCA_FUSE_DECODE_TAIL 1
+#endif
 // 1: the window's split kernels and the sparse part's split kernels of a step share a launch where the shapes allow
 #ifndef HGCA_FUSE_DENSE_GATHER
 #define HGCA_FUSE_DENSE_GATHER 1
@@ -788,8 +796,13 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     const int32_t row_bytes = shape->head_dim * (shape->dtype == HGCA_BF16 ? 2 : 4);
 
-    // Alg. 2: KV_gpu' = concat(KV_gpu, KV_in)
-    if ((rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, 1, s))) != HGCA_OK)
+    const bool one_launch = HGCA_FUSE_DENSE_GATHER && window.cap > 0 && cache->k_max > 0 && cache->pool_cap > 0 &&
+                            dense_gather_fusable(shape->dtype, shape->head_dim, group_of(shape));
+    // Alg. 2: KV_gpu' = concat(KV_gpu, KV_in): a launch of its own, or (token_joins_in_split) the window split that
+    // owns the token's position writes its rows and the step's last launch stores the new length
+    const bool token_joins_in_split = HGCA_FUSE_KV_APPEND && HGCA_FUSE_DECODE_TAIL && one_launch;
+    if (!token_joins_in_split &&
+        (rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, 1, s))) != HGCA_OK)
         return rc;
     // gpu_attention: split kernels of the window, leaving the scaled scores in a_gpu
     AttnArgs da{};
@@ -810,22 +823,26 @@ int hgca_managed_decode_step(const hgca_shape *shape, const hgca_cache_state *ca
     ga.chunk = pick_chunk(cache->k_max, rows, HGCA_TARGET_WGS_SPARSE);
     ga.part = partials_at(ws_sparse, wsp, std::max(1, n_splits_for(cache->k_max, ga.chunk)));
     // the two parts need nothing from each other: one launch where the shapes allow
-    if (HGCA_FUSE_DENSE_GATHER && window.cap > 0 && cache->k_max > 0 && cache->pool_cap > 0 &&
-        dense_gather_fusable(shape->dtype, shape->head_dim, group_of(shape))) {
-        if ((rc = from_hip(launch_dense_gather(shape->dtype, shape->head_dim, da, ga, s))) != HGCA_OK) return rc;
+    if (one_launch) {
+        if ((rc = from_hip(launch_dense_gather(shape->dtype, shape->head_dim, da, ga, s, token_joins_in_split ? k_in : nullptr,
+                                               token_joins_in_split ? v_in : nullptr))) != HGCA_OK)
+            return rc;
     } else {
         if ((rc = from_hip(launch_attn_partial_dense(shape->dtype, shape->head_dim, da, s))) != HGCA_OK) return rc;
         if ((rc = from_hip(launch_attn_partial_gather(shape->dtype, shape->head_dim, ga, s))) != HGCA_OK) return rc;
     }
-    // merge_state over all split partials; the window's own lse comes out of the same fold
+    // merge_state over all split partials; A_gpu = e^{s - lse_g} with the window's own lse from the same fold;
+    // Alg. 1: A_maw <- (1 - alpha) A_maw + alpha A_gpu (the inserted token has no history); eviction and
+    // sparsification where a window is full.  All three are per (sequence, head) row: one launch.
+    if (HGCA_FUSE_DECODE_TAIL)
+        return from_hip(launch_decode_tail(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, a_gpu, c,
+                                           shape->n_q_heads, alpha, beta, token_joins_in_split ? 1 : 0, s));
     float *lse_w = reinterpret_cast<float *>(static_cast<char *>(ws_dense) + wd.row_aux);
     if ((rc = from_hip(launch_combine2(shape->head_dim, rows, da.part, ga.part, o_out, o_dtype, lse_out, s, lse_w))) != HGCA_OK)
         return rc;
-    // A_gpu = e^{s - lse_g}; Alg. 1: A_maw <- (1 - alpha) A_maw + alpha A_gpu (the inserted token has no history)
     if ((rc = from_hip(launch_window_weights(a_gpu, lse_w, window.seq_lens, rows, shape->n_q_heads, window.cap, c.a_maw, 1,
                                              alpha, s))) != HGCA_OK)
         return rc;
-    // Alg. 1: eviction and sparsification where a window is full
     return from_hip(launch_kv_evict(c, shape->batch, shape->n_q_heads, beta, s));
 }
 

@@ -74,7 +74,11 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s);
 // The window's split kernels and the per-head gather's split kernels (launch_attn_partial_dense and
 // launch_attn_partial_gather with the same arguments) as one launch; bf16, groups of 1, 2 or 4, per-head lists.
 bool dense_gather_fusable(int dtype, int head_dim, int group);
-hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, const AttnArgs &gather, hipStream_t s);
+// With k_new / v_new ([B, Hkv, row], paged window with a per-sequence first block only) the window takes one more
+// token per sequence in the same launch: the split that owns its position writes its rows into the window's block
+// first; the stored length is NOT updated (pending_window_len gives the length the launch works with).
+hipError_t launch_dense_gather(int dtype, int head_dim, const AttnArgs &dense, const AttnArgs &gather, hipStream_t s,
+                               const void *k_new = nullptr, const void *v_new = nullptr);
 
 // Union of the index lists of the heads of each group: idx [B, Hq, k_max] / cnt [B, Hq] -> out [B, Hkv, k_max_out]
 // ascending, -1 padded, out_cnt [B, Hkv].  Positions must lie in [0, n_positions).
@@ -131,6 +135,20 @@ hipError_t launch_append_weights_f32(int head_dim, const AppendArgs &a, hipStrea
 
 constexpr int32_t kCacheWindowFull = 1, kCacheContextFull = 2, kCacheListFull = 4;   // sticky bits of *status
 
+// Length of a window that takes n_new tokens: len + n_new if they fit the window's capacity and the sequence's table
+// row; otherwise the window takes none of them, the stored length stands and *fail_bits (if given) names the reason.
+// Every kernel that has to agree on the outcome before the new length is stored applies this one rule.
+__device__ __forceinline__ int pending_window_len(int len, int first_block, int n_new, int cap, int block_size,
+                                                  int max_blocks, int32_t *fail_bits)
+{
+    const bool no_room = len + n_new > cap;
+    if (len < 0 || no_room || first_block + (len + n_new - 1) / block_size >= max_blocks) {
+        if (fail_bits) *fail_bits = no_room ? kCacheWindowFull : kCacheContextFull;
+        return len;
+    }
+    return len + n_new;
+}
+
 struct CacheDev {
     char *k_blocks, *v_blocks;
     const int32_t *block_table;
@@ -146,6 +164,13 @@ struct CacheDev {
 hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
                             int32_t n_kv_heads, int32_t row_bytes, int32_t n_tokens, hipStream_t s);
 hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s);
+// Fold of the window's (p) and the salient list's (q) split partials, window weights e^{s - lse_window} in place in
+// a_gpu [n_rows, win_cap] with Alg. 1's moving average (one new token), eviction and sparsification: one launch.
+// token_pending: the token's rows are in the window but the stored length does not count it yet (see
+// launch_dense_gather); the launch then stores the new length, or raises the status bit if the token did not fit.
+hipError_t launch_decode_tail(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
+                              float *lse, float *a_gpu, const CacheDev &c, int32_t n_q_heads, float alpha, double beta,
+                              int32_t token_pending, hipStream_t s);
 
 // Copy of listed pool entries into per-head contiguous storage (KV_ctx of Alg. 1).
 struct CtxCompactArgs {

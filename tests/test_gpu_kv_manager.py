@@ -207,13 +207,20 @@ def test_status_bits_for_full_list_full_window_and_full_context(gpu):
     torch.cuda.synchronize()
     assert int(C.win_lens.cpu()[0]) == 32 and int(C.status.cpu()[0]) == hgca.CACHE_WINDOW_FULL
     # evicting each time the window fills walks to the end of the 4-block table row: then the context is full
-    C = cache.LayerCache(torch.bfloat16, 1, 4, 2, 128, 16, 2, 4, 64, 0.1)
+    # (the one-call step inserts the token inside its first launch and stores the length in its last: same outcome)
     q = torch.ones(1, 4, 128, dtype=torch.bfloat16, device="cuda:0")
-    for _ in range(70):
-        C.decode_step(q, tok, tok, 0.5, 1.0)
-    torch.cuda.synchronize()
-    assert int(C.status.cpu()[0]) & hgca.CACHE_CONTEXT_FULL
-    assert int(C.pool_lens.cpu()[0]) + int(C.win_lens.cpu()[0]) == 64     # nothing written beyond the row
+    state = {}
+    for one_call in (False, True):
+        C = cache.LayerCache(torch.bfloat16, 1, 4, 2, 128, 16, 2, 4, 64, 0.1)
+        for _ in range(70):
+            C.decode_step(q, tok, tok, 0.5, 1.0, one_call=one_call)
+        torch.cuda.synchronize()
+        assert int(C.status.cpu()[0]) & hgca.CACHE_CONTEXT_FULL
+        assert int(C.pool_lens.cpu()[0]) + int(C.win_lens.cpu()[0]) == 64     # nothing written beyond the row
+        state[one_call] = (int(C.status.cpu()[0]), C.win_lens.cpu().tolist(), C.pool_lens.cpu().tolist(),
+                           C.first_win_block.cpu().tolist(), C.ctx_cnt.cpu().tolist(), C.lse.cpu().numpy().copy())
+    assert state[False][:5] == state[True][:5]
+    np.testing.assert_allclose(state[True][5], state[False][5], atol=2e-5, rtol=0)
 
 
 @pytest.mark.parametrize("one_call", [False, True], ids=["separate_calls", "one_call"])
