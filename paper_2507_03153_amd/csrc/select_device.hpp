@@ -343,6 +343,214 @@ struct Sel {
         return true;
     }
 
+    // Long rows (too long for LDS as fp32) through a PRE-FILTER: a sample of the row (kSampleChunks runs of 1024
+    // scores spread evenly over it) gives an estimate of the score that a little more than the wanted fraction k / n
+    // of the row exceeds; one pass over the row then keeps, per wave and in position order, only the scores at or
+    // above that estimate (a few per cent of the row) in LDS, and the exact selection -- histogram, threshold bin,
+    // exact ranking inside it, ordered compaction -- runs on those few thousand entries.  The row is read once, a
+    // score costs one compare, and nothing of the row but the retained entries is written anywhere.  The estimate
+    // is only a filter: if fewer than k entries pass it, a wave's list overflows or the threshold bin is crowded,
+    // the function returns false before it has written any output and the caller runs select_row.  `lists` is the workgroup's dynamic LDS (list_bytes of it).
+    static constexpr int kSampleLoads = 8;                       // 16-byte loads per thread that make up the sample
+    static constexpr int kSampleChunk = 1024;                    // scores of one run of the sample
+    static constexpr int kSampleChunks = kSelBlock * kSampleLoads * 4 / kSampleChunk;
+    static __device__ __forceinline__ bool select_row_prefiltered(const SelectArgs &a, SelShared &sh, float *lists,
+                                                                  int list_bytes, const float *sc, int32_t *out, int n,
+                                                                  int k, int64_t bh)
+    {
+        constexpr int kSample = kSampleChunks * kSampleChunk;
+        const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
+        const bool sc_vec = (a.kv.cap & 3) == 0;     // rows start 16-byte aligned
+        const int cap_w = list_bytes / (kSelWaves * 8);              // entries of one wave's list
+        // the fraction of the row asked for, raised by six standard deviations of its estimate from the sample
+        const float p = (float)k / (float)n;
+        const float p_est = p + 6.f * sqrtf(p / (float)kSample) + 8.f / (float)kSample;
+        // not worth it (or no room) unless the retained entries are few: uniform over the workgroup
+        if (n < 2 * kSample || p_est * (float)n * 1.25f > (float)(cap_w * kSelWaves) || p_est > 0.2f) return false;
+
+        // ---- the sample: range, histogram, the estimate ---------------------------------------------------
+        float4 v[kSampleLoads];
+#pragma unroll
+        for (int u = 0; u < kSampleLoads; ++u) {
+            const int j = u * kSelBlock + tid;                       // float4 of the sample
+            const int c = j / (kSampleChunk / 4);
+            const int start = (int)((int64_t)c * (n - kSampleChunk) / (kSampleChunks - 1)) & ~3;
+            v[u] = load4_padded(sc, sc_vec, start + 4 * (j % (kSampleChunk / 4)), n);
+        }
+        float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < kSampleLoads; ++u) {
+            const float s[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { mx = fmaxf(mx, s[e]); mn = fminf(mn, s[e]); }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            mn = fminf(mn, __shfl_xor(mn, off, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        }
+        if (lane == 0) { sh.wave_min[w] = mn; sh.wave_max[w] = mx; }
+        for (int i = tid; i < kBins; i += kSelBlock) sh.hist[i] = 0u;
+        if (tid == 0) sh.n_cand = 0;
+        if (tid < kSelWaves) { sh.wave_gt[tid] = 0; sh.wave_eq[tid] = 0; }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kSelWaves; ++i) { mn = fminf(mn, sh.wave_min[i]); mx = fmaxf(mx, sh.wave_max[i]); }
+        if (!(mx > mn) || mn == -INFINITY || mx == INFINITY) return false;   // constant, NaN or infinite sample (uniform)
+        Binning bin;
+        bin.lo = mn;
+        bin.inv_w = (float)kBins / (mx - mn);
+#pragma unroll
+        for (int u = 0; u < kSampleLoads; ++u) {
+            atomicAdd(&sh.hist[bin(v[u].x)], 1u);
+            atomicAdd(&sh.hist[bin(v[u].y)], 1u);
+            atomicAdd(&sh.hist[bin(v[u].z)], 1u);
+            atomicAdd(&sh.hist[bin(v[u].w)], 1u);
+        }
+        __syncthreads();
+        locate_rank(sh, kBins, (uint32_t)min(kSample, (int)ceilf(p_est * (float)kSample)));
+        const float floor_score = mn + (float)sh.found[0] * ((mx - mn) / (float)kBins);   // lower edge of that bin
+        __syncthreads();
+
+        // ---- the row, once: entries at or above the estimate go to the wave's list, in position order -------
+        const int seg = segment_length(n);
+        const int padded = (n + seg - 1) / seg * seg;
+        const int steps = w * seg < padded ? seg / kStep : 0;        // uniform over a wave
+        const int pos0 = w * seg + 4 * lane;
+        float *my_score = lists + (size_t)w * 2 * cap_w;             // the wave's list: scores, then positions
+        int32_t *my_pos = reinterpret_cast<int32_t *>(my_score + cap_w);
+        int held = 0;                                                // entries of the wave's list (uniform over the wave)
+        float top = mx;                                              // largest score seen (the sample's or the wave's)
+        constexpr int U = 4;                                         // steps whose loads are in flight together
+        for (int i0 = 0; i0 < steps; i0 += U) {
+            float4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                r[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (i0 + u < steps) r[u] = load4_padded(sc, sc_vec, min(pos0 + kStep * (i0 + u), (n + 3) / 4 * 4), n);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float s[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+                bool keep[4];
+                int before = held;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    keep[e] = s[e] >= floor_score;                   // padding (-inf) and NaN fail
+                    top = fmaxf(top, s[e]);
+                    const unsigned long long m = __ballot(keep[e]);
+                    before += (int)lanes_below(m);
+                    held += __popcll(m);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (keep[e] && before < cap_w) {
+                        my_score[before] = s[e];
+                        my_pos[before] = pos0 + kStep * (i0 + u) + e;
+                    }
+                    before += keep[e];
+                }
+            }
+        }
+        top = wave_max(top);
+        if (lane == 0) { sh.wave_max[w] = top; sh.scan_scratch[w] = (uint32_t)held; }
+        for (int i = tid; i < kBins; i += kSelBlock) sh.hist[i] = 0u;
+        __syncthreads();
+        uint32_t total = 0;
+        bool overflow = false;
+#pragma unroll
+        for (int i = 0; i < kSelWaves; ++i) {
+            total += sh.scan_scratch[i];
+            overflow |= sh.scan_scratch[i] > (uint32_t)cap_w;
+            top = fmaxf(top, sh.wave_max[i]);
+        }
+        if (overflow || total < (uint32_t)k || !(top > floor_score) || top == INFINITY) return false;   // uniform
+
+        // ---- exact selection among the retained entries (each wave walks its own list) ----------------------
+        Binning fine;
+        fine.lo = floor_score;
+        fine.inv_w = (float)kBins / (top - floor_score);
+        for (int j = lane; j < held; j += kWave) atomicAdd(&sh.hist[fine(my_score[j])], 1u);
+        __syncthreads();
+        locate_rank(sh, kBins, (uint32_t)k);
+        const int tb = (int)sh.found[0];
+        const uint32_t k_rem = sh.found[1];          // rank of the k-th entry inside bin tb
+        __syncthreads();                             // the histogram's space now takes the bin's entries
+        uint32_t above = 0;
+        for (int j = lane; j < held; j += kWave) {
+            const float sj = my_score[j];
+            const int b = fine(sj);
+            above += b > tb;
+            if (b == tb) {
+                const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
+                if (slot < (uint32_t)kMaxCand) { sh.cand_score()[slot] = sj; sh.cand_idx()[slot] = my_pos[j]; }
+            }
+        }
+        above = (uint32_t)wave_sum((float)above);    // exact: far below 2^24 per wave
+        __syncthreads();
+        const uint32_t n_cand = sh.n_cand;
+        if (n_cand > (uint32_t)kMaxCand) return false;               // crowded bin (uniform over the workgroup)
+        float my_s = 0.f;
+        int32_t my_idx = 0;
+        if ((uint32_t)tid < n_cand) {
+            my_s = sh.cand_score()[tid];
+            my_idx = sh.cand_idx()[tid];
+        }
+        if (n_cand <= (uint32_t)kWave) {             // ranked by the first wave alone out of its registers
+            if (w == 0) {
+                uint32_t gt = 0, eq_lower = 0;
+                for (uint32_t j = 0; j < n_cand; ++j) {
+                    const float sj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_s), j));
+                    const int32_t ij = __builtin_amdgcn_readlane(my_idx, j);
+                    gt += sj > my_s;
+                    eq_lower += (sj == my_s) && (ij < my_idx);
+                }
+                if ((uint32_t)lane < n_cand && gt + eq_lower == k_rem - 1) {
+                    sh.found[0] = __float_as_uint(my_s);
+                    sh.found[1] = k_rem - gt;
+                }
+            }
+        } else if ((uint32_t)tid < n_cand) {         // one entry per thread
+            uint32_t gt = 0, eq_lower = 0;
+            for (uint32_t j = 0; j < n_cand; ++j) {
+                const float sj = sh.cand_score()[j];
+                gt += sj > my_s;
+                eq_lower += (sj == my_s) && (sh.cand_idx()[j] < my_idx);
+            }
+            if (gt + eq_lower == k_rem - 1) { sh.found[0] = __float_as_uint(my_s); sh.found[1] = k_rem - gt; }
+        }
+        __syncthreads();
+        const float thr = __uint_as_float(sh.found[0]);
+        const uint32_t need_eq = sh.found[1];
+        if ((uint32_t)tid < n_cand) {                // per-wave counts of the kept entries: the bin's own ...
+            if (my_s > thr) atomicAdd(&sh.wave_gt[my_idx / seg], 1u);
+            if (my_s == thr) atomicAdd(&sh.wave_eq[my_idx / seg], 1u);
+        }
+        if (lane == 0) atomicAdd(&sh.wave_gt[w], above);             // ... and those above it
+        __syncthreads();
+        uint32_t run_gt = 0, run_eq = 0;             // entries above / equal to T in the lists of the waves before
+        for (int i = 0; i < w; ++i) { run_gt += sh.wave_gt[i]; run_eq += sh.wave_eq[i]; }
+
+        // ordered compaction of the lists (they are in position order, wave after wave): kept iff score > T, or
+        // score == T and fewer than need_eq equal scores stand before it
+        float *sel = a.sel_scores ? a.sel_scores + bh * a.k_max : nullptr;
+        for (int j0 = 0; j0 < held; j0 += kWave) {
+            const int j = j0 + lane;
+            const float sj = j < held ? my_score[j] : -INFINITY;
+            const bool gt = sj > thr, eq = sj == thr;
+            const unsigned long long m_gt = __ballot(gt), m_eq = __ballot(eq);
+            const uint32_t gt_before = run_gt + lanes_below(m_gt), eq_before = run_eq + lanes_below(m_eq);
+            if (gt || (eq && eq_before < need_eq)) {
+                const uint32_t at = gt_before + min(eq_before, need_eq);
+                out[at] = my_pos[j];
+                if (sel) sel[at] = sj;
+            }
+            run_gt += __popcll(m_gt);
+            run_eq += __popcll(m_eq);
+        }
+        return true;
+    }
+
     template <int MODE>
     static __device__ __forceinline__ void select_row(const SelectArgs &a, SelShared &sh, float *cache,
                                                       const float *sc, int32_t *out, int n, int k, int64_t bh)
@@ -700,11 +908,14 @@ struct Sel {
 template <int BLOCK, int REG_STEPS>
 __device__ __forceinline__ void select_row_any(const SelectArgs &a, typename Sel<BLOCK>::SelShared &sh, float *cache,
                                                const float *sc, int32_t *out, int n, int k, int64_t bh,
-                                               int cache_floats, int cache_bytes)
+                                               int cache_floats, int cache_bytes, int list_bytes)
 {
     using S = Sel<BLOCK>;
     if (REG_STEPS > 0 && S::segment_length(n) <= REG_STEPS * kStep) {      // the row fits the lanes' registers
         if (S::template select_row_in_registers<(REG_STEPS > 0 ? REG_STEPS : 1)>(a, sh, sc, out, n, k, bh)) return;
+        __syncthreads();                         // the general path starts over on the shared state
+    } else if (list_bytes > 0 && S::padded_length(n) > cache_floats) {     // too long for LDS as fp32: pre-filter
+        if (S::select_row_prefiltered(a, sh, cache, list_bytes, sc, out, n, k, bh)) return;
         __syncthreads();                         // the general path starts over on the shared state
     }
     if (S::padded_length(n) <= cache_floats) S::template select_row<kCachedScores>(a, sh, cache, sc, out, n, k, bh);
@@ -716,7 +927,7 @@ __device__ __forceinline__ void select_row_any(const SelectArgs &a, typename Sel
 // `bh` is the row (b * n_q_heads + h); sel_scores rows are addressed with it as well.
 template <int BLOCK, int REG_STEPS>
 __device__ __forceinline__ void select_one_row(const SelectArgs &a, typename Sel<BLOCK>::SelShared &sh, float *cache,
-                                               int64_t bh, int cache_floats, int cache_bytes)
+                                               int64_t bh, int cache_floats, int cache_bytes, int list_bytes)
 {
     const int b = (int)(bh / a.sh.n_q_heads);
     const int tid = threadIdx.x;
@@ -737,7 +948,7 @@ __device__ __forceinline__ void select_one_row(const SelectArgs &a, typename Sel
         }
         return;
     }
-    select_row_any<BLOCK, REG_STEPS>(a, sh, cache, sc, out, n, k, bh, cache_floats, cache_bytes);
+    select_row_any<BLOCK, REG_STEPS>(a, sh, cache, sc, out, n, k, bh, cache_floats, cache_bytes, list_bytes);
 }
 
 }  // namespace

@@ -14,6 +14,12 @@
 //      of the comparisons, so the pass needs no barrier per step; positions are
 //      staged in LDS and leave with coalesced stores.
 //
+// Rows too long to sit in LDS as fp32 (beyond 33 792 scores) that have a compute unit to themselves first try a
+// sampled pre-filter (select_row_prefiltered): an estimate of the threshold from 32 768 sampled scores, one pass over
+// the row that retains the few per cent at or above it in LDS, and the steps above on the retained entries only.
+// It gives the same result or gives up (then the steps above run on the whole row, held as one byte per score or
+// re-read from memory).  Measured on 256 rows of 122 880 scores, k = 4096: 63 -> 38 us.
+//
 // A row is one CU's work; with a handful of VALU operations per score and pass the
 // kernel is bound by that CU's instruction issue, so the passes are kept lean
 // (no validity tests thanks to the padding, float compares instead of integer
@@ -22,6 +28,7 @@
 // stand at the launch).
 #include "select_device.hpp"
 
+#include <algorithm>
 #include <atomic>
 
 namespace hgca {
@@ -36,17 +43,22 @@ namespace {
 #define HGCA_SEL_REG_STEPS_SMALL 0
 #endif
 
+// 1: rows too long for LDS as fp32 go through the sampled pre-filter first (large workgroups only)
+#ifndef HGCA_SEL_PREFILTER
+#define HGCA_SEL_PREFILTER 1
+#endif
+
 // One workgroup per (sequence, query head) row.  The small workgroups are held to 64 registers per lane so that
 // four of them fit a compute unit.
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK, BLOCK == kLargeBlock ? 1 : 8) void select_topk_kernel(SelectArgs a, int cache_floats,
-                                                                                        int cache_bytes)
+                                                                                        int cache_bytes, int list_bytes)
 {
     using S = Sel<BLOCK>;
     extern __shared__ __attribute__((aligned(16))) float s_cache[];
     __shared__ typename S::SelShared sh;
-    select_one_row<BLOCK, (BLOCK == kLargeBlock ? HGCA_SEL_REG_STEPS_LARGE : HGCA_SEL_REG_STEPS_SMALL)>(a, sh, s_cache, blockIdx.x,
-                                                                                                        cache_floats, cache_bytes);
+    select_one_row<BLOCK, (BLOCK == kLargeBlock ? HGCA_SEL_REG_STEPS_LARGE : HGCA_SEL_REG_STEPS_SMALL)>(
+        a, sh, s_cache, blockIdx.x, cache_floats, cache_bytes, list_bytes);
 }
 
 // The launch uses the small workgroups when there are more rows than compute units (256 on the MI355X) and two
@@ -82,9 +94,14 @@ hipError_t launch_select_block(const SelectArgs &a, int64_t rows, int max_cache_
         if (rc != hipSuccess) return rc;
         if (tracked) limit_lifted[dev].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(select_topk_kernel<BLOCK>, dim3((unsigned)rows), dim3(BLOCK),
-                       cache_floats ? (size_t)cache_floats * sizeof(float) : (size_t)cache_bytes, s, a, cache_floats,
-                       cache_bytes);
+    // rows that do not fit as fp32 try the pre-filter first when the workgroup is alone on its unit: its lists take
+    // the whole dynamic allocation (the byte cache of the general path, if that runs after all, uses the same memory)
+    const int list_bytes = HGCA_SEL_PREFILTER && BLOCK == kLargeBlock && cache_floats == 0
+                               ? kMaxCacheFloats * (int)sizeof(float) : 0;
+    const size_t lds = cache_floats ? (size_t)cache_floats * sizeof(float)
+                                    : std::max((size_t)cache_bytes, (size_t)list_bytes);
+    hipLaunchKernelGGL(select_topk_kernel<BLOCK>, dim3((unsigned)rows), dim3(BLOCK), lds, s, a, cache_floats,
+                       cache_bytes, list_bytes);
     return hipGetLastError();
 }
 

@@ -260,6 +260,12 @@ def test_decode_steps_maw_then_threshold_then_sparse_attention(gpu, oracle):
     (8, 32, 4096, 409, "maw"),
     # more rows than compute units (512-thread workgroups): rows held as fp32, rows held as bytes with plenty of ties
     (10, 32, 4096, 409, "maw"), (10, 32, 9000, 900, "coarse"), (9, 32, 20001, 6667, "normal"),
+    # rows too long for LDS as fp32 (sampled pre-filter, then the exact selection among what it retains): the usual
+    # case, a budget of one, a peaked row, ties everywhere (the filter gives up: crowded bin), scores that grow
+    # along the row (the last waves' lists overflow: the filter gives up), a budget too large for the filter
+    (2, 8, 122880, 4096, "normal"), (1, 4, 70001, 1, "normal"), (1, 4, 140000, 3000, "maw"),
+    (1, 2, 100000, 1500, "coarse"), (1, 4, 90000, 2500, "trend"), (1, 2, 80000, 30000, "normal"),
+    (1, 4, 100000, 2000, "tie"),                # a handful of equal scores exactly where the budget cuts
 ])
 def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kind):
     torch, hgca, _ = gpu
@@ -269,6 +275,14 @@ def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kin
     if kind == "maw":                                           # weights of a peaked softmax: many tiny values, exact zeros
         s = softmax(12.0 * z, axis=-1).astype(np.float32)
         s[s < 1e-12] = 0.0
+    elif kind == "tie":
+        s = z.astype(np.float32)
+        for b in range(B):
+            for h in range(Hq):
+                order = np.argsort(-s[b, h], kind="stable")
+                s[b, h, order[k + 40:k + 46]] = s[b, h, order[k - 1]]   # six more entries with the k-th largest score
+    elif kind == "trend":
+        s = (z + np.linspace(0.0, 12.0, cap)).astype(np.float32)
     elif kind == "coarse":
         s = np.round(z, 1).astype(np.float32)                   # plenty of exact ties
     else:
