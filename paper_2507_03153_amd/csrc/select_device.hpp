@@ -452,6 +452,18 @@ struct Sel {
                 }
             }
         }
+        return select_from_lists(a, sh, my_score, my_pos, held, cap_w, top, floor_score, seg, out, k, bh);
+    }
+
+    // The exact selection among the entries the waves retained (wave w: `held` entries in my_score / my_pos, in position
+    // order, all >= floor_score; top: the largest score the wave has seen).  Returns false, before any output is
+    // written, if a list overflowed its cap_w entries, fewer than k entries were retained, or the threshold bin is
+    // too crowded to rank its entries one per thread.  sh.n_cand, sh.wave_gt and sh.wave_eq must be zero on entry.
+    static __device__ __forceinline__ bool select_from_lists(const SelectArgs &a, SelShared &sh, const float *my_score,
+                                                             const int32_t *my_pos, int held, int cap_w, float top,
+                                                             float floor_score, int seg, int32_t *out, int k, int64_t bh)
+    {
+        const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
         top = wave_max(top);
         if (lane == 0) { sh.wave_max[w] = top; sh.scan_scratch[w] = (uint32_t)held; }
         for (int i = tid; i < kBins; i += kSelBlock) sh.hist[i] = 0u;
