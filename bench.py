@@ -443,6 +443,7 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
     q = torch.randn(B, n_q, Hq, d, generator=g).to(torch.bfloat16).to(dev)
     f32 = dict(dtype=torch.float32, device=dev)
     ws = hgca.append_workspace(L.shape, n_q, max(W, P), dev)
+    ws_t = hgca.append_tiers_workspace(L.shape, n_q, W, P, dev)
     ow, lw = torch.empty(B, n_q, Hq, d, **f32), torch.empty(B, n_q, Hq, **f32)
     op, lp = torch.empty_like(ow), torch.empty_like(lw)
     o, lse = torch.empty_like(ow), torch.empty_like(lw)
@@ -458,6 +459,11 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
         # the same attention with the weights rounded once to bf16 for the second contraction (HGCA_APPEND_ONE_PART_P)
         "append_attn_window_one_part_p": lambda: hgca.append_attn(L.shape, q, L.window, True, ow, lw, ws, one_part_p=True),
         "append_attn_pool_one_part_p": lambda: hgca.append_attn(L.shape, q, L.pool, False, op, lp, ws, one_part_p=True),
+        # both tiers in one call: one launch for the splits of window and pool, one fold (merged output + per-tier lse)
+        "append_attn_tiers": lambda: hgca.append_attn_tiers(L.shape, q, L.window, L.pool, o, lse, ws_t, lse_window_out=lw,
+                                                            lse_pool_out=lp),
+        "append_attn_tiers_one_part_p": lambda: hgca.append_attn_tiers(L.shape, q, L.window, L.pool, o, lse, ws_t,
+                                                                       lse_window_out=lw, lse_pool_out=lp, one_part_p=True),
     }
     ms = {}
     for name, fn in calls.items():
@@ -474,10 +480,12 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
     elem = 2
     kv_bytes = 2 * B * Hkv * (W + P) * d * elem                 # K and V of both tiers, once per KV head
     flops = 4.0 * B * Hq * n_q * (W + P) * d                    # QK^T and PV, 2 flops per multiply-add (causal skip ignored)
-    attn_ms = ms["append_attn_window"] + ms["append_attn_pool"] + ms["lse_merge"]
-    one_ms = ms["append_attn_window_one_part_p"] + ms["append_attn_pool_one_part_p"] + ms["lse_merge"]
+    attn_ms = ms["append_attn_tiers"]                           # window + pool + merge as the one call that serves them
+    one_ms = ms["append_attn_tiers_one_part_p"]
+    three_calls_ms = ms["append_attn_window"] + ms["append_attn_pool"] + ms["lse_merge"]
     weights_ms = ms["append_weights_window"] + ms["append_weights_pool"]
-    return {"n_q": n_q, "per_call_ms": ms, "attention_ms": attn_ms, "with_weights_ms": attn_ms + weights_ms,
+    return {"n_q": n_q, "per_call_ms": ms, "attention_ms": attn_ms, "attention_three_calls_ms": three_calls_ms,
+            "with_weights_ms": attn_ms + weights_ms,
             "tokens_per_s": B * n_q / (attn_ms * 1e-3),
             "kv_bytes": kv_bytes, "hbm_frac": kv_bytes / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "tflops": flops / (attn_ms * 1e-3) / 1e12, "mfma_frac_bf16": flops / (attn_ms * 1e-3) / 2.5e15,

@@ -547,6 +547,26 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q,
                      float *o_out, float *lse_out,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Both parts of the append branch of Alg. 2 in one call: attention of the N
+ * queries over the window (HGCA_APPEND_CAUSAL_TAIL in `flags` applies to the
+ * window) and over the COMPLETE older pool, merged per (sequence, query, head)
+ * with merge_state.  The same results as hgca_append_attn on each tier and
+ * hgca_lse_merge (up to the order of fp32 additions), in two launches instead
+ * of five: the splits of both tiers share one launch and one split size, and
+ * one fold of all split partials yields the merged output together with each
+ * tier's own log-sum-exp.  o_out fp32 [B, N, Hq, d], lse_out fp32 [B, N, Hq];
+ * lse_window_out / lse_pool_out (fp32 [B, N, Hq], optional) receive the
+ * per-tier lse that hgca_append_weights normalises with.  bf16 inputs only
+ * (HGCA_ERR_UNSUPPORTED for fp32: use the per-tier calls).  ws needs
+ * hgca_append_tiers_workspace_bytes(shape, n_q, window->cap, pool->cap). */
+size_t hgca_append_tiers_workspace_bytes(const hgca_shape *shape, int32_t n_q,
+                                         int32_t window_cap, int32_t pool_cap);
+int hgca_append_attn_tiers(const hgca_shape *shape, const void *q, int32_t n_q,
+                           const hgca_kv_view *window, const hgca_kv_view *pool,
+                           int32_t flags, float *o_out, float *lse_out,
+                           float *lse_window_out, float *lse_pool_out,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
 /* A_gpu / A_cpu of the append branch (Alg. 2 returns them; Alg. 1 re-evaluates
  * the salient set with ids = A_cpu > beta / A_cpu.size): one weight per head
  * and entry, the average over the N queries of the part's own softmax weights,

@@ -181,9 +181,16 @@ __device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, in
 // TILES row tiles of 16 query rows per wave (128 rows per workgroup, so 8 / TILES waves): with two tiles every K
 // and V operand read from LDS feeds two matrix instructions, and the two tiles' softmax chains are independent
 // work for the wave to overlap.
+//
+// A launch may serve TWO tiers (the window and the complete pool of an append turn: Alg. 2 runs the two attentions
+// side by side): the first a1.part.n_splits workgroups along x take the splits of a1, the rest those of a2, each
+// with its tier's view, mask rule, split size and partials; everything else (queries, shape) is common.  One launch
+// then pays one ramp-up and one tail, and the short tier's splits can be as long as the long tier's.
 template <int D, int G, bool SPLIT_P, int TILES>
-__global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel(AppendArgs a)
+__global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel(AppendArgs a1, AppendArgs a2)
 {
+    const bool second = (int)blockIdx.x >= a1.part.n_splits;     // uniform over the workgroup
+    const AppendArgs &a = second ? a2 : a1;
     constexpr int NW = kAWaves / TILES, BLOCK = NW * kWave;
     using S = DmaStage<D, NW>;
     constexpr int DT = D / 16;
@@ -197,7 +204,8 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
     __shared__ uint32_t s_row[kSub];
 
     const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int split = blockIdx.x, kvh = blockIdx.y / n_qb, qb = blockIdx.y % n_qb, b = blockIdx.z;
+    const int split = (int)blockIdx.x - (second ? a1.part.n_splits : 0);
+    const int kvh = blockIdx.y / n_qb, qb = blockIdx.y % n_qb, b = blockIdx.z;
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave, n = lane % 16, g = lane / 16;
     const int len = tier_len(a.kv, b);
     const int t0 = split * a.chunk;
@@ -559,15 +567,15 @@ hipError_t launch_weights_f32_group(const AppendArgs &a, dim3 grid, hipStream_t 
 }
 
 template <int D, bool SPLIT_P>
-hipError_t launch_attn_group(const AppendArgs &a, dim3 grid, hipStream_t s)
+hipError_t launch_attn_group(const AppendArgs &a, const AppendArgs &a2, dim3 grid, hipStream_t s)
 {
     constexpr int T = HGCA_APPEND_TILES;
     const dim3 block(kABlock / T);
     switch (a.sh.group) {
-    case 1: hipLaunchKernelGGL((append_attn_kernel<D, 1, SPLIT_P, T>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((append_attn_kernel<D, 2, SPLIT_P, T>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((append_attn_kernel<D, 4, SPLIT_P, T>), grid, block, 0, s, a); break;
-    case 8: hipLaunchKernelGGL((append_attn_kernel<D, 8, SPLIT_P, T>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((append_attn_kernel<D, 1, SPLIT_P, T>), grid, block, 0, s, a, a2); break;
+    case 2: hipLaunchKernelGGL((append_attn_kernel<D, 2, SPLIT_P, T>), grid, block, 0, s, a, a2); break;
+    case 4: hipLaunchKernelGGL((append_attn_kernel<D, 4, SPLIT_P, T>), grid, block, 0, s, a, a2); break;
+    case 8: hipLaunchKernelGGL((append_attn_kernel<D, 8, SPLIT_P, T>), grid, block, 0, s, a, a2); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -588,14 +596,27 @@ hipError_t launch_weights_group(const AppendArgs &a, dim3 grid, hipStream_t s)
 
 }  // namespace
 
+hipError_t launch_append_attn2(int head_dim, const AppendArgs &a, const AppendArgs &a2, hipStream_t s)
+{
+    const int n_splits = a.part.n_splits + a2.part.n_splits;
+    if (a.sh.batch == 0 || a.n_q == 0 || n_splits == 0) return hipSuccess;
+    if (a2.part.n_splits > 0 && (a2.n_q != a.n_q || a2.one_part_p != a.one_part_p || a2.q != a.q || a2.sh.group != a.sh.group ||
+                                 a2.sh.batch != a.sh.batch || a2.sh.n_kv_heads != a.sh.n_kv_heads))
+        return hipErrorInvalidValue;             // the two tiers share the queries and the launch shape
+    const int n_qb = (a.n_q * a.sh.group + kRowsPerBlock - 1) / kRowsPerBlock;
+    dim3 grid(n_splits, a.sh.n_kv_heads * n_qb, a.sh.batch);
+    if (head_dim == 64)
+        return a.one_part_p ? launch_attn_group<64, false>(a, a2, grid, s) : launch_attn_group<64, true>(a, a2, grid, s);
+    if (head_dim == 128)
+        return a.one_part_p ? launch_attn_group<128, false>(a, a2, grid, s) : launch_attn_group<128, true>(a, a2, grid, s);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s)
 {
-    if (a.sh.batch == 0 || a.n_q == 0 || a.part.n_splits == 0) return hipSuccess;
-    const int n_qb = (a.n_q * a.sh.group + kRowsPerBlock - 1) / kRowsPerBlock;
-    dim3 grid(a.part.n_splits, a.sh.n_kv_heads * n_qb, a.sh.batch);
-    if (head_dim == 64) return a.one_part_p ? launch_attn_group<64, false>(a, grid, s) : launch_attn_group<64, true>(a, grid, s);
-    if (head_dim == 128) return a.one_part_p ? launch_attn_group<128, false>(a, grid, s) : launch_attn_group<128, true>(a, grid, s);
-    return hipErrorInvalidValue;
+    AppendArgs none = a;                         // no second tier: every workgroup takes a split of `a`
+    none.part.n_splits = 0;
+    return launch_append_attn2(head_dim, a, none, s);
 }
 
 hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks, hipStream_t s)

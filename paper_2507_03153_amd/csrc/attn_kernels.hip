@@ -108,10 +108,11 @@ __global__ __launch_bounds__(kBlock) void dense_attn_mfma_kernel(KernelArgs a)
 
 // One workgroup folds one (b, h) row (fold_device.hpp); lse_p, if given, receives the log-sum-exp of set p alone.
 template <int D, bool OUT_BF16>
-__global__ __launch_bounds__(kFoldBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse, float *lse_p)
+__global__ __launch_bounds__(kFoldBlock) void combine_kernel(Partials p, Partials q, void *o, float *lse, float *lse_p,
+                                                             float *lse_q)
 {
     __shared__ FoldShared<D> sh;
-    if (lse_p) fold_row<D, OUT_BF16, true>(sh, p, q, o, lse, lse_p, blockIdx.x);     // uniform over the launch
+    if (lse_p) fold_row<D, OUT_BF16, true>(sh, p, q, o, lse, lse_p, blockIdx.x, lse_q);   // uniform over the launch
     else fold_row<D, OUT_BF16, false>(sh, p, q, o, lse, nullptr, blockIdx.x);
 }
 
@@ -276,14 +277,15 @@ hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float
 }
 
 hipError_t launch_combine2(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
-                           float *lse, hipStream_t s, float *lse_p)
+                           float *lse, hipStream_t s, float *lse_p, float *lse_q)
 {
+    if (lse_q && !lse_p) return hipErrorInvalidValue;
     if (n_rows == 0) return hipSuccess;
     const dim3 grid((unsigned)n_rows), block(kFoldBlock);
-    if (head_dim == 64 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<64, false>), grid, block, s, p, q, o, lse, lse_p);
-    else if (head_dim == 64 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<64, true>), grid, block, s, p, q, o, lse, lse_p);
-    else if (head_dim == 128 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<128, false>), grid, block, s, p, q, o, lse, lse_p);
-    else if (head_dim == 128 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<128, true>), grid, block, s, p, q, o, lse, lse_p);
+    if (head_dim == 64 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<64, false>), grid, block, s, p, q, o, lse, lse_p, lse_q);
+    else if (head_dim == 64 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<64, true>), grid, block, s, p, q, o, lse, lse_p, lse_q);
+    else if (head_dim == 128 && o_dtype == 0) HGCA_LAUNCH((combine_kernel<128, false>), grid, block, s, p, q, o, lse, lse_p, lse_q);
+    else if (head_dim == 128 && o_dtype == 1) HGCA_LAUNCH((combine_kernel<128, true>), grid, block, s, p, q, o, lse, lse_p, lse_q);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

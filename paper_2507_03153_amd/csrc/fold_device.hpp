@@ -23,9 +23,10 @@ template <int D> struct FoldShared {
 // the SG groups are then added through LDS.  Called by all kFoldBlock threads of a workgroup.  With WANT_P the
 // log-sum-exp of set p alone (the window part of a step: its attention weights are normalised by it) is formed by
 // the last wave, stored to lse_p[row] if lse_p is given, and returned to every thread; otherwise 0 is returned.
+// lse_q (with WANT_P only) receives the same for set q.
 template <int D, bool OUT_BF16, bool WANT_P>
 __device__ __forceinline__ float fold_row(FoldShared<D> &sh, const Partials &p, const Partials &q, void *o, float *lse,
-                                          float *lse_p, int64_t row)
+                                          float *lse_p, int64_t row, float *lse_q = nullptr)
 {
     constexpr int C4 = D / 4;                    // threads across the columns (one float4 each)
     constexpr int SG = kFoldBlock / C4;          // split groups
@@ -72,6 +73,18 @@ __device__ __forceinline__ float fold_row(FoldShared<D> &sh, const Partials &p, 
             sh.lse_p = v;
             if (lse_p) lse_p[row] = v;
         }
+    }
+    // set q alone, on the wave before the last, if asked for (uniform over the launch)
+    if (WANT_P && lse_q && tid / kWave == kFoldWaves - 2) {
+        const int lane = tid % kWave, nq = q.n_splits;
+        float Mq = -INFINITY;
+        for (int s = lane; s < nq; s += kWave) Mq = fmaxf(Mq, q.m[row * nq + s]);
+        Mq = wave_max(Mq);
+        float Lq = 0.f;
+        if (Mq != -INFINITY)
+            for (int s = lane; s < nq; s += kWave) Lq = fmaf(q.l[row * nq + s], expf(q.m[row * nq + s] - Mq), Lq);
+        Lq = wave_sum(Lq);
+        if (lane == 0) lse_q[row] = (Mq != -INFINITY) ? Mq + logf(Lq) : -INFINITY;
     }
     __syncthreads();
 #pragma unroll

@@ -29,6 +29,13 @@ constexpr size_t kAlign = 256;
 #define HGCA_TARGET_WGS_SPARSE_SCORED 2048
 #endif
 
+// Workgroups the append-stage attention aims at per launch: what the device holds at once (two per compute unit).
+// Every workgroup writes a partial of 128 rows x d floats (64 KB, read again by the fold: the K/V bytes of four
+// 64-token steps), so splits are as long as filling the device allows.  Measured on the 8B shape, N = 32, with
+// 512 / 768 / 1024 / 1536: window 55.7 / 61.0 / 66.0 / 74.8 us, pool 258.5 / 273.4 / 266.6 / 288.1 us.
+#ifndef HGCA_APPEND_TARGET_WGS
+#define HGCA_APPEND_TARGET_WGS 512
+#endif
 // 1: the token of a managed decode step is written into the window by the window split that reads it (needs the two below)
 #ifndef HGCA_FUSE_KV_APPEND
 #define HGCA_FUSE_KV_APPEND 1
@@ -882,7 +889,7 @@ int append_want_splits(const hgca_shape *s, int32_t n_q)
 {
     const int64_t n_qb = ((int64_t)n_q * group_of(s) + 127) / 128;
     const int64_t units = std::max<int64_t>(1, (int64_t)s->batch * s->n_kv_heads * n_qb);
-    return (int)std::max<int64_t>(1, 1024 / units);
+    return (int)std::max<int64_t>(1, HGCA_APPEND_TARGET_WGS / units);
 }
 
 int append_chunk(const hgca_shape *s, int32_t n_q, int64_t cap)
@@ -992,6 +999,88 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const 
     return from_hip(launch_combine(shape->head_dim, rows, a.part, o_out, lse_out, s));
 }
 
+namespace {
+
+// Workspace of the two-tier append attention: split partials of the window and of the pool (splits of one common
+// size, chosen for the two tiers together), and the two per-tier lse rows for callers that do not ask for them.
+struct TiersWs {
+    size_t o_w, m_w, l_w, o_p, m_p, l_p, lse_w, lse_p, total;
+    int chunk, n_w, n_p;
+};
+
+TiersWs tiers_layout(const hgca_shape *s, int32_t n_q, int64_t win_cap, int64_t pool_cap)
+{
+    TiersWs w{};
+    const int want = append_want_splits(s, n_q);
+    int64_t chunk = (std::max<int64_t>(win_cap + pool_cap, 1) + want - 1) / want;
+    chunk = (chunk + 63) / 64 * 64;
+    w.chunk = (int)std::min<int64_t>(kMaxAppendChunk, std::max<int64_t>(kMinChunk, chunk));
+    w.n_w = win_cap > 0 ? n_splits_for(win_cap, w.chunk) : 0;
+    w.n_p = pool_cap > 0 ? n_splits_for(pool_cap, w.chunk) : 0;
+    const size_t rows = (size_t)s->batch * n_q * s->n_q_heads;
+    size_t at = 0;
+    w.o_w = at; at += align_up(rows * w.n_w * s->head_dim * sizeof(float));
+    w.m_w = at; at += align_up(rows * w.n_w * sizeof(float));
+    w.l_w = at; at += align_up(rows * w.n_w * sizeof(float));
+    w.o_p = at; at += align_up(rows * w.n_p * s->head_dim * sizeof(float));
+    w.m_p = at; at += align_up(rows * w.n_p * sizeof(float));
+    w.l_p = at; at += align_up(rows * w.n_p * sizeof(float));
+    w.lse_w = at; at += align_up(rows * sizeof(float));
+    w.lse_p = at; at += align_up(rows * sizeof(float));
+    w.total = std::max<size_t>(at, kAlign);
+    return w;
+}
+
+}  // namespace
+
+size_t hgca_append_tiers_workspace_bytes(const hgca_shape *shape, int32_t n_q, int32_t window_cap, int32_t pool_cap)
+{
+    if (check_shape(shape) != HGCA_OK || n_q < 0 || window_cap < 0 || pool_cap < 0) return 0;
+    return tiers_layout(shape, n_q, window_cap, pool_cap).total;
+}
+
+int hgca_append_attn_tiers(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *window,
+                           const hgca_kv_view *pool, int32_t flags, float *o_out, float *lse_out, float *lse_window_out,
+                           float *lse_pool_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_append(shape, q, n_q, window, true);
+    if (rc != HGCA_OK) return rc;
+    if ((rc = check_append(shape, q, n_q, pool, true)) != HGCA_OK) return rc;
+    if (flags & ~(HGCA_APPEND_CAUSAL_TAIL | HGCA_APPEND_ONE_PART_P)) return HGCA_ERR_INVALID_ARG;
+    if (shape->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;      // fp32 inputs: one call per tier and hgca_lse_merge
+    if (shape->batch == 0 || n_q == 0) return HGCA_OK;
+    if (!o_out || !lse_out || !aligned16(o_out)) return HGCA_ERR_INVALID_ARG;
+    if ((int64_t)shape->n_kv_heads * (((int64_t)n_q * group_of(shape) + 127) / 128) > 65535) return HGCA_ERR_UNSUPPORTED;
+    const TiersWs w = tiers_layout(shape, n_q, window->cap, pool->cap);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return HGCA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+
+    AppendArgs aw{}, ap{};
+    aw.sh = ap.sh = to_dev(shape);
+    aw.q = ap.q = q;
+    aw.n_q = ap.n_q = n_q;
+    aw.one_part_p = ap.one_part_p = (flags & HGCA_APPEND_ONE_PART_P) ? 1 : 0;
+    aw.chunk = ap.chunk = w.chunk;
+    aw.kv = to_dev(window);
+    aw.causal_tail = (flags & HGCA_APPEND_CAUSAL_TAIL) ? 1 : 0;
+    aw.part = Partials{reinterpret_cast<float *>(base + w.o_w), reinterpret_cast<float *>(base + w.m_w),
+                       reinterpret_cast<float *>(base + w.l_w), w.n_w};
+    ap.kv = to_dev(pool);
+    ap.causal_tail = 0;
+    ap.part = Partials{reinterpret_cast<float *>(base + w.o_p), reinterpret_cast<float *>(base + w.m_p),
+                       reinterpret_cast<float *>(base + w.l_p), w.n_p};
+    // the pool's splits take the lower block numbers: they are the bulk of the launch
+    if ((rc = from_hip(launch_append_attn2(shape->head_dim, ap, aw, s))) != HGCA_OK) return rc;
+    // merge_state over the splits of both tiers at once; each tier's own lse comes out of the same fold
+    const int64_t rows = (int64_t)shape->batch * n_q * shape->n_q_heads;
+    float *lse_w = lse_window_out ? lse_window_out : reinterpret_cast<float *>(base + w.lse_w);
+    float *lse_p = lse_pool_out ? lse_pool_out : reinterpret_cast<float *>(base + w.lse_p);
+    const bool want_tiers = lse_window_out || lse_pool_out;
+    return from_hip(launch_combine2(shape->head_dim, rows, aw.part, ap.part, o_out, 0, lse_out, s,
+                                    want_tiers ? lse_w : nullptr, want_tiers ? lse_p : nullptr));
+}
+
 int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier,
                         int32_t causal_tail, const float *lse, float *a_out, void *hip_stream)
 {
@@ -1029,7 +1118,8 @@ ManagedAppendWs managed_append_layout(const hgca_shape *s, int32_t n_q, int32_t 
 {
     ManagedAppendWs w{};
     const size_t rows = (size_t)s->batch * n_q * s->n_q_heads;
-    w.attn_bytes = append_layout(s, n_q, std::max(win_cap, pool_cap)).total;
+    w.attn_bytes = std::max(append_layout(s, n_q, std::max(win_cap, pool_cap)).total,
+                            tiers_layout(s, n_q, win_cap, pool_cap).total);
     size_t at = 0;
     w.attn = at; at += align_up(w.attn_bytes);
     w.o_w = at; at += align_up(rows * s->head_dim * sizeof(float));
@@ -1091,16 +1181,23 @@ int hgca_managed_append_step(const hgca_shape *shape, const hgca_cache_state *ca
     // Alg. 2, append branch: KV_gpu' = concat(KV_gpu, KV_in)
     if ((rc = from_hip(launch_kv_append(c, k_in, v_in, nullptr, shape->batch, shape->n_kv_heads, row_bytes, n_q, s))) != HGCA_OK)
         return rc;
-    // gpu_attention over the window (causal among the incoming tokens), cpu_attention over the complete offloaded cache
-    if ((rc = hgca_append_attn(shape, q, n_q, &window, flags | HGCA_APPEND_CAUSAL_TAIL, o_w, lse_w, base + w.attn,
-                               w.attn_bytes, hip_stream)) != HGCA_OK)
-        return rc;
-    if ((rc = hgca_append_attn(shape, q, n_q, &pool, flags, o_p, lse_p, base + w.attn, w.attn_bytes, hip_stream)) != HGCA_OK)
-        return rc;
-    // merge_state per (sequence, query, head)
-    hgca_shape merged = *shape;
-    merged.batch = shape->batch * n_q;
-    if ((rc = hgca_lse_merge(&merged, o_p, lse_p, o_w, lse_w, o_out, HGCA_F32, lse_out, hip_stream)) != HGCA_OK) return rc;
+    // gpu_attention over the window (causal among the incoming tokens), cpu_attention over the complete offloaded
+    // cache, merge_state per (sequence, query, head): bf16 as one launch for both tiers and one fold; fp32 as a call
+    // per tier and a merge
+    if (shape->dtype == HGCA_BF16) {
+        if ((rc = hgca_append_attn_tiers(shape, q, n_q, &window, &pool, flags | HGCA_APPEND_CAUSAL_TAIL, o_out, lse_out,
+                                         lse_w, lse_p, base + w.attn, w.attn_bytes, hip_stream)) != HGCA_OK)
+            return rc;
+    } else {
+        if ((rc = hgca_append_attn(shape, q, n_q, &window, flags | HGCA_APPEND_CAUSAL_TAIL, o_w, lse_w, base + w.attn,
+                                   w.attn_bytes, hip_stream)) != HGCA_OK)
+            return rc;
+        if ((rc = hgca_append_attn(shape, q, n_q, &pool, flags, o_p, lse_p, base + w.attn, w.attn_bytes, hip_stream)) != HGCA_OK)
+            return rc;
+        hgca_shape merged = *shape;
+        merged.batch = shape->batch * n_q;
+        if ((rc = hgca_lse_merge(&merged, o_p, lse_p, o_w, lse_w, o_out, HGCA_F32, lse_out, hip_stream)) != HGCA_OK) return rc;
+    }
     // A_gpu, A_cpu: the query-averaged weights of the two parts
     if ((rc = hgca_append_weights(shape, q, n_q, &window, 1, lse_w, a_gpu, hip_stream)) != HGCA_OK) return rc;
     if ((rc = hgca_append_weights(shape, q, n_q, &pool, 0, lse_p, a_cpu, hip_stream)) != HGCA_OK) return rc;

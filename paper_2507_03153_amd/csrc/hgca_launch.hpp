@@ -43,7 +43,8 @@ hipError_t launch_attn_partial_gather(int dtype, int head_dim, const AttnArgs &a
 hipError_t launch_combine(int head_dim, int64_t n_rows, const Partials &p, float *o, float *lse, hipStream_t s);
 // Folds the splits of two partial sets (either may have n_splits == 0) into one result; o_dtype 0 fp32, 1 bf16.
 hipError_t launch_combine2(int head_dim, int64_t n_rows, const Partials &p, const Partials &q, void *o, int o_dtype,
-                           float *lse, hipStream_t s, float *lse_p = nullptr);   // lse_p: optional lse of set p alone
+                           float *lse, hipStream_t s, float *lse_p = nullptr,   // lse_p / lse_q: optional lse of set p / q alone
+                           float *lse_q = nullptr);
 
 hipError_t launch_merge(int head_dim, int64_t n_rows, const float *o_a, const float *lse_a, const float *o_b,
                         const float *lse_b, void *o_out, int o_dtype, float *lse_out, hipStream_t s);
@@ -127,6 +128,8 @@ struct AppendArgs {
     float *a_out;              // weights: [B, Hq, cap]
 };
 hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s);
+// two tiers in one launch (same queries and shape; each tier with its own view, mask rule, split size and partials)
+hipError_t launch_append_attn2(int head_dim, const AppendArgs &a, const AppendArgs &a2, hipStream_t s);
 hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks, hipStream_t s);
 // the same for fp32 inputs (q [B, N, Hq, d] fp32, fp32 tier): VALU pass, 64 tokens per workgroup
 hipError_t launch_append_weights_f32(int head_dim, const AppendArgs &a, hipStream_t s);

@@ -24,6 +24,7 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
+           "hgca_append_tiers_workspace_bytes", "hgca_append_attn_tiers",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
            "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact",
            "hgca_managed_decode_step", "hgca_dense_window_attn_static", "hgca_hybrid_decode_step_selected", "hgca_kv_append_tokens",
@@ -96,6 +97,10 @@ def lib() -> ctypes.CDLL:
         L.hgca_append_workspace_bytes.argtypes = [ps, i32, i32]
         L.hgca_append_attn.restype = ctypes.c_int
         L.hgca_append_attn.argtypes = [ps, vp, i32, pk, i32, vp, vp, vp, sz, vp]
+        L.hgca_append_tiers_workspace_bytes.restype = ctypes.c_size_t
+        L.hgca_append_tiers_workspace_bytes.argtypes = [ps, i32, i32, i32]
+        L.hgca_append_attn_tiers.restype = ctypes.c_int
+        L.hgca_append_attn_tiers.argtypes = [ps, vp, i32, pk, pk, i32, vp, vp, vp, vp, vp, sz, vp]
         L.hgca_append_weights.restype = ctypes.c_int
         L.hgca_append_weights.argtypes = [ps, vp, i32, pk, i32, vp, vp, vp]
         L.hgca_kv_append.restype = ctypes.c_int
@@ -389,6 +394,31 @@ def append_attn(shape: Shape, q, tier: Tier, causal_tail: bool, o_out, lse_out, 
     _check(lib().hgca_append_attn(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), flags,
                                   _ptr(o_out), _ptr(lse_out), _ptr(ws), ws.numel(), _stream(stream)),
            "hgca_append_attn")
+
+
+def append_tiers_workspace(shape: Shape, n_q: int, window_cap: int, pool_cap: int, device) -> torch.Tensor:
+    n = int(lib().hgca_append_tiers_workspace_bytes(ctypes.byref(shape), int(n_q), int(window_cap), int(pool_cap)))
+    if n == 0:
+        raise HgcaError(ERR_INVALID_ARG, "hgca_append_tiers_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def append_attn_tiers(shape: Shape, q, window: Tier, pool: Tier, o_out, lse_out, ws, lse_window_out=None,
+                      lse_pool_out=None, causal_tail: bool = True, one_part_p: bool = False, stream=None) -> None:
+    """Attention of q [B,N,Hq,d] bf16 over the window (causal among its last N tokens) and over the whole pool, merged:
+    o_out [B,N,Hq,d], lse_out [B,N,Hq] fp32; the per-tier lse rows are optional outputs."""
+    for t in (q, o_out, lse_out, ws):
+        _require_gpu(t)
+    for t in (lse_window_out, lse_pool_out):
+        if t is not None:
+            _require_gpu(t)
+    kw, kp = window.view(), pool.view()
+    flags = (APPEND_CAUSAL_TAIL if causal_tail else 0) | (APPEND_ONE_PART_P if one_part_p else 0)
+    _check(lib().hgca_append_attn_tiers(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kw), ctypes.byref(kp),
+                                        flags, _ptr(o_out), _ptr(lse_out),
+                                        _ptr(lse_window_out) if lse_window_out is not None else None,
+                                        _ptr(lse_pool_out) if lse_pool_out is not None else None,
+                                        _ptr(ws), ws.numel(), _stream(stream)), "hgca_append_attn_tiers")
 
 
 def append_weights(shape: Shape, q, tier: Tier, causal_tail: bool, lse, a_out, stream=None) -> None:

@@ -318,6 +318,25 @@ def test_append_entry_points_reject_bad_arguments(hg):
     assert attn(shape=hg.Shape(hg.BF16, 1, 2048, 2048, 128, 0.088), n_q=4096) == hg.ERR_UNSUPPORTED
     assert attn(shape=hg.Shape(hg.BF16, 1, 2047, 2047, 128, 0.088), n_q=4096, ws_bytes=64) == hg.ERR_WORKSPACE
 
+    # both tiers in one call
+    assert L.hgca_append_tiers_workspace_bytes(byref(sh), 32, 4096, 28672) > 0
+    assert L.hgca_append_tiers_workspace_bytes(byref(sh), 32, -1, 64) == 0
+    assert L.hgca_append_tiers_workspace_bytes(byref(sh), -1, 64, 64) == 0
+
+    def tiers(shape=sh, q=FAKE, n_q=4, o=FAKE, lse=FAKE, ws=FAKE, ws_bytes=1 << 40, flags=1):
+        return L.hgca_append_attn_tiers(byref(shape), q, n_q, byref(view), byref(view), flags, o, lse, None, None, ws,
+                                        ws_bytes, None)
+    assert tiers(q=None) == hg.ERR_INVALID_ARG
+    assert tiers(flags=4) == hg.ERR_INVALID_ARG
+    assert tiers(n_q=5000) == hg.ERR_INVALID_ARG
+    assert tiers(o=None) == hg.ERR_INVALID_ARG
+    assert tiers(lse=None) == hg.ERR_INVALID_ARG
+    assert tiers(ws=None) == hg.ERR_WORKSPACE
+    assert tiers(ws_bytes=64) == hg.ERR_WORKSPACE
+    assert tiers(shape=hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)) == hg.ERR_UNSUPPORTED     # per-tier calls serve fp32
+    assert tiers(shape=hg.Shape(hg.BF16, 1, 2048, 2048, 128, 0.088), n_q=4096) == hg.ERR_UNSUPPORTED
+    assert tiers(n_q=0) == hg.OK
+
     def weights(q=FAKE, n_q=4, lse=FAKE, a=FAKE):
         return L.hgca_append_weights(byref(sh), q, n_q, byref(view), 0, lse, a, None)
     assert weights(q=None) == hg.ERR_INVALID_ARG

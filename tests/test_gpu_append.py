@@ -119,6 +119,22 @@ def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=
     check("pool", op, lp, o_c, l_c)
     check("merged", o, lse, o_ref, l_ref)
 
+    # both tiers in one call (one launch for the splits of both, one fold): the merged result and each tier's lse
+    ws2 = hgca.append_tiers_workspace(shape, N, W, P, dev)
+    o2, lse2 = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
+    lw2, lp2 = torch.full_like(lw, float("nan")), torch.full_like(lw, float("nan"))
+    hgca.append_attn_tiers(shape, qd, win, pool, o2, lse2, ws2, lse_window_out=lw2, lse_pool_out=lp2)
+    o3, lse3 = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
+    hgca.append_attn_tiers(shape, qd, win, pool, o3, lse3, ws2)                  # without the per-tier outputs
+    torch.cuda.synchronize()
+    check("two tiers, one call", o2, lse2, o_ref, l_ref)
+    assert torch.equal(o3, o2) and torch.equal(lse3, lse2)
+    for name, got, want in (("window lse", lw2, l_g), ("pool lse", lp2, l_c)):
+        got = got.double().cpu().numpy()
+        assert np.array_equal(np.isneginf(got), np.isneginf(want)), name
+        fin = ~np.isneginf(want)
+        assert np.max(np.abs(got[fin] - want[fin]), initial=0.0) <= 2e-5, name
+
     # the same with the weights rounded once to bf16 for the second product: lse is untouched (bit for bit); every
     # weight is off by at most 2^-9 of itself and the weights sum to 1, so |dO| <= 2^-9 max|v| (about 9e-3 for
     # N(0,1) values; reached when a query sees only a few tokens)
@@ -221,6 +237,15 @@ def test_append_full_size_c2_every_unit(gpu):
     hgca.append_attn(shape, qd, pool, False, op2, lp2, ws)
     torch.cuda.synchronize()
     assert torch.equal(ow2, ow) and torch.equal(lw2, lw) and torch.equal(op2, op) and torch.equal(lp2, lp)
+    # both tiers in one call, as bench.py times it: the merged result and the per-tier lse agree with the calls above
+    ws_t = hgca.append_tiers_workspace(shape, N, W, P, dev)
+    o_t, lse_t = torch.full_like(ow, float("nan")), torch.full_like(lw, float("nan"))
+    lw_t, lp_t = torch.full_like(lw, float("nan")), torch.full_like(lw, float("nan"))
+    hgca.append_attn_tiers(shape, qd, win, pool, o_t, lse_t, ws_t, lse_window_out=lw_t, lse_pool_out=lp_t)
+    torch.cuda.synchronize()
+    # (other split sizes, hence another order of the fp32 sums: both are held to the oracle below, each to its bar)
+    assert float((o_t - o).abs().max()) <= 4e-4 and float((lse_t - lse).abs().max()) <= 4e-5
+    assert float((lw_t - lw).abs().max()) <= 4e-5 and float((lp_t - lp).abs().max()) <= 4e-5
     # every averaged weight row sums to 1 over what is visible (holds at any size)
     assert float((a_gpu.sum(-1) - 1).abs().max()) <= 1e-4 and float((a_cpu.sum(-1) - 1).abs().max()) <= 1e-4
 
@@ -228,7 +253,9 @@ def test_append_full_size_c2_every_unit(gpu):
     # query-averaged weight rows (a few of them printed)
     f = lambda x: wl.bf16_bits_to_f32(x).astype(np.float64)
     got = {name: t.double().cpu().numpy() for name, t in (("O_gpu", ow), ("lse_g", lw), ("O_cpu", op), ("lse_c", lp),
-                                                          ("O", o), ("lse", lse), ("A_gpu", a_gpu), ("A_cpu", a_cpu))}
+                                                          ("O", o), ("lse", lse), ("A_gpu", a_gpu), ("A_cpu", a_cpu),
+                                                          ("O_tiers", o_t), ("lse_tiers", lse_t), ("lse_g_tiers", lw_t),
+                                                          ("lse_c_tiers", lp_t))}
 
     def unit_group(b, kvh):
         """The G heads that share KV head kvh of sequence b: worst error per quantity."""
@@ -240,7 +267,8 @@ def test_append_full_size_c2_every_unit(gpu):
             o_c, l_c, A_c = ap.part_attention(qs, kp, vp, pl_[b:b + 1], scale, False)
             o_r, l_r = ap.merge_state(o_c, l_c, o_g, l_g)
             want = {"O_gpu": o_g[0, :, 0], "lse_g": l_g[0, :, 0], "O_cpu": o_c[0, :, 0], "lse_c": l_c[0, :, 0],
-                    "O": o_r[0, :, 0], "lse": l_r[0, :, 0], "A_gpu": A_g[0, 0].mean(axis=0), "A_cpu": A_c[0, 0].mean(axis=0)}
+                    "O": o_r[0, :, 0], "lse": l_r[0, :, 0], "A_gpu": A_g[0, 0].mean(axis=0), "A_cpu": A_c[0, 0].mean(axis=0),
+                    "O_tiers": o_r[0, :, 0], "lse_tiers": l_r[0, :, 0], "lse_g_tiers": l_g[0, :, 0], "lse_c_tiers": l_c[0, :, 0]}
             for name, ref in want.items():
                 mine = got[name][b, h] if name.startswith("A_") else got[name][b, :, h]
                 worst[name] = max(worst.get(name, 0.0), float(np.max(np.abs(mine - ref))))
@@ -254,8 +282,9 @@ def test_append_full_size_c2_every_unit(gpu):
     for b, kvh, errs in results:
         if kvh in (0, Hkv - 1):
             say(f"    (b={b}, heads {kvh * G}..{kvh * G + G - 1}): " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
-        assert max(errs["O_gpu"], errs["O_cpu"], errs["O"]) <= 2e-4, (b, kvh, errs)
-        assert max(errs["lse_g"], errs["lse_c"], errs["lse"], errs["A_gpu"], errs["A_cpu"]) <= 2e-5, (b, kvh, errs)
+        assert max(errs["O_gpu"], errs["O_cpu"], errs["O"], errs["O_tiers"]) <= 2e-4, (b, kvh, errs)
+        assert max(errs["lse_g"], errs["lse_c"], errs["lse"], errs["A_gpu"], errs["A_cpu"], errs["lse_tiers"],
+                   errs["lse_g_tiers"], errs["lse_c_tiers"]) <= 2e-5, (b, kvh, errs)
 
 
 def run_case_f32(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=False):
