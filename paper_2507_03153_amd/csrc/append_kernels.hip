@@ -28,6 +28,9 @@ namespace hgca {
 
 namespace {
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
 constexpr int kABlock = 512;
 constexpr int kAWaves = kABlock / kWave;
 constexpr int kStepBlocks = 2;                   // 32-token contraction blocks per step
@@ -254,24 +257,34 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
         // raw scores: sv[x][8*kb + 4*tt + r] belongs to step token 32*kb + 16*tt + 4*g + r and row n of tile x
         float sv[TILES][8 * kStepBlocks];
         const bool masked = min(in_split, vis_min - step0) < kStepTokens;   // uniform over the wave
+        {
+            // the slices of the contraction outermost: the 4 x TILES accumulators take turns, so no matrix instruction
+            // waits for the one before it on the same accumulator
+            constexpr int NT = 2 * kStepBlocks;                  // 16-token tiles of the step
+            floatx4 c[NT][TILES];
 #pragma unroll
-        for (int t = 0; t < 2 * kStepBlocks; ++t) {              // 16-token tiles of the step
-            floatx4 c[TILES];
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int x = 0; x < TILES; ++x) c[x] = floatx4{0.f, 0.f, 0.f, 0.f};
+                for (int x = 0; x < TILES; ++x) c[t][x] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk) {
-                const uint4 ka = *reinterpret_cast<const uint4 *>(k_stage + t * 16 * S::kRowBytes + k_lane[kk]);
 #pragma unroll
-                for (int x = 0; x < TILES; ++x)
-                    c[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qop[x][kk], c[x], 0, 0, 0);
+                for (int t = 0; t < NT; ++t) {
+                    const uint4 ka = *reinterpret_cast<const uint4 *>(k_stage + t * 16 * S::kRowBytes + k_lane[kk]);
+#pragma unroll
+                    for (int x = 0; x < TILES; ++x)
+                        c[t][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qop[x][kk], c[t][x], 0, 0, 0);
+                }
             }
 #pragma unroll
-            for (int x = 0; x < TILES; ++x)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) sv[x][4 * t + r] = c[x][r];
+                for (int x = 0; x < TILES; ++x)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sv[x][4 * t + r] = c[t][x][r];
         }
         if (masked) {                                            // steps that touch a length or causal boundary
+            asm volatile("" ::: "memory");                       // a real branch: the selects below are not speculated into every step
 #pragma unroll
             for (int x = 0; x < TILES; ++x) {
                 const int limit = min(in_split, vis[x] - step0);
@@ -302,13 +315,24 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) acc[x][dt] *= corr;
             }
+            // round to nearest even, two weights per conversion; the low part carries the rounding error: the high
+            // parts are widened again from the packed pair (a shift and a mask) rather than converted one by one
 #pragma unroll
-            for (int kb = 0; kb < kStepBlocks; ++kb)
+            for (int kb = 0; kb < kStepBlocks; ++kb) {
+                uint32_t hw[4], lw[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {                    // round to nearest even; the low part carries the rounding error
-                    ph[x][kb][e] = (__bf16)sv[x][8 * kb + e];
-                    pl[x][kb][e] = SPLIT_P ? (__bf16)(sv[x][8 * kb + e] - (float)ph[x][kb][e]) : (__bf16)0.f;
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float2v pr = {sv[x][8 * kb + 2 * e2], sv[x][8 * kb + 2 * e2 + 1]};
+                    hw[e2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                    lw[e2] = 0u;
+                    if (SPLIT_P) {
+                        const float2v lo = {pr[0] - __uint_as_float(hw[e2] << 16), pr[1] - __uint_as_float(hw[e2] & 0xffff0000u)};
+                        lw[e2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+                    }
                 }
+                ph[x][kb] = __builtin_bit_cast(bf16x8, make_uint4(hw[0], hw[1], hw[2], hw[3]));
+                pl[x][kb] = __builtin_bit_cast(bf16x8, make_uint4(lw[0], lw[1], lw[2], lw[3]));
+            }
         }
         // O^T += V^T P^T, one 16-column tile of the output at a time
 #pragma unroll
