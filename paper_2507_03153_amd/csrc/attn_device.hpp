@@ -20,6 +20,10 @@ constexpr int kWaves = kBlock / kWave;
 #define HGCA_UNROLL 4
 #endif
 constexpr int kUnroll = HGCA_UNROLL;   // 16-byte loads a lane keeps in flight in the K / V passes
+// bit 0: the gather's first V loads are issued before the split's softmax; bit 1: the window split's as well
+#ifndef HGCA_V_PREFETCH
+#define HGCA_V_PREFETCH 3
+#endif
 
 
 struct KernelArgs {
@@ -72,10 +76,28 @@ __device__ __forceinline__ void split_softmax(float (*s_p)[LD], float *s_m, floa
 }
 
 // o[g][:] = sum_j p[g][j] v_j over the split, reduced over the workgroup and written as a partial.
-template <typename T, int D, int NH, bool GATHER, int BLOCK = kBlock, int UNROLL = kUnroll, int LD = kMaxChunk>
+// The first UNROLL loads of a lane's V pass (the rows value_pass takes first), for a caller that wants them in
+// flight before the weights are ready: the addresses depend on the row map only.
+template <typename T, int D, int BLOCK = kBlock, int UNROLL = kUnroll>
+__device__ __forceinline__ void value_prefetch(const KernelArgs &a, int nt, const RowMap &rows, uint4 (&vr)[UNROLL])
+{
+    constexpr int LPR = D / Elem<T>::kPerLoad, RPW = kWave / LPR, RPI = (BLOCK / kWave) * RPW;
+    constexpr size_t ROW_BYTES = D * sizeof(T);
+    const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave, r = lane / LPR, c = lane % LPR;
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int j = min(u * RPI + w * RPW + r, nt - 1);
+        vr[u] = load16_stream(a.kv.v + rows(j) * ROW_BYTES + c * 16);
+    }
+}
+
+// V pass of a split: o = sum_j p_j v_j per head, reduced over the workgroup, and the split's partial (m, l, o).
+// With PRE the first UNROLL loads of every lane have been issued by value_prefetch (`first`).
+template <typename T, int D, int NH, bool GATHER, int BLOCK = kBlock, int UNROLL = kUnroll, int LD = kMaxChunk, bool PRE = false>
 __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[LD],
                                            float (*s_red)[NH][D], const float *s_m, const float *s_l,
-                                           int64_t bh0, int split, int nt, const RowMap &rows)
+                                           int64_t bh0, int split, int nt, const RowMap &rows,
+                                           const uint4 *first = nullptr)
 {
     constexpr int EPL = Elem<T>::kPerLoad;       // elements per lane per load
     constexpr int LPR = D / EPL;                 // lanes per row
@@ -92,13 +114,7 @@ __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[LD]
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
 
-    for (int base = 0; base < nt; base += RPI * UNROLL) {
-        uint4 vr[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int j = min(base + u * RPI + w * RPW + r, nt - 1);
-            vr[u] = load16_stream(a.kv.v + rows(j) * ROW_BYTES + c * 16);
-        }
+    auto consume = [&](int base, const uint4 (&vr)[UNROLL]) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int j = base + u * RPI + w * RPW + r;
@@ -112,6 +128,21 @@ __device__ __forceinline__ void value_pass(const KernelArgs &a, float (*s_p)[LD]
                 for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
             }
         }
+    };
+    if (PRE) {
+        uint4 vr[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) vr[u] = first[u];
+        consume(0, vr);
+    }
+    for (int base = PRE ? RPI * UNROLL : 0; base < nt; base += RPI * UNROLL) {
+        uint4 vr[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int j = min(base + u * RPI + w * RPW + r, nt - 1);
+            vr[u] = load16_stream(a.kv.v + rows(j) * ROW_BYTES + c * 16);
+        }
+        consume(base, vr);
     }
 
     // rows live in different lane groups of a wave, then in different waves
@@ -242,6 +273,14 @@ struct SplitValu {
         if (MODE == kScores) return;
         if (MODE == kDense && a.scores) __syncthreads();   // the softmax below overwrites the scores other waves are still storing
 
+        if (HGCA_V_PREFETCH && GATHER) {             // the first V rows travel while the softmax statistics are formed
+            uint4 first[kUnroll];
+            value_prefetch<T, D>(a, nt, rows, first);
+            split_softmax<NH>(s_p, s_m, s_l, nt);
+            __syncthreads();
+            value_pass<T, D, NH, GATHER, kBlock, kUnroll, kMaxChunk, true>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows, first);
+            return;
+        }
         split_softmax<NH>(s_p, s_m, s_l, nt);
         __syncthreads();
         value_pass<T, D, NH, GATHER>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows);
@@ -441,6 +480,15 @@ struct DenseSplit {
         if (a.scores) {                          // uniform over the workgroup
             store_split_scores<G, BLOCK, LD>(a, s_p, bh0, t0, nt);
             __syncthreads();                     // the softmax below overwrites the scores other waves are still storing
+        }
+        if (HGCA_V_PREFETCH & 2 && !kPvMfma) {       // the first V rows travel while the softmax statistics are formed
+            uint4 first[UNROLL];
+            value_prefetch<bf16_t, D, BLOCK, UNROLL>(a, nt, rows, first);
+            split_softmax<G, BLOCK, LD>(s_p, s_m, s_l, nt);
+            __syncthreads();
+            value_pass<bf16_t, D, G, false, BLOCK, UNROLL, LD, true>(a, s_p, reinterpret_cast<float(*)[G][D]>(s_buf), s_m,
+                                                                     s_l, bh0, split, nt, rows, first);
+            return;
         }
         split_softmax<G, BLOCK, LD>(s_p, s_m, s_l, nt);
         __syncthreads();
