@@ -345,6 +345,7 @@ def main() -> int:
         out["paper_literal_decode_blocks_of_64"] = decode_loop_timing(torch, hgca, cfg, layers[0], k_max, dev,
                                                                       block_size=64)
         out["append_stage"] = append_stage_timing(torch, hgca, cfg, layers[0], dev)
+        out["paper_literal_append_turn"] = append_turn_timing(torch, hgca, cfg, layers[0], k_max, dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host_layers[0], args.cpu_seconds)
     print(json.dumps(out), flush=True)
@@ -494,6 +495,55 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
             "one_part_p": {"attention_ms": one_ms, "hbm_frac": kv_bytes / (one_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                            "tflops": flops / (one_ms * 1e-3) / 1e12,
                            "mfma_frac_bf16": flops / (one_ms * 1e-3) / 2.5e15}}
+
+
+def append_turn_timing(torch, hgca, cfg, L, k_max, dev, n_q: int = 32, turns: int = 8, block_size: int = 16) -> dict:
+    """Whole append turns over a managed cache at the workload's shape (hgca_managed_append_step: insert of n_q tokens
+    per sequence, attention over the window and the complete pool, merge, query-averaged weights of both parts,
+    moving averages, re-evaluation of the salient lists, eviction of the blocks the insert pushed out).  The cache
+    starts as in the decode loop; the turns run back to back in one timed region."""
+    from paper_2507_03153_amd import cache
+
+    B, Hq, Hkv, d, W, P = cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.W, cfg.P
+    win_blocks, pool_blocks = W // block_size, P // block_size
+    n_blk = -(-n_q // block_size)
+    spare = (turns + 3) * n_blk + 4
+    C = cache.LayerCache(L.q.dtype, B, Hq, Hkv, d, block_size, win_blocks, pool_blocks + win_blocks + spare,
+                         4 * k_max, float(L.shape.sm_scale), dev, win_cap_blocks=win_blocks + n_blk)
+    for dst, pool, win in ((C.k_blocks, L.pool.k, L.window.k), (C.v_blocks, L.pool.v, L.window.v)):
+        view = dst.view(B, C.max_blocks, Hkv, block_size, d)
+        view[:, :pool_blocks] = pool.reshape(B, Hkv, pool_blocks, block_size, d).permute(0, 2, 1, 3, 4)
+        view[:, pool_blocks:pool_blocks + win_blocks - 1] = \
+            win[:, :, :W - block_size].reshape(B, Hkv, win_blocks - 1, block_size, d).permute(0, 2, 1, 3, 4)
+    C.first_win_block.fill_(pool_blocks)
+    C.pool_lens.fill_(pool_blocks * block_size)
+    C.win_lens.fill_(W - block_size)
+    C.a_maw.fill_(1.0 / W)
+    g = torch.Generator(device="cpu").manual_seed(11)
+    q = torch.randn(B, n_q, Hq, d, generator=g).to(L.q.dtype).to(dev)
+    k_in = torch.randn(B, n_q, Hkv, d, generator=g).to(L.q.dtype).to(dev)
+    v_in = torch.randn(B, n_q, Hkv, d, generator=g).to(L.q.dtype).to(dev)
+    BETA = 2.0                                                 # keeps a few thousand entries per head on these inputs
+    stream = torch.cuda.current_stream()
+    C.append_step(q, k_in, v_in, 0.3, BETA)                    # warm-up turns (the first allocates the turn's buffers)
+    C.append_step(q, k_in, v_in, 0.3, BETA)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall = time.perf_counter()
+    e0.record(stream)
+    for _ in range(turns):
+        C.append_step(q, k_in, v_in, 0.3, BETA)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t_wall) * 1e3 / turns
+    ms = max(e0.elapsed_time(e1) / turns, wall)
+    kv_bytes = 2 * B * Hkv * (W + P) * d * 2 + B * Hkv * (W + P) * d * 2      # K and V once for the attention, K again for the weights
+    return {"n_q": n_q, "turns": turns, "ms_per_turn": ms,
+            "tokens_per_s": B * n_q / (ms * 1e-3), "kv_bytes": kv_bytes,
+            "hbm_frac": kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "beta": BETA, "cache_status": int(C.status.cpu()[0]),
+            "salient_per_head_after": C.ctx_cnt.float().mean().item(),
+            "calls_per_turn": "hgca_managed_append_step (insert, both tiers' attention in one launch, fold, weights of "
+                              "window and pool, moving average, re-evaluation, eviction: 8 kernels)"}
 
 
 def copy_calibration(torch, dev) -> int:

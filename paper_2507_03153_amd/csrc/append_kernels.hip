@@ -37,7 +37,56 @@ constexpr int kStepBlocks = 2;                   // 32-token contraction blocks 
 constexpr int kStepTokens = 32 * kStepBlocks;
 constexpr int kRowsPerBlock = 128;               // query rows per workgroup = 8 tiles of 16, one per wave
 static_assert(kRowsPerBlock == 16 * kAWaves, "one row tile per wave");
-constexpr int kSub = kMaxChunk;                  // tokens per refill of the row table
+constexpr int kSub = kMaxChunk;                  // entries of the table of block rows (paged tiers)
+
+// Where the rows of a pass over part of a split live.  A contiguous tier is plain arithmetic.  A paged tier gets a
+// table in LDS with one entry per BLOCK the pass touches (the row of the block's first token for this KV head), so
+// one filling of kSub entries covers (kSub - 1) * block_size tokens -- a whole split for blocks of 16 tokens -- and
+// the load pipeline is not drained for refills.
+struct BlockRows {
+    const uint32_t *table;                       // LDS; nullptr => row = base + j
+    uint32_t base;
+    int32_t bs, shift, off;                      // block size, log2 of it (-1: not a power of two), first token's place in its block
+    __device__ __forceinline__ uint32_t operator()(int j) const {
+        if (!table) return base + (uint32_t)j;
+        const int t = off + j;
+        return shift >= 0 ? table[t >> shift] + (uint32_t)(t & (bs - 1)) : table[t / bs] + (uint32_t)(t % bs);
+    }
+};
+
+// tokens a pass may cover so that its blocks fit the table, a multiple of the step
+__device__ __forceinline__ int pass_length(const KvDev &kv, int nt_total) {
+    if (!kv.block_table) return max(nt_total, 1);
+    const int64_t t = (int64_t)(kSub - 1) * kv.block_size;
+    return (int)max((int64_t)kStepTokens, min(t, (int64_t)1 << 30) / kStepTokens * kStepTokens);
+}
+
+// `first` is the tier position of the pass's first token, nt the number of tokens; contains a barrier iff the tier
+// is paged (uniform over the workgroup).
+template <int BLOCK>
+__device__ __forceinline__ BlockRows make_block_rows(uint32_t *s_tab, const KvDev &kv, int n_kv_heads, int b, int kvh,
+                                                     int first, int nt)
+{
+    b = kv_seq(kv, b);
+    BlockRows m;
+    m.bs = max(kv.block_size, 1);
+    m.shift = (m.bs & (m.bs - 1)) == 0 ? __builtin_ctz(m.bs) : -1;
+    if (!kv.block_table) {
+        m.table = nullptr;
+        m.base = (uint32_t)(((int64_t)b * n_kv_heads + kvh) * kv.cap + first);
+        m.off = 0;
+        return m;
+    }
+    const int32_t *blocks = kv.block_table + (int64_t)b * kv.max_blocks + (kv.first_block ? kv.first_block[b] : 0);
+    const int blk0 = first / m.bs, n_blk = (first + nt - 1) / m.bs - blk0 + 1;      // <= kSub by pass_length
+    for (int i = threadIdx.x; i < n_blk; i += BLOCK)
+        s_tab[i] = (uint32_t)(((int64_t)blocks[blk0 + i] * n_kv_heads + kvh) * m.bs);
+    __syncthreads();
+    m.table = s_tab;
+    m.base = 0;
+    m.off = first - blk0 * m.bs;
+    return m;
+}
 
 // The value of the lane ROT places further on in the same row of 16 lanes (DPP row_ror).
 template <int ROT>
@@ -153,7 +202,7 @@ __device__ __forceinline__ void wait_for_own_loads() { __builtin_amdgcn_s_waitcn
 // Requests the K and the V rows of a step.  All row numbers are looked up before the first load is issued: the
 // lookup of a paged tier reads a table in LDS, and an LDS read placed after an LDS-direct load waits for that load.
 template <int D, int NW, bool WITH_V = true>
-__device__ __forceinline__ void dma_step(const KvDev &kv, const RowMap &rows, int step, int nsub, char *k_stage,
+__device__ __forceinline__ void dma_step(const KvDev &kv, const BlockRows &rows, int step, int nsub, char *k_stage,
                                          char *v_stage)
 {
     using S = DmaStage<D, NW>;
@@ -211,8 +260,11 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
     const int kvh = blockIdx.y / n_qb, qb = blockIdx.y % n_qb, b = blockIdx.z;
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave, n = lane % 16, g = lane / 16;
     const int len = tier_len(a.kv, b);
-    const int t0 = split * a.chunk;
-    const int nt_total = min(a.chunk, len - t0);                 // <= 0: nothing of this split is valid
+    // the tier's actual length is shared out evenly among its splits (a.chunk, set from the capacity, bounds it):
+    // every split of a sequence then has the same work however far its length is from the capacity
+    const int chunk = min(a.chunk, ((len + a.part.n_splits - 1) / a.part.n_splits + kStepTokens - 1) / kStepTokens * kStepTokens);
+    const int t0 = split * chunk;
+    const int nt_total = min(chunk, len - t0);                   // <= 0: nothing of this split is valid
 
     const int tile_row0 = qb * kRowsPerBlock + w * 16 * TILES;   // first row of the wave's first tile
     const bool wave_live = tile_row0 < a.n_q * G;                // uniform over the wave
@@ -368,13 +420,13 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
         }
     };
 
-    // a paged tier needs a row table in LDS, refilled every kSub tokens (which drains the load pipeline);
-    // a contiguous tier is plain arithmetic and takes the whole split in one pass
-    const int sub_len = a.kv.block_table ? kSub : max(nt_total, 1);
+    // a paged tier needs a table of block rows in LDS, which covers a whole split unless the blocks are tiny;
+    // a contiguous tier is plain arithmetic
+    const int sub_len = pass_length(a.kv, nt_total);
     for (int sub0 = 0; sub0 < nt_total; sub0 += sub_len) {
         const int nsub = min(sub_len, nt_total - sub0);
         __syncthreads();                         // the previous table and stages are no longer in use
-        const RowMap rows = make_row_map<false, BLOCK>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
+        const BlockRows rows = make_block_rows<BLOCK>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub);
         // Step s reads the stages of its parity and requests the rows of step s + 1 into the stages of the other
         // parity, which were last read in step s - 1: the barrier at the top of the step (before which every wave
         // waits for its own loads) orders both.
@@ -438,7 +490,7 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     for (int kk = 0; kk < D / 32; ++kk) k_lane[kk] = S::k_offset(n, 4 * kk + g);
 
     const int n_qb = (a.n_q * G + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int sub_len = a.kv.block_table ? kSub : max(nt_total, 1);
+    const int sub_len = pass_length(a.kv, nt_total);
     for (int qb = 0; qb < n_qb && nt_total > 0; ++qb) {
         const RowInfo ri = row_info<G>(a, b, kvh, qb * kRowsPerBlock + w * 16 + n);
         const int vis = !ri.valid ? 0 : a.causal_tail ? min(max(len - a.n_q + ri.query + 1, 0), len) : len;
@@ -451,7 +503,7 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
         for (int sub0 = 0; sub0 < nt_total; sub0 += sub_len) {
             const int nsub = min(sub_len, nt_total - sub0);
             __syncthreads();                     // table, stages and sums of the previous pass are no longer in use
-            const RowMap rows = make_row_map<false, kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub, nullptr);
+            const BlockRows rows = make_block_rows<kABlock>(s_row, a.kv, a.sh.n_kv_heads, b, kvh, t0 + sub0, nsub);
             int pending = -1;                    // step whose per-wave sums wait in s_part[pending & 1]
             auto fold = [&](int step) {          // one thread per entry, waves added in a fixed order
                 for (int i = tid; i < G * kStepTokens; i += kABlock) {

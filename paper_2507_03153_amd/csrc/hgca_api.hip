@@ -1001,22 +1001,42 @@ int hgca_append_attn(const hgca_shape *shape, const void *q, int32_t n_q, const 
 
 namespace {
 
-// Workspace of the two-tier append attention: split partials of the window and of the pool (splits of one common
-// size, chosen for the two tiers together), and the two per-tier lse rows for callers that do not ask for them.
+// Workspace of the two-tier append attention: split partials of the window and of the pool (the split counts are
+// chosen for the two tiers together), and the two per-tier lse rows for callers that do not ask for them.
 struct TiersWs {
     size_t o_w, m_w, l_w, o_p, m_p, l_p, lse_w, lse_p, total;
-    int chunk, n_w, n_p;
+    int chunk_w, chunk_p, n_w, n_p;
 };
 
 TiersWs tiers_layout(const hgca_shape *s, int32_t n_q, int64_t win_cap, int64_t pool_cap)
 {
     TiersWs w{};
+    // The splits of a unit are shared out between the tiers in proportion to their capacities (each tier that has
+    // any capacity gets at least one), so that the launch has about as many workgroups as the device holds at once;
+    // a tier whose share would make its splits longer than kMaxAppendChunk gets more.  The kernel then shares a
+    // tier's ACTUAL length out evenly among its splits (the capacity only bounds it).
     const int want = append_want_splits(s, n_q);
-    int64_t chunk = (std::max<int64_t>(win_cap + pool_cap, 1) + want - 1) / want;
-    chunk = (chunk + 63) / 64 * 64;
-    w.chunk = (int)std::min<int64_t>(kMaxAppendChunk, std::max<int64_t>(kMinChunk, chunk));
-    w.n_w = win_cap > 0 ? n_splits_for(win_cap, w.chunk) : 0;
-    w.n_p = pool_cap > 0 ? n_splits_for(pool_cap, w.chunk) : 0;
+    const int64_t total = win_cap + pool_cap;
+    auto splits = [&](int64_t cap, int64_t other) -> int {
+        if (cap <= 0) return 0;
+        int64_t n = other > 0 ? std::max<int64_t>(1, std::min<int64_t>(want - 1, (cap * want + total / 2) / total)) : want;
+        n = std::max<int64_t>(n, (cap + kMaxAppendChunk - 1) / kMaxAppendChunk);
+        return (int)std::min<int64_t>(n, (cap + kMinChunk - 1) / kMinChunk);
+    };
+    auto chunk_of = [](int64_t cap, int n) -> int {
+        if (n == 0) return kMinChunk;
+        return (int)std::max<int64_t>(kMinChunk, ((cap + n - 1) / n + 63) / 64 * 64);
+    };
+    w.n_w = splits(win_cap, pool_cap);
+    w.n_p = pool_cap > 0 ? (win_cap > 0 ? std::max(1, std::max(want - w.n_w, 1)) : want) : 0;
+    if (pool_cap > 0) {
+        w.n_p = (int)std::max<int64_t>(w.n_p, (pool_cap + kMaxAppendChunk - 1) / kMaxAppendChunk);
+        w.n_p = (int)std::min<int64_t>(w.n_p, (pool_cap + kMinChunk - 1) / kMinChunk);
+    }
+    w.chunk_w = chunk_of(win_cap, w.n_w);
+    w.chunk_p = chunk_of(pool_cap, w.n_p);
+    w.n_w = win_cap > 0 ? n_splits_for(win_cap, w.chunk_w) : 0;
+    w.n_p = pool_cap > 0 ? n_splits_for(pool_cap, w.chunk_p) : 0;
     const size_t rows = (size_t)s->batch * n_q * s->n_q_heads;
     size_t at = 0;
     w.o_w = at; at += align_up(rows * w.n_w * s->head_dim * sizeof(float));
@@ -1061,7 +1081,8 @@ int hgca_append_attn_tiers(const hgca_shape *shape, const void *q, int32_t n_q, 
     aw.q = ap.q = q;
     aw.n_q = ap.n_q = n_q;
     aw.one_part_p = ap.one_part_p = (flags & HGCA_APPEND_ONE_PART_P) ? 1 : 0;
-    aw.chunk = ap.chunk = w.chunk;
+    aw.chunk = w.chunk_w;
+    ap.chunk = w.chunk_p;
     aw.kv = to_dev(window);
     aw.causal_tail = (flags & HGCA_APPEND_CAUSAL_TAIL) ? 1 : 0;
     aw.part = Partials{reinterpret_cast<float *>(base + w.o_w), reinterpret_cast<float *>(base + w.m_w),

@@ -113,7 +113,7 @@ hipError_t launch_threshold_select(const ThresholdArgs &a, int64_t n_rows, hipSt
 
 // ---- append stage: N queries per sequence over one tier (bf16, MFMA) ----
 
-constexpr int kMaxAppendChunk = 4096;   // tokens of one split of the append-stage attention at most
+constexpr int kMaxAppendChunk = 8192;   // tokens of one split of the append-stage attention at most
 
 struct AppendArgs {
     ShapeDev sh;
