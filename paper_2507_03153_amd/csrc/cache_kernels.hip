@@ -5,6 +5,8 @@
 // is copied.  What does move is the per-entry moving average of attention weights, which is kept
 // per window position: the evicted entries' averages are thresholded (Sec. 3.2.2) into the per-head
 // lists of salient pool positions and the rest of the row shifts down.
+#include <algorithm>
+
 #include "hgca_launch.hpp"
 #include "fold_device.hpp"
 #include "row_map.hpp"
@@ -14,9 +16,11 @@ namespace hgca {
 
 namespace {
 
-// One workgroup per sequence: the K and V rows of the n_tokens incoming tokens of every KV head go to the window
-// positions len .. len + n_tokens - 1 (slot p % block_size of window block p / block_size); then the length grows.
-// A sequence whose window capacity or table row cannot take all of them receives none (status bit).
+// The K and V rows of the n_tokens incoming tokens of every KV head go to the window positions len .. len + n_tokens
+// - 1 (slot p % block_size of window block p / block_size); then the length grows.  A sequence whose window capacity
+// or table row cannot take all of them receives none (status bit).  gridDim.y workgroups share a sequence's rows
+// (16-byte pieces dealt round-robin, four loads in flight per thread); the last of them to finish (an arrival counter
+// in plan[4b + 3], left at zero) stores the new length: by then every workgroup of the sequence has read the old one.
 __global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const char *k_in, const char *v_in,
                                                               const int32_t *active, int32_t n_kv_heads,
                                                               int32_t row_bytes, int32_t n_tokens)
@@ -27,35 +31,49 @@ __global__ __launch_bounds__(kRowBlock) void kv_append_kernel(CacheDev c, const 
     const int first = c.first_win_block[b];
     int32_t fail_bits = 0;
     if (pending_window_len(len, first, n_tokens, c.win_cap, c.block_size, c.max_blocks, &fail_bits) == len) {   // uniform
-        if (threadIdx.x == 0) atomicOr(c.status, fail_bits);
+        if (threadIdx.x == 0 && blockIdx.y == 0) atomicOr(c.status, fail_bits);
         return;
     }
     const int pieces = row_bytes / 16;                         // 16-byte pieces of one row
     const int per_token = n_kv_heads * pieces;
-    for (int i = threadIdx.x; i < n_tokens * per_token; i += kRowBlock) {
-        const int t = i / per_token, kvh = (i % per_token) / pieces, p = i % pieces;
-        const int pos = len + t;
-        const int64_t blk = c.block_table[(int64_t)b * c.max_blocks + first + pos / c.block_size];
-        const int64_t dst = ((blk * n_kv_heads + kvh) * c.block_size + pos % c.block_size) * row_bytes + 16 * p;
-        const int64_t src = (((int64_t)b * n_tokens + t) * n_kv_heads + kvh) * row_bytes + 16 * p;
-        *reinterpret_cast<uint4 *>(c.k_blocks + dst) = *reinterpret_cast<const uint4 *>(k_in + src);
-        *reinterpret_cast<uint4 *>(c.v_blocks + dst) = *reinterpret_cast<const uint4 *>(v_in + src);
+    const int total = n_tokens * per_token, stride = kRowBlock * (int)gridDim.y;
+    constexpr int U = 4;
+    for (int i0 = (int)blockIdx.y * kRowBlock + (int)threadIdx.x; i0 < total; i0 += U * stride) {
+        uint4 kr[U], vr[U];
+        int64_t dst[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = min(i0 + u * stride, total - 1);
+            const int t = i / per_token, kvh = (i % per_token) / pieces, p = i % pieces;
+            const int pos = len + t;
+            const int64_t blk = c.block_table[(int64_t)b * c.max_blocks + first + pos / c.block_size];
+            dst[u] = ((blk * n_kv_heads + kvh) * c.block_size + pos % c.block_size) * row_bytes + 16 * p;
+            const int64_t src = (((int64_t)b * n_tokens + t) * n_kv_heads + kvh) * row_bytes + 16 * p;
+            kr[u] = *reinterpret_cast<const uint4 *>(k_in + src);
+            vr[u] = *reinterpret_cast<const uint4 *>(v_in + src);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i0 + u * stride < total) {
+                *reinterpret_cast<uint4 *>(c.k_blocks + dst[u]) = kr[u];
+                *reinterpret_cast<uint4 *>(c.v_blocks + dst[u]) = vr[u];
+            }
+        }
     }
     __syncthreads();                                           // every thread has read `len` by now
-    if (threadIdx.x == 0) c.win_lens[b] = len + n_tokens;
+    if (threadIdx.x == 0) {
+        if (gridDim.y == 1) {
+            c.win_lens[b] = len + n_tokens;
+        } else {
+            int32_t *arrived = c.plan + 4 * b + 3;
+            if (atomicAdd(arrived, 1) == (int)gridDim.y - 1) {
+                *arrived = 0;
+                c.win_lens[b] = len + n_tokens;
+            }
+        }
+    }
 }
 
-// Eviction and sparsification of Alg. 1 for one (sequence, query head) row, called by all kRowBlock threads of the
-// row's workgroup.  Every workgroup of a sequence takes the same decision from the same state (if l_cur >= l_max:
-// evict the smallest whole number of blocks that brings the window below l_max); for a sequence that evicts, the
-// evicted entries whose moving average exceeds beta / l_cur join the head's list of salient pool positions
-// (appended in position order), optionally the evicted averages are saved at their pool positions, and the row
-// shifts down by l_evict.  The last workgroup of the sequence to finish (an arrival counter in plan[4b + 3], left
-// at zero) moves the boundary: by then every workgroup of the sequence has read the state it is about to change.
-// l_cur is the window's length as the caller read it (every thread of the workgroup, before a barrier).  With
-// store_len the stored length is not l_cur yet (a token joined the window in this step without its length having
-// been stored): the last workgroup stores it also when nothing is evicted, and raises fail_bits (if any) in the
-// cache's status word.
 // Alg. 1's eviction rule: whole blocks a window of l_cur tokens gives up (0 below l_max).
 __device__ __forceinline__ int blocks_to_evict(const CacheDev &c, int l_cur)
 {
@@ -248,7 +266,10 @@ hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_i
                             int32_t n_kv_heads, int32_t row_bytes, int32_t n_tokens, hipStream_t s)
 {
     if (batch == 0 || n_tokens == 0) return hipSuccess;
-    hipLaunchKernelGGL(kv_append_kernel, dim3(batch), dim3(kRowBlock), 0, s, c, static_cast<const char *>(k_in),
+    // one workgroup per sequence for a token; for N tokens as many as there are rounds of kRowBlock pieces, up to 16
+    const int64_t pieces = (int64_t)n_tokens * n_kv_heads * (row_bytes / 16);
+    const unsigned parts = (unsigned)std::max<int64_t>(1, std::min<int64_t>(16, pieces / (4 * kRowBlock)));
+    hipLaunchKernelGGL(kv_append_kernel, dim3(batch, parts), dim3(kRowBlock), 0, s, c, static_cast<const char *>(k_in),
                        static_cast<const char *>(v_in), active, n_kv_heads, row_bytes, n_tokens);
     return hipGetLastError();
 }

@@ -39,14 +39,26 @@ __device__ __forceinline__ int threshold_compact(CompactShared &sh, const float 
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
     int base = start;
     int buf = 0;
+    // the loads of a step are issued one step ahead, so a step does not begin with a round trip to memory
+    float nx[kPerThread];
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int t = e * kRowBlock + tid;
+        nx[e] = t < n ? wr[t] : 0.f;
+    }
     for (int t0 = 0; t0 < n && (!STOP_WHEN_FULL || base < k_max); t0 += kRowStep, buf ^= 1) {
         float x[kPerThread];
         bool keep[kPerThread];
         int below[kPerThread];
 #pragma unroll
         for (int e = 0; e < kPerThread; ++e) {
+            x[e] = nx[e];
+            const int tn = t0 + kRowStep + e * kRowBlock + tid;
+            nx[e] = tn < n ? wr[tn] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) {
             const int t = t0 + e * kRowBlock + tid;
-            x[e] = t < n ? wr[t] : 0.f;
             keep[e] = t < n && (double)x[e] > thr;
             const uint64_t mask = __ballot(keep[e]);
             below[e] = lanes_below_in(mask);
