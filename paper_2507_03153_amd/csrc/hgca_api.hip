@@ -29,6 +29,10 @@ constexpr size_t kAlign = 256;
 #define HGCA_TARGET_WGS_SPARSE_SCORED 2048
 #endif
 
+// workgroups the append-stage weights pass aims at (its tokens per workgroup are halved from 2048 until it has them)
+#ifndef HGCA_WEIGHTS_TARGET_WGS
+#define HGCA_WEIGHTS_TARGET_WGS 1024
+#endif
 // Workgroups the append-stage attention aims at per launch: what the device holds at once (two per compute unit).
 // Every workgroup writes a partial of 128 rows x d floats (64 KB, read again by the fold: the K/V bytes of four
 // 64-token steps), so splits are as long as filling the device allows.  Measured on the 8B shape, N = 32, with
@@ -1122,7 +1126,7 @@ int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, con
         return from_hip(launch_append_weights_f32(shape->head_dim, a, static_cast<hipStream_t>(hip_stream)));
     const int64_t units = (int64_t)shape->batch * shape->n_kv_heads;
     a.chunk = 2048;                                  // tokens per workgroup, halved until the GPU is filled
-    while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < 1024) a.chunk /= 2;
+    while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < HGCA_WEIGHTS_TARGET_WGS) a.chunk /= 2;
     return from_hip(launch_append_weights(shape->head_dim, a, n_splits_for(tier->cap, a.chunk),
                                           static_cast<hipStream_t>(hip_stream)));
 }
