@@ -149,6 +149,17 @@ def test_decode_loop_in_one_call_per_step(gpu):
     assert status == 0
 
 
+def test_decode_loop_in_one_call_other_group_sizes(gpu):
+    """Groups of 2 (two launches per step: the token joins inside the window's split launch) and of 8 (insert, window
+    splits and gather as launches of their own, the tail as one): the same loop, the same checks."""
+    _, _, status = run_loop(gpu, B=2, Hq=4, Hkv=2, d=64, block_size=32, win_blocks=3, max_blocks=9, k_max=256,
+                            prefill=(7, 70), steps=130, alpha=0.4, beta=0.8, seed=21, one_call=True)
+    assert status == 0
+    _, _, status = run_loop(gpu, B=2, Hq=8, Hkv=1, d=128, block_size=16, win_blocks=3, max_blocks=14, k_max=256,
+                            prefill=(0, 33), steps=140, alpha=0.3, beta=1.0, seed=22, one_call=True)
+    assert status == 0
+
+
 def test_decode_loop_with_sharply_peaked_attention(gpu):
     """Every 7th key leans ten times as far towards the queries' direction: scaled scores of about 70 against
     N(0,1) for the rest, so the window weights are ~1/n_boosted on a few entries and underflow to zero on the others;
