@@ -8,6 +8,10 @@ namespace hgca {
 
 namespace {
 
+// 16-byte loads per thread that make up the pre-filter's sample in the 512-thread workgroups (2: 4 096 scores)
+#ifndef HGCA_SEL_SMALL_SAMPLE_LOADS
+#define HGCA_SEL_SMALL_SAMPLE_LOADS 2
+#endif
 #ifndef HGCA_SEL_BINS
 #define HGCA_SEL_BINS 4096
 #endif
@@ -343,7 +347,7 @@ struct Sel {
         return true;
     }
 
-    // Long rows (too long for LDS as fp32) through a PRE-FILTER: a sample of the row (kSampleChunks runs of 1024
+    // Long rows (too long for LDS as fp32) through a PRE-FILTER: a sample of the row (runs of 256
     // scores spread evenly over it) gives an estimate of the score that a little more than the wanted fraction k / n
     // of the row exceeds; one pass over the row then keeps, per wave and in position order, only the scores at or
     // above that estimate (a few per cent of the row) in LDS, and the exact selection -- histogram, threshold bin,
@@ -351,14 +355,16 @@ struct Sel {
     // score costs one compare, and nothing of the row but the retained entries is written anywhere.  The estimate
     // is only a filter: if fewer than k entries pass it, a wave's list overflows or the threshold bin is crowded,
     // the function returns false before it has written any output and the caller runs select_row.  `lists` is the workgroup's dynamic LDS (list_bytes of it).
-    static constexpr int kSampleLoads = 8;                       // 16-byte loads per thread that make up the sample
-    static constexpr int kSampleChunk = 1024;                    // scores of one run of the sample
-    static constexpr int kSampleChunks = kSelBlock * kSampleLoads * 4 / kSampleChunk;
+    // kSampleLoads 16-byte loads per thread make up the sample (8 for the large workgroups: 32 768 scores).
+    static constexpr int kSampleChunk = 256;                     // scores of one run of the sample: what a wave takes with one load
+    template <int kSampleLoads>
     static __device__ __forceinline__ bool select_row_prefiltered(const SelectArgs &a, SelShared &sh, float *lists,
                                                                   int list_bytes, const float *sc, int32_t *out, int n,
                                                                   int k, int64_t bh)
     {
+        constexpr int kSampleChunks = kSelBlock * kSampleLoads * 4 / kSampleChunk;
         constexpr int kSample = kSampleChunks * kSampleChunk;
+        static_assert(kSampleChunks >= 2, "the sample is spread over the row");
         const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
         const bool sc_vec = (a.kv.cap & 3) == 0;     // rows start 16-byte aligned
         const int cap_w = list_bytes / (kSelWaves * 8);              // entries of one wave's list
@@ -927,7 +933,9 @@ __device__ __forceinline__ void select_row_any(const SelectArgs &a, typename Sel
         if (S::template select_row_in_registers<(REG_STEPS > 0 ? REG_STEPS : 1)>(a, sh, sc, out, n, k, bh)) return;
         __syncthreads();                         // the general path starts over on the shared state
     } else if (list_bytes > 0 && S::padded_length(n) > cache_floats) {     // too long for LDS as fp32: pre-filter
-        if (S::select_row_prefiltered(a, sh, cache, list_bytes, sc, out, n, k, bh)) return;
+        if (S::template select_row_prefiltered<(BLOCK == kLargeBlock ? 8 : HGCA_SEL_SMALL_SAMPLE_LOADS)>(a, sh, cache, list_bytes, sc,
+                                                                                                       out, n, k, bh))
+            return;
         __syncthreads();                         // the general path starts over on the shared state
     }
     if (S::padded_length(n) <= cache_floats) S::template select_row<kCachedScores>(a, sh, cache, sc, out, n, k, bh);

@@ -14,11 +14,13 @@
 //      of the comparisons, so the pass needs no barrier per step; positions are
 //      staged in LDS and leave with coalesced stores.
 //
-// Rows too long to sit in LDS as fp32 (beyond 33 792 scores) that have a compute unit to themselves first try a
-// sampled pre-filter (select_row_prefiltered): an estimate of the threshold from 32 768 sampled scores, one pass over
-// the row that retains the few per cent at or above it in LDS, and the steps above on the retained entries only.
-// It gives the same result or gives up (then the steps above run on the whole row, held as one byte per score or
-// re-read from memory).  Measured on 256 rows of 122 880 scores, k = 4096: 63 -> 38 us.
+// Rows that do not sit in LDS as fp32 (beyond 33 792 scores for the large workgroups, beyond 4 096 for the small
+// ones) first try a sampled pre-filter (select_row_prefiltered): an estimate of the threshold from a sample of the
+// row (32 768 scores, 4 096 in the small workgroups: runs of 256 spread evenly over the row), one pass over the row
+// that retains the few per cent at or above it in LDS, and the steps above on the retained entries only.  It gives
+// the same result or gives up (then the steps above run on the whole row, held as one byte per score or re-read
+// from memory).  Measured: 256 rows of 122 880 scores, k = 4096: 63 -> 38 us; 1280 rows of 14 336, k = 1024:
+// 48 -> 35 us; 2048 rows of 14 336, k = 1433: 68 -> 51 us; 512 rows of 50 000, k = 2500: 53 -> 32 us.
 //
 // A row is one CU's work; with a handful of VALU operations per score and pass the
 // kernel is bound by that CU's instruction issue, so the passes are kept lean
@@ -46,6 +48,9 @@ namespace {
 // 1: rows too long for LDS as fp32 go through the sampled pre-filter first (large workgroups only)
 #ifndef HGCA_SEL_PREFILTER
 #define HGCA_SEL_PREFILTER 1
+#endif
+#ifndef HGCA_SEL_PREFILTER_SMALL
+#define HGCA_SEL_PREFILTER_SMALL 1
 #endif
 
 // One workgroup per (sequence, query head) row.  The small workgroups are held to 64 registers per lane so that
@@ -96,8 +101,10 @@ hipError_t launch_select_block(const SelectArgs &a, int64_t rows, int max_cache_
     }
     // rows that do not fit as fp32 try the pre-filter first when the workgroup is alone on its unit: its lists take
     // the whole dynamic allocation (the byte cache of the general path, if that runs after all, uses the same memory)
-    const int list_bytes = HGCA_SEL_PREFILTER && BLOCK == kLargeBlock && cache_floats == 0
-                               ? kMaxCacheFloats * (int)sizeof(float) : 0;
+    // (the small workgroups, when asked to, keep their lists in the allocation of their byte cache)
+    const int list_bytes = !HGCA_SEL_PREFILTER || cache_floats != 0 ? 0
+                           : BLOCK == kLargeBlock ? kMaxCacheFloats * (int)sizeof(float)
+                           : HGCA_SEL_PREFILTER_SMALL && cache_bytes ? std::min(kSmallMaxPadded, 2 * cache_bytes) : 0;
     const size_t lds = cache_floats ? (size_t)cache_floats * sizeof(float)
                                     : std::max((size_t)cache_bytes, (size_t)list_bytes);
     hipLaunchKernelGGL(select_topk_kernel<BLOCK>, dim3((unsigned)rows), dim3(BLOCK), lds, s, a, cache_floats,
