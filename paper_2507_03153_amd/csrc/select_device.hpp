@@ -45,6 +45,10 @@ struct Binning {
     }
 };
 
+// The histogram's range is taken over the FINITE scores: an infinite end would make the bin width zero or the scaled
+// scores NaN.  Infinite scores (a caller's masked positions, say) then fall into the end bins by clamping.
+__device__ __forceinline__ float finite_or(float s, float otherwise) { return fabsf(s) < INFINITY ? s : otherwise; }
+
 // Four consecutive scores starting at position t (a multiple of 4); positions at or beyond n read -inf.
 __device__ __forceinline__ float4 load4_padded(const float *sc, bool sc_vec, int t, int n)
 {
@@ -210,8 +214,8 @@ struct Sel {
             const float s[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                mx = fmaxf(mx, s[e]);                                 // padding is -inf: no effect
-                mn = fminf(mn, i < steps && pos0 + kStep * i + e < n ? s[e] : INFINITY);
+                mx = fmaxf(mx, finite_or(s[e], -INFINITY));           // padding is -inf: no effect
+                mn = fminf(mn, finite_or(s[e], INFINITY));
             }
         }
 #pragma unroll
@@ -258,9 +262,10 @@ struct Sel {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float x = bin.scaled(s[e]);
-                    const bool over = x >= edge_hi;
+                    const bool over = tb != kBins - 1 && x >= edge_hi;   // the topmost bin holds +inf as well
                     above += over;
-                    if (x >= edge_lo && !over) {
+                    // (bin 0 also holds what the truncation sent there: -inf and scores below the range)
+                    if (!over && (tb == 0 ? pos0 + kStep * i + e < n : x >= edge_lo)) {
                         const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
                         if (slot < (uint32_t)kMaxCand) { sh.cand_score()[slot] = s[e]; sh.cand_idx()[slot] = pos0 + kStep * i + e; }
                     }
@@ -388,7 +393,7 @@ struct Sel {
         for (int u = 0; u < kSampleLoads; ++u) {
             const float s[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { mx = fmaxf(mx, s[e]); mn = fminf(mn, s[e]); }
+            for (int e = 0; e < 4; ++e) { mx = fmaxf(mx, finite_or(s[e], -INFINITY)); mn = fminf(mn, finite_or(s[e], INFINITY)); }
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
@@ -402,7 +407,7 @@ struct Sel {
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < kSelWaves; ++i) { mn = fminf(mn, sh.wave_min[i]); mx = fmaxf(mx, sh.wave_max[i]); }
-        if (!(mx > mn) || mn == -INFINITY || mx == INFINITY) return false;   // constant, NaN or infinite sample (uniform)
+        if (!(mx > mn)) return false;                // a constant sample, or nothing finite in it (uniform)
         Binning bin;
         bin.lo = mn;
         bin.inv_w = (float)kBins / (mx - mn);
@@ -443,7 +448,7 @@ struct Sel {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     keep[e] = s[e] >= floor_score;                   // padding (-inf) and NaN fail
-                    top = fmaxf(top, s[e]);
+                    top = fmaxf(top, finite_or(s[e], -INFINITY));
                     const unsigned long long m = __ballot(keep[e]);
                     before += (int)lanes_below(m);
                     held += __popcll(m);
@@ -482,7 +487,7 @@ struct Sel {
             overflow |= sh.scan_scratch[i] > (uint32_t)cap_w;
             top = fmaxf(top, sh.wave_max[i]);
         }
-        if (overflow || total < (uint32_t)k || !(top > floor_score) || top == INFINITY) return false;   // uniform
+        if (overflow || total < (uint32_t)k || !(top > floor_score)) return false;   // uniform
 
         // ---- exact selection among the retained entries (each wave walks its own list) ----------------------
         Binning fine;
@@ -607,8 +612,8 @@ struct Sel {
                         const float s[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            mx = fmaxf(mx, s[e]);                            // padding is -inf: no effect
-                            mn = fminf(mn, 4 * i + e < n ? s[e] : INFINITY);
+                            mx = fmaxf(mx, finite_or(s[e], -INFINITY));      // padding is -inf: no effect
+                            mn = fminf(mn, finite_or(s[e], INFINITY));
                         }
                     }
                 }
@@ -656,7 +661,8 @@ struct Sel {
         // ---- pass 2: count the entries above the threshold bin, collect those inside it ---------------------
         // bin(s) > tb and bin(s) == tb are decided on the scaled score itself (two float compares against
         // the bin's edges give the same answer as the truncation and clamps of the histogram pass; the
-        // topmost bin has no upper edge, padding and NaN fail both compares)
+        // topmost bin has no upper edge; bin 0 has no lower edge: it holds -inf as well, so there every
+        // valid position that is not above counts as inside)
         const float edge_lo = (float)tb, edge_hi = (tb == kBins - 1) ? INFINITY : (float)(tb + 1);
         uint32_t above = 0;
         const uint32_t tb7 = (uint32_t)tb >> kCoarseShift;          // kCachedBins: the 7 cached bits of the threshold bin
@@ -670,8 +676,8 @@ struct Sel {
                 inside = b == tb && pos < n;
             } else {
                 const float x = bin.scaled(sc_e);
-                over = x >= edge_hi;
-                inside = x >= edge_lo && !over;
+                over = tb != kBins - 1 && x >= edge_hi;           // the topmost bin holds +inf as well
+                inside = !over && (tb == 0 ? pos < n : x >= edge_lo);    // bin 0 also holds -inf and what lies below the range
             }
             if (inside) {
                 const uint32_t slot = atomicAdd(&sh.n_cand, 1u);

@@ -270,6 +270,12 @@ def test_decode_steps_maw_then_threshold_then_sparse_attention(gpu, oracle):
     # 4 096 scores): the usual case, a tie at the cut, a trend (the filter gives up), a budget beyond its reach
     (9, 32, 14336, 1024, "normal"), (9, 32, 12000, 700, "tie"), (9, 32, 14000, 800, "trend"), (9, 32, 9000, 2000, "normal"),
     (9, 32, 8300, 1, "maw"),
+    # infinite scores (a caller's masked positions): a few of either sign; so many -inf that the budget reaches into
+    # them (ties among them are cut by position); on every path: registers, LDS, bytes, pre-filter, from memory
+    (2, 8, 700, 100, "inf"), (2, 4, 28672, 2048, "inf"), (1, 4, 33000, 1200, "inf"), (1, 4, 100000, 2000, "inf"),
+    (2, 4, 200000, 25000, "inf"), (9, 32, 9000, 900, "inf"),
+    (2, 8, 700, 500, "masked"), (2, 4, 28672, 20000, "masked"), (1, 4, 40000, 30000, "masked"),
+    (1, 2, 150000, 100000, "masked"), (9, 32, 9000, 6000, "masked"),
 ])
 def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kind):
     torch, hgca, _ = gpu
@@ -279,6 +285,12 @@ def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kin
     if kind == "maw":                                           # weights of a peaked softmax: many tiny values, exact zeros
         s = softmax(12.0 * z, axis=-1).astype(np.float32)
         s[s < 1e-12] = 0.0
+    elif kind == "inf":
+        s = z.astype(np.float32)
+        s[:, :, rng.integers(0, cap, 5)] = np.inf
+        s[:, :, rng.integers(0, cap, 5)] = -np.inf
+    elif kind == "masked":                                      # half of the positions are -inf
+        s = np.where(rng.random((B, Hq, cap)) < 0.5, -np.inf, z).astype(np.float32)
     elif kind == "tie":
         s = z.astype(np.float32)
         for b in range(B):
