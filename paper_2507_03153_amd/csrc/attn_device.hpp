@@ -87,7 +87,8 @@ __device__ __forceinline__ void value_prefetch(const KernelArgs &a, int nt, cons
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int j = min(u * RPI + w * RPW + r, nt - 1);
-        vr[u] = load16_stream(a.kv.v + rows(j) * ROW_BYTES + c * 16);
+        vr[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (nt > 0) vr[u] = load16_stream(a.kv.v + rows(j) * ROW_BYTES + c * 16);   // (uniform; a split is never empty here)
     }
 }
 
