@@ -8,9 +8,10 @@ namespace hgca {
 
 namespace {
 
-// 16-byte loads per thread that make up the pre-filter's sample in the 512-thread workgroups (2: 4 096 scores)
+// 16-byte loads per thread that make up the pre-filter's sample in the 512-thread workgroups (1: 2 048 scores, so
+// rows from 4 096 scores on are served; with 2 the ragged batch of 2048 rows is 3 us slower, the others the same)
 #ifndef HGCA_SEL_SMALL_SAMPLE_LOADS
-#define HGCA_SEL_SMALL_SAMPLE_LOADS 2
+#define HGCA_SEL_SMALL_SAMPLE_LOADS 1
 #endif
 #ifndef HGCA_SEL_BINS
 #define HGCA_SEL_BINS 4096

@@ -16,7 +16,7 @@
 //
 // Rows that do not sit in LDS as fp32 (beyond 33 792 scores for the large workgroups, beyond 4 096 for the small
 // ones) first try a sampled pre-filter (select_row_prefiltered): an estimate of the threshold from a sample of the
-// row (32 768 scores, 4 096 in the small workgroups: runs of 256 spread evenly over the row), one pass over the row
+// row (32 768 scores, 2 048 in the small workgroups: runs of 256 spread evenly over the row), one pass over the row
 // that retains the few per cent at or above it in LDS, and the steps above on the retained entries only.  It gives
 // the same result or gives up (then the steps above run on the whole row, held as one byte per score or re-read
 // from memory).  Measured: 256 rows of 122 880 scores, k = 4096: 63 -> 38 us; 1280 rows of 14 336, k = 1024:

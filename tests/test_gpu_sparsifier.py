@@ -267,7 +267,7 @@ def test_decode_steps_maw_then_threshold_then_sparse_attention(gpu, oracle):
     (1, 2, 100000, 1500, "coarse"), (1, 4, 90000, 2500, "trend"), (1, 2, 80000, 30000, "normal"),
     (1, 4, 100000, 2000, "tie"),                # a handful of equal scores exactly where the budget cuts
     # more rows than compute units AND rows held as bytes: the 512-thread workgroups try the pre-filter too (sample of
-    # 4 096 scores): the usual case, a tie at the cut, a trend (the filter gives up), a budget beyond its reach
+    # 2 048 scores): the usual case, a tie at the cut, a trend (the filter gives up), a budget beyond its reach
     (9, 32, 14336, 1024, "normal"), (9, 32, 12000, 700, "tie"), (9, 32, 14000, 800, "trend"), (9, 32, 9000, 2000, "normal"),
     (9, 32, 8300, 1, "maw"),
     # infinite scores (a caller's masked positions): a few of either sign; so many -inf that the budget reaches into
