@@ -543,7 +543,7 @@ def append_turn_timing(torch, hgca, cfg, L, k_max, dev, n_q: int = 32, turns: in
             "hbm_frac": kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "beta": BETA, "cache_status": int(C.status.cpu()[0]),
             "salient_per_head_after": C.ctx_cnt.float().mean().item(),
             "calls_per_turn": "hgca_managed_append_step (insert, both tiers' attention in one launch, fold, weights of "
-                              "window and pool, moving average, re-evaluation, eviction: 8 kernels)"}
+                              "window and pool, then moving average + re-evaluation + eviction per row: 6 kernels)"}
 
 
 def copy_calibration(torch, dev) -> int:

@@ -208,6 +208,47 @@ __global__ __launch_bounds__(kRowBlock) void decode_tail_kernel(Partials p, Part
     }
 }
 
+// The tail of an append turn over the managed cache as one launch, one workgroup per (sequence, query head) row:
+// Alg. 1's moving average with the query-averaged A_gpu (the n_new newest entries take their first weight), the
+// re-evaluation of Sec. 3.2.2 (the head's salient list is REPLACED by the pool positions with A_cpu > beta / pool
+// length, ascending, -1 padded; a list that is too short raises the status bit), then eviction and sparsification of
+// the row.  The three steps of a row need nothing from other rows.
+__global__ __launch_bounds__(kRowBlock) void append_tail_kernel(CacheDev c, const float *a_gpu, const float *a_cpu,
+                                                                int32_t n_q_heads, int32_t n_new, float alpha, double beta)
+{
+    __shared__ CompactShared s_compact;
+    const int64_t row = blockIdx.x;
+    const int b = (int)(row / n_q_heads), tid = threadIdx.x;
+    const int l_cur = c.win_lens[b];
+    // moving average over the window row
+    {
+        const int n = min(max(l_cur, 0), c.win_cap), first_new = n - min(n_new, n);
+        const float keep = 1.f - alpha;
+        float *m = c.a_maw + row * c.win_cap;
+        const float *a = a_gpu + row * c.win_cap;
+        for (int j = tid; j < n; j += kRowBlock) {
+            const float x = a[j];
+            m[j] = j >= first_new ? x : fmaf(alpha, x, keep * m[j]);
+        }
+    }
+    // re-evaluation over the pool row
+    if (c.pool_cap > 0 && a_cpu) {
+        const int n_pool = min(max(c.pool_lens[b], 0), c.pool_cap);
+        int32_t *idx = c.ctx_idx + row * c.k_max;
+        float unused = 0.f;
+        const int passing = threshold_compact<false>(s_compact, a_cpu + row * (int64_t)c.pool_cap, n_pool,
+                                                     beta / (double)c.pool_lens[b], idx, 0, c.k_max, 0, nullptr, unused);
+        const int kept = min(passing, c.k_max);
+        if (tid == 0) {
+            c.ctx_cnt[row] = kept;
+            if (passing > c.k_max) atomicOr(c.status, kCacheListFull);
+        }
+        for (int j = kept + tid; j < c.k_max; j += kRowBlock) idx[j] = -1;
+    }
+    __syncthreads();                                           // the averages and the new list are written before the eviction reads them
+    evict_row(s_compact, c, row, n_q_heads, beta, l_cur, false, 0);
+}
+
 // KV_ctx of Alg. 1 (per head, the salient entries in contiguous storage): the K and V rows of the listed pool
 // positions are copied, in list order, behind the rows a head already holds.  One workgroup copies kCtxRows
 // listed entries of one (sequence, head): 16 bytes per lane, consecutive lanes on consecutive pieces of a row,
@@ -290,6 +331,15 @@ hipError_t launch_decode_tail(int head_dim, int64_t n_rows, const Partials &p, c
     else HGCA_TAIL_CASE(128, true);
     else return hipErrorInvalidValue;
 #undef HGCA_TAIL_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_append_tail(const CacheDev &c, const float *a_gpu, const float *a_cpu, int32_t batch, int32_t n_q_heads,
+                              int32_t n_new, float alpha, double beta, hipStream_t s)
+{
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(append_tail_kernel, dim3((unsigned)((int64_t)batch * n_q_heads)), dim3(kRowBlock), 0, s, c, a_gpu, a_cpu,
+                       n_q_heads, n_new, alpha, beta);
     return hipGetLastError();
 }
 

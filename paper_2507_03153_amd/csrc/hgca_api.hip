@@ -40,6 +40,10 @@ constexpr size_t kAlign = 256;
 #ifndef HGCA_APPEND_TARGET_WGS
 #define HGCA_APPEND_TARGET_WGS 512
 #endif
+// 1: moving average, re-evaluation and eviction of an append turn are one launch
+#ifndef HGCA_FUSE_APPEND_TAIL
+#define HGCA_FUSE_APPEND_TAIL 1
+#endif
 // 1: the token of a managed decode step is written into the window by the window split that reads it (needs the two below)
 #ifndef HGCA_FUSE_KV_APPEND
 #define HGCA_FUSE_KV_APPEND 1
@@ -1226,7 +1230,11 @@ int hgca_managed_append_step(const hgca_shape *shape, const hgca_cache_state *ca
     // A_gpu, A_cpu: the query-averaged weights of the two parts
     if ((rc = hgca_append_weights(shape, q, n_q, &window, 1, lse_w, a_gpu, hip_stream)) != HGCA_OK) return rc;
     if ((rc = hgca_append_weights(shape, q, n_q, &pool, 0, lse_p, a_cpu, hip_stream)) != HGCA_OK) return rc;
-    // Alg. 1: moving averages (the n_q new entries take their first observed weight)
+    // Alg. 1: moving averages (the n_q new entries take their first observed weight), re-evaluation of the salient
+    // lists (Sec. 3.2.2: ids = A_cpu > beta / A_cpu.size), eviction of as many whole blocks as it takes: per row, one launch
+    if (HGCA_FUSE_APPEND_TAIL)
+        return from_hip(launch_append_tail(c, a_gpu, cache->pool_cap > 0 ? a_cpu : nullptr, shape->batch, shape->n_q_heads,
+                                           n_q, alpha, beta, s));
     const int64_t rows = (int64_t)shape->batch * shape->n_q_heads;
     if ((rc = from_hip(launch_maw_update(c.a_maw, a_gpu, c.win_lens, rows, shape->n_q_heads, c.win_cap, n_q, alpha, s))) != HGCA_OK)
         return rc;

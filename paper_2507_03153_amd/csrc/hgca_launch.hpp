@@ -167,6 +167,10 @@ struct CacheDev {
 hipError_t launch_kv_append(const CacheDev &c, const void *k_in, const void *v_in, const int32_t *active, int32_t batch,
                             int32_t n_kv_heads, int32_t row_bytes, int32_t n_tokens, hipStream_t s);
 hipError_t launch_kv_evict(const CacheDev &c, int32_t batch, int32_t n_q_heads, double beta, hipStream_t s);
+// Tail of an append turn: moving average with a_gpu (n_new new entries), salient lists replaced from a_cpu (may be
+// null when the cache has no pool capacity), eviction and sparsification: one launch, one workgroup per row.
+hipError_t launch_append_tail(const CacheDev &c, const float *a_gpu, const float *a_cpu, int32_t batch, int32_t n_q_heads,
+                              int32_t n_new, float alpha, double beta, hipStream_t s);
 // Fold of the window's (p) and the salient list's (q) split partials, window weights e^{s - lse_window} in place in
 // a_gpu [n_rows, win_cap] with Alg. 1's moving average (one new token), eviction and sparsification: one launch.
 // token_pending: the token's rows are in the window but the stored length does not count it yet (see
