@@ -463,6 +463,7 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
         # both tiers in one call: one launch for the splits of window and pool, one fold (merged output + per-tier lse)
         "append_attn_tiers": lambda: hgca.append_attn_tiers(L.shape, q, L.window, L.pool, o, lse, ws_t, lse_window_out=lw,
                                                             lse_pool_out=lp),
+        "append_weights_tiers": lambda: hgca.append_weights_tiers(L.shape, q, L.window, L.pool, lw, lp, a_gpu, a_cpu),
         "append_attn_tiers_one_part_p": lambda: hgca.append_attn_tiers(L.shape, q, L.window, L.pool, o, lse, ws_t,
                                                                        lse_window_out=lw, lse_pool_out=lp, one_part_p=True),
     }
@@ -484,7 +485,7 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
     attn_ms = ms["append_attn_tiers"]                           # window + pool + merge as the one call that serves them
     one_ms = ms["append_attn_tiers_one_part_p"]
     three_calls_ms = ms["append_attn_window"] + ms["append_attn_pool"] + ms["lse_merge"]
-    weights_ms = ms["append_weights_window"] + ms["append_weights_pool"]
+    weights_ms = ms["append_weights_tiers"]
     return {"n_q": n_q, "per_call_ms": ms, "attention_ms": attn_ms, "attention_three_calls_ms": three_calls_ms,
             "with_weights_ms": attn_ms + weights_ms,
             "tokens_per_s": B * n_q / (attn_ms * 1e-3),
@@ -543,7 +544,7 @@ def append_turn_timing(torch, hgca, cfg, L, k_max, dev, n_q: int = 32, turns: in
             "hbm_frac": kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "beta": BETA, "cache_status": int(C.status.cpu()[0]),
             "salient_per_head_after": C.ctx_cnt.float().mean().item(),
             "calls_per_turn": "hgca_managed_append_step (insert, both tiers' attention in one launch, fold, weights of "
-                              "window and pool, then moving average + re-evaluation + eviction per row: 6 kernels)"}
+                              "window and pool in one launch, then moving average + re-evaluation + eviction per row: 5 kernels)"}
 
 
 def copy_calibration(torch, dev) -> int:

@@ -578,6 +578,17 @@ int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q,
                         const hgca_kv_view *tier, int32_t causal_tail,
                         const float *lse, float *a_out, void *hip_stream);
 
+/* The same for both tiers of an append turn in one launch (bf16 inputs;
+ * HGCA_ERR_UNSUPPORTED for fp32: one call per tier): a_gpu [B,Hq,window->cap]
+ * from lse_window (causal_tail applies to the window), a_cpu [B,Hq,pool->cap]
+ * from lse_pool, as hgca_append_attn_tiers returns them.  A tier of capacity 0
+ * is skipped (its pointers may be NULL). */
+int hgca_append_weights_tiers(const hgca_shape *shape, const void *q, int32_t n_q,
+                              const hgca_kv_view *window, const hgca_kv_view *pool,
+                              int32_t causal_tail, const float *lse_window,
+                              const float *lse_pool, float *a_gpu, float *a_cpu,
+                              void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

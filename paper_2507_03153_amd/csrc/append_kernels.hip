@@ -465,8 +465,11 @@ __global__ __launch_bounds__(kABlock / TILES, 4 / TILES) void append_attn_kernel
 // owns a_out[b, heads of kvh, t0 .. t0 + chunk): every step the waves' sums go through LDS to one thread
 // per entry, which writes (first block of 128 query rows) or adds to (further blocks) the entry.
 template <int D, int G>
-__global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
+__global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a1, AppendArgs a2, int n1)
 {
+    // a launch may serve two tiers: the first n1 workgroups along x take chunks of a1's tier, the rest of a2's
+    const bool second = (int)blockIdx.x >= n1;                   // uniform over the workgroup
+    const AppendArgs &a = second ? a2 : a1;
     using S = DmaStage<D, kAWaves>;
     // the K rows of a step arrive by LDS-direct loads, as in the attention kernel: two stages as separate arrays
     __shared__ __attribute__((aligned(1024))) char s_k0[S::kBytes];
@@ -474,7 +477,7 @@ __global__ __launch_bounds__(kABlock) void append_weights_kernel(AppendArgs a)
     __shared__ uint32_t s_row[kSub];
     __shared__ __attribute__((aligned(16))) float s_part[2][kAWaves][G][kStepTokens];   // read after the next step's barrier
 
-    const int chunk_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int chunk_id = (int)blockIdx.x - (second ? n1 : 0), kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave, n = lane % 16, g = lane / 16;
     const int len = tier_len(a.kv, b);
     const int t0 = chunk_id * a.chunk;
@@ -658,13 +661,13 @@ hipError_t launch_attn_group(const AppendArgs &a, const AppendArgs &a2, dim3 gri
 }
 
 template <int D>
-hipError_t launch_weights_group(const AppendArgs &a, dim3 grid, hipStream_t s)
+hipError_t launch_weights_group(const AppendArgs &a, const AppendArgs &a2, int n1, dim3 grid, hipStream_t s)
 {
     switch (a.sh.group) {
-    case 1: hipLaunchKernelGGL((append_weights_kernel<D, 1>), grid, dim3(kABlock), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((append_weights_kernel<D, 2>), grid, dim3(kABlock), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((append_weights_kernel<D, 4>), grid, dim3(kABlock), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((append_weights_kernel<D, 8>), grid, dim3(kABlock), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((append_weights_kernel<D, 1>), grid, dim3(kABlock), 0, s, a, a2, n1); break;
+    case 2: hipLaunchKernelGGL((append_weights_kernel<D, 2>), grid, dim3(kABlock), 0, s, a, a2, n1); break;
+    case 4: hipLaunchKernelGGL((append_weights_kernel<D, 4>), grid, dim3(kABlock), 0, s, a, a2, n1); break;
+    case 8: hipLaunchKernelGGL((append_weights_kernel<D, 8>), grid, dim3(kABlock), 0, s, a, a2, n1); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -695,13 +698,22 @@ hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s)
     return launch_append_attn2(head_dim, a, none, s);
 }
 
+hipError_t launch_append_weights2(int head_dim, const AppendArgs &a, int n_chunks, const AppendArgs &a2, int n_chunks2,
+                                  hipStream_t s)
+{
+    if (a.sh.batch == 0 || n_chunks + n_chunks2 == 0) return hipSuccess;
+    if (n_chunks2 > 0 && (a2.n_q != a.n_q || a2.q != a.q || a2.sh.group != a.sh.group || a2.sh.batch != a.sh.batch ||
+                          a2.sh.n_kv_heads != a.sh.n_kv_heads))
+        return hipErrorInvalidValue;             // the two tiers share the queries and the launch shape
+    dim3 grid(n_chunks + n_chunks2, a.sh.n_kv_heads, a.sh.batch);
+    if (head_dim == 64) return launch_weights_group<64>(a, a2, n_chunks, grid, s);
+    if (head_dim == 128) return launch_weights_group<128>(a, a2, n_chunks, grid, s);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks, hipStream_t s)
 {
-    if (a.sh.batch == 0 || n_chunks == 0) return hipSuccess;
-    dim3 grid(n_chunks, a.sh.n_kv_heads, a.sh.batch);
-    if (head_dim == 64) return launch_weights_group<64>(a, grid, s);
-    if (head_dim == 128) return launch_weights_group<128>(a, grid, s);
-    return hipErrorInvalidValue;
+    return launch_append_weights2(head_dim, a, n_chunks, a, 0, s);
 }
 
 hipError_t launch_append_weights_f32(int head_dim, const AppendArgs &a, hipStream_t s)

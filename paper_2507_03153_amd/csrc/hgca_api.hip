@@ -1110,6 +1110,45 @@ int hgca_append_attn_tiers(const hgca_shape *shape, const void *q, int32_t n_q, 
                                     want_tiers ? lse_w : nullptr, want_tiers ? lse_p : nullptr));
 }
 
+namespace {
+
+// Arguments of the weights pass over one tier (bf16) and the number of workgroups along x it takes.
+int weights_args(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier, int32_t causal_tail,
+                 const float *lse, float *a_out, AppendArgs *a)
+{
+    a->sh = to_dev(shape);
+    a->q = q;
+    a->kv = to_dev(tier);
+    a->n_q = n_q;
+    a->causal_tail = causal_tail ? 1 : 0;
+    a->lse = lse;
+    a->a_out = a_out;
+    const int64_t units = (int64_t)shape->batch * shape->n_kv_heads;
+    a->chunk = 2048;                                 // tokens per workgroup, halved until the GPU is filled
+    while (a->chunk > 64 && units * n_splits_for(tier->cap, a->chunk) < HGCA_WEIGHTS_TARGET_WGS) a->chunk /= 2;
+    return tier->cap > 0 ? n_splits_for(tier->cap, a->chunk) : 0;
+}
+
+}  // namespace
+
+int hgca_append_weights_tiers(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *window,
+                              const hgca_kv_view *pool, int32_t causal_tail, const float *lse_window, const float *lse_pool,
+                              float *a_gpu, float *a_cpu, void *hip_stream)
+{
+    int rc = check_append(shape, q, n_q, window, false);
+    if (rc != HGCA_OK) return rc;
+    if ((rc = check_append(shape, q, n_q, pool, false)) != HGCA_OK) return rc;
+    if (n_q == 0) return HGCA_ERR_INVALID_ARG;       // an average over no query is undefined
+    if (shape->dtype != HGCA_BF16) return HGCA_ERR_UNSUPPORTED;      // fp32 inputs: one call per tier
+    if (shape->batch == 0) return HGCA_OK;
+    if ((window->cap > 0 && (!lse_window || !a_gpu)) || (pool->cap > 0 && (!lse_pool || !a_cpu))) return HGCA_ERR_INVALID_ARG;
+    AppendArgs aw{}, ap{};
+    const int n_w = weights_args(shape, q, n_q, window, causal_tail, lse_window, a_gpu, &aw);
+    const int n_p = weights_args(shape, q, n_q, pool, 0, lse_pool, a_cpu, &ap);
+    // the pool's workgroups take the lower block numbers: they are the bulk of the launch
+    return from_hip(launch_append_weights2(shape->head_dim, ap, n_p, aw, n_w, static_cast<hipStream_t>(hip_stream)));
+}
+
 int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, const hgca_kv_view *tier,
                         int32_t causal_tail, const float *lse, float *a_out, void *hip_stream)
 {
@@ -1119,20 +1158,10 @@ int hgca_append_weights(const hgca_shape *shape, const void *q, int32_t n_q, con
     if (shape->batch == 0 || tier->cap == 0) return HGCA_OK;
     if (!lse || !a_out) return HGCA_ERR_INVALID_ARG;
     AppendArgs a{};
-    a.sh = to_dev(shape);
-    a.q = q;
-    a.kv = to_dev(tier);
-    a.n_q = n_q;
-    a.causal_tail = causal_tail ? 1 : 0;
-    a.lse = lse;
-    a.a_out = a_out;
+    const int n_chunks = weights_args(shape, q, n_q, tier, causal_tail, lse, a_out, &a);
     if (shape->dtype == HGCA_F32)
         return from_hip(launch_append_weights_f32(shape->head_dim, a, static_cast<hipStream_t>(hip_stream)));
-    const int64_t units = (int64_t)shape->batch * shape->n_kv_heads;
-    a.chunk = 2048;                                  // tokens per workgroup, halved until the GPU is filled
-    while (a.chunk > 64 && units * n_splits_for(tier->cap, a.chunk) < HGCA_WEIGHTS_TARGET_WGS) a.chunk /= 2;
-    return from_hip(launch_append_weights(shape->head_dim, a, n_splits_for(tier->cap, a.chunk),
-                                          static_cast<hipStream_t>(hip_stream)));
+    return from_hip(launch_append_weights(shape->head_dim, a, n_chunks, static_cast<hipStream_t>(hip_stream)));
 }
 
 namespace {
@@ -1227,9 +1256,14 @@ int hgca_managed_append_step(const hgca_shape *shape, const hgca_cache_state *ca
         merged.batch = shape->batch * n_q;
         if ((rc = hgca_lse_merge(&merged, o_p, lse_p, o_w, lse_w, o_out, HGCA_F32, lse_out, hip_stream)) != HGCA_OK) return rc;
     }
-    // A_gpu, A_cpu: the query-averaged weights of the two parts
-    if ((rc = hgca_append_weights(shape, q, n_q, &window, 1, lse_w, a_gpu, hip_stream)) != HGCA_OK) return rc;
-    if ((rc = hgca_append_weights(shape, q, n_q, &pool, 0, lse_p, a_cpu, hip_stream)) != HGCA_OK) return rc;
+    // A_gpu, A_cpu: the query-averaged weights of the two parts (bf16: one launch for both)
+    if (shape->dtype == HGCA_BF16) {
+        if ((rc = hgca_append_weights_tiers(shape, q, n_q, &window, &pool, 1, lse_w, lse_p, a_gpu, a_cpu, hip_stream)) != HGCA_OK)
+            return rc;
+    } else {
+        if ((rc = hgca_append_weights(shape, q, n_q, &window, 1, lse_w, a_gpu, hip_stream)) != HGCA_OK) return rc;
+        if ((rc = hgca_append_weights(shape, q, n_q, &pool, 0, lse_p, a_cpu, hip_stream)) != HGCA_OK) return rc;
+    }
     // Alg. 1: moving averages (the n_q new entries take their first observed weight), re-evaluation of the salient
     // lists (Sec. 3.2.2: ids = A_cpu > beta / A_cpu.size), eviction of as many whole blocks as it takes: per row, one launch
     if (HGCA_FUSE_APPEND_TAIL)

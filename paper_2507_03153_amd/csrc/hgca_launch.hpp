@@ -131,6 +131,9 @@ hipError_t launch_append_attn(int head_dim, const AppendArgs &a, hipStream_t s);
 // two tiers in one launch (same queries and shape; each tier with its own view, mask rule, split size and partials)
 hipError_t launch_append_attn2(int head_dim, const AppendArgs &a, const AppendArgs &a2, hipStream_t s);
 hipError_t launch_append_weights(int head_dim, const AppendArgs &a, int n_chunks, hipStream_t s);
+// the weights of two tiers (same queries and shape) in one launch
+hipError_t launch_append_weights2(int head_dim, const AppendArgs &a, int n_chunks, const AppendArgs &a2, int n_chunks2,
+                                  hipStream_t s);
 // the same for fp32 inputs (q [B, N, Hq, d] fp32, fp32 tier): VALU pass, 64 tokens per workgroup
 hipError_t launch_append_weights_f32(int head_dim, const AppendArgs &a, hipStream_t s);
 

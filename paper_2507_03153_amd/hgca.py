@@ -24,7 +24,7 @@ EXPORTS = ("hgca_status_string", "hgca_workspace_bytes", "hgca_dense_window_attn
            "hgca_pool_scores", "hgca_select_salient", "hgca_sparse_attn", "hgca_lse_merge_splits", "hgca_lse_merge",
            "hgca_dense_window_attn_weights", "hgca_maw_update", "hgca_threshold_select", "hgca_select_topk",
            "hgca_kv_append", "hgca_kv_evict", "hgca_append_workspace_bytes", "hgca_append_attn",
-           "hgca_append_tiers_workspace_bytes", "hgca_append_attn_tiers",
+           "hgca_append_tiers_workspace_bytes", "hgca_append_attn_tiers", "hgca_append_weights_tiers",
            "hgca_append_weights", "hgca_dense_window_attn_maw", "hgca_select_salient_grouped", "hgca_union_lists",
            "hgca_sparse_attn_grouped", "hgca_hybrid_decode_step", "hgca_ctx_compact",
            "hgca_managed_decode_step", "hgca_dense_window_attn_static", "hgca_hybrid_decode_step_selected", "hgca_kv_append_tokens",
@@ -97,6 +97,8 @@ def lib() -> ctypes.CDLL:
         L.hgca_append_workspace_bytes.argtypes = [ps, i32, i32]
         L.hgca_append_attn.restype = ctypes.c_int
         L.hgca_append_attn.argtypes = [ps, vp, i32, pk, i32, vp, vp, vp, sz, vp]
+        L.hgca_append_weights_tiers.restype = ctypes.c_int
+        L.hgca_append_weights_tiers.argtypes = [ps, vp, i32, pk, pk, i32, vp, vp, vp, vp, vp]
         L.hgca_append_tiers_workspace_bytes.restype = ctypes.c_size_t
         L.hgca_append_tiers_workspace_bytes.argtypes = [ps, i32, i32, i32]
         L.hgca_append_attn_tiers.restype = ctypes.c_int
@@ -428,6 +430,17 @@ def append_weights(shape: Shape, q, tier: Tier, causal_tail: bool, lse, a_out, s
     kv = tier.view()
     _check(lib().hgca_append_weights(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kv), int(causal_tail),
                                      _ptr(lse), _ptr(a_out), _stream(stream)), "hgca_append_weights")
+
+
+def append_weights_tiers(shape: Shape, q, window: Tier, pool: Tier, lse_window, lse_pool, a_gpu, a_cpu,
+                         causal_tail: bool = True, stream=None) -> None:
+    """Query-averaged weights of window and pool in one launch (bf16); the lse rows from append_attn_tiers."""
+    for t in (q, lse_window, lse_pool, a_gpu, a_cpu):
+        _require_gpu(t)
+    kw, kp = window.view(), pool.view()
+    _check(lib().hgca_append_weights_tiers(ctypes.byref(shape), _ptr(q), int(q.shape[1]), ctypes.byref(kw), ctypes.byref(kp),
+                                           int(causal_tail), _ptr(lse_window), _ptr(lse_pool), _ptr(a_gpu), _ptr(a_cpu),
+                                           _stream(stream)), "hgca_append_weights_tiers")
 
 
 def dense_window_attn_maw(shape: Shape, q, window: Tier, o_out, lse_out, a_out, a_maw, n_new: int, alpha: float, ws,

@@ -337,6 +337,14 @@ def test_append_entry_points_reject_bad_arguments(hg):
     assert tiers(shape=hg.Shape(hg.BF16, 1, 2048, 2048, 128, 0.088), n_q=4096) == hg.ERR_UNSUPPORTED
     assert tiers(n_q=0) == hg.OK
 
+    def weights2(shape=sh, q=FAKE, n_q=4, lw=FAKE, lp=FAKE, ag=FAKE, ac=FAKE):
+        return L.hgca_append_weights_tiers(byref(shape), q, n_q, byref(view), byref(view), 1, lw, lp, ag, ac, None)
+    assert weights2(q=None) == hg.ERR_INVALID_ARG
+    assert weights2(n_q=0) == hg.ERR_INVALID_ARG
+    assert weights2(lw=None) == hg.ERR_INVALID_ARG
+    assert weights2(ac=None) == hg.ERR_INVALID_ARG
+    assert weights2(shape=hg.Shape(hg.F32, 2, 8, 2, 128, 0.088)) == hg.ERR_UNSUPPORTED
+
     def weights(q=FAKE, n_q=4, lse=FAKE, a=FAKE):
         return L.hgca_append_weights(byref(sh), q, n_q, byref(view), 0, lse, a, None)
     assert weights(q=None) == hg.ERR_INVALID_ARG

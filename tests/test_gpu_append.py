@@ -149,7 +149,13 @@ def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=
         say(f"    {name}, one-part P: max|dO|={err:.2e}")
         assert np.all(np.isfinite(got.cpu().numpy())) and err <= 1e-2
 
-    for name, a_t, A, lens, cap in (("A_gpu", a_gpu, A_g, wl_, W), ("A_cpu", a_cpu, A_c, pl_, P)):
+    # the weights of both tiers in one launch, normalised by the per-tier lse of the two-tier attention call
+    a_gpu2 = torch.full((B, Hq, W), float("nan"), **f32)
+    a_cpu2 = torch.full((B, Hq, max(P, 1)), float("nan"), **f32)
+    hgca.append_weights_tiers(shape, qd, win, pool, lw2, lp2, a_gpu2, a_cpu2)
+    torch.cuda.synchronize()
+    for name, a_t, A, lens, cap in (("A_gpu", a_gpu, A_g, wl_, W), ("A_cpu", a_cpu, A_c, pl_, P),
+                                    ("A_gpu, two tiers", a_gpu2, A_g, wl_, W), ("A_cpu, two tiers", a_cpu2, A_c, pl_, P)):
         a_t = a_t.double().cpu().numpy()[:, :, :cap]
         a_r = A.mean(axis=2)
         err = np.max(np.abs(a_t - a_r), initial=0.0)
@@ -157,7 +163,7 @@ def run_case(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, paged=
         assert err <= 2e-5
         for b in range(B):
             assert np.all(a_t[b, :, lens[b]:] == 0.0)
-            if lens[b] and (name == "A_cpu" or lens[b] >= N):
+            if lens[b] and (name.startswith("A_cpu") or lens[b] >= N):
                 assert np.max(np.abs(a_t[b, :, :lens[b]].sum(-1) - 1.0)) <= 1e-4
     return shape, a_cpu, A_c.mean(axis=2), pl_
 
@@ -342,7 +348,7 @@ def run_case_f32(gpu, seed, B, N, Hq, Hkv, d, W, P, w_lens=None, p_lens=None, pa
         assert err <= 1e-5
         for b in range(B):
             assert np.all(a_t[b, :, lens[b]:] == 0.0)
-            if lens[b] and (name == "A_cpu" or lens[b] >= N):
+            if lens[b] and (name.startswith("A_cpu") or lens[b] >= N):
                 assert np.max(np.abs(a_t[b, :, :lens[b]].sum(-1) - 1.0)) <= 1e-5
 
 
