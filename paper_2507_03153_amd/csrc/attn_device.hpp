@@ -185,9 +185,9 @@ __device__ __forceinline__ void store_split_scores(const KernelArgs &a, const fl
         }
         return;
     }
-    for (int i = threadIdx.x; i < NH * nt; i += BLOCK) {
-        const int g = i / nt, j = i % nt;
-        a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
+    for (int i = threadIdx.x; i < NH * LD; i += BLOCK) {         // indexed by the compile-time row length: no division by nt
+        const int g = i / LD, j = i % LD;
+        if (j < nt) a.scores[(bh0 + g) * (int64_t)a.kv.cap + t0 + j] = s_p[g][j];
     }
 }
 

@@ -215,7 +215,7 @@ struct Sel {
             const float s[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                mx = fmaxf(mx, finite_or(s[e], -INFINITY));           // padding is -inf: no effect
+                mx = fmaxf(mx, s[e]);                                 // padding is -inf: no effect; +inf: see below
                 mn = fminf(mn, finite_or(s[e], INFINITY));
             }
         }
@@ -232,6 +232,7 @@ struct Sel {
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < kSelWaves; ++i) { mn = fminf(mn, sh.wave_min[i]); mx = fmaxf(mx, sh.wave_max[i]); }
+        if (mx == INFINITY) return false;            // a +inf score: the general path takes its range over finite scores (uniform)
         Binning bin;
         bin.lo = mn;
         bin.inv_w = (mx > mn) ? (float)kBins / (mx - mn) : 0.f;
@@ -251,10 +252,13 @@ struct Sel {
         const int tb = (int)sh.found[0];
         const uint32_t k_rem = sh.found[1];          // rank of the k-th entry inside bin tb
         __syncthreads();
+        // Bin 0 also holds -inf scores and the topmost bin everything from the maximum on; the two compares below do
+        // not see them as inside those bins, so a threshold in an end bin goes to the general path (uniform).
+        if (tb == 0 || tb == kBins - 1) return false;
 
-        // entries above the threshold bin are counted, those inside it listed (the same two compares against the
-        // bin's edges as in select_row: padding and NaN fail both)
-        const float edge_lo = (float)tb, edge_hi = (tb == kBins - 1) ? INFINITY : (float)(tb + 1);
+        // entries above the threshold bin are counted, those inside it listed (two compares against the bin's edges;
+        // padding fails both)
+        const float edge_lo = (float)tb, edge_hi = (float)(tb + 1);
         uint32_t above = 0;
 #pragma unroll
         for (int i = 0; i < STEPS; ++i) {
@@ -263,10 +267,9 @@ struct Sel {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float x = bin.scaled(s[e]);
-                    const bool over = tb != kBins - 1 && x >= edge_hi;   // the topmost bin holds +inf as well
+                    const bool over = x >= edge_hi;
                     above += over;
-                    // (bin 0 also holds what the truncation sent there: -inf and scores below the range)
-                    if (!over && (tb == 0 ? pos0 + kStep * i + e < n : x >= edge_lo)) {
+                    if (x >= edge_lo && !over) {
                         const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
                         if (slot < (uint32_t)kMaxCand) { sh.cand_score()[slot] = s[e]; sh.cand_idx()[slot] = pos0 + kStep * i + e; }
                     }
