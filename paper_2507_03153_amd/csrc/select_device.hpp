@@ -452,7 +452,7 @@ struct Sel {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     keep[e] = s[e] >= floor_score;                   // padding (-inf) and NaN fail
-                    top = fmaxf(top, finite_or(s[e], -INFINITY));
+                    top = fmaxf(top, s[e]);
                     const unsigned long long m = __ballot(keep[e]);
                     before += (int)lanes_below(m);
                     held += __popcll(m);
@@ -491,7 +491,7 @@ struct Sel {
             overflow |= sh.scan_scratch[i] > (uint32_t)cap_w;
             top = fmaxf(top, sh.wave_max[i]);
         }
-        if (overflow || total < (uint32_t)k || !(top > floor_score)) return false;   // uniform
+        if (overflow || total < (uint32_t)k || !(top > floor_score) || top == INFINITY) return false;   // uniform (+inf: the whole-row path)
 
         // ---- exact selection among the retained entries (each wave walks its own list) ----------------------
         Binning fine;
