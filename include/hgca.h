@@ -157,8 +157,10 @@ int hgca_select_salient(const hgca_shape *shape, const void *q,
 /* The second pass of hgca_select_salient on scores the caller supplies (Sec.
  * 3.2.2: the sparsifier ranks entries by a per-head relevance value, which may
  * as well be the moving average of attention weights that hgca_maw_update
- * keeps): per (b, h) row of scores (device fp32 [B,Hq,cap], 16-byte aligned,
- * finite values; with infinities or NaN the selection is unspecified) keep
+ * keeps): per (b, h) row of scores (device fp32 [B,Hq,cap], 16-byte aligned;
+ * +inf and -inf are ordinary values here, e.g. -inf for positions a caller has
+ * masked: they rank above / below every finite score, ties among them by
+ * position; with NaN the selection is unspecified) keep
  * the k_b = min(k, len_b) largest of the first len_b = seq_lens[b] entries (all
  * `cap` if seq_lens is NULL).  Tie rule, budgets,
  * k_max, idx_out, cnt_out and sel_scores_out as in hgca_select_salient.  Only
