@@ -200,6 +200,26 @@ def test_select_given_matches_stable_argsort_and_the_scoring_select(oracle):
     assert np.array_equal(i1, i2) and np.array_equal(c1, c2)
 
 
+def test_select_given_with_infinite_scores_matches_stable_argsort(oracle):
+    """+inf and -inf are ordinary values (masked positions): they rank above / below every finite score, ties among
+    them by position; also when the budget reaches into the -inf entries."""
+    rng = np.random.default_rng(14)
+    B, Hq, cap = 2, 3, 80
+    s = rng.standard_normal((B, Hq, cap))
+    s[:, :, rng.integers(0, cap, 6)] = np.inf
+    s[:, :, rng.integers(0, cap, 30)] = -np.inf
+    for k in (1, 5, 40, 70, 79):
+        idx, cnt = oracle.select_given(s, k, k)
+        for b in range(B):
+            for h in range(Hq):
+                order = np.argsort(-s[b, h], kind="stable")[:k]
+                assert cnt[b, h] == k and idx[b, h].tolist() == sorted(order.tolist())
+    hand = np.array([[[-np.inf, 2.0, np.inf, -np.inf, np.inf, 0.5]]])
+    assert oracle.select_given(hand, 1, 1)[0][0, 0].tolist() == [2]
+    assert oracle.select_given(hand, 3, 3)[0][0, 0].tolist() == [1, 2, 4]
+    assert oracle.select_given(hand, 5, 5)[0][0, 0].tolist() == [0, 1, 2, 4, 5]
+
+
 def test_select_given_hand_worked(oracle):
     s = np.array([[[0.1, 0.7, 0.7, -1.0, 0.3]]])
     idx, cnt = oracle.select_given(s, 2, 3)
