@@ -323,6 +323,70 @@ def test_select_topk_on_supplied_scores_is_exact(gpu, oracle, B, Hq, cap, k, kin
         assert np.array_equal(sel[kept], want[kept])            # the kept entries' own scores, bit for bit
 
 
+def test_seeded_sweep_of_supplied_scores(gpu, oracle):
+    """Forty seeded draws of (rows, row length, budget, score distribution, lengths) through hgca_select_topk: few
+    long rows and many short ones, ties, trends along the row, peaked and bimodal rows, a constant first half,
+    infinities; positions, counts and kept scores bit for bit against the oracle."""
+    torch, hgca, _ = gpu
+    dev = "cuda:0"
+    rng = np.random.default_rng(4711)
+    for it in range(40):
+        if it % 2 == 0:                                         # few long rows: the 1024-thread workgroups
+            B, Hq = int(rng.integers(1, 3)), int(rng.choice([1, 2, 4]))
+            cap = int(rng.choice([34000, 66000, 70001, 100000, 131072, 140000]))
+        else:                                                   # more rows than compute units: the 512-thread ones
+            B, Hq = int(rng.integers(9, 12)), 32
+            cap = int(rng.choice([4100, 8192, 8300, 9001, 12000, 14336, 20000]))
+        k = int(rng.choice([1, 7, 64, 300, 1024, 2048, 4096, cap // 20, cap // 8, cap // 3]))
+        k = max(1, min(k, cap - 1))
+        kind = str(rng.choice(["normal", "coarse", "trend", "peaked", "bimodal", "sawtooth", "tie", "const_head", "inf"]))
+        z = rng.standard_normal((B, Hq, cap))
+        if kind == "coarse":
+            s = np.round(z, int(rng.integers(0, 3)))
+        elif kind == "trend":
+            s = z + np.linspace(0, float(rng.choice([-12, 3, 12])), cap)
+        elif kind == "peaked":
+            s = np.exp(6 * z)
+            s[s < 1e-6] = 0
+        elif kind == "bimodal":
+            s = z + 8.0 * (rng.random((B, Hq, cap)) < 0.03)
+        elif kind == "sawtooth":
+            s = z + 4.0 * ((np.arange(cap) // 256) % 7 == 0)
+        elif kind == "tie":
+            s = z.copy()
+            for b in range(B):
+                for h in range(Hq):
+                    order = np.argsort(-s[b, h], kind="stable")
+                    s[b, h, order[k:k + int(rng.integers(1, 40))]] = s[b, h, order[k - 1]]
+        elif kind == "const_head":
+            s = z.copy()
+            s[:, :, :cap // 2] = 0.25
+        elif kind == "inf":
+            s = z.copy()
+            s[:, :, rng.integers(0, cap, 5)] = np.inf
+            s[:, :, rng.integers(0, cap, 5)] = -np.inf
+        else:
+            s = z
+        s = s.astype(np.float32)
+        lens = rng.integers(0, cap + 1, B).astype(np.int32)
+        lens[0] = cap
+        use_lens = bool(rng.random() < 0.5)
+        say(f"\n[case] sweep {it}: B={B} Hq={Hq} cap={cap} k={k} scores={kind} lens={use_lens}")
+        sh = hgca.Shape(hgca.BF16, B, Hq, Hq, 128, 1.0)
+        idx = torch.full((B, Hq, k), -7, dtype=torch.int32, device=dev)
+        cnt = torch.full((B, Hq), -7, dtype=torch.int32, device=dev)
+        sel = torch.full((B, Hq, k), float("nan"), dtype=torch.float32, device=dev)
+        hgca.select_topk(sh, torch.from_numpy(s).to(dev), torch.from_numpy(lens).to(dev) if use_lens else None, cap, k, k,
+                         idx, cnt, sel)
+        torch.cuda.synchronize()
+        idx_ref, cnt_ref = oracle.select_given(s, k, k, lens=lens if use_lens else None)
+        idx_g, cnt_g, sel_g = idx.cpu().numpy(), cnt.cpu().numpy(), sel.cpu().numpy()
+        assert np.array_equal(cnt_g, cnt_ref) and np.array_equal(idx_g, idx_ref)
+        kept = np.arange(k)[None, None, :] < cnt_g[:, :, None]
+        want = np.take_along_axis(s, np.where(kept, idx_g, 0).astype(np.int64), axis=2)
+        assert np.array_equal(sel_g[kept], want[kept])
+
+
 def test_dense_with_moving_average_equals_the_two_calls(gpu, oracle):
     torch, hgca, runner = gpu
     cfg = wl.scaled(wl.CONFIGS["C5"], B=4, Hq=8, Hkv=2, W=256, P=1792, ragged=(100, 2048))
