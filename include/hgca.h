@@ -210,9 +210,10 @@ int hgca_lse_merge_splits(const hgca_shape *shape,
  * top-k selection over the pool with the current query (as
  * hgca_select_salient), sparse part over the selected entries, merge_state.
  * Same results as hgca_dense_window_attn + hgca_select_salient +
- * hgca_sparse_attn (with the selection's scores) + hgca_lse_merge_splits, bit
- * for bit, for one crossing of the boundary: the kept entries' scores stay in
- * the workspace and one fold produces O.  idx_out / cnt_out receive
+ * hgca_sparse_attn (with the selection's scores) + hgca_lse_merge_splits (the
+ * same selection; O and lse up to the order of the fp32 sums), for one
+ * crossing of the boundary: the kept entries' scores stay in the workspace
+ * and one fold produces O.  idx_out / cnt_out receive
  * the selection (reusable by later steps through hgca_sparse_attn); o_out is
  * [B,Hq,d] in o_dtype, lse_out [B,Hq] optional.  ws_dense needs
  * hgca_workspace_bytes(shape, window->cap, 0, 0), ws_sparse
@@ -231,9 +232,10 @@ int hgca_hybrid_decode_step(const hgca_shape *shape, const void *q,
  * entries are already selected (kv_manager.load returns KV_ctx), so the step is
  * gpu_attention over the window beside cpu_attention over each head's listed
  * entries, then merge_state.  Same results as hgca_dense_window_attn and
- * hgca_sparse_attn with deferred results + hgca_lse_merge_splits, bit for bit,
- * in one crossing of the boundary; the split kernels of the two parts, which
- * need nothing from each other, share one launch where the shapes allow.
+ * hgca_sparse_attn with deferred results + hgca_lse_merge_splits (up to the
+ * order of the fp32 sums: the split sizes differ), in one crossing of the
+ * boundary; the split kernels of the two parts, which need nothing from each
+ * other, share one launch where the shapes allow.
  * idx / cnt / k_max / sel_scores as in hgca_sparse_attn (sel_scores NULL unless
  * it holds the scores of the listed entries for THIS q).  o_out is [B,Hq,d] in
  * o_dtype, lse_out [B,Hq] optional.  ws_dense needs

@@ -75,6 +75,17 @@ def assert_selection(name, idx, cnt, scores, lens, k_b, eps):
     return n_band
 
 
+def _same_up_to_summation_order(torch, a, b):
+    """Two runs of the same arithmetic with differently sized splits: O within 2e-6, lse within 4e-6 (a few fp32 ulps
+    of sums of a few thousand terms), the same rows empty."""
+    finite = torch.isfinite(b.lse)
+    assert torch.equal(torch.isfinite(a.lse), finite)
+    if a.o.numel():
+        assert float((a.o - b.o).abs().max()) <= 2e-6
+    if finite.any():
+        assert float((a.lse[finite] - b.lse[finite]).abs().max()) <= 4e-6
+
+
 def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
     torch, hgca, runner = gpu
     say(f"\n[case] {cfg.name} dtype={cfg.dtype} B={cfg.B} Hq={cfg.Hq} Hkv={cfg.Hkv} d={cfg.d} W={cfg.W} "
@@ -171,9 +182,10 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
         one.run(D, select=True)
         torch.cuda.synchronize()
         assert_partial("hybrid, one call", one.o, one.lse, o_h, l_h, tol if n_band else min(tol, tight))
-        # same kernels on the same data as the separate calls: identical bits
+        # the same selection as the separate calls; O and lse up to the order of the fp32 sums (a window that shares
+        # its launch with the sparse part is cut into longer splits than one that has a launch of its own)
         assert torch.equal(one.idx[..., :L.k_max], fused.idx[..., :L.k_max]) and torch.equal(one.cnt, fused.cnt)
-        assert torch.equal(one.o, fused.o) and torch.equal(one.lse, fused.lse)
+        _same_up_to_summation_order(torch, one, fused)
         fused.run(D, select=False)                             # reused selection: K and V gathered
         torch.cuda.synchronize()
         assert_partial("steady, fused tail", fused.o, fused.lse, o_h, l_h, tol if n_band else min(tol, tight))
@@ -185,12 +197,12 @@ def run_case(gpu, oracle, cfg, layer=0, check_end_to_end=True):
         one.run(D, select=False)
         torch.cuda.synchronize()
         assert_partial("selected step, one call", one.o, one.lse, ou, lu, min(tol, tight))
-        # the same split kernels as the separate deferred calls on the same lists: identical bits
+        # the same split kernels as the separate deferred calls on the same lists
         fused.idx.copy_(one.idx)
         fused.cnt.copy_(one.cnt)
         fused.run(D, select=False)
         torch.cuda.synchronize()
-        assert torch.equal(one.o, fused.o) and torch.equal(one.lse, fused.lse)
+        _same_up_to_summation_order(torch, one, fused)
     return step, D, L
 
 
