@@ -195,7 +195,8 @@ __device__ __forceinline__ void store_split_scores(const KernelArgs &a, const fl
 
 // One split of softmax attention on the VALU path (any dtype and head_dim): dense over a tier, gathered through a
 // list of positions, or the score pass alone.  `unit` is the query head (per-head lists) or the KV head.
-template <typename T, int D, int NH, int MODE>
+// UNROLL: 16-byte loads a lane keeps in flight in the K and V passes.
+template <typename T, int D, int NH, int MODE, int UNROLL = kUnroll>
 struct SplitValu {
     static constexpr int kPBytes = NH * kMaxChunk * 4, kRowBytes = kMaxChunk * 4, kRedBytes = kWaves * NH * D * 4;
     static constexpr int kLdsBytes = kPBytes + kRowBytes + kRedBytes + 64;
@@ -246,15 +247,15 @@ struct SplitValu {
         }
 
         // K pass: scores of the split into LDS
-        for (int base = 0; MODE != kGatherScored && base < nt; base += RPI * kUnroll) {
-            uint4 kr[kUnroll];
+        for (int base = 0; MODE != kGatherScored && base < nt; base += RPI * UNROLL) {
+            uint4 kr[UNROLL];
     #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
+            for (int u = 0; u < UNROLL; ++u) {
                 const int j = min(base + u * RPI + w * RPW + r, nt - 1);
                 kr[u] = load16_stream(a.kv.k + rows(j) * ROW_BYTES + c * 16);
             }
     #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
+            for (int u = 0; u < UNROLL; ++u) {
                 const int j = base + u * RPI + w * RPW + r;
                 float kf[EPL];
                 Elem<T>::expand(kr[u], kf);
@@ -275,16 +276,16 @@ struct SplitValu {
         if (MODE == kDense && a.scores) __syncthreads();   // the softmax below overwrites the scores other waves are still storing
 
         if (HGCA_V_PREFETCH && GATHER) {             // the first V rows travel while the softmax statistics are formed
-            uint4 first[kUnroll];
-            value_prefetch<T, D>(a, nt, rows, first);
+            uint4 first[UNROLL];
+            value_prefetch<T, D, kBlock, UNROLL>(a, nt, rows, first);
             split_softmax<NH>(s_p, s_m, s_l, nt);
             __syncthreads();
-            value_pass<T, D, NH, GATHER, kBlock, kUnroll, kMaxChunk, true>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows, first);
+            value_pass<T, D, NH, GATHER, kBlock, UNROLL, kMaxChunk, true>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows, first);
             return;
         }
         split_softmax<NH>(s_p, s_m, s_l, nt);
         __syncthreads();
-        value_pass<T, D, NH, GATHER>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows);
+        value_pass<T, D, NH, GATHER, kBlock, UNROLL>(a, s_p, s_red, s_m, s_l, bh0, split, nt, rows);
     }
 };
 

@@ -16,6 +16,10 @@ namespace {
 #ifndef HGCA_DG_OCC
 #define HGCA_DG_OCC 5                            // waves per SIMD the register budget is set for
 #endif
+#ifndef HGCA_DG_GATHER_UNROLL
+#define HGCA_DG_GATHER_UNROLL 8                  // K / V loads a lane of a sparse split keeps in flight (4 in a launch of
+#endif                                           // its own, where eight 64-register workgroups share a unit; here the
+                                                 // register budget is the window body's: 66.8 against 67.9 us per steady step)
 #ifndef HGCA_DG_UNROLL
 #define HGCA_DG_UNROLL 4                         // V loads a lane of a window split keeps in flight
 #endif
@@ -27,7 +31,7 @@ __global__ __launch_bounds__(kBlock, HGCA_DG_OCC) void dense_gather_kernel(Kerne
                                                                           const char *v_new)
 {
     using DS = DenseSplit<D, G, kBlock, HGCA_DG_UNROLL, LD>;   // LDS sized for window splits of up to LD tokens
-    using GS = SplitValu<bf16_t, D, 1, GMODE>;
+    using GS = SplitValu<bf16_t, D, 1, GMODE, HGCA_DG_GATHER_UNROLL>;
     constexpr int kLds = DS::kLdsBytes > GS::kLdsBytes ? DS::kLdsBytes : GS::kLdsBytes;
     __shared__ __attribute__((aligned(16))) char s_lds[kLds];
     // the part with more bytes to move takes the lower block numbers and starts first (the other fills in behind it)
