@@ -434,7 +434,7 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
                               "(7 kernels)"}
 
 
-def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20) -> dict:
+def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 40) -> dict:
     """The append branch (N incoming tokens per sequence) on the workload's tensors: causal attention over the
     window (whose last N tokens stand for the incoming ones), attention over the COMPLETE pool, merge, and the
     query-averaged weights of both parts (what the KV manager's re-evaluation thresholds).  Both contractions run on
@@ -469,7 +469,9 @@ def append_stage_timing(torch, hgca, cfg, L, dev, n_q: int = 32, reps: int = 20)
     }
     ms = {}
     for name, fn in calls.items():
-        for _ in range(3):
+        # these kernels keep matrix cores, vector units, LDS and HBM busy at once and the device settles to its
+        # clocks for that mix only after some tens of calls (a call takes 20 % longer in between): 60 untimed calls
+        for _ in range(60):
             fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -508,7 +510,8 @@ def append_turn_timing(torch, hgca, cfg, L, k_max, dev, n_q: int = 32, turns: in
     B, Hq, Hkv, d, W, P = cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.W, cfg.P
     win_blocks, pool_blocks = W // block_size, P // block_size
     n_blk = -(-n_q // block_size)
-    spare = (turns + 3) * n_blk + 4
+    warm_turns = 8
+    spare = (turns + warm_turns + 1) * n_blk + 4
     C = cache.LayerCache(L.q.dtype, B, Hq, Hkv, d, block_size, win_blocks, pool_blocks + win_blocks + spare,
                          4 * k_max, float(L.shape.sm_scale), dev, win_cap_blocks=win_blocks + n_blk)
     for dst, pool, win in ((C.k_blocks, L.pool.k, L.window.k), (C.v_blocks, L.pool.v, L.window.v)):
@@ -526,8 +529,8 @@ def append_turn_timing(torch, hgca, cfg, L, k_max, dev, n_q: int = 32, turns: in
     v_in = torch.randn(B, n_q, Hkv, d, generator=g).to(L.q.dtype).to(dev)
     BETA = 2.0                                                 # keeps a few thousand entries per head on these inputs
     stream = torch.cuda.current_stream()
-    C.append_step(q, k_in, v_in, 0.3, BETA)                    # warm-up turns (the first allocates the turn's buffers)
-    C.append_step(q, k_in, v_in, 0.3, BETA)
+    for _ in range(warm_turns):                                # untimed (the first allocates the turn's buffers; the device
+        C.append_step(q, k_in, v_in, 0.3, BETA)                # settles to its clocks for this mix of work over some ms)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall = time.perf_counter()
