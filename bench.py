@@ -362,10 +362,11 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
 
     B, Hq, Hkv, d, W, P = cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.W, cfg.P
     win_blocks, pool_blocks = W // block_size, P // block_size
-    runs = 3                                                   # timed runs below, each with a block of warm-up
-    spare = runs * (n_steps // block_size + 1) + 4             # blocks for every step run below
+    runs = 3                                                   # timed runs below, each with its untimed steps first
+    warm = max(64, block_size)                                 # untimed steps per run: the device settles to its clocks
+    spare = runs * ((n_steps + warm) // block_size + 1) + 4    # blocks for every step run below
     C = cache.LayerCache(L.q.dtype, B, Hq, Hkv, d, block_size, win_blocks, pool_blocks + win_blocks + spare,
-                         k_max + runs * (n_steps + block_size), float(L.shape.sm_scale), dev)
+                         k_max + runs * (n_steps + warm + block_size), float(L.shape.sm_scale), dev)
 
     def to_blocks(dst, src, first):                            # [B,Hkv,n,d] -> blocks first.. of every sequence
         n_blk = src.shape[2] // block_size
@@ -390,7 +391,7 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
         def run(n):
             for _ in range(n):
                 C.decode_step(L.q, k_in, v_in, 0.3, 1.0, one_call=one_call)
-        run(block_size)                                        # warm-up: one block of steps, one eviction
+        run(warm)                                              # untimed steps, with their evictions
         torch.cuda.synchronize()
         t_wall = time.perf_counter()
         e0.record(stream)
@@ -407,7 +408,7 @@ def decode_loop_timing(torch, hgca, cfg, L, k_max, dev, block_size: int = 16, n_
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         C.decode_step(L.q, k_in, v_in, 0.3, 1.0, one_call=True)
-    for _ in range(block_size - 1):                            # the capture ran no step; finish a block of warm-up
+    for _ in range(warm - 1):                                  # the capture ran no step; the untimed steps of this run
         graph.replay()
     torch.cuda.synchronize()
     t_wall = time.perf_counter()
