@@ -13,9 +13,9 @@ seeded synthetic K/V already resident in HBM.  Steps cycle over L independently 
 layers so that consecutive steps do not re-read K/V still held in L2 / Infinity Cache.
 Prints ONE JSON line.
 
-`value` is the full step (selection every step) as ONE call of hgca_hybrid_decode_step: split kernels
-of the window part, score pass over the pool, per-head top-k, gather of the kept entries' V rows,
-one fold of all split partials.  `separate_calls_deferred` is the same five kernels through
+`value` is the full step (selection every step) as ONE call of hgca_hybrid_decode_step: score pass over
+the pool, per-head top-k, one launch for the window's split kernels and the gather of the kept entries' V
+rows, one fold of all split partials.  `separate_calls_deferred` is the same work as five kernels through
 hgca_dense_window_attn (result deferred), hgca_select_salient, hgca_sparse_attn (result deferred)
 and hgca_lse_merge_splits; `four_calls` is the step with each part folding its own splits and
 hgca_lse_merge joining them.  In all of them the selection hands the scores of
